@@ -1,0 +1,155 @@
+"""ctypes front end of the CPU oracle (oracle/affmae_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu-baseline leg.  The product package never imports this module,
+and this module never imports the product package.
+
+All floating-point tensors cross as float64 numpy arrays (callers convert the
+stored fp32 / bf16 values exactly); indices are int32; coordinates are fp32
+because the neighbour search is defined on fp32 arithmetic.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "affmae_oracle.c")
+_LIB = os.path.join(_HERE, "libaffmae_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fused multiply-add, no fast-math)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+               "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        for name in ("oracle_centroids", "oracle_knn", "oracle_knn_bruteforce",
+                     "oracle_pla_fwd", "oracle_pla_bwd", "oracle_num_threads"):
+            getattr(_lib, name).restype = ctypes.c_int
+        _lib.oracle_set_num_threads.restype = None
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f64(a, shape=None) -> Optional[np.ndarray]:
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError(f"shape {a.shape} != expected {shape}")
+    return a
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"{what} failed with oracle status {rc}")
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().oracle_set_num_threads(ctypes.c_int(int(n)))
+
+
+def centroids(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int) -> np.ndarray:
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    B, N, _ = coords.shape
+    if cluster_id is not None:
+        cluster_id = np.ascontiguousarray(cluster_id, dtype=np.int32)
+    out = np.empty((B, N // S, 2), dtype=np.float32)
+    _check(_load().oracle_centroids(_p(coords), _p(cluster_id), B, N, S, _p(out)), "oracle_centroids")
+    return out
+
+
+def knn(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int, M: int, K: int
+        ) -> Tuple[np.ndarray, np.ndarray]:
+    """Clustered neighbour search -> (nbr_idx [B,N,K], near_clusters [B,G,M])."""
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    B, N, two = coords.shape
+    assert two == 2
+    if cluster_id is not None:
+        cluster_id = np.ascontiguousarray(cluster_id, dtype=np.int32)
+        assert cluster_id.shape == (B, N)
+    if S <= 0 or N % S:
+        raise ValueError("N must be a positive multiple of S")
+    nbr = np.empty((B, N, K), dtype=np.int32)
+    near = np.empty((B, N // S, M), dtype=np.int32)
+    _check(_load().oracle_knn(_p(coords), _p(cluster_id), B, N, S, M, K, _p(nbr), _p(near)), "oracle_knn")
+    return nbr, near
+
+
+def knn_bruteforce(coords: np.ndarray, K: int) -> np.ndarray:
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    B, N, _ = coords.shape
+    nbr = np.empty((B, N, K), dtype=np.int32)
+    _check(_load().oracle_knn_bruteforce(_p(coords), B, N, K, _p(nbr)), "oracle_knn_bruteforce")
+    return nbr
+
+
+def pla_fwd(q, k, v, bias, nbr_idx, scale: float, k_blank=None, v_blank=None, want_prob: bool = False):
+    """Local attention forward -> (out [B,N,H,d], lse [B,N,H][, prob [B,N,H,K+1]])."""
+    q = _f64(q)
+    B, N, H, d = q.shape
+    k = _f64(k, q.shape)
+    v = _f64(v, q.shape)
+    nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    K = nbr_idx.shape[2]
+    assert nbr_idx.shape == (B, N, K)
+    bias = _f64(bias, (B, N, K, H))
+    k_blank = _f64(k_blank, (H, d))
+    v_blank = _f64(v_blank, (H, d))
+    out = np.empty((B, N, H, d), dtype=np.float64)
+    lse = np.empty((B, N, H), dtype=np.float64)
+    prob = np.empty((B, N, H, K + 1), dtype=np.float64) if want_prob else None
+    _check(_load().oracle_pla_fwd(_p(q), _p(k), _p(v), _p(bias), _p(nbr_idx), _p(k_blank), _p(v_blank),
+                                  B, N, H, d, K, ctypes.c_double(scale), _p(out), _p(lse), _p(prob)),
+           "oracle_pla_fwd")
+    return (out, lse, prob) if want_prob else (out, lse)
+
+
+def pla_bwd(q, k, v, bias, nbr_idx, dout, scale: float, k_blank=None, v_blank=None):
+    """Local attention backward -> dict(dq, dk, dv, dbias[, dk_blank, dv_blank])."""
+    q = _f64(q)
+    B, N, H, d = q.shape
+    k = _f64(k, q.shape)
+    v = _f64(v, q.shape)
+    dout = _f64(dout, q.shape)
+    nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    K = nbr_idx.shape[2]
+    bias = _f64(bias, (B, N, K, H))
+    k_blank = _f64(k_blank, (H, d))
+    v_blank = _f64(v_blank, (H, d))
+    dq = np.empty_like(q)
+    dk = np.empty_like(q)
+    dv = np.empty_like(q)
+    dbias = np.empty((B, N, K, H), dtype=np.float64)
+    dkb = np.empty((H, d), dtype=np.float64) if k_blank is not None else None
+    dvb = np.empty((H, d), dtype=np.float64) if k_blank is not None else None
+    _check(_load().oracle_pla_bwd(_p(q), _p(k), _p(v), _p(bias), _p(nbr_idx), _p(k_blank), _p(v_blank),
+                                  _p(dout), B, N, H, d, K, ctypes.c_double(scale), _p(dq), _p(dk), _p(dv),
+                                  _p(dbias), _p(dkb), _p(dvb)), "oracle_pla_bwd")
+    res = {"dq": dq, "dk": dk, "dv": dv, "dbias": dbias}
+    if dkb is not None:
+        res["dk_blank"] = dkb
+        res["dv_blank"] = dvb
+    return res

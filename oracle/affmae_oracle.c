@@ -1,0 +1,427 @@
+/*
+ * CPU oracle for the neighbourhood-attention hot path of AFFMAE.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow definition that the
+ * GPU library is checked against.  It shares no code, header, table or helper
+ * with the HIP path, and nothing in the product may call it: only the tests,
+ * the smoke check and the benchmark's cpu-baseline leg do.
+ *
+ * What it follows:
+ *   - neighbourhood construction: Sec. "AutoFocusFormer" (tokens carry a 2-D
+ *     coordinate, are grouped into equal-size clusters, and every token gets a
+ *     fixed-size neighbourhood by nearest-neighbour search over coordinates);
+ *   - local attention: the FlashNbhdAttn equation of Sec. "Flash-style Cluster
+ *     Attention and Fast Decoder KNN":
+ *         softmax(Q_n [K_n K_blank]^T + B_n) [V_n V_blank]
+ *     written out per token and head, in double precision, with no tiling;
+ *   - backward: the chain rule applied to that equation (the paper does not
+ *     print it).
+ *
+ * Readings taken where the paper is silent (each is listed in the design notes):
+ *   - distance = squared Euclidean distance evaluated in fp32 as
+ *     fl(fl(dx*dx) + fl(dy*dy)), dx = fl(ax-bx), dy = fl(ay-by); no fused
+ *     multiply-add, no square root;
+ *   - order = lexicographic (distance, index), lower wins; lists ascending;
+ *   - "nearest clusters" = by distance between cluster centroids, a centroid
+ *     being the fp32 rounding of the double-precision mean of the members taken
+ *     in ascending token order; the cluster itself is included;
+ *   - a token is a candidate for its own neighbourhood;
+ *   - an explicit logit scale multiplies Q K^T; the blank column has no bias.
+ *
+ * Parity pins (tests/test_oracle_*.py): brute force over all pairs with a
+ * library sort, hand-derived grid fixtures, exact integer arithmetic on integer
+ * coordinates, dense masked softmax attention built from library matmuls,
+ * reverse-mode autodiff of that dense form, central finite differences, and
+ * the invariants of softmax.
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_CLUSTER (-2)
+#define ORACLE_ERR_ALLOC (-3)
+
+/* Number of threads the image-parallel loops will use (1 without OpenMP). */
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
+/* fp32 squared distance, every operation rounded on its own. */
+static float dist2_f32(float ax, float ay, float bx, float by) {
+  float dx = ax - bx;
+  float dy = ay - by;
+  float xx = dx * dx;
+  float yy = dy * dy;
+  return xx + yy;
+}
+
+typedef struct {
+  float d2;
+  int32_t idx;
+} cand_t;
+
+static int cand_less(const void *pa, const void *pb) {
+  const cand_t *a = (const cand_t *)pa, *b = (const cand_t *)pb;
+  if (a->d2 < b->d2) return -1;
+  if (a->d2 > b->d2) return 1;
+  if (a->idx < b->idx) return -1;
+  if (a->idx > b->idx) return 1;
+  return 0;
+}
+
+/*
+ * Member lists of one image.  cluster_id == NULL means token i belongs to
+ * cluster i / S.  members[c*S + r] = r-th token of cluster c in ascending token
+ * order.  Fails unless every cluster has exactly S members.
+ */
+static int build_members(const int32_t *cluster_id, int N, int S, int32_t *members) {
+  int G = N / S;
+  int *count = (int *)calloc((size_t)G, sizeof(int));
+  if (!count) return ORACLE_ERR_ALLOC;
+  int rc = ORACLE_OK;
+  for (int i = 0; i < N && rc == ORACLE_OK; ++i) {
+    int c = cluster_id ? cluster_id[i] : i / S;
+    if (c < 0 || c >= G || count[c] >= S) {
+      rc = ORACLE_ERR_CLUSTER;
+      break;
+    }
+    members[(size_t)c * S + count[c]++] = i;
+  }
+  for (int c = 0; c < G && rc == ORACLE_OK; ++c)
+    if (count[c] != S) rc = ORACLE_ERR_CLUSTER;
+  free(count);
+  return rc;
+}
+
+/* Centroid of each cluster: double sum in member order, divide, round to fp32. */
+static void image_centroids(const float *coords, const int32_t *members, int G, int S,
+                            float *centroid) {
+  for (int c = 0; c < G; ++c) {
+    double sx = 0.0, sy = 0.0;
+    for (int r = 0; r < S; ++r) {
+      int i = members[(size_t)c * S + r];
+      sx += (double)coords[2 * (size_t)i + 0];
+      sy += (double)coords[2 * (size_t)i + 1];
+    }
+    centroid[2 * c + 0] = (float)(sx / (double)S);
+    centroid[2 * c + 1] = (float)(sy / (double)S);
+  }
+}
+
+/*
+ * oracle_centroids: coords [B,N,2] fp32, cluster_id [B,N] or NULL
+ *   -> centroid [B,G,2] fp32, G = N/S.
+ */
+int oracle_centroids(const float *coords, const int32_t *cluster_id, int B, int N, int S,
+                     float *centroid) {
+  if (!coords || !centroid || B < 0 || N <= 0 || S <= 0 || N % S) return ORACLE_ERR_ARG;
+  int G = N / S;
+  int32_t *members = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+  if (!members) return ORACLE_ERR_ALLOC;
+  int rc = ORACLE_OK;
+  for (int b = 0; b < B && rc == ORACLE_OK; ++b) {
+    rc = build_members(cluster_id ? cluster_id + (size_t)b * N : NULL, N, S, members);
+    if (rc == ORACLE_OK)
+      image_centroids(coords + (size_t)b * N * 2, members, G, S, centroid + (size_t)b * G * 2);
+  }
+  free(members);
+  return rc;
+}
+
+/*
+ * oracle_knn: clustered neighbour search.
+ *   coords [B,N,2] fp32; cluster_id [B,N] int32 or NULL (= i / S);
+ *   1 <= M <= G = N/S; 1 <= K <= M*S.
+ *   near_clusters [B,G,M] (may be NULL): for each cluster the M clusters with
+ *     nearest centroids, ascending (distance, cluster index); the cluster
+ *     itself takes part.
+ *   nbr_idx [B,N,K]: for each token the K nearest tokens among the members of
+ *     its cluster's M nearest clusters, ascending (distance, token index).
+ */
+int oracle_knn(const float *coords, const int32_t *cluster_id, int B, int N, int S, int M, int K,
+               int32_t *nbr_idx, int32_t *near_clusters) {
+  if (!coords || !nbr_idx || B < 0 || N <= 0 || S <= 0 || N % S) return ORACLE_ERR_ARG;
+  int G = N / S;
+  if (M < 1 || M > G || K < 1 || (long long)K > (long long)M * S) return ORACLE_ERR_ARG;
+  int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b) {
+    const float *xy = coords + (size_t)b * N * 2;
+    int32_t *members = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    int32_t *cluster_of = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    float *centroid = (float *)malloc((size_t)G * 2 * sizeof(float));
+    int32_t *near = (int32_t *)malloc((size_t)G * M * sizeof(int32_t));
+    cand_t *cand = (cand_t *)malloc((size_t)(M * S > G ? M * S : G) * sizeof(cand_t));
+    int rc = (members && cluster_of && centroid && near && cand) ? ORACLE_OK : ORACLE_ERR_ALLOC;
+    if (rc == ORACLE_OK) rc = build_members(cluster_id ? cluster_id + (size_t)b * N : NULL, N, S, members);
+    if (rc == ORACLE_OK) {
+      for (int c = 0; c < G; ++c)
+        for (int r = 0; r < S; ++r) cluster_of[members[(size_t)c * S + r]] = c;
+      image_centroids(xy, members, G, S, centroid);
+      /* nearest clusters by centroid distance */
+      for (int c = 0; c < G; ++c) {
+        for (int e = 0; e < G; ++e) {
+          cand[e].d2 = dist2_f32(centroid[2 * c], centroid[2 * c + 1], centroid[2 * e], centroid[2 * e + 1]);
+          cand[e].idx = e;
+        }
+        qsort(cand, (size_t)G, sizeof(cand_t), cand_less);
+        for (int m = 0; m < M; ++m) near[(size_t)c * M + m] = cand[m].idx;
+      }
+      if (near_clusters)
+        memcpy(near_clusters + (size_t)b * G * M, near, (size_t)G * M * sizeof(int32_t));
+      /* per token: all members of the near clusters are candidates */
+      for (int i = 0; i < N; ++i) {
+        int c = cluster_of[i];
+        int n = 0;
+        for (int m = 0; m < M; ++m) {
+          int e = near[(size_t)c * M + m];
+          for (int r = 0; r < S; ++r) {
+            int j = members[(size_t)e * S + r];
+            cand[n].d2 = dist2_f32(xy[2 * (size_t)i], xy[2 * (size_t)i + 1], xy[2 * (size_t)j], xy[2 * (size_t)j + 1]);
+            cand[n].idx = j;
+            ++n;
+          }
+        }
+        qsort(cand, (size_t)n, sizeof(cand_t), cand_less);
+        int32_t *dst = nbr_idx + ((size_t)b * N + i) * K;
+        for (int t = 0; t < K; ++t) dst[t] = cand[t].idx;
+      }
+    }
+    free(members); free(cluster_of); free(centroid); free(near); free(cand);
+    if (rc != ORACLE_OK) {
+#pragma omp critical
+      status = rc;
+    }
+  }
+  return status;
+}
+
+/* oracle_knn_bruteforce: every token of the image is a candidate. */
+int oracle_knn_bruteforce(const float *coords, int B, int N, int K, int32_t *nbr_idx) {
+  if (!coords || !nbr_idx || B < 0 || N <= 0 || K < 1 || K > N) return ORACLE_ERR_ARG;
+  int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b) {
+    const float *xy = coords + (size_t)b * N * 2;
+    cand_t *cand = (cand_t *)malloc((size_t)N * sizeof(cand_t));
+    if (!cand) {
+#pragma omp critical
+      status = ORACLE_ERR_ALLOC;
+      continue;
+    }
+    for (int i = 0; i < N; ++i) {
+      for (int j = 0; j < N; ++j) {
+        cand[j].d2 = dist2_f32(xy[2 * (size_t)i], xy[2 * (size_t)i + 1], xy[2 * (size_t)j], xy[2 * (size_t)j + 1]);
+        cand[j].idx = j;
+      }
+      qsort(cand, (size_t)N, sizeof(cand_t), cand_less);
+      int32_t *dst = nbr_idx + ((size_t)b * N + i) * K;
+      for (int t = 0; t < K; ++t) dst[t] = cand[t].idx;
+    }
+    free(cand);
+  }
+  return status;
+}
+
+/*
+ * Softmax row of one (image, token, head): fills s[0..Kt) with the logits and
+ * p[0..Kt) with the probabilities, returns log(sum exp(s)).  Kt = K (+1 with a
+ * blank column, which is slot K).
+ */
+static double attention_row(const double *q, const double *k, const double *bias,
+                            const int32_t *nbr, const double *k_blank, int b, int i, int h,
+                            int N, int H, int d, int K, double scale, double *s, double *p) {
+  const double *qi = q + (((size_t)b * N + i) * H + h) * d;
+  int Kt = K;
+  for (int j = 0; j < K; ++j) {
+    int n = nbr[((size_t)b * N + i) * K + j];
+    const double *kn = k + (((size_t)b * N + n) * H + h) * d;
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) acc += qi[t] * kn[t];
+    s[j] = scale * acc + (bias ? bias[(((size_t)b * N + i) * K + j) * H + h] : 0.0);
+  }
+  if (k_blank) {
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) acc += qi[t] * k_blank[(size_t)h * d + t];
+    s[K] = scale * acc;
+    Kt = K + 1;
+  }
+  double m = s[0];
+  for (int j = 1; j < Kt; ++j)
+    if (s[j] > m) m = s[j];
+  double z = 0.0;
+  for (int j = 0; j < Kt; ++j) {
+    p[j] = exp(s[j] - m);
+    z += p[j];
+  }
+  for (int j = 0; j < Kt; ++j) p[j] /= z;
+  return m + log(z);
+}
+
+static int check_nbr(const int32_t *nbr, size_t count, int N) {
+  for (size_t t = 0; t < count; ++t)
+    if (nbr[t] < 0 || nbr[t] >= N) return ORACLE_ERR_ARG;
+  return ORACLE_OK;
+}
+
+/*
+ * oracle_pla_fwd: q,k,v [B,N,H,d]; bias [B,N,K,H] or NULL; nbr_idx [B,N,K] with
+ * values in [0,N) (repeats allowed: every slot is its own softmax column);
+ * k_blank,v_blank [H,d] or both NULL.
+ *   out [B,N,H,d]; lse [B,N,H] natural log of the softmax denominator;
+ *   prob (may be NULL) [B,N,H,K+1] probabilities, slot K = blank (0 if none).
+ */
+int oracle_pla_fwd(const double *q, const double *k, const double *v, const double *bias,
+                   const int32_t *nbr_idx, const double *k_blank, const double *v_blank, int B,
+                   int N, int H, int d, int K, double scale, double *out, double *lse,
+                   double *prob) {
+  if (!q || !k || !v || !nbr_idx || !out || !lse) return ORACLE_ERR_ARG;
+  if (B < 0 || N <= 0 || H <= 0 || d <= 0 || K <= 0) return ORACLE_ERR_ARG;
+  if ((k_blank == NULL) != (v_blank == NULL)) return ORACLE_ERR_ARG;
+  if (check_nbr(nbr_idx, (size_t)B * N * K, N) != ORACLE_OK) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+  for (int b = 0; b < B; ++b) {
+    double *s = (double *)malloc((size_t)(K + 1) * sizeof(double));
+    double *p = (double *)malloc((size_t)(K + 1) * sizeof(double));
+    for (int i = 0; i < N; ++i)
+      for (int h = 0; h < H; ++h) {
+        double l = attention_row(q, k, bias, nbr_idx, k_blank, b, i, h, N, H, d, K, scale, s, p);
+        double *o = out + (((size_t)b * N + i) * H + h) * d;
+        for (int t = 0; t < d; ++t) o[t] = 0.0;
+        for (int j = 0; j < K; ++j) {
+          int n = nbr_idx[((size_t)b * N + i) * K + j];
+          const double *vn = v + (((size_t)b * N + n) * H + h) * d;
+          for (int t = 0; t < d; ++t) o[t] += p[j] * vn[t];
+        }
+        if (v_blank)
+          for (int t = 0; t < d; ++t) o[t] += p[K] * v_blank[(size_t)h * d + t];
+        lse[((size_t)b * N + i) * H + h] = l;
+        if (prob) {
+          double *pr = prob + (((size_t)b * N + i) * H + h) * (K + 1);
+          for (int j = 0; j < K; ++j) pr[j] = p[j];
+          pr[K] = k_blank ? p[K] : 0.0;
+        }
+      }
+    free(s);
+    free(p);
+  }
+  return ORACLE_OK;
+}
+
+/*
+ * oracle_pla_bwd: gradients of L = sum(dout * out) with respect to q, k, v,
+ * bias and the blank rows.  With p the softmax row of (b,i,h):
+ *   dP_j  = <dout_i, v_j>             (v_j = neighbour row or blank row)
+ *   D     = sum_j p_j dP_j
+ *   dS_j  = p_j (dP_j - D)
+ *   dbias[b,i,j,h]   = dS_j                      (j < K)
+ *   dq_i            += scale * dS_j * k_j
+ *   dk[n(i,j)]      += scale * dS_j * q_i,   dv[n(i,j)] += p_j * dout_i
+ *   dk_blank[h]     += scale * dS_K * q_i,   dv_blank[h] += p_K * dout_i
+ * All outputs are overwritten.  dbias, dk_blank, dv_blank may be NULL.
+ */
+int oracle_pla_bwd(const double *q, const double *k, const double *v, const double *bias,
+                   const int32_t *nbr_idx, const double *k_blank, const double *v_blank,
+                   const double *dout, int B, int N, int H, int d, int K, double scale, double *dq,
+                   double *dk, double *dv, double *dbias, double *dk_blank, double *dv_blank) {
+  if (!q || !k || !v || !nbr_idx || !dout || !dq || !dk || !dv) return ORACLE_ERR_ARG;
+  if (B < 0 || N <= 0 || H <= 0 || d <= 0 || K <= 0) return ORACLE_ERR_ARG;
+  if ((k_blank == NULL) != (v_blank == NULL)) return ORACLE_ERR_ARG;
+  if (check_nbr(nbr_idx, (size_t)B * N * K, N) != ORACLE_OK) return ORACLE_ERR_ARG;
+  size_t per_image = (size_t)N * H * d;
+  memset(dq, 0, (size_t)B * per_image * sizeof(double));
+  memset(dk, 0, (size_t)B * per_image * sizeof(double));
+  memset(dv, 0, (size_t)B * per_image * sizeof(double));
+  if (dk_blank) memset(dk_blank, 0, (size_t)H * d * sizeof(double));
+  if (dv_blank) memset(dv_blank, 0, (size_t)H * d * sizeof(double));
+  /* blank-row gradients sum over images: one partial per image, added in image order */
+  double *blank_part = NULL;
+  if (k_blank && (dk_blank || dv_blank)) {
+    blank_part = (double *)calloc((size_t)B * 2 * H * d, sizeof(double));
+    if (!blank_part) return ORACLE_ERR_ALLOC;
+  }
+#pragma omp parallel for schedule(static)
+  for (int b = 0; b < B; ++b) {
+    double *s = (double *)malloc((size_t)(K + 1) * sizeof(double));
+    double *p = (double *)malloc((size_t)(K + 1) * sizeof(double));
+    double *dP = (double *)malloc((size_t)(K + 1) * sizeof(double));
+    for (int i = 0; i < N; ++i)
+      for (int h = 0; h < H; ++h) {
+        attention_row(q, k, bias, nbr_idx, k_blank, b, i, h, N, H, d, K, scale, s, p);
+        int Kt = k_blank ? K + 1 : K;
+        size_t qoff = (((size_t)b * N + i) * H + h) * d;
+        const double *qi = q + qoff;
+        const double *gi = dout + qoff;
+        double D = 0.0;
+        for (int j = 0; j < Kt; ++j) {
+          const double *vn;
+          if (j < K) {
+            int n = nbr_idx[((size_t)b * N + i) * K + j];
+            vn = v + (((size_t)b * N + n) * H + h) * d;
+          } else {
+            vn = v_blank + (size_t)h * d;
+          }
+          double acc = 0.0;
+          for (int t = 0; t < d; ++t) acc += gi[t] * vn[t];
+          dP[j] = acc;
+          D += p[j] * acc;
+        }
+        for (int j = 0; j < Kt; ++j) {
+          double dS = p[j] * (dP[j] - D);
+          if (j < K) {
+            int n = nbr_idx[((size_t)b * N + i) * K + j];
+            size_t noff = (((size_t)b * N + n) * H + h) * d;
+            if (dbias) dbias[(((size_t)b * N + i) * K + j) * H + h] = dS;
+            for (int t = 0; t < d; ++t) {
+              dq[qoff + t] += scale * dS * k[noff + t];
+              dk[noff + t] += scale * dS * qi[t];
+              dv[noff + t] += p[j] * gi[t];
+            }
+          } else {
+            double *pk = blank_part ? blank_part + ((size_t)b * 2 + 0) * H * d + (size_t)h * d : NULL;
+            double *pv = blank_part ? blank_part + ((size_t)b * 2 + 1) * H * d + (size_t)h * d : NULL;
+            for (int t = 0; t < d; ++t) {
+              dq[qoff + t] += scale * dS * k_blank[(size_t)h * d + t];
+              if (pk) {
+                pk[t] += scale * dS * qi[t];
+                pv[t] += p[j] * gi[t];
+              }
+            }
+          }
+        }
+      }
+    free(s);
+    free(p);
+    free(dP);
+  }
+  if (blank_part) {
+    for (int b = 0; b < B; ++b)
+      for (int e = 0; e < H * d; ++e) {
+        if (dk_blank) dk_blank[e] += blank_part[((size_t)b * 2 + 0) * H * d + e];
+        if (dv_blank) dv_blank[e] += blank_part[((size_t)b * 2 + 1) * H * d + e];
+      }
+    free(blank_part);
+  }
+  return ORACLE_OK;
+}
