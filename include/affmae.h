@@ -1,0 +1,164 @@
+/*
+ * affmae.h - C ABI of the MI355X (gfx950) neighbourhood-attention library.
+ *
+ * The library implements the data-parallel hot path of AFFMAE's off-grid
+ * hierarchical backbone: the batched neighbour search that builds fixed-size
+ * neighbourhoods over irregular 2-D token coordinates, and local attention,
+ * forward and backward, over each token's K neighbours.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *     never allocates, frees or keeps them.  Tensors are dense, row-major, in
+ *     the shapes stated below.  B = images, N = tokens per image, H = heads,
+ *     d = channels per head, K = neighbours per token, S = tokens per cluster,
+ *     G = N / S clusters per image, M = clusters searched per cluster.
+ *   - Token and cluster indices are per image (0..N-1, 0..G-1), int32.
+ *   - `workspace` is caller-owned device scratch of at least the number of
+ *     bytes the matching *_workspace_bytes() call returns (256-byte aligned);
+ *     its contents are undefined before and after a call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls validate their arguments on the host, enqueue kernels on `stream`
+ *     and return without synchronising.  Calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Return value: AFFMAE_OK (0) or a negative affmae_status.  When an error
+ *     is returned nothing has been enqueued.  No exception crosses the ABI.
+ *   - Outputs are fully overwritten (never accumulated into).
+ *   - The host cannot see tensor contents.  Index values outside their range
+ *     (cluster_id, nbr_idx, near_clusters) never cause out-of-bounds accesses,
+ *     but the results for the affected tokens are unspecified.
+ */
+#ifndef AFFMAE_H_
+#define AFFMAE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AFFMAE_OK = 0,
+  AFFMAE_ERR_NULL = -1,        /* a required pointer is NULL                     */
+  AFFMAE_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent         */
+  AFFMAE_ERR_DTYPE = -3,       /* unknown storage type                           */
+  AFFMAE_ERR_WORKSPACE = -4,   /* workspace missing, too small or misaligned     */
+  AFFMAE_ERR_UNSUPPORTED = -5, /* valid request outside the implemented limits   */
+  AFFMAE_ERR_DEVICE = -6       /* the HIP runtime refused a launch               */
+} affmae_status;
+
+typedef enum { AFFMAE_F32 = 0, AFFMAE_BF16 = 1 } affmae_dtype;
+
+/* Implemented limits (AFFMAE_ERR_UNSUPPORTED beyond them). */
+#define AFFMAE_MAX_K 64          /* neighbours per token                         */
+#define AFFMAE_MAX_NEAR 64       /* M, clusters searched per cluster             */
+
+/* Human-readable name of a status code; never NULL. */
+const char* affmae_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int affmae_version(void);
+
+/*
+ * affmae_knn - neighbourhood construction (paper, Sec. "AutoFocusFormer":
+ * tokens are grouped into equal-size clusters and every token gets a
+ * fixed-size neighbourhood by nearest-neighbour search over 2-D coordinates;
+ * the table is built once per encoder stage and reused, Sec. "Limitations").
+ *
+ *   coords        in  [B,N,2] fp32 (x,y), finite.
+ *   cluster_id    in  [B,N] int32 with every cluster holding exactly S tokens,
+ *                     or NULL meaning cluster_id[b,i] = i / S (tokens stored in
+ *                     cluster order).
+ *   B,N,S,M,K         N % S == 0, 1 <= M <= min(G, AFFMAE_MAX_NEAR),
+ *                     1 <= K <= min(M*S, AFFMAE_MAX_K).  M == G is exact kNN.
+ *   nbr_idx       out [B,N,K]: the K nearest tokens among the members of the M
+ *                     clusters nearest to the token's own cluster, ascending in
+ *                     (distance, token index).  The token itself takes part.
+ *   near_clusters out [B,G,M] or NULL: the M clusters with nearest centroids,
+ *                     ascending in (distance, cluster index), the cluster
+ *                     itself included.
+ *
+ * Arithmetic is fixed so that results are unique: distance is the fp32 value
+ * fl(fl(dx*dx) + fl(dy*dy)) with dx = fl(ax-bx), dy = fl(ay-by) (no fused
+ * multiply-add, no square root); a centroid is the fp32 rounding of the
+ * double-precision mean of the members summed in ascending token order.
+ */
+size_t affmae_knn_workspace_bytes(int B, int N, int S, int M, int K);
+int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int S, int M, int K,
+               int32_t* nbr_idx, int32_t* near_clusters, void* workspace, size_t workspace_bytes,
+               void* stream);
+
+/*
+ * affmae_pla_fwd - local attention over each token's neighbourhood (paper,
+ * Sec. "Flash-style Cluster Attention and Fast Decoder KNN", the FlashNbhdAttn
+ * equation): for every image b, token i and head h
+ *     s_j   = scale * <q[b,i,h,:], k[b,n(i,j),h,:]> + bias[b,i,j,h]   (j < K)
+ *     s_K   = scale * <q[b,i,h,:], k_blank[h,:]>                      (if given)
+ *     p     = softmax(s)
+ *     out[b,i,h,:] = sum_j p_j v[b,n(i,j),h,:]  (+ p_K v_blank[h,:])
+ *     lse[b,i,h]   = log(sum_j exp(s_j))
+ * computed without storing the score matrix, with fp32 softmax statistics and
+ * accumulators whatever the storage type.
+ *
+ *   q,k,v         in  [B,N,H,d] of `dtype`.
+ *   bias          in  [B,N,K,H] of `dtype`, or NULL (= 0).
+ *   nbr_idx       in  [B,N,K] int32, values in [0,N); it need not come from
+ *                     affmae_knn and may list a token more than once (each
+ *                     slot is its own softmax column) unless near_clusters is
+ *                     given.
+ *   near_clusters in  [B,G,M] int32 or NULL.  Non-NULL is a promise that
+ *                     tokens are stored in cluster order (cluster = i / S),
+ *                     that every neighbour of a token of cluster c lies in one
+ *                     of near_clusters[b,c,:], and that a token's neighbours
+ *                     are pairwise distinct - what affmae_knn produces with
+ *                     cluster_id == NULL.  It allows the cluster-tiled kernels.
+ *                     With NULL, S and M are ignored.
+ *   k_blank,v_blank in [H,d] of `dtype`, or both NULL.
+ *   d                 16, 32 or 64.  1 <= K <= AFFMAE_MAX_K.
+ *   out           out [B,N,H,d] of `dtype` (round to nearest even).
+ *   lse           out [B,N,H] fp32.
+ */
+size_t affmae_pla_fwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
+                                      int clustered);
+int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias,
+                   const int32_t* nbr_idx, const int32_t* near_clusters, const void* k_blank,
+                   const void* v_blank, int B, int N, int H, int d, int K, int S, int M, float scale,
+                   int dtype, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/*
+ * affmae_pla_bwd - gradients of affmae_pla_fwd (the paper trains through the
+ * attention but prints no backward; this is the chain rule on the equation
+ * above).  With p recomputed from lse and g = dout:
+ *     dP_j = <g[b,i,h,:], v_j>,  D = sum_j p_j dP_j,  dS_j = p_j (dP_j - D)
+ *     dbias[b,i,j,h]  = dS_j
+ *     dq[b,i,h,:]     = scale * sum_j dS_j k_j
+ *     dk[b,n(i,j),h,:] += scale * dS_j q[b,i,h,:]
+ *     dv[b,n(i,j),h,:] += p_j g[b,i,h,:]
+ *     dk_blank[h,:]   = scale * sum_{b,i} dS_K q[b,i,h,:]
+ *     dv_blank[h,:]   = sum_{b,i} p_K g[b,i,h,:]
+ *
+ *   inputs as affmae_pla_fwd, plus
+ *   out           in  [B,N,H,d] of `dtype`: forward output (may be NULL; the
+ *                     current kernels rebuild D from p and dP instead).
+ *   lse           in  [B,N,H] fp32 from the forward call.
+ *   dout          in  [B,N,H,d] of `dtype`.
+ *   dq,dk,dv      out [B,N,H,d] of `dtype`; sums are formed in fp32.  The order
+ *                     of the additions into dk/dv may differ between runs.
+ *   dbias         out [B,N,K,H] of `dtype`, or NULL to skip.
+ *   dk_blank,dv_blank out [H,d] fp32, or NULL (both required when blanks given
+ *                     and their gradients are wanted).
+ */
+size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
+                                      int clustered);
+int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias,
+                   const int32_t* nbr_idx, const int32_t* near_clusters, const void* k_blank,
+                   const void* v_blank, const void* out, const float* lse, const void* dout, int B,
+                   int N, int H, int d, int K, int S, int M, float scale, int dtype, void* dq,
+                   void* dk, void* dv, void* dbias, float* dk_blank, float* dv_blank,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AFFMAE_H_ */

@@ -1,0 +1,19 @@
+"""MI355X-native neighbourhood attention for AFFMAE's off-grid backbone.
+
+The compute lives in libaffmae.so (hand-written HIP for gfx950, C ABI declared
+in include/affmae.h).  This package is the thin Python binding: it marshals
+torch device tensors into that ABI and owns no arithmetic.  There is no CPU or
+PyTorch fallback: without the built library every call raises.
+"""
+from .binding import (  # noqa: F401
+    AffmaeError,
+    affmae_knn,
+    affmae_pla_bwd,
+    affmae_pla_fwd,
+    library_path,
+    load_library,
+    status_string,
+)
+
+__all__ = ["AffmaeError", "affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd", "library_path", "load_library",
+           "status_string"]

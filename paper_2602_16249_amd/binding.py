@@ -1,0 +1,225 @@
+"""ctypes binding of libaffmae.so.  Argument marshalling only.
+
+torch is used for device memory (outputs and workspaces are torch tensors) and
+for the current HIP stream; every step of the computation runs inside the
+library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libaffmae.so")
+_lib = None
+
+AFFMAE_F32 = 0
+AFFMAE_BF16 = 1
+
+_c_int = ctypes.c_int
+_c_void_p = ctypes.c_void_p
+_c_size_t = ctypes.c_size_t
+_c_float = ctypes.c_float
+
+
+class AffmaeError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} returned {status}: {status_string(status)}")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libaffmae.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build_library  # needs hipcc
+        build_library()
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.affmae_status_string.restype = ctypes.c_char_p
+    lib.affmae_status_string.argtypes = [_c_int]
+    lib.affmae_version.restype = _c_int
+    lib.affmae_knn_workspace_bytes.restype = _c_size_t
+    lib.affmae_knn_workspace_bytes.argtypes = [_c_int] * 5
+    lib.affmae_knn.restype = _c_int
+    lib.affmae_knn.argtypes = [_c_void_p, _c_void_p] + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_void_p, _c_size_t,
+                                                                      _c_void_p]
+    for name in ("affmae_pla_fwd_workspace_bytes", "affmae_pla_bwd_workspace_bytes"):
+        f = getattr(lib, name)
+        f.restype = _c_size_t
+        f.argtypes = [_c_int] * 9
+    lib.affmae_pla_fwd.restype = _c_int
+    lib.affmae_pla_fwd.argtypes = ([_c_void_p] * 8 + [_c_int] * 7 + [_c_float, _c_int] + [_c_void_p, _c_void_p]
+                                   + [_c_void_p, _c_size_t, _c_void_p])
+    lib.affmae_pla_bwd.restype = _c_int
+    lib.affmae_pla_bwd.argtypes = ([_c_void_p] * 11 + [_c_int] * 7 + [_c_float, _c_int] + [_c_void_p] * 6
+                                   + [_c_void_p, _c_size_t, _c_void_p])
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().affmae_status_string(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None, shape=None) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t
+
+
+def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return AFFMAE_F32
+    if t.dtype == torch.bfloat16:
+        return AFFMAE_BF16
+    raise ValueError(f"unsupported storage dtype {t.dtype}")
+
+
+def affmae_knn(coords: torch.Tensor, cluster_id: Optional[torch.Tensor], S: int, M: int, K: int,
+               nbr_idx: Optional[torch.Tensor] = None, near_clusters: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """coords [B,N,2] fp32, cluster_id [B,N] int32 or None -> (nbr_idx [B,N,K], near_clusters [B,G,M])."""
+    lib = load_library()
+    _dev(coords, "coords", torch.float32)
+    B, N, two = coords.shape
+    if two != 2:
+        raise ValueError("coords must be [B,N,2]")
+    if cluster_id is not None:
+        _dev(cluster_id, "cluster_id", torch.int32, (B, N))
+    G = N // S if S > 0 else 0
+    if nbr_idx is None:
+        nbr_idx = torch.empty((B, N, K), dtype=torch.int32, device=coords.device)
+    if near_clusters is None:
+        near_clusters = torch.empty((B, max(G, 0), M), dtype=torch.int32, device=coords.device)
+    _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
+    _dev(near_clusters, "near_clusters", torch.int32, (B, G, M))
+    need = lib.affmae_knn_workspace_bytes(B, N, S, M, K)
+    if workspace is None:
+        workspace = _workspace(max(need, 256), coords.device)
+    rc = lib.affmae_knn(_ptr(coords), _ptr(cluster_id), B, N, S, M, K, _ptr(nbr_idx), _ptr(near_clusters),
+                        _ptr(workspace), workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_knn", rc)
+    return nbr_idx, near_clusters
+
+
+def affmae_pla_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Optional[torch.Tensor],
+                   nbr_idx: torch.Tensor, scale: float, near_clusters: Optional[torch.Tensor] = None,
+                   S: int = 0, M: int = 0, k_blank: Optional[torch.Tensor] = None,
+                   v_blank: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                   lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None
+                   ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Local attention forward -> (out [B,N,H,d] in q's dtype, lse [B,N,H] fp32)."""
+    lib = load_library()
+    code = _dtype_code(q)
+    _dev(q, "q")
+    B, N, H, d = q.shape
+    _dev(k, "k", q.dtype, q.shape)
+    _dev(v, "v", q.dtype, q.shape)
+    _dev(nbr_idx, "nbr_idx", torch.int32)
+    K = nbr_idx.shape[2]
+    _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
+    if bias is not None:
+        _dev(bias, "bias", q.dtype, (B, N, K, H))
+    if near_clusters is not None:
+        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+    if k_blank is not None:
+        _dev(k_blank, "k_blank", q.dtype, (H, d))
+        _dev(v_blank, "v_blank", q.dtype, (H, d))
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, N, H), dtype=torch.float32, device=q.device)
+    _dev(out, "out", q.dtype, q.shape)
+    _dev(lse, "lse", torch.float32, (B, N, H))
+    need = lib.affmae_pla_fwd_workspace_bytes(B, N, H, d, K, S, M, code, int(near_clusters is not None))
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    rc = lib.affmae_pla_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(bias), _ptr(nbr_idx), _ptr(near_clusters),
+                            _ptr(k_blank), _ptr(v_blank), B, N, H, d, K, S, M, float(scale), code, _ptr(out),
+                            _ptr(lse), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_pla_fwd", rc)
+    return out, lse
+
+
+def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Optional[torch.Tensor],
+                   nbr_idx: torch.Tensor, out: Optional[torch.Tensor], lse: torch.Tensor, dout: torch.Tensor,
+                   scale: float, near_clusters: Optional[torch.Tensor] = None, S: int = 0, M: int = 0,
+                   k_blank: Optional[torch.Tensor] = None, v_blank: Optional[torch.Tensor] = None,
+                   want_dbias: bool = True, grads: Optional[Dict[str, torch.Tensor]] = None,
+                   workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """Local attention backward -> dict(dq, dk, dv[, dbias][, dk_blank, dv_blank])."""
+    lib = load_library()
+    code = _dtype_code(q)
+    _dev(q, "q")
+    B, N, H, d = q.shape
+    _dev(k, "k", q.dtype, q.shape)
+    _dev(v, "v", q.dtype, q.shape)
+    _dev(dout, "dout", q.dtype, q.shape)
+    if out is not None:
+        _dev(out, "out", q.dtype, q.shape)
+    K = nbr_idx.shape[2]
+    _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
+    _dev(lse, "lse", torch.float32, (B, N, H))
+    if bias is not None:
+        _dev(bias, "bias", q.dtype, (B, N, K, H))
+    if near_clusters is not None:
+        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+    if k_blank is not None:
+        _dev(k_blank, "k_blank", q.dtype, (H, d))
+        _dev(v_blank, "v_blank", q.dtype, (H, d))
+    g = dict(grads) if grads else {}
+    for name in ("dq", "dk", "dv"):
+        if name not in g:
+            g[name] = torch.empty_like(q)
+        _dev(g[name], name, q.dtype, q.shape)
+    if want_dbias:
+        if "dbias" not in g:
+            g["dbias"] = torch.empty((B, N, K, H), dtype=q.dtype, device=q.device)
+        _dev(g["dbias"], "dbias", q.dtype, (B, N, K, H))
+    if k_blank is not None:
+        for name in ("dk_blank", "dv_blank"):
+            if name not in g:
+                g[name] = torch.empty((H, d), dtype=torch.float32, device=q.device)
+            _dev(g[name], name, torch.float32, (H, d))
+    need = lib.affmae_pla_bwd_workspace_bytes(B, N, H, d, K, S, M, code, int(near_clusters is not None))
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    rc = lib.affmae_pla_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(bias), _ptr(nbr_idx), _ptr(near_clusters),
+                            _ptr(k_blank), _ptr(v_blank), _ptr(out), _ptr(lse), _ptr(dout), B, N, H, d, K, S, M,
+                            float(scale), code, _ptr(g["dq"]), _ptr(g["dk"]), _ptr(g["dv"]), _ptr(g.get("dbias")),
+                            _ptr(g.get("dk_blank")), _ptr(g.get("dv_blank")), _ptr(workspace),
+                            0 if workspace is None else workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_pla_bwd", rc)
+    return g

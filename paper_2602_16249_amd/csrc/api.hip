@@ -1,0 +1,162 @@
+// C ABI of the library: host-side argument validation and kernel dispatch.
+// Declarations and the meaning of every argument are in include/affmae.h.
+#include "../../include/affmae.h"
+
+#include "launch.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+struct KnnPlan {
+  size_t centroid_off, near_off, members_off, total;
+};
+KnnPlan knn_plan(int B, int N, int S, int M) {
+  KnnPlan p;
+  const size_t G = (size_t)N / S;
+  size_t off = 0;
+  p.centroid_off = off;
+  off += align_up((size_t)B * G * 2 * sizeof(float));
+  p.near_off = off;
+  off += align_up((size_t)B * G * M * sizeof(int32_t));
+  p.members_off = off;
+  off += align_up((size_t)B * N * sizeof(int32_t));
+  p.total = off;
+  return p;
+}
+
+int check_knn_shape(int B, int N, int S, int M, int K) {
+  if (B < 1 || N < 1 || S < 1 || M < 1 || K < 1) return AFFMAE_ERR_SHAPE;
+  if (N % S) return AFFMAE_ERR_SHAPE;
+  const int G = N / S;
+  if (M > G) return AFFMAE_ERR_SHAPE;
+  if ((long long)K > (long long)M * S) return AFFMAE_ERR_SHAPE;
+  if (K > AFFMAE_MAX_K || M > AFFMAE_MAX_NEAR) return AFFMAE_ERR_UNSUPPORTED;
+  if ((long long)M * S > 4096) return AFFMAE_ERR_UNSUPPORTED;  // candidate staging: 16 B each in 64 KB of LDS
+  return AFFMAE_OK;
+}
+
+int check_pla_shape(int B, int N, int H, int d, int K, int dtype) {
+  if (dtype != AFFMAE_F32 && dtype != AFFMAE_BF16) return AFFMAE_ERR_DTYPE;
+  if (B < 1 || N < 1 || H < 1 || d < 1 || K < 1) return AFFMAE_ERR_SHAPE;
+  if (d != 16 && d != 32 && d != 64) return AFFMAE_ERR_UNSUPPORTED;
+  if (K > AFFMAE_MAX_K) return AFFMAE_ERR_UNSUPPORTED;
+  // per-wave LDS of the gather kernels: (K+1) * (1 + 2H) floats (+ 2*H*d with blanks), four waves
+  if ((size_t)4 * ((size_t)(K + 1) * (1 + 2 * (size_t)H) + 2 * (size_t)H * d) * sizeof(float) > 64 * 1024)
+    return AFFMAE_ERR_UNSUPPORTED;
+  return AFFMAE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* affmae_status_string(int status) {
+  switch (status) {
+    case AFFMAE_OK: return "ok";
+    case AFFMAE_ERR_NULL: return "a required pointer is NULL";
+    case AFFMAE_ERR_SHAPE: return "a size is non-positive or inconsistent";
+    case AFFMAE_ERR_DTYPE: return "unknown storage type";
+    case AFFMAE_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case AFFMAE_ERR_UNSUPPORTED: return "request outside the implemented limits";
+    case AFFMAE_ERR_DEVICE: return "the HIP runtime refused a launch";
+    default: return "unknown status";
+  }
+}
+
+int affmae_version(void) { return 100; }
+
+size_t affmae_knn_workspace_bytes(int B, int N, int S, int M, int K) {
+  if (check_knn_shape(B, N, S, M, K) != AFFMAE_OK) return 0;
+  return knn_plan(B, N, S, M).total;
+}
+
+int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int S, int M, int K,
+               int32_t* nbr_idx, int32_t* near_clusters, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!coords || !nbr_idx) return AFFMAE_ERR_NULL;
+  const int rc = check_knn_shape(B, N, S, M, K);
+  if (rc != AFFMAE_OK) return rc;
+  const KnnPlan plan = knn_plan(B, N, S, M);
+  if (!workspace || workspace_bytes < plan.total || misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(workspace);
+  affmae::KnnArgs a;
+  a.coords = coords;
+  a.cluster_id = cluster_id;
+  a.B = B; a.N = N; a.S = S; a.M = M; a.K = K; a.G = N / S;
+  a.nbr_idx = nbr_idx;
+  a.near_clusters = near_clusters ? near_clusters : reinterpret_cast<int32_t*>(ws + plan.near_off);
+  a.centroid = reinterpret_cast<float*>(ws + plan.centroid_off);
+  a.members = reinterpret_cast<int32_t*>(ws + plan.members_off);
+  return affmae::launch_knn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+
+size_t affmae_pla_fwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
+  (void)S; (void)M; (void)clustered;
+  if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
+  return 0;
+}
+
+int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
+                   const int32_t* near_clusters, const void* k_blank, const void* v_blank, int B, int N, int H,
+                   int d, int K, int S, int M, float scale, int dtype, void* out, float* lse, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !nbr_idx || !out || !lse) return AFFMAE_ERR_NULL;
+  if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
+  const int rc = check_pla_shape(B, N, H, d, K, dtype);
+  if (rc != AFFMAE_OK) return rc;
+  if (near_clusters) {
+    if (S < 1 || M < 1 || N % S || M > N / S) return AFFMAE_ERR_SHAPE;
+  }
+  if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
+  if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
+  (void)workspace; (void)workspace_bytes;
+  affmae::PlaArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.bias = bias; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
+  a.k_blank = k_blank; a.v_blank = v_blank;
+  a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
+  a.out = out; a.lse = lse; a.workspace = workspace;
+  return affmae::launch_pla_fwd_general(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK
+                                                                                           : AFFMAE_ERR_DEVICE;
+}
+
+size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
+  (void)S; (void)M; (void)clustered;
+  if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
+  return align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
+}
+
+int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
+                   const int32_t* near_clusters, const void* k_blank, const void* v_blank, const void* out,
+                   const float* lse, const void* dout, int B, int N, int H, int d, int K, int S, int M, float scale,
+                   int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank, float* dv_blank,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !nbr_idx || !lse || !dout || !dq || !dk || !dv) return AFFMAE_ERR_NULL;
+  if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
+  if ((dk_blank == nullptr) != (dv_blank == nullptr)) return AFFMAE_ERR_NULL;
+  const int rc = check_pla_shape(B, N, H, d, K, dtype);
+  if (rc != AFFMAE_OK) return rc;
+  if (near_clusters) {
+    if (S < 1 || M < 1 || N % S || M > N / S) return AFFMAE_ERR_SHAPE;
+  }
+  if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(dout, 16) || misaligned(dq, 16) ||
+      misaligned(dk, 16) || misaligned(dv, 16))
+    return AFFMAE_ERR_SHAPE;
+  if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
+  const size_t need = affmae_pla_bwd_workspace_bytes(B, N, H, d, K, S, M, dtype, near_clusters != nullptr);
+  if (need && (!workspace || workspace_bytes < need || misaligned(workspace, kAlign))) return AFFMAE_ERR_WORKSPACE;
+  (void)out;
+  affmae::PlaArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.bias = bias; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
+  a.k_blank = k_blank; a.v_blank = v_blank;
+  a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
+  a.out = const_cast<void*>(out); a.lse = const_cast<float*>(lse); a.dout = dout;
+  a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias; a.dk_blank = dk_blank; a.dv_blank = dv_blank;
+  a.workspace = workspace;
+  return affmae::launch_pla_bwd_general(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK
+                                                                                           : AFFMAE_ERR_DEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+// Internal launcher interface between the C-ABI translation unit and the
+// kernel translation units.  Every launcher enqueues on `stream`, performs no
+// synchronisation and returns the hipError_t of its last launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace affmae {
+
+struct KnnArgs {
+  const float* coords;        // [B,N,2]
+  const int32_t* cluster_id;  // [B,N] or nullptr
+  int B, N, S, M, K, G;
+  int32_t* nbr_idx;        // [B,N,K]
+  int32_t* near_clusters;  // [B,G,M] (never null here: points into workspace if the caller passed none)
+  float* centroid;         // [B,G,2] workspace
+  int32_t* members;        // [B,N] workspace, used only with cluster_id
+};
+hipError_t launch_knn(const KnnArgs& a, hipStream_t stream);
+
+struct PlaArgs {
+  const void *q, *k, *v, *bias;
+  const int32_t* nbr_idx;
+  const int32_t* near_clusters;
+  const void *k_blank, *v_blank;
+  int B, N, H, d, K, S, M;
+  float scale;
+  int dtype;
+  // forward outputs / backward inputs
+  void* out;
+  float* lse;
+  // backward only
+  const void* dout;
+  void *dq, *dk, *dv, *dbias;
+  float *dk_blank, *dv_blank;
+  void* workspace;
+};
+hipError_t launch_pla_fwd_general(const PlaArgs& a, hipStream_t stream);
+hipError_t launch_pla_bwd_general(const PlaArgs& a, hipStream_t stream);
+size_t pla_bwd_general_workspace_bytes(int B, int N, int H, int d, int dtype);
+
+}  // namespace affmae

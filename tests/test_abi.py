@@ -1,0 +1,84 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_16249_amd as aff
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "affmae.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(affmae_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = aff.load_library()
+    names = _declared_symbols()
+    assert {"affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert aff.status_string(0) == "ok"
+    for code in range(-6, 0):
+        assert aff.status_string(code) not in ("ok", "unknown status")
+    assert aff.status_string(-99) == "unknown status"
+
+
+def test_knn_rejects_bad_arguments_on_host():
+    lib = aff.load_library()
+    one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    assert lib.affmae_knn(None, None, 1, 64, 8, 2, 4, one, None, one, 1 << 20, None) == -1
+    assert lib.affmae_knn(one, None, 1, 65, 8, 2, 4, one, None, one, 1 << 20, None) == -2     # N % S
+    assert lib.affmae_knn(one, None, 1, 64, 8, 9, 4, one, None, one, 1 << 20, None) == -2     # M > G
+    assert lib.affmae_knn(one, None, 1, 64, 8, 2, 17, one, None, one, 1 << 20, None) == -2    # K > M*S
+    assert lib.affmae_knn(one, None, 1, 1024, 16, 8, 64 + 1, one, None, one, 1 << 20, None) == -5
+    assert lib.affmae_knn(one, None, 1, 64, 8, 2, 4, one, None, None, 0, None) == -4          # no workspace
+    assert lib.affmae_knn(one, None, 1, 64, 8, 2, 4, one, None, one, 16, None) == -4          # too small
+    assert lib.affmae_knn_workspace_bytes(1, 64, 8, 2, 4) > 0
+    assert lib.affmae_knn_workspace_bytes(1, 65, 8, 2, 4) == 0
+
+
+def test_attention_rejects_bad_arguments_on_host():
+    lib = aff.load_library()
+    p = ctypes.c_void_p(4096)
+    args = dict(B=1, N=64, H=2, d=32, K=8, S=8, M=2)
+
+    def fwd(q=p, k=p, v=p, nbr=p, out=p, lse=p, dtype=1, kb=None, vb=None, near=None, **kw):
+        a = dict(args)
+        a.update(kw)
+        return lib.affmae_pla_fwd(q, k, v, None, nbr, near, kb, vb, a["B"], a["N"], a["H"], a["d"], a["K"], a["S"],
+                                  a["M"], 1.0, dtype, out, lse, None, 0, None)
+
+    assert fwd(q=None) == -1
+    assert fwd(kb=p) == -1            # blank key without blank value
+    assert fwd(dtype=7) == -3
+    assert fwd(d=24) == -5
+    assert fwd(K=65) == -5
+    assert fwd(B=0) == -2
+    assert fwd(near=p, S=7) == -2     # N % S with a cluster promise
+    assert fwd(q=ctypes.c_void_p(4098)) == -2   # misaligned rows
+
+    def bwd(ws=None, ws_bytes=0, dq=p, **kw):
+        a = dict(args)
+        a.update(kw)
+        return lib.affmae_pla_bwd(p, p, p, None, p, None, None, None, None, p, p, a["B"], a["N"], a["H"], a["d"],
+                                  a["K"], a["S"], a["M"], 1.0, 1, dq, p, p, None, None, None, ws, ws_bytes, None)
+
+    assert bwd(dq=None) == -1
+    assert bwd() == -4                # bf16 needs an fp32 accumulation workspace
+    assert lib.affmae_pla_bwd_workspace_bytes(1, 64, 2, 32, 8, 8, 2, 1, 0) >= 2 * 64 * 64 * 4
+    assert lib.affmae_pla_bwd_workspace_bytes(1, 64, 2, 32, 8, 8, 2, 0, 0) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        aff.affmae_knn(torch.zeros(1, 64, 2), None, 8, 2, 4)

@@ -1,0 +1,87 @@
+"""GPU parity: affmae_pla_fwd / affmae_pla_bwd against the CPU oracle.
+
+Tolerance (per tensor, forward and every gradient): max|gpu - ref| / max|ref|
+<= 1e-5 for fp32 storage and <= 2e-2 for bf16 storage; the oracle runs in
+double precision on the same stored (already rounded) inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import check_attention
+from workloads import CONFIGS, make_features, make_workload, random_neighbours
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_fp32_config():
+    """B=1, N=256, C=64, 2 heads, K=16 exact neighbours, fp32."""
+    cfg = CONFIGS["tiny_f32"]
+    w = make_workload(cfg)
+    nbr = oracle.knn_bruteforce(w["coords"], cfg.K)
+    errs = check_attention(w, nbr, "f32", 1.0 / np.sqrt(cfg.d))
+    print(errs)
+
+
+GATHER_CASES = [
+    # dtype, B, N, H, d, K, blank, distinct
+    ("f32", 2, 200, 2, 32, 16, False, True),
+    ("f32", 1, 130, 3, 16, 7, True, False),    # repeats, odd sizes, blank token
+    ("f32", 1, 96, 1, 64, 64, True, True),     # K at the limit
+    ("f32", 2, 64, 4, 32, 1, False, True),     # K = 1: out = v[nbr]
+    ("bf16", 2, 200, 2, 32, 48, False, True),
+    ("bf16", 1, 130, 8, 32, 48, True, False),
+    ("bf16", 1, 77, 2, 64, 33, True, True),
+    ("bf16", 1, 300, 4, 16, 5, False, False),
+]
+
+
+@pytest.mark.parametrize("dtype,B,N,H,d,K,blank,distinct", GATHER_CASES)
+def test_arbitrary_neighbour_tables(dtype, B, N, H, d, K, blank, distinct):
+    """No cluster promise: any indices, repeats allowed (gather kernels)."""
+    print(f"case {dtype} B={B} N={N} H={H} d={d} K={K} blank={blank} distinct={distinct}", flush=True)
+    rng = np.random.default_rng(100 + N + K)
+    w = make_features(B, N, H, d, K, dtype, rng, blank=blank)
+    nbr = random_neighbours(B, N, K, rng, distinct=distinct)
+    check_attention(w, nbr, dtype, 1.0 / np.sqrt(d), blank=blank)
+
+
+def test_no_bias_argument():
+    rng = np.random.default_rng(3)
+    w = make_features(1, 128, 2, 32, 12, "bf16", rng)
+    w["bias"] = None
+    nbr = random_neighbours(1, 128, 12, rng)
+    check_attention(w, nbr, "bf16", 0.2)
+
+
+CLUSTER_CASES = [
+    # name, B, N, C, H, K, S, M, blank
+    ("mae_pt_s1_1024", 2, 1024, 64, 2, 48, 64, 8, False),
+    ("mae_pt_s1_1024", 1, 1024, 64, 2, 48, 64, 8, True),
+    ("merged_stage", 3, 512, 256, 8, 48, 32, 8, False),
+    ("knn_scale", 2, 1024, 128, 4, 48, 64, 8, False),
+    ("knn_scale", 1, 960, 96, 3, 20, 48, 5, True),     # ragged: S=48, M=5, H=3
+]
+
+
+@pytest.mark.parametrize("name,B,N,C,H,K,S,M,blank", CLUSTER_CASES)
+@pytest.mark.parametrize("promise", [False, True])
+def test_clustered_tables(name, B, N, C, H, K, S, M, blank, promise):
+    """kNN tables of small clustered token sets, with and without the cluster
+    promise (near_clusters) that selects the cluster-tiled kernels."""
+    print(f"case {name} B={B} N={N} C={C} H={H} K={K} S={S} M={M} blank={blank} promise={promise}", flush=True)
+    cfg = CONFIGS[name].scaled(B=B, N=N, C=C, H=H, K=K, S=S, M=M)
+    w = make_workload(cfg, blank=blank)
+    nbr, near = oracle.knn(w["coords"], None, S, M, K)
+    check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near if promise else None, S=S, M=M, blank=blank)
+
+
+@pytest.mark.parametrize("name", ["mae_pt_s1_1024", "ft_s1_1024", "merged_stage", "knn_scale"])
+def test_full_size_configs(name):
+    """The benchmark's configurations at full size in the launch configuration
+    the benchmark times (cluster promise given), every element compared."""
+    cfg = CONFIGS[name]
+    print(f"case {name} full size", flush=True)
+    w = make_workload(cfg)
+    nbr, near = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
+    errs = check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M)
+    print(errs)
