@@ -158,6 +158,18 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
                    void* dk, void* dv, void* dbias, float* dk_blank, float* dv_blank,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Optional per-kernel timing, for benchmarks.  While enabled, every kernel the
+ * library launches is bracketed by two HIP events on the launch stream.  The
+ * read and reset calls synchronise the device.  Timing must stay disabled under
+ * HIP graph capture.  Not thread-safe against concurrent launches.
+ *   affmae_timing_read: fills the `index`-th entry (kernel name, total
+ *   milliseconds, number of launches) if it exists; returns the entry count.
+ */
+void affmae_timing_enable(int on);
+void affmae_timing_reset(void);
+int affmae_timing_read(int index, char* name, int name_len, double* total_ms, int* count);
+
 #ifdef __cplusplus
 }
 #endif

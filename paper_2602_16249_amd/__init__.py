@@ -13,6 +13,9 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     status_string,
+    timing_enable,
+    timing_read,
+    timing_reset,
 )
 
 __all__ = ["AffmaeError", "affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd", "library_path", "load_library",

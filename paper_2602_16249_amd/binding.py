@@ -223,3 +223,27 @@ def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
     if rc != 0:
         raise AffmaeError("affmae_pla_bwd", rc)
     return g
+
+
+def timing_enable(on: bool) -> None:
+    """Bracket every kernel launch of the library with HIP events (benchmarks only)."""
+    load_library().affmae_timing_enable(int(bool(on)))
+
+
+def timing_reset() -> None:
+    load_library().affmae_timing_reset()
+
+
+def timing_read() -> Dict[str, Tuple[float, int]]:
+    """Per kernel name: (total milliseconds, launches) since the last reset."""
+    lib = load_library()
+    lib.affmae_timing_read.restype = _c_int
+    out = {}
+    n = lib.affmae_timing_read(-1, None, 0, None, None)
+    for i in range(n):
+        name = ctypes.create_string_buffer(128)
+        ms = ctypes.c_double(0.0)
+        cnt = ctypes.c_int(0)
+        lib.affmae_timing_read(i, name, 128, ctypes.byref(ms), ctypes.byref(cnt))
+        out[name.value.decode()] = (ms.value, cnt.value)
+    return out

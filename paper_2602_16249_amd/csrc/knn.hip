@@ -10,6 +10,7 @@
 // compiled with -ffp-contract=off.
 #include "device_util.h"
 #include "launch.h"
+#include "timing.h"
 
 namespace affmae {
 namespace {
@@ -202,16 +203,16 @@ __global__ __launch_bounds__(256) void knn_kernel(const float* __restrict__ coor
 hipError_t launch_knn(const KnnArgs& a, hipStream_t stream) {
   const int32_t* members = nullptr;
   if (a.cluster_id) {
-    hipLaunchKernelGGL(members_kernel, dim3(a.B), dim3(256), 0, stream, a.cluster_id, a.N, a.S, a.G, a.members);
+    AFFMAE_LAUNCH("members_kernel", stream, members_kernel, dim3(a.B), dim3(256), 0, stream, a.cluster_id, a.N, a.S, a.G, a.members);
     members = a.members;
   }
   const int BG = a.B * a.G;
-  hipLaunchKernelGGL(centroid_kernel, dim3((BG + 255) / 256), dim3(256), 0, stream, a.coords, members, a.B, a.N,
+  AFFMAE_LAUNCH("centroid_kernel", stream, centroid_kernel, dim3((BG + 255) / 256), dim3(256), 0, stream, a.coords, members, a.B, a.N,
                      a.S, a.G, a.centroid);
-  hipLaunchKernelGGL(near_kernel, dim3((BG + 3) / 4), dim3(256), 0, stream, a.centroid, a.B, a.G, a.M,
+  AFFMAE_LAUNCH("near_kernel", stream, near_kernel, dim3((BG + 3) / 4), dim3(256), 0, stream, a.centroid, a.B, a.G, a.M,
                      a.near_clusters);
   const size_t lds = (size_t)a.M * a.S * sizeof(float4);
-  hipLaunchKernelGGL(knn_kernel, dim3(BG), dim3(256), lds, stream, a.coords, members, a.near_clusters, a.N, a.S,
+  AFFMAE_LAUNCH("knn_kernel", stream, knn_kernel, dim3(BG), dim3(256), lds, stream, a.coords, members, a.near_clusters, a.N, a.S,
                      a.M, a.K, a.G, a.nbr_idx);
   return hipGetLastError();
 }

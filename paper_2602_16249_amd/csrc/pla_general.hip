@@ -8,6 +8,7 @@
 // pass through LDS to the channel-parallel accumulation phase.
 #include "device_util.h"
 #include "launch.h"
+#include "timing.h"
 
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 
@@ -192,7 +193,7 @@ hipError_t fwd_impl(const PlaArgs& a, hipStream_t stream) {
   const int Kp = a.K + 1;
   const size_t lds = kWavesPerBlock * (Kp + (size_t)a.H * Kp) * sizeof(float);
   const int grid = grid_for((size_t)tokens, kWavesPerBlock, 1 << 20);
-  hipLaunchKernelGGL((pla_fwd_general_kernel<T, D>), dim3(grid), dim3(256), lds, stream, (const T*)a.q,
+  AFFMAE_LAUNCH("pla_fwd_general_kernel", stream, (pla_fwd_general_kernel<T, D>), dim3(grid), dim3(256), lds, stream, (const T*)a.q,
                      (const T*)a.k, (const T*)a.v, (const T*)a.bias, a.nbr_idx, (const T*)a.k_blank,
                      (const T*)a.v_blank, tokens, a.N, a.H, a.K, a.scale, (T*)a.out, a.lse);
   return hipGetLastError();
@@ -211,26 +212,26 @@ hipError_t bwd_impl(const PlaArgs& a, hipStream_t stream) {
     dv_acc = dk_acc + elems;
   }
   const int zgrid = grid_for(elems, 256 * 8, 4096);
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(zgrid), dim3(256), 0, stream, dk_acc, elems);
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(zgrid), dim3(256), 0, stream, dv_acc, elems);
+  AFFMAE_LAUNCH("fill_zero_kernel", stream, fill_zero_kernel, dim3(zgrid), dim3(256), 0, stream, dk_acc, elems);
+  AFFMAE_LAUNCH("fill_zero_kernel", stream, fill_zero_kernel, dim3(zgrid), dim3(256), 0, stream, dv_acc, elems);
   const bool blank_grad = a.k_blank && a.dk_blank;
   if (blank_grad) {
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, stream, a.dk_blank, (size_t)a.H * D);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, stream, a.dv_blank, (size_t)a.H * D);
+    AFFMAE_LAUNCH("fill_zero_kernel", stream, fill_zero_kernel, dim3(1), dim3(256), 0, stream, a.dk_blank, (size_t)a.H * D);
+    AFFMAE_LAUNCH("fill_zero_kernel", stream, fill_zero_kernel, dim3(1), dim3(256), 0, stream, a.dv_blank, (size_t)a.H * D);
   }
   const int Kp = a.K + 1;
   const size_t per_wave = Kp + 2 * (size_t)a.H * Kp + (blank_grad ? 2 * (size_t)a.H * D : 0);
   const size_t lds = kWavesPerBlock * per_wave * sizeof(float);
   // With blank gradients every wave keeps a running sum, so bound the grid.
   const int grid = grid_for((size_t)tokens, kWavesPerBlock, blank_grad ? 2048 : (1 << 20));
-  hipLaunchKernelGGL((pla_bwd_general_kernel<T, D>), dim3(grid), dim3(256), lds, stream, (const T*)a.q,
+  AFFMAE_LAUNCH("pla_bwd_general_kernel", stream, (pla_bwd_general_kernel<T, D>), dim3(grid), dim3(256), lds, stream, (const T*)a.q,
                      (const T*)a.k, (const T*)a.v, (const T*)a.bias, a.nbr_idx, (const T*)a.k_blank,
                      (const T*)a.v_blank, a.lse, (const T*)a.dout, tokens, a.N, a.H, a.K, a.scale, (T*)a.dq, dk_acc,
                      dv_acc, (T*)a.dbias, a.dk_blank, a.dv_blank);
   if (a.dtype != 0) {
     const int cgrid = grid_for(elems, 256 * 8, 4096);
-    hipLaunchKernelGGL(cast_bf16_kernel, dim3(cgrid), dim3(256), 0, stream, dk_acc, (bf16_t*)a.dk, elems);
-    hipLaunchKernelGGL(cast_bf16_kernel, dim3(cgrid), dim3(256), 0, stream, dv_acc, (bf16_t*)a.dv, elems);
+    AFFMAE_LAUNCH("cast_bf16_kernel", stream, cast_bf16_kernel, dim3(cgrid), dim3(256), 0, stream, dk_acc, (bf16_t*)a.dk, elems);
+    AFFMAE_LAUNCH("cast_bf16_kernel", stream, cast_bf16_kernel, dim3(cgrid), dim3(256), 0, stream, dv_acc, (bf16_t*)a.dv, elems);
   }
   return hipGetLastError();
 }
