@@ -118,8 +118,10 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
   a.k_blank = k_blank; a.v_blank = v_blank;
   a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
   a.out = out; a.lse = lse; a.workspace = workspace;
-  return affmae::launch_pla_fwd_general(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK
-                                                                                           : AFFMAE_ERR_DEVICE;
+  const hipError_t err = affmae::pla_cluster_supported(a)
+                             ? affmae::launch_pla_fwd_cluster(a, static_cast<hipStream_t>(stream))
+                             : affmae::launch_pla_fwd_general(a, static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
 }
 
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {

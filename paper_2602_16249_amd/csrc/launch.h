@@ -41,4 +41,8 @@ hipError_t launch_pla_fwd_general(const PlaArgs& a, hipStream_t stream);
 hipError_t launch_pla_bwd_general(const PlaArgs& a, hipStream_t stream);
 size_t pla_bwd_general_workspace_bytes(int B, int N, int H, int d, int dtype);
 
+// Cluster-tiled kernels (bf16, d = 32, cluster promise given).
+bool pla_cluster_supported(const PlaArgs& a);
+hipError_t launch_pla_fwd_cluster(const PlaArgs& a, hipStream_t stream);
+
 }  // namespace affmae
