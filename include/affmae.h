@@ -89,6 +89,27 @@ int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int
                void* stream);
 
 /*
+ * affmae_pla_plan - re-tiles a clustered neighbour table for the cluster-tiled
+ * attention kernels (paper, Sec. "Limitations": neighbourhood tables are cached
+ * per encoder stage; the plan is that cache in the layout the tiled kernels read,
+ * built once per table and passed to every forward and backward call that uses
+ * the table).  Optional: without a plan the attention calls rebuild it in their
+ * workspace on every call.
+ *
+ *   nbr_idx, near_clusters  in  as produced by affmae_knn with cluster_id == NULL
+ *                               (the promise described under affmae_pla_fwd).
+ *   plan                    out caller-owned device buffer of affmae_pla_plan_bytes()
+ *                               bytes, 256-byte aligned; opaque.
+ * affmae_pla_plan_bytes returns 0, and affmae_pla_plan AFFMAE_ERR_UNSUPPORTED,
+ * when the shapes are outside what the tiled kernels take (they need S % 16 == 0,
+ * M*S <= 1024, N <= 2^20); the attention calls then use the gather kernels and
+ * ignore `plan`.
+ */
+size_t affmae_pla_plan_bytes(int B, int N, int K, int S, int M);
+int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B, int N, int K, int S,
+                    int M, void* plan, size_t plan_bytes, void* stream);
+
+/*
  * affmae_pla_fwd - local attention over each token's neighbourhood (paper,
  * Sec. "Flash-style Cluster Attention and Fast Decoder KNN", the FlashNbhdAttn
  * equation): for every image b, token i and head h
@@ -111,8 +132,11 @@ int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int
  *                     that every neighbour of a token of cluster c lies in one
  *                     of near_clusters[b,c,:], and that a token's neighbours
  *                     are pairwise distinct - what affmae_knn produces with
- *                     cluster_id == NULL.  It allows the cluster-tiled kernels.
- *                     With NULL, S and M are ignored.
+ *                     cluster_id == NULL.  It allows the cluster-tiled kernels
+ *                     (bf16 storage, d == 32, S % 16 == 0, M*S <= 1024); inputs
+ *                     must then be finite.  With NULL, S and M are ignored.
+ *   plan          in  NULL, or the buffer affmae_pla_plan filled for this
+ *                     nbr_idx / near_clusters and these B,N,K,S,M.
  *   k_blank,v_blank in [H,d] of `dtype`, or both NULL.
  *   d                 16, 32 or 64.  1 <= K <= AFFMAE_MAX_K.
  *   out           out [B,N,H,d] of `dtype` (round to nearest even).
@@ -121,10 +145,10 @@ int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int
 size_t affmae_pla_fwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
                                       int clustered);
 int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias,
-                   const int32_t* nbr_idx, const int32_t* near_clusters, const void* k_blank,
-                   const void* v_blank, int B, int N, int H, int d, int K, int S, int M, float scale,
-                   int dtype, void* out, float* lse, void* workspace, size_t workspace_bytes,
-                   void* stream);
+                   const int32_t* nbr_idx, const int32_t* near_clusters, const void* plan,
+                   const void* k_blank, const void* v_blank, int B, int N, int H, int d, int K, int S,
+                   int M, float scale, int dtype, void* out, float* lse, void* workspace,
+                   size_t workspace_bytes, void* stream);
 
 /*
  * affmae_pla_bwd - gradients of affmae_pla_fwd (the paper trains through the
@@ -152,11 +176,11 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
                                       int clustered);
 int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias,
-                   const int32_t* nbr_idx, const int32_t* near_clusters, const void* k_blank,
-                   const void* v_blank, const void* out, const float* lse, const void* dout, int B,
-                   int N, int H, int d, int K, int S, int M, float scale, int dtype, void* dq,
-                   void* dk, void* dv, void* dbias, float* dk_blank, float* dv_blank,
-                   void* workspace, size_t workspace_bytes, void* stream);
+                   const int32_t* nbr_idx, const int32_t* near_clusters, const void* plan,
+                   const void* k_blank, const void* v_blank, const void* out, const float* lse,
+                   const void* dout, int B, int N, int H, int d, int K, int S, int M, float scale,
+                   int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank,
+                   float* dv_blank, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Optional per-kernel timing, for benchmarks.  While enabled, every kernel the

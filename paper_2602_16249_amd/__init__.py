@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     affmae_knn,
     affmae_pla_bwd,
     affmae_pla_fwd,
+    affmae_pla_plan,
     library_path,
     load_library,
     status_string,
@@ -18,5 +19,5 @@ from .binding import (  # noqa: F401
     timing_reset,
 )
 
-__all__ = ["AffmaeError", "affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd", "library_path", "load_library",
+__all__ = ["AffmaeError", "affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd", "affmae_pla_plan", "library_path", "load_library",
            "status_string"]

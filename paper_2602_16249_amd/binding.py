@@ -57,11 +57,15 @@ def load_library():
         f.restype = _c_size_t
         f.argtypes = [_c_int] * 9
     lib.affmae_pla_fwd.restype = _c_int
-    lib.affmae_pla_fwd.argtypes = ([_c_void_p] * 8 + [_c_int] * 7 + [_c_float, _c_int] + [_c_void_p, _c_void_p]
+    lib.affmae_pla_fwd.argtypes = ([_c_void_p] * 9 + [_c_int] * 7 + [_c_float, _c_int] + [_c_void_p, _c_void_p]
                                    + [_c_void_p, _c_size_t, _c_void_p])
     lib.affmae_pla_bwd.restype = _c_int
-    lib.affmae_pla_bwd.argtypes = ([_c_void_p] * 11 + [_c_int] * 7 + [_c_float, _c_int] + [_c_void_p] * 6
+    lib.affmae_pla_bwd.argtypes = ([_c_void_p] * 12 + [_c_int] * 7 + [_c_float, _c_int] + [_c_void_p] * 6
                                    + [_c_void_p, _c_size_t, _c_void_p])
+    lib.affmae_pla_plan_bytes.restype = _c_size_t
+    lib.affmae_pla_plan_bytes.argtypes = [_c_int] * 5
+    lib.affmae_pla_plan.restype = _c_int
+    lib.affmae_pla_plan.argtypes = [_c_void_p, _c_void_p] + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]
     _lib = lib
     return lib
 
@@ -132,12 +136,31 @@ def affmae_knn(coords: torch.Tensor, cluster_id: Optional[torch.Tensor], S: int,
     return nbr_idx, near_clusters
 
 
+def affmae_pla_plan(nbr_idx: torch.Tensor, near_clusters: torch.Tensor, S: int, M: int,
+                    plan: Optional[torch.Tensor] = None) -> Optional[torch.Tensor]:
+    """Re-tile a clustered neighbour table for the tiled attention kernels.  Returns the opaque
+    plan buffer, or None when the shapes are outside what those kernels take."""
+    lib = load_library()
+    _dev(nbr_idx, "nbr_idx", torch.int32)
+    B, N, K = nbr_idx.shape
+    _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+    need = lib.affmae_pla_plan_bytes(B, N, K, S, M)
+    if need == 0:
+        return None
+    if plan is None:
+        plan = torch.empty(need, dtype=torch.uint8, device=nbr_idx.device)
+    rc = lib.affmae_pla_plan(_ptr(nbr_idx), _ptr(near_clusters), B, N, K, S, M, _ptr(plan), plan.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_pla_plan", rc)
+    return plan
+
+
 def affmae_pla_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Optional[torch.Tensor],
                    nbr_idx: torch.Tensor, scale: float, near_clusters: Optional[torch.Tensor] = None,
                    S: int = 0, M: int = 0, k_blank: Optional[torch.Tensor] = None,
                    v_blank: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                   lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None
-                   ) -> Tuple[torch.Tensor, torch.Tensor]:
+                   lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                   plan: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """Local attention forward -> (out [B,N,H,d] in q's dtype, lse [B,N,H] fp32)."""
     lib = load_library()
     code = _dtype_code(q)
@@ -164,7 +187,7 @@ def affmae_pla_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
     need = lib.affmae_pla_fwd_workspace_bytes(B, N, H, d, K, S, M, code, int(near_clusters is not None))
     if workspace is None:
         workspace = _workspace(need, q.device)
-    rc = lib.affmae_pla_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(bias), _ptr(nbr_idx), _ptr(near_clusters),
+    rc = lib.affmae_pla_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(bias), _ptr(nbr_idx), _ptr(near_clusters), _ptr(plan),
                             _ptr(k_blank), _ptr(v_blank), B, N, H, d, K, S, M, float(scale), code, _ptr(out),
                             _ptr(lse), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
     if rc != 0:
@@ -177,7 +200,8 @@ def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
                    scale: float, near_clusters: Optional[torch.Tensor] = None, S: int = 0, M: int = 0,
                    k_blank: Optional[torch.Tensor] = None, v_blank: Optional[torch.Tensor] = None,
                    want_dbias: bool = True, grads: Optional[Dict[str, torch.Tensor]] = None,
-                   workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+                   workspace: Optional[torch.Tensor] = None, plan: Optional[torch.Tensor] = None
+                   ) -> Dict[str, torch.Tensor]:
     """Local attention backward -> dict(dq, dk, dv[, dbias][, dk_blank, dv_blank])."""
     lib = load_library()
     code = _dtype_code(q)
@@ -215,7 +239,7 @@ def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
     need = lib.affmae_pla_bwd_workspace_bytes(B, N, H, d, K, S, M, code, int(near_clusters is not None))
     if workspace is None:
         workspace = _workspace(need, q.device)
-    rc = lib.affmae_pla_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(bias), _ptr(nbr_idx), _ptr(near_clusters),
+    rc = lib.affmae_pla_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(bias), _ptr(nbr_idx), _ptr(near_clusters), _ptr(plan),
                             _ptr(k_blank), _ptr(v_blank), _ptr(out), _ptr(lse), _ptr(dout), B, N, H, d, K, S, M,
                             float(scale), code, _ptr(g["dq"]), _ptr(g["dk"]), _ptr(g["dv"]), _ptr(g.get("dbias")),
                             _ptr(g.get("dk_blank")), _ptr(g.get("dv_blank")), _ptr(workspace),

@@ -50,6 +50,15 @@ int check_pla_shape(int B, int N, int H, int d, int K, int dtype) {
   return AFFMAE_OK;
 }
 
+// Shapes the cluster-tiled kernels take (storage type and head size are checked by the caller).
+bool tiled_shape_ok(int B, int N, int K, int S, int M) {
+  affmae::PlaArgs a = {};
+  a.B = B; a.N = N; a.K = K; a.S = S; a.M = M; a.d = 32; a.dtype = AFFMAE_BF16;
+  static const int32_t dummy = 0;
+  a.near_clusters = &dummy;  // only tested for being non-null
+  return B >= 1 && N >= 1 && K >= 1 && S >= 1 && M >= 1 && N % S == 0 && affmae::pla_cluster_supported(a);
+}
+
 }  // namespace
 
 extern "C" {
@@ -93,16 +102,33 @@ int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int
   return affmae::launch_knn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
 }
 
+size_t affmae_pla_plan_bytes(int B, int N, int K, int S, int M) {
+  if (!tiled_shape_ok(B, N, K, S, M)) return 0;
+  return affmae::pla_plan_bytes(B, N, K, S, M);
+}
+
+int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B, int N, int K, int S, int M,
+                    void* plan, size_t plan_bytes, void* stream) {
+  if (!nbr_idx || !near_clusters || !plan) return AFFMAE_ERR_NULL;
+  if (B < 1 || N < 1 || K < 1 || S < 1 || M < 1 || N % S || M > N / S) return AFFMAE_ERR_SHAPE;
+  if (!tiled_shape_ok(B, N, K, S, M)) return AFFMAE_ERR_UNSUPPORTED;
+  if (plan_bytes < affmae::pla_plan_bytes(B, N, K, S, M) || misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
+  return affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, plan, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess
+             ? AFFMAE_OK
+             : AFFMAE_ERR_DEVICE;
+}
+
 size_t affmae_pla_fwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
-  (void)S; (void)M; (void)clustered;
   if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
+  if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && N % S == 0) return affmae_pla_plan_bytes(B, N, K, S, M);
   return 0;
 }
 
 int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
-                   const int32_t* near_clusters, const void* k_blank, const void* v_blank, int B, int N, int H,
-                   int d, int K, int S, int M, float scale, int dtype, void* out, float* lse, void* workspace,
-                   size_t workspace_bytes, void* stream) {
+                   const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank, int B,
+                   int N, int H, int d, int K, int S, int M, float scale, int dtype, void* out, float* lse,
+                   void* workspace, size_t workspace_bytes, void* stream) {
   if (!q || !k || !v || !nbr_idx || !out || !lse) return AFFMAE_ERR_NULL;
   if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
   const int rc = check_pla_shape(B, N, H, d, K, dtype);
@@ -112,16 +138,23 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
   }
   if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
   if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
-  (void)workspace; (void)workspace_bytes;
   affmae::PlaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.bias = bias; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
   a.k_blank = k_blank; a.v_blank = v_blank;
   a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
   a.out = out; a.lse = lse; a.workspace = workspace;
-  const hipError_t err = affmae::pla_cluster_supported(a)
-                             ? affmae::launch_pla_fwd_cluster(a, static_cast<hipStream_t>(stream))
-                             : affmae::launch_pla_fwd_general(a, static_cast<hipStream_t>(stream));
-  return err == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!affmae::pla_cluster_supported(a))
+    return affmae::launch_pla_fwd_general(a, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+  if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
+  if (!plan) {  // no cached plan: rebuild it in the workspace
+    const size_t need = affmae::pla_plan_bytes(B, N, K, S, M);
+    if (!workspace || workspace_bytes < need || misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
+    if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, workspace, st) != hipSuccess)
+      return AFFMAE_ERR_DEVICE;
+    plan = workspace;
+  }
+  return affmae::launch_pla_fwd_cluster(a, plan, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
 }
 
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
@@ -131,10 +164,10 @@ size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, 
 }
 
 int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
-                   const int32_t* near_clusters, const void* k_blank, const void* v_blank, const void* out,
-                   const float* lse, const void* dout, int B, int N, int H, int d, int K, int S, int M, float scale,
-                   int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank, float* dv_blank,
-                   void* workspace, size_t workspace_bytes, void* stream) {
+                   const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank,
+                   const void* out, const float* lse, const void* dout, int B, int N, int H, int d, int K, int S,
+                   int M, float scale, int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank,
+                   float* dv_blank, void* workspace, size_t workspace_bytes, void* stream) {
   if (!q || !k || !v || !nbr_idx || !lse || !dout || !dq || !dk || !dv) return AFFMAE_ERR_NULL;
   if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
   if ((dk_blank == nullptr) != (dv_blank == nullptr)) return AFFMAE_ERR_NULL;
@@ -149,7 +182,7 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
   if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
   const size_t need = affmae_pla_bwd_workspace_bytes(B, N, H, d, K, S, M, dtype, near_clusters != nullptr);
   if (need && (!workspace || workspace_bytes < need || misaligned(workspace, kAlign))) return AFFMAE_ERR_WORKSPACE;
-  (void)out;
+  (void)out; (void)plan;
   affmae::PlaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.bias = bias; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
   a.k_blank = k_blank; a.v_blank = v_blank;

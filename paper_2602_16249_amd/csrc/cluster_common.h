@@ -1,0 +1,87 @@
+// Shared definitions of the cluster-tiled attention kernels (bf16, d = 32).
+//
+// Tokens are handled in tiles of 16 consecutive tokens ("token tiles"); a strip
+// is the token tile seen as 16 queries.  Because clusters hold a multiple of 16
+// tokens in cluster order, a token tile never straddles clusters.
+//
+// The plan (built by pla_plan.hip from the neighbour table) describes, per
+// strip, which token tiles hold at least one neighbour of one of its queries
+// ("slots", at most kMaxSlots) and, for every (query, neighbour slot j), where
+// that neighbour sits: entry = slot * 256 + query * 16 + (token % 16).
+#pragma once
+
+#include "device_util.h"
+
+namespace affmae {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kD = 32;                 // channels per head
+constexpr int kMaxSlots = 64;          // token tiles one strip may touch (M*S/16 <= 64)
+constexpr int kMaxEntries = 16;        // 16 queries * K (<= 64) neighbours / 64 lanes
+constexpr uint32_t kNoEntry = 0xffffu;
+
+union Frag8 {
+  bf16x8 v;
+  uint4 u4;
+  uint2 u2[2];
+  uint32_t u[4];
+  uint16_t h[8];
+};
+
+union Frag4 {
+  s16x4 v;
+  uint2 u2;
+  uint32_t u[2];
+  uint16_t h[4];
+};
+
+// Layout of the plan buffer.
+struct PlanLayout {
+  int strips;        // B * N / 16
+  int slot_stride;   // uint16 per strip in the slot table: [0] = count, [1 + s] = token tile of slot s
+  int K;
+  size_t slots_off;    // uint16 [strips][slot_stride]
+  size_t entries_off;  // uint16 [strips][16 * K]
+  size_t total;
+};
+
+inline size_t plan_align(size_t n) { return (n + 255) / 256 * 256; }
+
+inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
+  PlanLayout L;
+  L.strips = (int)((long long)B * N / 16);
+  int max_slots = (int)((long long)M * S / 16);
+  L.slot_stride = 1 + max_slots + (max_slots & 1);  // room to pad to an even number of slots
+  if (L.slot_stride & 1) L.slot_stride += 1;
+  L.K = K;
+  size_t off = 0;
+  L.slots_off = off;
+  off += plan_align((size_t)L.strips * L.slot_stride * sizeof(uint16_t));
+  L.entries_off = off;
+  off += plan_align((size_t)L.strips * 16 * K * sizeof(uint16_t));
+  L.total = off;
+  return L;
+}
+
+__device__ __forceinline__ int fast_div(int n, uint32_t magic) { return (int)__umulhi((uint32_t)n, magic); }
+inline uint32_t div_magic(int d) { return (uint32_t)((1ull << 32) / (uint32_t)d) + 1u; }
+
+__device__ __forceinline__ uint32_t wave_or32(uint32_t x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x |= __shfl_xor(x, o);
+  return x;
+}
+
+// Two fp32 -> packed bf16 (round to nearest even), low half first.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  f32x2 f = {lo, hi};
+  bf16x2 b = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, b);
+}
+
+}  // namespace affmae

@@ -41,8 +41,11 @@ hipError_t launch_pla_fwd_general(const PlaArgs& a, hipStream_t stream);
 hipError_t launch_pla_bwd_general(const PlaArgs& a, hipStream_t stream);
 size_t pla_bwd_general_workspace_bytes(int B, int N, int H, int d, int dtype);
 
-// Cluster-tiled kernels (bf16, d = 32, cluster promise given).
+// Cluster-tiled kernels (bf16, d = 32, cluster promise given), driven by a plan.
 bool pla_cluster_supported(const PlaArgs& a);
-hipError_t launch_pla_fwd_cluster(const PlaArgs& a, hipStream_t stream);
+size_t pla_plan_bytes(int B, int N, int K, int S, int M);
+hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, int N, int K, int S, int M, void* plan,
+                           hipStream_t stream);
+hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_t stream);
 
 }  // namespace affmae

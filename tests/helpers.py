@@ -28,15 +28,16 @@ def rel_err(got, ref: np.ndarray) -> float:
     return float(np.abs(got - ref).max() / (den if den > 0 else 1.0))
 
 
-def run_gpu_attention(w, nbr, dtype, scale, near=None, S=0, M=0, blank=False):
+def run_gpu_attention(w, nbr, dtype, scale, near=None, S=0, M=0, blank=False, use_plan=False):
     q, k, v, dout = (to_dev(w[n], dtype) for n in ("q", "k", "v", "dout"))
     bias = to_dev(w["bias"], dtype) if w.get("bias") is not None else None
     nbr_d = torch.from_numpy(np.ascontiguousarray(nbr, dtype=np.int32)).cuda()
     near_d = torch.from_numpy(np.ascontiguousarray(near, dtype=np.int32)).cuda() if near is not None else None
     kb = to_dev(w["k_blank"], dtype) if blank else None
     vb = to_dev(w["v_blank"], dtype) if blank else None
-    out, lse = aff.affmae_pla_fwd(q, k, v, bias, nbr_d, scale, near_d, S, M, kb, vb)
-    g = aff.affmae_pla_bwd(q, k, v, bias, nbr_d, out, lse, dout, scale, near_d, S, M, kb, vb)
+    plan = aff.affmae_pla_plan(nbr_d, near_d, S, M) if (use_plan and near_d is not None) else None
+    out, lse = aff.affmae_pla_fwd(q, k, v, bias, nbr_d, scale, near_d, S, M, kb, vb, plan=plan)
+    g = aff.affmae_pla_bwd(q, k, v, bias, nbr_d, out, lse, dout, scale, near_d, S, M, kb, vb, plan=plan)
     torch.cuda.synchronize()
     return out, lse, g
 
@@ -49,9 +50,9 @@ def run_oracle_attention(w, nbr, scale, blank=False):
     return out, lse, g
 
 
-def check_attention(w, nbr, dtype, scale, near=None, S=0, M=0, blank=False, tol=None):
+def check_attention(w, nbr, dtype, scale, near=None, S=0, M=0, blank=False, tol=None, use_plan=False):
     tol = TOL[dtype] if tol is None else tol
-    out, lse, g = run_gpu_attention(w, nbr, dtype, scale, near, S, M, blank)
+    out, lse, g = run_gpu_attention(w, nbr, dtype, scale, near, S, M, blank, use_plan)
     rout, rlse, rg = run_oracle_attention(w, nbr, scale, blank)
     errs = {"out": rel_err(out, rout), "lse": rel_err(lse, rlse)}
     for name in rg:

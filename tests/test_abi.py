@@ -54,7 +54,7 @@ def test_attention_rejects_bad_arguments_on_host():
     def fwd(q=p, k=p, v=p, nbr=p, out=p, lse=p, dtype=1, kb=None, vb=None, near=None, **kw):
         a = dict(args)
         a.update(kw)
-        return lib.affmae_pla_fwd(q, k, v, None, nbr, near, kb, vb, a["B"], a["N"], a["H"], a["d"], a["K"], a["S"],
+        return lib.affmae_pla_fwd(q, k, v, None, nbr, near, None, kb, vb, a["B"], a["N"], a["H"], a["d"], a["K"], a["S"],
                                   a["M"], 1.0, dtype, out, lse, None, 0, None)
 
     assert fwd(q=None) == -1
@@ -69,7 +69,7 @@ def test_attention_rejects_bad_arguments_on_host():
     def bwd(ws=None, ws_bytes=0, dq=p, **kw):
         a = dict(args)
         a.update(kw)
-        return lib.affmae_pla_bwd(p, p, p, None, p, None, None, None, None, p, p, a["B"], a["N"], a["H"], a["d"],
+        return lib.affmae_pla_bwd(p, p, p, None, p, None, None, None, None, None, p, p, a["B"], a["N"], a["H"], a["d"],
                                   a["K"], a["S"], a["M"], 1.0, 1, dq, p, p, None, None, None, ws, ws_bytes, None)
 
     assert bwd(dq=None) == -1

@@ -60,19 +60,23 @@ CLUSTER_CASES = [
     ("merged_stage", 3, 512, 256, 8, 48, 32, 8, False),
     ("knn_scale", 2, 1024, 128, 4, 48, 64, 8, False),
     ("knn_scale", 1, 960, 96, 3, 20, 48, 5, True),     # ragged: S=48, M=5, H=3
+    ("merged_stage", 2, 512, 64, 2, 64, 16, 32, False),  # 32 candidate tiles per strip: two passes of the bias tile
+    ("tiny_f32", 1, 256, 64, 2, 16, 256, 1, False),    # one cluster per image (exact kNN), bf16 storage here
 ]
 
 
 @pytest.mark.parametrize("name,B,N,C,H,K,S,M,blank", CLUSTER_CASES)
-@pytest.mark.parametrize("promise", [False, True])
+@pytest.mark.parametrize("promise", ["none", "promise", "plan"])
 def test_clustered_tables(name, B, N, C, H, K, S, M, blank, promise):
-    """kNN tables of small clustered token sets, with and without the cluster
-    promise (near_clusters) that selects the cluster-tiled kernels."""
+    """kNN tables of small clustered token sets: without the cluster promise
+    (gather kernels), with it (near_clusters; tiled kernels, plan rebuilt inside
+    the call) and with a plan built once by affmae_pla_plan."""
     print(f"case {name} B={B} N={N} C={C} H={H} K={K} S={S} M={M} blank={blank} promise={promise}", flush=True)
-    cfg = CONFIGS[name].scaled(B=B, N=N, C=C, H=H, K=K, S=S, M=M)
+    cfg = CONFIGS[name].scaled(B=B, N=N, C=C, H=H, K=K, S=S, M=M, dtype="bf16")
     w = make_workload(cfg, blank=blank)
     nbr, near = oracle.knn(w["coords"], None, S, M, K)
-    check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near if promise else None, S=S, M=M, blank=blank)
+    check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near if promise != "none" else None, S=S, M=M,
+                    blank=blank, use_plan=promise == "plan")
 
 
 @pytest.mark.parametrize("name", ["mae_pt_s1_1024", "ft_s1_1024", "merged_stage", "knn_scale"])
@@ -83,5 +87,5 @@ def test_full_size_configs(name):
     print(f"case {name} full size", flush=True)
     w = make_workload(cfg)
     nbr, near = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
-    errs = check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M)
+    errs = check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, use_plan=True)
     print(errs)
