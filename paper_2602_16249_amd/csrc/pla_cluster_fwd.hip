@@ -40,12 +40,19 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
 }
 
-__global__ __launch_bounds__(256) void pla_fwd_cluster_kernel(FwdParams p) {
+// ENT = entries per lane = ceil(16 * K / 64).
+template <int ENT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
   __shared__ __align__(16) bf16_t scratch_all[4][kSlotCap * 256];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int g = lane >> 4, r = lane & 15;
-  const int sg = blockIdx.x * 4 + wave;
+  // Consecutive strips share K/V rows; workgroups are dealt round-robin to the 8 XCDs (one L2
+  // each), so give every XCD a contiguous range of strips.
+  const int nblk = gridDim.x;
+  const int per_xcd = (nblk + 7) >> 3;
+  const int blk = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int sg = blk * 4 + wave;
   if (sg >= p.strips) return;  // wave-uniform; the kernel has no workgroup barrier
   bf16_t* scratch = scratch_all[wave];
   const int b = sg / p.strips_per_image;
@@ -58,39 +65,35 @@ __global__ __launch_bounds__(256) void pla_fwd_cluster_kernel(FwdParams p) {
   const int ntiles = min((int)__builtin_amdgcn_readfirstlane((int)sl[0]), kMaxSlots);
   const int my_tile = (lane < p.slot_stride - 1) ? (int)sl[1 + lane] : 0;
 
-  uint32_t ent[kMaxEntries];  // low half: plan entry, high half: bias bits of the current head
-#pragma unroll
-  for (int t = 0; t < kMaxEntries; ++t) {
-    const int e = t * kWave + lane;
-    ent[t] = (e < nent) ? (uint32_t)p.entries[(size_t)sg * nent + e] : kNoEntry;
-  }
   Frag8 idf[2];  // identity operand, one per 16-channel half: lane (column r, rows 8g..8g+7)
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int i = 0; i < 8; ++i) idf[dt].h[i] = (8 * g + i == r + 16 * dt) ? 0x3f80u : 0u;
+  const uint16_t* ent_ptr = p.entries + (size_t)sg * nent + lane;
 
   for (int h = 0; h < p.H; ++h) {
     Frag8 qf;  // Q^T operand: lane (query r, channels 8g..8g+7)
     qf.u4 = *reinterpret_cast<const uint4*>(p.q + (tok0 + r) * C + h * kD + g * 8);
-#pragma unroll
-    for (int t = 0; t < kMaxEntries; ++t) {
-      const int e = t * kWave + lane;
-      uint32_t bits = 0;
-      if (p.bias && e < nent) bits = p.bias[((size_t)tok0 * p.K + e) * p.H + h];
-      ent[t] = (ent[t] & 0xffffu) | (bits << 16);
-    }
+    const bf16_t* bias_ptr = p.bias ? p.bias + ((size_t)tok0 * p.K + lane) * p.H + h : nullptr;
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
     for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCap) {
       const int nsl = min(kSlotCap, ntiles - slot0);
       // bias tile: -inf everywhere, then the bias of the real (query, neighbour) pairs
+      uint32_t ent[ENT];  // low half: plan entry, high half: bias bits
+#pragma unroll
+      for (int t = 0; t < ENT; ++t) {
+        const bool live = t * kWave + lane < nent;
+        ent[t] = live ? (uint32_t)ent_ptr[t * kWave] : kNoEntry;
+        if (live && bias_ptr) ent[t] |= (uint32_t)bias_ptr[(size_t)t * kWave * p.H] << 16;
+      }
       for (int s = 0; s < nsl; ++s)
         *reinterpret_cast<uint2*>(scratch + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
       wave_lds_sync();
 #pragma unroll
-      for (int t = 0; t < kMaxEntries; ++t) {
+      for (int t = 0; t < ENT; ++t) {
         const uint32_t off = ent[t] & 0xffffu;
         const uint32_t rel = off - (uint32_t)slot0 * 256u;
         if (off != kNoEntry && rel < (uint32_t)nsl * 256u) scratch[rel] = (bf16_t)(ent[t] >> 16);
@@ -98,21 +101,17 @@ __global__ __launch_bounds__(256) void pla_fwd_cluster_kernel(FwdParams p) {
       wave_lds_sync();
 
       const int npairs = (nsl + 1) >> 1;
-      Frag8 nk[2], nv[2];
-      auto load_pair = [&](int pr) {
+      auto load_pair = [&](int pr, Frag8(&kf)[2], Frag8(&vf)[2]) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const int s = min(2 * pr + tt, nsl - 1);
           const int tile = __builtin_amdgcn_readlane(my_tile, slot0 + s);
           const size_t row = ((size_t)(img_base + (long long)tile * 16 + r)) * C + h * kD + g * 8;
-          nk[tt].u4 = *reinterpret_cast<const uint4*>(p.k + row);
-          nv[tt].u4 = *reinterpret_cast<const uint4*>(p.v + row);
+          kf[tt].u4 = *reinterpret_cast<const uint4*>(p.k + row);
+          vf[tt].u4 = *reinterpret_cast<const uint4*>(p.v + row);
         }
       };
-      load_pair(0);
-      for (int pr = 0; pr < npairs; ++pr) {
-        Frag8 kf[2] = {nk[0], nk[1]}, vf[2] = {nv[0], nv[1]};
-        if (pr + 1 < npairs) load_pair(pr + 1);
+      auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
         const bool has1 = 2 * pr + 1 < nsl;
         float s[8];
 #pragma unroll
@@ -165,6 +164,17 @@ __global__ __launch_bounds__(256) void pla_fwd_cluster_kernel(FwdParams p) {
             vt.u[2 * tt + 1] = pack_bf16x2(c[2], c[3]);
           }
           acc[dt] = mfma32(vt, pf, acc[dt]);
+        }
+      };
+      // two register sets in turn, so that the loads of the next pair fly during this pair's math
+      Frag8 kA[2], vA[2], kB[2], vB[2];
+      load_pair(0, kA, vA);
+      for (int pr = 0; pr < npairs; pr += 2) {
+        if (pr + 1 < npairs) load_pair(pr + 1, kB, vB);
+        compute_pair(pr, kA, vA);
+        if (pr + 1 < npairs) {
+          if (pr + 2 < npairs) load_pair(pr + 2, kA, vA);
+          compute_pair(pr + 1, kB, vB);
         }
       }
       wave_lds_sync();  // the next pass overwrites the bias tile
@@ -230,8 +240,17 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride;
   p.scale = a.scale;
   p.out = (bf16_t*)a.out; p.lse = a.lse;
-  AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel, dim3((L.strips + 3) / 4), dim3(256), 0,
-                stream, p);
+  // the XCD-contiguous remap needs a grid that is a multiple of 8; surplus waves exit at once
+  const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);
+  const int ent = (16 * a.K + kWave - 1) / kWave;
+  if (ent <= 4)
+    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<4>, grid, dim3(256), 0, stream, p);
+  else if (ent <= 8)
+    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<8>, grid, dim3(256), 0, stream, p);
+  else if (ent <= 12)
+    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<12>, grid, dim3(256), 0, stream, p);
+  else
+    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<16>, grid, dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
