@@ -163,15 +163,17 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
  *     dv_blank[h,:]   = sum_{b,i} p_K g[b,i,h,:]
  *
  *   inputs as affmae_pla_fwd, plus
- *   out           in  [B,N,H,d] of `dtype`: forward output (may be NULL; the
- *                     current kernels rebuild D from p and dP instead).
+ *   out           in  [B,N,H,d] of `dtype`: forward output.  Required by the
+ *                     cluster-tiled kernels (they take D = <dout, out>); the
+ *                     gather kernels rebuild D from p and dP and accept NULL.
  *   lse           in  [B,N,H] fp32 from the forward call.
  *   dout          in  [B,N,H,d] of `dtype`.
  *   dq,dk,dv      out [B,N,H,d] of `dtype`; sums are formed in fp32.  The order
  *                     of the additions into dk/dv may differ between runs.
  *   dbias         out [B,N,K,H] of `dtype`, or NULL to skip.
  *   dk_blank,dv_blank out [H,d] fp32, or NULL (both required when blanks given
- *                     and their gradients are wanted).
+ *                     and their gradients are wanted).  Calls with blank tokens
+ *                     use the gather kernels even when near_clusters is given.
  */
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
                                       int clustered);

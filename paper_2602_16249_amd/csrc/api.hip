@@ -158,9 +158,12 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
 }
 
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
-  (void)S; (void)M; (void)clustered;
   if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
-  return align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
+  const size_t gather = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
+  size_t tiled = 0;
+  if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && N % S == 0 && tiled_shape_ok(B, N, K, S, M))
+    tiled = align_up(affmae::pla_plan_bytes(B, N, K, S, M)) + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, true);
+  return gather > tiled ? gather : tiled;  // blank tokens send a clustered call to the gather kernels
 }
 
 int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
@@ -180,9 +183,7 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
       misaligned(dk, 16) || misaligned(dv, 16))
     return AFFMAE_ERR_SHAPE;
   if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
-  const size_t need = affmae_pla_bwd_workspace_bytes(B, N, H, d, K, S, M, dtype, near_clusters != nullptr);
-  if (need && (!workspace || workspace_bytes < need || misaligned(workspace, kAlign))) return AFFMAE_ERR_WORKSPACE;
-  (void)out; (void)plan;
+  if (workspace && misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
   affmae::PlaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.bias = bias; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
   a.k_blank = k_blank; a.v_blank = v_blank;
@@ -190,8 +191,26 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
   a.out = const_cast<void*>(out); a.lse = const_cast<float*>(lse); a.dout = dout;
   a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias; a.dk_blank = dk_blank; a.dv_blank = dv_blank;
   a.workspace = workspace;
-  return affmae::launch_pla_bwd_general(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK
-                                                                                           : AFFMAE_ERR_DEVICE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // The tiled kernels do not form the blank-row gradients; such calls take the gather kernels.
+  if (affmae::pla_cluster_supported(a) && !k_blank) {
+    if (!out) return AFFMAE_ERR_NULL;
+    if (misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
+    if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
+    const size_t plan_bytes = plan ? 0 : align_up(affmae::pla_plan_bytes(B, N, K, S, M));
+    const size_t need = plan_bytes + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, dbias == nullptr);
+    if (!workspace || workspace_bytes < need) return AFFMAE_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    if (!plan) {
+      if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, ws, st) != hipSuccess)
+        return AFFMAE_ERR_DEVICE;
+      plan = ws;
+    }
+    return affmae::launch_pla_bwd_cluster(a, plan, ws + plan_bytes, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+  }
+  const size_t need = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
+  if (need && (!workspace || workspace_bytes < need)) return AFFMAE_ERR_WORKSPACE;
+  return affmae::launch_pla_bwd_general(a, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
 }
 
 }  // extern "C"

@@ -38,13 +38,22 @@ union Frag4 {
   uint16_t h[4];
 };
 
-// Layout of the plan buffer.
+// Layout of the plan buffer.  "Incidence" = (strip, slot): a strip and one of the token tiles it touches.
+// The reverse tables list, per token tile, the incidences that touch it (sorted, so that sums formed
+// along a list do not depend on scheduling); jmat gives, per incidence, for every (token of the tile,
+// query of the strip) the neighbour slot j under which the query lists that token, or 0xff.
 struct PlanLayout {
-  int strips;        // B * N / 16
+  int strips;        // B * N / 16 (also the number of token tiles)
+  int max_slots;     // M * S / 16
   int slot_stride;   // uint16 per strip in the slot table: [0] = count, [1 + s] = token tile of slot s
   int K;
-  size_t slots_off;    // uint16 [strips][slot_stride]
-  size_t entries_off;  // uint16 [strips][16 * K]
+  size_t slots_off;       // uint16 [strips][slot_stride]
+  size_t entries_off;     // uint16 [strips][16 * K]
+  size_t rev_count_off;   // int32  [strips]      incidences per token tile
+  size_t rev_offset_off;  // int32  [strips + 1]  exclusive prefix sum of rev_count
+  size_t rev_cursor_off;  // int32  [strips]      build-time cursors
+  size_t rev_list_off;    // uint32 [strips * max_slots]  (strip within image) << 8 | slot
+  size_t jmat_off;        // uint8  [strips][max_slots][16 tokens][16 queries]
   size_t total;
 };
 
@@ -54,6 +63,7 @@ inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   PlanLayout L;
   L.strips = (int)((long long)B * N / 16);
   int max_slots = (int)((long long)M * S / 16);
+  L.max_slots = max_slots;
   L.slot_stride = 1 + max_slots + (max_slots & 1);  // room to pad to an even number of slots
   if (L.slot_stride & 1) L.slot_stride += 1;
   L.K = K;
@@ -62,6 +72,16 @@ inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   off += plan_align((size_t)L.strips * L.slot_stride * sizeof(uint16_t));
   L.entries_off = off;
   off += plan_align((size_t)L.strips * 16 * K * sizeof(uint16_t));
+  L.rev_count_off = off;
+  off += plan_align((size_t)L.strips * sizeof(int32_t));
+  L.rev_offset_off = off;
+  off += plan_align(((size_t)L.strips + 1) * sizeof(int32_t));
+  L.rev_cursor_off = off;
+  off += plan_align((size_t)L.strips * sizeof(int32_t));
+  L.rev_list_off = off;
+  off += plan_align((size_t)L.strips * max_slots * sizeof(uint32_t));
+  L.jmat_off = off;
+  off += plan_align((size_t)L.strips * max_slots * 256);
   L.total = off;
   return L;
 }

@@ -1,0 +1,383 @@
+// Cluster-tiled local attention, backward (chain rule on the FlashNbhdAttn
+// equation of Sec. "Flash-style Cluster Attention and Fast Decoder KNN"; the
+// paper prints no backward).  Same preconditions and plan as the forward
+// kernel.  Two kernels:
+//
+//  query-stationary (one wave per strip of 16 queries): recomputes the
+//    probabilities p from lse tile by tile exactly as the forward pass forms the
+//    scores, forms dP = V dO^T with MFMAs, dS = p (dP - D) with D = <dout, out>,
+//    accumulates dQ^T = K^T dS^T (K transposed by an MFMA against the identity),
+//    and leaves p and dS of the real (query, neighbour) pairs in compact
+//    [token, slot, head] arrays: dS is dbias, p goes to the workspace;
+//
+//  key-stationary (one wave per tile of 16 tokens): walks the sorted list of
+//    strips that touch the tile, gathers their p and dS for the tile's tokens
+//    from the compact arrays (the plan's slot-index tile says where), and
+//    accumulates dK^T = Q^T dS and dV^T = dO^T P in registers, so dk and dv are
+//    written once, without atomics and in a fixed summation order.
+#include "cluster_common.h"
+#include "launch.h"
+#include "timing.h"
+
+namespace affmae {
+namespace {
+
+constexpr int kSlotCapB = 12;  // token tiles resident per wave: two bf16 tiles each (12 KB)
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct BwdParams {
+  const bf16_t *q, *k, *v, *bias, *out, *dout;
+  const float* lse;
+  const uint16_t *slots, *entries;
+  const int32_t* rev_offset;
+  const uint32_t* rev_list;
+  const uint8_t* jmat;
+  int N, H, K, strips, strips_per_image, slot_stride, max_slots;
+  float scale;
+  bf16_t *dq, *dk, *dv;
+  bf16_t* ds;  // [B,N,K,H] dS: the caller's dbias, or workspace
+  bf16_t* pc;  // [B,N,K,H] p, workspace
+};
+
+__device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ void make_identity(Frag8 (&idf)[2], int g, int r) {
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) idf[dt].h[i] = (8 * g + i == r + 16 * dt) ? 0x3f80u : 0u;
+}
+
+__device__ __forceinline__ int xcd_contiguous_block() {
+  // Workgroups are dealt round-robin to the 8 XCDs (one L2 each); neighbouring strips and tiles share
+  // rows, so give every XCD a contiguous range.  The grid is a multiple of 8.
+  const int per_xcd = gridDim.x >> 3;
+  return (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+}
+
+// ------------------------------------------------------------------------------------------------
+// query-stationary kernel
+template <int ENT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pla_bwd_query_kernel(BwdParams p) {
+  __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256];
+  __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int g = lane >> 4, r = lane & 15;
+  const int sg = xcd_contiguous_block() * 4 + wave;
+  if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier in this kernel
+  bf16_t* dstile = ds_all[wave];  // holds the bias tile first, dS after a tile has been processed
+  bf16_t* ptile = p_all[wave];
+  const int b = sg / p.strips_per_image;
+  const long long img_base = (long long)b * p.N;
+  const long long tok0 = (long long)sg * 16;
+  const int C = p.H * kD;
+  const int nent = 16 * p.K;
+
+  const uint16_t* sl = p.slots + (size_t)sg * p.slot_stride;
+  const int ntiles = min((int)__builtin_amdgcn_readfirstlane((int)sl[0]), kMaxSlots);
+  const int my_tile = (lane < p.slot_stride - 1) ? (int)sl[1 + lane] : 0;
+  Frag8 idf[2];
+  make_identity(idf, g, r);
+  const uint16_t* ent_ptr = p.entries + (size_t)sg * nent + lane;
+
+  for (int h = 0; h < p.H; ++h) {
+    Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
+    const size_t qrow = (size_t)(tok0 + r) * C + h * kD + g * 8;
+    qf.u4 = *reinterpret_cast<const uint4*>(p.q + qrow);
+    gf.u4 = *reinterpret_cast<const uint4*>(p.dout + qrow);
+    of.u4 = *reinterpret_cast<const uint4*>(p.out + qrow);
+    float Dq = 0.f;  // D of query r
+#pragma unroll
+    for (int i = 0; i < 8; ++i) Dq = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(of.h[i]), Dq);
+    Dq += __shfl_xor(Dq, 16);
+    Dq += __shfl_xor(Dq, 32);
+    const float nl2 = -p.lse[(size_t)(tok0 + r) * p.H + h] * kLog2e;
+    const size_t cbase = ((size_t)tok0 * p.K + lane) * p.H + h;  // compact arrays: entry `lane` of head h
+    const bf16_t* bias_ptr = p.bias ? p.bias + cbase : nullptr;
+    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+
+    for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCapB) {
+      const int nsl = min(kSlotCapB, ntiles - slot0);
+      {
+        uint32_t ent[ENT];  // low half: plan entry, high half: bias bits
+#pragma unroll
+        for (int t = 0; t < ENT; ++t) {
+          const bool live = t * kWave + lane < nent;
+          ent[t] = live ? (uint32_t)ent_ptr[t * kWave] : kNoEntry;
+          if (live && bias_ptr) ent[t] |= (uint32_t)bias_ptr[(size_t)t * kWave * p.H] << 16;
+        }
+        for (int s = 0; s < nsl; ++s)
+          *reinterpret_cast<uint2*>(dstile + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
+        wave_lds_sync();
+#pragma unroll
+        for (int t = 0; t < ENT; ++t) {
+          const uint32_t off = ent[t] & 0xffffu;
+          const uint32_t rel = off - (uint32_t)slot0 * 256u;
+          if (off != kNoEntry && rel < (uint32_t)nsl * 256u) dstile[rel] = (bf16_t)(ent[t] >> 16);
+        }
+        wave_lds_sync();
+      }
+
+      const int npairs = (nsl + 1) >> 1;
+      auto load_pair = [&](int pr, Frag8(&kf)[2], Frag8(&vf)[2]) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          const int s = min(2 * pr + tt, nsl - 1);
+          const int tile = __builtin_amdgcn_readlane(my_tile, slot0 + s);
+          const size_t row = ((size_t)(img_base + (long long)tile * 16 + r)) * C + h * kD + g * 8;
+          kf[tt].u4 = *reinterpret_cast<const uint4*>(p.k + row);
+          vf[tt].u4 = *reinterpret_cast<const uint4*>(p.v + row);
+        }
+      };
+      auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
+        const bool has1 = 2 * pr + 1 < nsl;
+        Frag8 dsf;  // dS^T operand: k-slots 0..3 = first tile's tokens 4g..4g+3, 4..7 = second tile's
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          if (tt == 0 || has1) {
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            const f32x4 st = mfma32(kf[tt], qf, z);   // <k[token 4g+i], q[query r]>
+            const f32x4 dpt = mfma32(vf[tt], gf, z);  // <v[token 4g+i], dout[query r]>
+            bf16_t* cell = dstile + (2 * pr + tt) * 256 + r * 16 + g * 4;
+            const uint2 bm = *reinterpret_cast<const uint2*>(cell);
+            float pv[4], dsv[4];
+            pv[0] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[0], p.scale, __uint_as_float(bm.x << 16)), kLog2e, nl2));
+            pv[1] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[1], p.scale, __uint_as_float(bm.x & 0xffff0000u)), kLog2e, nl2));
+            pv[2] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[2], p.scale, __uint_as_float(bm.y << 16)), kLog2e, nl2));
+            pv[3] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[3], p.scale, __uint_as_float(bm.y & 0xffff0000u)), kLog2e, nl2));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dsv[i] = pv[i] * (dpt[i] - Dq);
+            uint2 pw, dw;
+            pw.x = pack_bf16x2(pv[0], pv[1]);
+            pw.y = pack_bf16x2(pv[2], pv[3]);
+            dw.x = pack_bf16x2(dsv[0], dsv[1]);
+            dw.y = pack_bf16x2(dsv[2], dsv[3]);
+            *reinterpret_cast<uint2*>(ptile + (2 * pr + tt) * 256 + r * 16 + g * 4) = pw;
+            *reinterpret_cast<uint2*>(cell) = dw;  // the bias of these cells is no longer needed
+            dsf.u[2 * tt + 0] = dw.x;
+            dsf.u[2 * tt + 1] = dw.y;
+          } else {
+            dsf.u[2 * tt + 0] = 0u;
+            dsf.u[2 * tt + 1] = 0u;
+          }
+        }
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          Frag8 kt;  // K^T operand: lane (channel 16dt + r, the same tokens), via K x identity
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            f32x4 c = {0.f, 0.f, 0.f, 0.f};
+            c = mfma32(kf[tt], idf[dt], c);  // c[i] = k[token 4g+i][channel 16dt + r]
+            kt.u[2 * tt + 0] = pack_bf16x2(c[0], c[1]);
+            kt.u[2 * tt + 1] = pack_bf16x2(c[2], c[3]);
+          }
+          acc[dt] = mfma32(kt, dsf, acc[dt]);  // dq^T[channel 16dt + 4g+i][query r]
+        }
+      };
+      Frag8 kA[2], vA[2], kB[2], vB[2];
+      load_pair(0, kA, vA);
+      for (int pr = 0; pr < npairs; pr += 2) {
+        if (pr + 1 < npairs) load_pair(pr + 1, kB, vB);
+        compute_pair(pr, kA, vA);
+        if (pr + 1 < npairs) {
+          if (pr + 2 < npairs) load_pair(pr + 2, kA, vA);
+          compute_pair(pr + 1, kB, vB);
+        }
+      }
+      wave_lds_sync();
+      // compact p and dS of the real pairs: [token, slot, head]
+#pragma unroll
+      for (int t = 0; t < ENT; ++t) {
+        const bool live = t * kWave + lane < nent;
+        const uint32_t off = live ? (uint32_t)ent_ptr[t * kWave] : kNoEntry;  // read again: cheaper than keeping it
+        const uint32_t rel = off - (uint32_t)slot0 * 256u;
+        if (live && off != kNoEntry && rel < (uint32_t)nsl * 256u) {
+          p.ds[cbase + (size_t)t * kWave * p.H] = dstile[rel];
+          p.pc[cbase + (size_t)t * kWave * p.H] = ptile[rel];
+        } else if (live && off == kNoEntry && slot0 == 0) {
+          p.ds[cbase + (size_t)t * kWave * p.H] = 0;
+          p.pc[cbase + (size_t)t * kWave * p.H] = 0;
+        }
+      }
+      wave_lds_sync();
+    }
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+      uint2 o;
+      o.x = pack_bf16x2(acc[dt][0] * p.scale, acc[dt][1] * p.scale);
+      o.y = pack_bf16x2(acc[dt][2] * p.scale, acc[dt][3] * p.scale);
+      *reinterpret_cast<uint2*>(p.dq + (size_t)(tok0 + r) * C + h * kD + dt * 16 + g * 4) = o;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// key-stationary kernel
+struct KeyItem {
+  Frag8 qf, gf;      // strip's q and dout rows: lane (query r, channels 8g..8g+7)
+  uint16_t pv[4];    // p[query 4g+i][token r] (bf16 bits, 0 where the query does not list the token)
+  uint16_t dsv[4];   // dS likewise
+};
+
+template <int HG>  // heads handled per sweep over the tile's list
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_bwd_key_kernel(BwdParams p) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int g = lane >> 4, r = lane & 15;
+  const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
+  if (kt >= p.strips) return;
+  const int b = kt / p.strips_per_image;
+  const int C = p.H * kD;
+  const size_t strip_base = (size_t)b * p.strips_per_image;
+  const int lo = p.rev_offset[kt];
+  const int n = p.rev_offset[kt + 1] - lo;
+  Frag8 idf[2];
+  make_identity(idf, g, r);
+
+  for (int hg = 0; hg < p.H; hg += HG) {
+    f32x4 dk[HG][2], dv[HG][2];
+#pragma unroll
+    for (int hh = 0; hh < HG; ++hh)
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) {
+        dk[hh][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        dv[hh][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    for (int base = 0; base < n; base += kWave) {
+      const int nb = min(kWave, n - base);
+      const uint32_t mine = (lane < nb) ? p.rev_list[lo + base + lane] : 0u;
+      const int nw = nb * HG;  // work items: (incidence, head of the group)
+      auto item_strip = [&](int w, int& slot, int& h) -> size_t {
+        const int i = (HG == 2) ? (w >> 1) : w;
+        h = hg + ((HG == 2) ? (w & 1) : 0);
+        const uint32_t inc = __builtin_amdgcn_readlane(mine, i);
+        slot = (int)(inc & 255u);
+        return strip_base + (inc >> 8);
+      };
+      auto fetch_jm = [&](int w) -> uint32_t {
+        int slot, h;
+        const size_t sgq = item_strip(w, slot, h);
+        return *reinterpret_cast<const uint32_t*>(p.jmat + (sgq * p.max_slots + slot) * 256 + r * 16 + g * 4);
+      };
+      auto fetch_rest = [&](int w, uint32_t jm, KeyItem& it) {
+        int slot, h;
+        const size_t sgq = item_strip(w, slot, h);
+        const size_t tokq0 = sgq * 16;
+        const size_t qrow = (tokq0 + r) * C + h * kD + g * 8;
+        it.qf.u4 = *reinterpret_cast<const uint4*>(p.q + qrow);
+        it.gf.u4 = *reinterpret_cast<const uint4*>(p.dout + qrow);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t j = (jm >> (8 * i)) & 255u;
+          const bool hit = j != 255u;
+          const size_t idx = ((tokq0 + 4 * g + i) * p.K + (hit ? j : 0u)) * p.H + h;
+          const uint16_t pvv = p.pc[idx], dvv = p.ds[idx];
+          it.pv[i] = hit ? pvv : (uint16_t)0;
+          it.dsv[i] = hit ? dvv : (uint16_t)0;
+        }
+      };
+      auto compute = [&](const KeyItem& it, f32x4(&dkh)[2], f32x4(&dvh)[2]) {
+        Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
+        pf.u[0] = (uint32_t)it.pv[0] | ((uint32_t)it.pv[1] << 16);
+        pf.u[1] = (uint32_t)it.pv[2] | ((uint32_t)it.pv[3] << 16);
+        df.u[0] = (uint32_t)it.dsv[0] | ((uint32_t)it.dsv[1] << 16);
+        df.u[1] = (uint32_t)it.dsv[2] | ((uint32_t)it.dsv[3] << 16);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+          const f32x4 cq = mfma32(it.qf, idf[dt], z);  // q[query 4g+i][channel 16dt + r]
+          const f32x4 cg = mfma32(it.gf, idf[dt], z);  // dout likewise
+          Frag4 qT, gT;  // operand A: lane (channel 16dt + r, queries 4g..4g+3)
+          qT.u[0] = pack_bf16x2(cq[0], cq[1]);
+          qT.u[1] = pack_bf16x2(cq[2], cq[3]);
+          gT.u[0] = pack_bf16x2(cg[0], cg[1]);
+          gT.u[1] = pack_bf16x2(cg[2], cg[3]);
+          dkh[dt] = mfma16(qT, df, dkh[dt]);  // dk^T[channel 16dt + 4g+i][token r]
+          dvh[dt] = mfma16(gT, pf, dvh[dt]);
+        }
+      };
+      KeyItem A, B;
+      uint32_t jm_a = fetch_jm(0), jm_b = (nw > 1) ? fetch_jm(1) : 0u;
+      fetch_rest(0, jm_a, A);
+      for (int w = 0; w < nw; w += 2) {
+        if (w + 1 < nw) fetch_rest(w + 1, jm_b, B);
+        if (w + 2 < nw) jm_a = fetch_jm(w + 2);
+        compute(A, dk[0], dv[0]);
+        if (w + 1 < nw) {
+          if (w + 2 < nw) fetch_rest(w + 2, jm_a, A);
+          if (w + 3 < nw) jm_b = fetch_jm(w + 3);
+          compute(B, dk[HG - 1], dv[HG - 1]);
+        }
+      }
+    }
+#pragma unroll
+    for (int hh = 0; hh < HG; ++hh) {
+      const int h = hg + hh;
+      if (h < p.H) {
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          const size_t at = ((size_t)kt * 16 + r) * C + h * kD + dt * 16 + g * 4;
+          uint2 o;
+          o.x = pack_bf16x2(dk[hh][dt][0] * p.scale, dk[hh][dt][1] * p.scale);
+          o.y = pack_bf16x2(dk[hh][dt][2] * p.scale, dk[hh][dt][3] * p.scale);
+          *reinterpret_cast<uint2*>(p.dk + at) = o;
+          o.x = pack_bf16x2(dv[hh][dt][0], dv[hh][dt][1]);
+          o.y = pack_bf16x2(dv[hh][dt][2], dv[hh][dt][3]);
+          *reinterpret_cast<uint2*>(p.dv + at) = o;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, bool need_ds) {
+  const size_t one = plan_align((size_t)B * N * K * H * sizeof(bf16_t));
+  return need_ds ? 2 * one : one;
+}
+
+hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* workspace, hipStream_t stream) {
+  const PlanLayout L = make_plan_layout(a.B, a.N, a.K, a.S, a.M);
+  const char* base = static_cast<const char*>(plan);
+  BwdParams p;
+  p.q = (const bf16_t*)a.q; p.k = (const bf16_t*)a.k; p.v = (const bf16_t*)a.v; p.bias = (const bf16_t*)a.bias;
+  p.out = (const bf16_t*)a.out; p.dout = (const bf16_t*)a.dout; p.lse = a.lse;
+  p.slots = reinterpret_cast<const uint16_t*>(base + L.slots_off);
+  p.entries = reinterpret_cast<const uint16_t*>(base + L.entries_off);
+  p.rev_offset = reinterpret_cast<const int32_t*>(base + L.rev_offset_off);
+  p.rev_list = reinterpret_cast<const uint32_t*>(base + L.rev_list_off);
+  p.jmat = reinterpret_cast<const uint8_t*>(base + L.jmat_off);
+  p.N = a.N; p.H = a.H; p.K = a.K;
+  p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
+  p.scale = a.scale;
+  p.dq = (bf16_t*)a.dq; p.dk = (bf16_t*)a.dk; p.dv = (bf16_t*)a.dv;
+  char* ws = static_cast<char*>(workspace);
+  const size_t one = plan_align((size_t)a.B * a.N * a.K * a.H * sizeof(bf16_t));
+  p.pc = reinterpret_cast<bf16_t*>(ws);
+  p.ds = a.dbias ? (bf16_t*)a.dbias : reinterpret_cast<bf16_t*>(ws + one);
+
+  const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);  // multiple of 8 for the XCD-contiguous mapping
+  const int ent = (16 * a.K + kWave - 1) / kWave;
+  if (ent <= 4)
+    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<4>, grid, dim3(256), 0, stream, p);
+  else if (ent <= 8)
+    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<8>, grid, dim3(256), 0, stream, p);
+  else if (ent <= 12)
+    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<12>, grid, dim3(256), 0, stream, p);
+  else
+    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<16>, grid, dim3(256), 0, stream, p);
+  if (a.H % 2 == 0)
+    AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<2>, grid, dim3(256), 0, stream, p);
+  else
+    AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<1>, grid, dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace affmae

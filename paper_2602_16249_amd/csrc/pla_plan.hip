@@ -1,7 +1,8 @@
 // Plan of the cluster-tiled attention kernels, built from the neighbour table
 // (paper, Sec. "Limitations": neighbourhood tables are cached per encoder stage
 // and reused by every block; the plan is such a table in the layout the tiled
-// kernels read).  One wave per strip of 16 queries.
+// kernels read).  Forward tables: one wave per strip of 16 queries.  Reverse
+// tables (which strips touch a token tile): count, prefix sum, fill, sort.
 #include "cluster_common.h"
 #include "launch.h"
 #include "timing.h"
@@ -14,9 +15,14 @@ struct PlanParams {
   const int32_t* near;     // [B,G,M]
   int N, K, S, M, G;
   uint32_t s_magic, k_magic;
-  int strips, strips_per_image, slot_stride;
+  int strips, strips_per_image, slot_stride, max_slots;
   uint16_t* slots;    // [strips][slot_stride]
   uint16_t* entries;  // [strips][16*K]
+  int32_t* rev_count;
+  int32_t* rev_offset;
+  int32_t* rev_cursor;
+  uint32_t* rev_list;
+  uint8_t* jmat;
 };
 
 __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
@@ -24,10 +30,23 @@ __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
   return ((unsigned long long)hi << 32) | lo;
 }
 
+__global__ __launch_bounds__(256) void plan_zero_kernel(int32_t* a, int32_t* b, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    a[i] = 0;
+    b[i] = 0;
+  }
+}
+
+constexpr int kJmatPass = 16;  // slots whose 16x16 slot-index tiles are assembled in LDS at a time
+
 __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
+  __shared__ __align__(16) uint8_t jm_all[4][kJmatPass * 256];
   const int lane = threadIdx.x & (kWave - 1);
-  const int sg = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  if (sg >= p.strips) return;  // wave-uniform
+  const int wave = threadIdx.x / kWave;
+  const int sg = blockIdx.x * (blockDim.x / kWave) + wave;
+  if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier below
+  uint8_t* jm = jm_all[wave];
   const int b = sg / p.strips_per_image;
   const int q0 = (sg - b * p.strips_per_image) * 16;  // first query, within the image
   const int c = fast_div(q0, p.s_magic);
@@ -60,31 +79,119 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   }
   mask = wave_or64(mask);
   uint16_t* ent = p.entries + (size_t)sg * nent;
+  uint32_t off[kMaxEntries];
 #pragma unroll
   for (int t = 0; t < kMaxEntries; ++t) {
     const int e = t * kWave + lane;
+    off[t] = kNoEntry;
     if (e < nent) {
-      uint32_t off = kNoEntry;
       if (ct[t] >= 0) {
         const int slot = __popcll(mask & ((1ull << ct[t]) - 1ull));
-        off = (uint32_t)(slot * 256 + fast_div(e, p.k_magic) * 16 + (tok[t] & 15));
+        off[t] = (uint32_t)(slot * 256 + fast_div(e, p.k_magic) * 16 + (tok[t] & 15));
       }
-      ent[e] = (uint16_t)off;
+      ent[e] = (uint16_t)off[t];
     }
   }
   // slot table: count, then the token tile of every slot; padding repeats a valid tile
   uint16_t* sl = p.slots + (size_t)sg * p.slot_stride;
   const int count = __popcll(mask);
-  int my_tile = -1;
   if ((mask >> lane) & 1ull) {
     const int m = lane / tiles_per_cluster, tt = lane - m * tiles_per_cluster;
     const int e = min(max(near_c[m], 0), p.G - 1);
-    my_tile = e * tiles_per_cluster + tt;  // token tile within the image
+    const int my_tile = e * tiles_per_cluster + tt;  // token tile within the image
     sl[1 + __popcll(mask & ((1ull << lane) - 1ull))] = (uint16_t)my_tile;
+    atomicAdd(p.rev_count + (size_t)b * p.strips_per_image + my_tile, 1);
   }
   const int own_tile = q0 >> 4;
   if (lane == 0) sl[0] = (uint16_t)count;
   for (int s = count + lane; s < p.slot_stride - 1; s += kWave) sl[1 + s] = (uint16_t)own_tile;
+
+  // jmat[slot][token][query] = neighbour slot j, assembled in LDS and written out in rows
+  uint8_t* jout = p.jmat + (size_t)sg * p.max_slots * 256;
+  for (int s0 = 0; s0 < count; s0 += kJmatPass) {
+    const int ns = min(kJmatPass, count - s0);
+    for (int w = lane; w < ns * 64; w += kWave) reinterpret_cast<uint32_t*>(jm)[w] = 0xffffffffu;
+    wave_lds_sync();
+#pragma unroll
+    for (int t = 0; t < kMaxEntries; ++t) {
+      const uint32_t rel = off[t] - (uint32_t)s0 * 256u;
+      if (off[t] != kNoEntry && rel < (uint32_t)ns * 256u) {
+        const int e = t * kWave + lane;
+        const int qi = (off[t] >> 4) & 15, cand = off[t] & 15;
+        jm[(rel & ~255u) + cand * 16 + qi] = (uint8_t)(e - qi * p.K);
+      }
+    }
+    wave_lds_sync();
+    for (int w = lane; w < ns * 64; w += kWave)
+      reinterpret_cast<uint32_t*>(jout + (size_t)s0 * 256)[w] = reinterpret_cast<const uint32_t*>(jm)[w];
+    wave_lds_sync();
+  }
+}
+
+// Exclusive prefix sum of rev_count (one workgroup; n is at most a few hundred thousand).
+__global__ __launch_bounds__(1024) void plan_scan_kernel(const int32_t* __restrict__ count, int32_t* __restrict__ offset,
+                                                        int n) {
+  __shared__ int32_t part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n + 1023) / 1024;
+  const int lo = min(tid * per, n), hi = min(lo + per, n);
+  int sum = 0;
+  for (int i = lo; i < hi; ++i) sum += count[i];
+  part[tid] = sum;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int v = (tid >= o) ? part[tid - o] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int run = part[tid] - sum;
+  for (int i = lo; i < hi; ++i) {
+    offset[i] = run;
+    run += count[i];
+  }
+  if (tid == 1023) offset[n] = part[1023];
+}
+
+// Every strip appends itself to the list of each token tile it touches.
+__global__ __launch_bounds__(256) void plan_fill_kernel(PlanParams p) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int sg = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (sg >= p.strips) return;
+  const int b = sg / p.strips_per_image;
+  const int strip_in_image = sg - b * p.strips_per_image;
+  const uint16_t* sl = p.slots + (size_t)sg * p.slot_stride;
+  const int count = min((int)sl[0], p.max_slots);
+  if (lane < count) {
+    const size_t kt = (size_t)b * p.strips_per_image + sl[1 + lane];
+    const int at = atomicAdd(p.rev_cursor + kt, 1);
+    p.rev_list[(size_t)p.rev_offset[kt] + at] = ((uint32_t)strip_in_image << 8) | (uint32_t)lane;
+  }
+}
+
+// Sort every token tile's list ascending: rank by counting (lists are short).
+__global__ __launch_bounds__(256) void plan_sort_kernel(PlanParams p) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int kt = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (kt >= p.strips) return;
+  const int lo = p.rev_offset[kt], n = p.rev_offset[kt + 1] - lo;
+  uint32_t* list = p.rev_list + lo;
+  if (n <= kWave) {
+    const uint32_t mine = lane < n ? list[lane] : 0xffffffffu;
+    int rank = 0;
+    for (int j = 0; j < n; ++j) rank += (__shfl(mine, j) < mine) ? 1 : 0;  // entries are distinct
+    if (lane < n) list[rank] = mine;  // every lane has read its element before any write lands (one wave)
+  } else if (lane == 0) {
+    for (int i = 1; i < n; ++i) {  // insertion sort; only for unusually popular tiles
+      const uint32_t v = list[i];
+      int j = i - 1;
+      while (j >= 0 && list[j] > v) {
+        list[j + 1] = list[j];
+        --j;
+      }
+      list[j + 1] = v;
+    }
+  }
 }
 
 }  // namespace
@@ -92,14 +199,27 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
 hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, int N, int K, int S, int M, void* plan,
                            hipStream_t stream) {
   const PlanLayout L = make_plan_layout(B, N, K, S, M);
+  char* base = static_cast<char*>(plan);
   PlanParams p;
   p.nbr_idx = nbr_idx; p.near = near;
   p.N = N; p.K = K; p.S = S; p.M = M; p.G = N / S;
   p.s_magic = div_magic(S); p.k_magic = div_magic(K);
-  p.strips = L.strips; p.strips_per_image = N / 16; p.slot_stride = L.slot_stride;
-  p.slots = reinterpret_cast<uint16_t*>(static_cast<char*>(plan) + L.slots_off);
-  p.entries = reinterpret_cast<uint16_t*>(static_cast<char*>(plan) + L.entries_off);
-  AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel, dim3((L.strips + 3) / 4), dim3(256), 0, stream, p);
+  p.strips = L.strips; p.strips_per_image = N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
+  p.slots = reinterpret_cast<uint16_t*>(base + L.slots_off);
+  p.entries = reinterpret_cast<uint16_t*>(base + L.entries_off);
+  p.rev_count = reinterpret_cast<int32_t*>(base + L.rev_count_off);
+  p.rev_offset = reinterpret_cast<int32_t*>(base + L.rev_offset_off);
+  p.rev_cursor = reinterpret_cast<int32_t*>(base + L.rev_cursor_off);
+  p.rev_list = reinterpret_cast<uint32_t*>(base + L.rev_list_off);
+  p.jmat = reinterpret_cast<uint8_t*>(base + L.jmat_off);
+  const dim3 per_strip((L.strips + 3) / 4);
+  AFFMAE_LAUNCH("plan_zero_kernel", stream, plan_zero_kernel, dim3((L.strips + 255) / 256), dim3(256), 0, stream,
+                p.rev_count, p.rev_cursor, L.strips);
+  AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel, per_strip, dim3(256), 0, stream, p);
+  AFFMAE_LAUNCH("plan_scan_kernel", stream, plan_scan_kernel, dim3(1), dim3(1024), 0, stream, p.rev_count,
+                p.rev_offset, L.strips);
+  AFFMAE_LAUNCH("plan_fill_kernel", stream, plan_fill_kernel, per_strip, dim3(256), 0, stream, p);
+  AFFMAE_LAUNCH("plan_sort_kernel", stream, plan_sort_kernel, per_strip, dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
