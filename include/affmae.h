@@ -113,7 +113,7 @@ int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B,
  * affmae_pla_fwd - local attention over each token's neighbourhood (paper,
  * Sec. "Flash-style Cluster Attention and Fast Decoder KNN", the FlashNbhdAttn
  * equation): for every image b, token i and head h
- *     s_j   = scale * <q[b,i,h,:], k[b,n(i,j),h,:]> + bias[b,i,j,h]   (j < K)
+ *     s_j   = scale * <q[b,i,h,:], k[b,n(i,j),h,:]> + bias[b,i,h,j]   (j < K)
  *     s_K   = scale * <q[b,i,h,:], k_blank[h,:]>                      (if given)
  *     p     = softmax(s)
  *     out[b,i,h,:] = sum_j p_j v[b,n(i,j),h,:]  (+ p_K v_blank[h,:])
@@ -122,7 +122,8 @@ int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B,
  * accumulators whatever the storage type.
  *
  *   q,k,v         in  [B,N,H,d] of `dtype`.
- *   bias          in  [B,N,K,H] of `dtype`, or NULL (= 0).
+ *   bias          in  [B,N,H,K] of `dtype`, or NULL (= 0): one row of K values per
+ *                     (token, head), in the order of the token's neighbour list.
  *   nbr_idx       in  [B,N,K] int32, values in [0,N); it need not come from
  *                     affmae_knn and may list a token more than once (each
  *                     slot is its own softmax column) unless near_clusters is
@@ -155,7 +156,7 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
  * attention but prints no backward; this is the chain rule on the equation
  * above).  With p recomputed from lse and g = dout:
  *     dP_j = <g[b,i,h,:], v_j>,  D = sum_j p_j dP_j,  dS_j = p_j (dP_j - D)
- *     dbias[b,i,j,h]  = dS_j
+ *     dbias[b,i,h,j]  = dS_j
  *     dq[b,i,h,:]     = scale * sum_j dS_j k_j
  *     dk[b,n(i,j),h,:] += scale * dS_j q[b,i,h,:]
  *     dv[b,n(i,j),h,:] += p_j g[b,i,h,:]
@@ -170,7 +171,7 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
  *   dout          in  [B,N,H,d] of `dtype`.
  *   dq,dk,dv      out [B,N,H,d] of `dtype`; sums are formed in fp32.  The order
  *                     of the additions into dk/dv may differ between runs.
- *   dbias         out [B,N,K,H] of `dtype`, or NULL to skip.
+ *   dbias         out [B,N,H,K] of `dtype`, or NULL to skip.
  *   dk_blank,dv_blank out [H,d] fp32, or NULL (both required when blanks given
  *                     and their gradients are wanted).  Calls with blank tokens
  *                     use the gather kernels even when near_clusters is given.

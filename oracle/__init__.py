@@ -115,7 +115,7 @@ def pla_fwd(q, k, v, bias, nbr_idx, scale: float, k_blank=None, v_blank=None, wa
     nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
     K = nbr_idx.shape[2]
     assert nbr_idx.shape == (B, N, K)
-    bias = _f64(bias, (B, N, K, H))
+    bias = _f64(bias, (B, N, H, K))
     k_blank = _f64(k_blank, (H, d))
     v_blank = _f64(v_blank, (H, d))
     out = np.empty((B, N, H, d), dtype=np.float64)
@@ -136,13 +136,13 @@ def pla_bwd(q, k, v, bias, nbr_idx, dout, scale: float, k_blank=None, v_blank=No
     dout = _f64(dout, q.shape)
     nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
     K = nbr_idx.shape[2]
-    bias = _f64(bias, (B, N, K, H))
+    bias = _f64(bias, (B, N, H, K))
     k_blank = _f64(k_blank, (H, d))
     v_blank = _f64(v_blank, (H, d))
     dq = np.empty_like(q)
     dk = np.empty_like(q)
     dv = np.empty_like(q)
-    dbias = np.empty((B, N, K, H), dtype=np.float64)
+    dbias = np.empty((B, N, H, K), dtype=np.float64)
     dkb = np.empty((H, d), dtype=np.float64) if k_blank is not None else None
     dvb = np.empty((H, d), dtype=np.float64) if k_blank is not None else None
     _check(_load().oracle_pla_bwd(_p(q), _p(k), _p(v), _p(bias), _p(nbr_idx), _p(k_blank), _p(v_blank),

@@ -259,7 +259,7 @@ static double attention_row(const double *q, const double *k, const double *bias
     const double *kn = k + (((size_t)b * N + n) * H + h) * d;
     double acc = 0.0;
     for (int t = 0; t < d; ++t) acc += qi[t] * kn[t];
-    s[j] = scale * acc + (bias ? bias[(((size_t)b * N + i) * K + j) * H + h] : 0.0);
+    s[j] = scale * acc + (bias ? bias[(((size_t)b * N + i) * H + h) * K + j] : 0.0);
   }
   if (k_blank) {
     double acc = 0.0;
@@ -286,7 +286,7 @@ static int check_nbr(const int32_t *nbr, size_t count, int N) {
 }
 
 /*
- * oracle_pla_fwd: q,k,v [B,N,H,d]; bias [B,N,K,H] or NULL; nbr_idx [B,N,K] with
+ * oracle_pla_fwd: q,k,v [B,N,H,d]; bias [B,N,H,K] or NULL; nbr_idx [B,N,K] with
  * values in [0,N) (repeats allowed: every slot is its own softmax column);
  * k_blank,v_blank [H,d] or both NULL.
  *   out [B,N,H,d]; lse [B,N,H] natural log of the softmax denominator;
@@ -335,7 +335,7 @@ int oracle_pla_fwd(const double *q, const double *k, const double *v, const doub
  *   dP_j  = <dout_i, v_j>             (v_j = neighbour row or blank row)
  *   D     = sum_j p_j dP_j
  *   dS_j  = p_j (dP_j - D)
- *   dbias[b,i,j,h]   = dS_j                      (j < K)
+ *   dbias[b,i,h,j]   = dS_j                      (j < K)
  *   dq_i            += scale * dS_j * k_j
  *   dk[n(i,j)]      += scale * dS_j * q_i,   dv[n(i,j)] += p_j * dout_i
  *   dk_blank[h]     += scale * dS_K * q_i,   dv_blank[h] += p_K * dout_i
@@ -392,7 +392,7 @@ int oracle_pla_bwd(const double *q, const double *k, const double *v, const doub
           if (j < K) {
             int n = nbr_idx[((size_t)b * N + i) * K + j];
             size_t noff = (((size_t)b * N + n) * H + h) * d;
-            if (dbias) dbias[(((size_t)b * N + i) * K + j) * H + h] = dS;
+            if (dbias) dbias[(((size_t)b * N + i) * H + h) * K + j] = dS;
             for (int t = 0; t < d; ++t) {
               dq[qoff + t] += scale * dS * k[noff + t];
               dk[noff + t] += scale * dS * qi[t];

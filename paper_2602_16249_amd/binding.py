@@ -172,7 +172,7 @@ def affmae_pla_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
     K = nbr_idx.shape[2]
     _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
     if bias is not None:
-        _dev(bias, "bias", q.dtype, (B, N, K, H))
+        _dev(bias, "bias", q.dtype, (B, N, H, K))
     if near_clusters is not None:
         _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
     if k_blank is not None:
@@ -216,7 +216,7 @@ def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
     _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
     _dev(lse, "lse", torch.float32, (B, N, H))
     if bias is not None:
-        _dev(bias, "bias", q.dtype, (B, N, K, H))
+        _dev(bias, "bias", q.dtype, (B, N, H, K))
     if near_clusters is not None:
         _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
     if k_blank is not None:
@@ -229,8 +229,8 @@ def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
         _dev(g[name], name, q.dtype, q.shape)
     if want_dbias:
         if "dbias" not in g:
-            g["dbias"] = torch.empty((B, N, K, H), dtype=q.dtype, device=q.device)
-        _dev(g["dbias"], "dbias", q.dtype, (B, N, K, H))
+            g["dbias"] = torch.empty((B, N, H, K), dtype=q.dtype, device=q.device)
+        _dev(g["dbias"], "dbias", q.dtype, (B, N, H, K))
     if k_blank is not None:
         for name in ("dk_blank", "dv_blank"):
             if name not in g:

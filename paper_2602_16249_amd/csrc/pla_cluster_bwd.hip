@@ -8,7 +8,7 @@
 //    scores, forms dP = V dO^T with MFMAs, dS = p (dP - D) with D = <dout, out>,
 //    accumulates dQ^T = K^T dS^T (K transposed by an MFMA against the identity),
 //    and leaves p and dS of the real (query, neighbour) pairs in compact
-//    [token, slot, head] arrays: dS is dbias, p goes to the workspace;
+//    [token, head, slot] arrays: dS is dbias, p goes to the workspace;
 //
 //  key-stationary (one wave per tile of 16 tokens): walks the sorted list of
 //    strips that touch the tile, gathers their p and dS for the tile's tokens
@@ -33,10 +33,11 @@ struct BwdParams {
   const uint32_t* rev_list;
   const uint8_t* jmat;
   int N, H, K, strips, strips_per_image, slot_stride, max_slots;
+  uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
   float scale;
   bf16_t *dq, *dk, *dv;
-  bf16_t* ds;  // [B,N,K,H] dS: the caller's dbias, or workspace
-  bf16_t* pc;  // [B,N,K,H] p, workspace
+  bf16_t* ds;  // [B,N,H,K] dS: the caller's dbias, or workspace
+  bf16_t* pc;  // [B,N,H,K] p, workspace
 };
 
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
@@ -62,9 +63,10 @@ __device__ __forceinline__ int xcd_contiguous_block() {
 
 // ------------------------------------------------------------------------------------------------
 // query-stationary kernel
-template <int ENT>
+// Items per lane as in the forward kernel: NT chunks of 8 slots (K % 8 == 0) or NT single entries.
+template <int NT, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pla_bwd_query_kernel(BwdParams p) {
-  __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256];
+  __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
@@ -77,14 +79,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const long long img_base = (long long)b * p.N;
   const long long tok0 = (long long)sg * 16;
   const int C = p.H * kD;
-  const int nent = 16 * p.K;
+  const int K = p.K;
 
   const uint16_t* sl = p.slots + (size_t)sg * p.slot_stride;
-  const int ntiles = min((int)__builtin_amdgcn_readfirstlane((int)sl[0]), kMaxSlots);
+  const int cnt_raw = sl[0];
   const int my_tile = (lane < p.slot_stride - 1) ? (int)sl[1 + lane] : 0;
+  constexpr int EW = VEC ? 4 : 1;  // 32-bit words per item
+  uint32_t ent[NT][EW];
+  uint32_t item_off[NT];  // element offset of the item's first value within head 0's [token, head, :] rows
+  bool item_live[NT];
+  const int items = VEC ? 2 * K : 16 * K;
+  const int chunks_per_query = K >> 3;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int i = t * kWave + lane;
+    const bool live = i < items;
+    item_live[t] = live;
+    const int ii = live ? i : 0;
+    if (VEC) {
+      const uint4 w = *reinterpret_cast<const uint4*>(p.entries + (size_t)sg * 16 * K + (size_t)ii * 8);
+      ent[t][0] = live ? w.x : 0xffffffffu;
+      ent[t][EW > 1 ? 1 : 0] = live ? w.y : 0xffffffffu;
+      ent[t][EW > 2 ? 2 : 0] = live ? w.z : 0xffffffffu;
+      ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
+      const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
+      item_off[t] = (uint32_t)(qi * p.H * K + j0);
+    } else {
+      ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
+      const int qi = fast_div(ii, p.k_magic);
+      item_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
+    }
+  }
+  const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
   Frag8 idf[2];
   make_identity(idf, g, r);
-  const uint16_t* ent_ptr = p.entries + (size_t)sg * nent + lane;
+  const char* kimg = reinterpret_cast<const char*>(p.k + (size_t)img_base * C);
+  const char* vimg = reinterpret_cast<const char*>(p.v + (size_t)img_base * C);
+  const uint32_t lane_off = (uint32_t)(r * C + g * 8) * 2u;
+  const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
+  const size_t strip_rows = (size_t)tok0 * p.H * K;  // first element of the strip's [token, head, :] rows
 
   for (int h = 0; h < p.H; ++h) {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
@@ -95,31 +128,46 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     float Dq = 0.f;  // D of query r
 #pragma unroll
     for (int i = 0; i < 8; ++i) Dq = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(of.h[i]), Dq);
-    Dq += __shfl_xor(Dq, 16);
-    Dq += __shfl_xor(Dq, 32);
+    Dq = group_sum(Dq);
     const float nl2 = -p.lse[(size_t)(tok0 + r) * p.H + h] * kLog2e;
-    const size_t cbase = ((size_t)tok0 * p.K + lane) * p.H + h;  // compact arrays: entry `lane` of head h
-    const bf16_t* bias_ptr = p.bias ? p.bias + cbase : nullptr;
+    const size_t head_rows = strip_rows + (size_t)h * K;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    uint32_t pacc[NT][EW], dacc[NT][EW];  // p and dS of this lane's items (packed bf16), gathered pass by pass
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int e = 0; e < EW; ++e) pacc[t][e] = dacc[t][e] = 0u;
 
     for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCapB) {
       const int nsl = min(kSlotCapB, ntiles - slot0);
+      const uint32_t lo = (uint32_t)slot0 * 256u, span = (uint32_t)nsl * 256u;
       {
-        uint32_t ent[ENT];  // low half: plan entry, high half: bias bits
+        uint32_t bw[NT][EW];  // bias of this lane's items
 #pragma unroll
-        for (int t = 0; t < ENT; ++t) {
-          const bool live = t * kWave + lane < nent;
-          ent[t] = live ? (uint32_t)ent_ptr[t * kWave] : kNoEntry;
-          if (live && bias_ptr) ent[t] |= (uint32_t)bias_ptr[(size_t)t * kWave * p.H] << 16;
+        for (int t = 0; t < NT; ++t) {
+          if (VEC) {
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (p.bias && item_live[t]) w = *reinterpret_cast<const uint4*>(p.bias + head_rows + item_off[t]);
+            bw[t][0] = w.x;
+            bw[t][EW > 1 ? 1 : 0] = w.y;
+            bw[t][EW > 2 ? 2 : 0] = w.z;
+            bw[t][EW > 3 ? 3 : 0] = w.w;
+          } else {
+            bw[t][0] = (p.bias && item_live[t]) ? (uint32_t)p.bias[head_rows + item_off[t]] : 0u;
+          }
         }
         for (int s = 0; s < nsl; ++s)
           *reinterpret_cast<uint2*>(dstile + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
         wave_lds_sync();
 #pragma unroll
-        for (int t = 0; t < ENT; ++t) {
-          const uint32_t off = ent[t] & 0xffffu;
-          const uint32_t rel = off - (uint32_t)slot0 * 256u;
-          if (off != kNoEntry && rel < (uint32_t)nsl * 256u) dstile[rel] = (bf16_t)(ent[t] >> 16);
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+          for (int e = 0; e < (VEC ? 8 : 1); ++e) {
+            const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
+            const uint32_t bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
+            const uint32_t rel = off - lo;  // other passes, kNoEntry and dead items fall outside [0, span)
+            dstile[rel < span ? rel : (uint32_t)kSlotCapB * 256u] = (bf16_t)bits;
+          }
         }
         wave_lds_sync();
       }
@@ -129,10 +177,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const int s = min(2 * pr + tt, nsl - 1);
-          const int tile = __builtin_amdgcn_readlane(my_tile, slot0 + s);
-          const size_t row = ((size_t)(img_base + (long long)tile * 16 + r)) * C + h * kD + g * 8;
-          kf[tt].u4 = *reinterpret_cast<const uint4*>(p.k + row);
-          vf[tt].u4 = *reinterpret_cast<const uint4*>(p.v + row);
+          const uint32_t tile = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + s);
+          const size_t tbase = (size_t)tile * tile_bytes + (size_t)(h * kD * 2);
+          kf[tt].u4 = *reinterpret_cast<const uint4*>(kimg + tbase + lane_off);
+          vf[tt].u4 = *reinterpret_cast<const uint4*>(vimg + tbase + lane_off);
         }
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
@@ -191,21 +239,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         }
       }
       wave_lds_sync();
-      // compact p and dS of the real pairs: [token, slot, head]
+      // collect p and dS of this pass's real (query, neighbour) pairs
 #pragma unroll
-      for (int t = 0; t < ENT; ++t) {
-        const bool live = t * kWave + lane < nent;
-        const uint32_t off = live ? (uint32_t)ent_ptr[t * kWave] : kNoEntry;  // read again: cheaper than keeping it
-        const uint32_t rel = off - (uint32_t)slot0 * 256u;
-        if (live && off != kNoEntry && rel < (uint32_t)nsl * 256u) {
-          p.ds[cbase + (size_t)t * kWave * p.H] = dstile[rel];
-          p.pc[cbase + (size_t)t * kWave * p.H] = ptile[rel];
-        } else if (live && off == kNoEntry && slot0 == 0) {
-          p.ds[cbase + (size_t)t * kWave * p.H] = 0;
-          p.pc[cbase + (size_t)t * kWave * p.H] = 0;
+      for (int t = 0; t < NT; ++t) {
+#pragma unroll
+        for (int e = 0; e < (VEC ? 8 : 1); ++e) {
+          const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
+          const uint32_t rel = off - lo;
+          const bool in = rel < span;
+          const uint32_t at = in ? rel : 0u;
+          const uint32_t dsv = dstile[at], pv = ptile[at];
+          dacc[t][e >> 1] |= (in ? dsv : 0u) << (16 * (e & 1));
+          pacc[t][e >> 1] |= (in ? pv : 0u) << (16 * (e & 1));
         }
       }
       wave_lds_sync();
+    }
+    // compact arrays [token, head, slot]: whole 16-byte pieces when K is a multiple of 8
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (item_live[t]) {
+        if (VEC) {
+          *reinterpret_cast<uint4*>(p.ds + head_rows + item_off[t]) =
+              make_uint4(dacc[t][0], dacc[t][EW > 1 ? 1 : 0], dacc[t][EW > 2 ? 2 : 0], dacc[t][EW > 3 ? 3 : 0]);
+          *reinterpret_cast<uint4*>(p.pc + head_rows + item_off[t]) =
+              make_uint4(pacc[t][0], pacc[t][EW > 1 ? 1 : 0], pacc[t][EW > 2 ? 2 : 0], pacc[t][EW > 3 ? 3 : 0]);
+        } else {
+          p.ds[head_rows + item_off[t]] = (bf16_t)dacc[t][0];
+          p.pc[head_rows + item_off[t]] = (bf16_t)pacc[t][0];
+        }
+      }
     }
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt) {
@@ -276,7 +339,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         for (int i = 0; i < 4; ++i) {
           const uint32_t j = (jm >> (8 * i)) & 255u;
           const bool hit = j != 255u;
-          const size_t idx = ((tokq0 + 4 * g + i) * p.K + (hit ? j : 0u)) * p.H + h;
+          const size_t idx = ((tokq0 + 4 * g + i) * p.H + h) * p.K + (hit ? j : 0u);
           const uint16_t pvv = p.pc[idx], dvv = p.ds[idx];
           it.pv[i] = hit ? pvv : (uint16_t)0;
           it.dsv[i] = hit ? dvv : (uint16_t)0;
@@ -364,15 +427,22 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.ds = a.dbias ? (bf16_t*)a.dbias : reinterpret_cast<bf16_t*>(ws + one);
 
   const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);  // multiple of 8 for the XCD-contiguous mapping
-  const int ent = (16 * a.K + kWave - 1) / kWave;
-  if (ent <= 4)
-    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<4>, grid, dim3(256), 0, stream, p);
-  else if (ent <= 8)
-    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<8>, grid, dim3(256), 0, stream, p);
-  else if (ent <= 12)
-    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<12>, grid, dim3(256), 0, stream, p);
-  else
-    AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, pla_bwd_query_kernel<16>, grid, dim3(256), 0, stream, p);
+  p.k_magic = div_magic(a.K);
+  p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
+  const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0) &&
+                   reinterpret_cast<uintptr_t>(p.ds) % 16 == 0;
+#define AFFMAE_BWDQ(NT, VEC) \
+  AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (pla_bwd_query_kernel<NT, VEC>), grid, dim3(256), 0, stream, p)
+  if (vec) {
+    if (2 * a.K <= kWave) AFFMAE_BWDQ(1, true); else AFFMAE_BWDQ(2, true);
+  } else {
+    const int ent = (16 * a.K + kWave - 1) / kWave;
+    if (ent <= 4) AFFMAE_BWDQ(4, false);
+    else if (ent <= 8) AFFMAE_BWDQ(8, false);
+    else if (ent <= 12) AFFMAE_BWDQ(12, false);
+    else AFFMAE_BWDQ(16, false);
+  }
+#undef AFFMAE_BWDQ
   if (a.H % 2 == 0)
     AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<2>, grid, dim3(256), 0, stream, p);
   else

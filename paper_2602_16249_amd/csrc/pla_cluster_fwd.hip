@@ -31,6 +31,7 @@ struct FwdParams {
   const bf16_t *q, *k, *v, *bias, *k_blank, *v_blank;
   const uint16_t *slots, *entries;
   int N, H, K, strips, strips_per_image, slot_stride;
+  uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
   float scale;
   bf16_t* out;
   float* lse;
@@ -40,17 +41,18 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
 }
 
-// ENT = entries per lane = ceil(16 * K / 64).
-template <int ENT>
+// Per strip the plan holds 16*K entries, one per (query, neighbour slot), query-major; bias rows
+// [token, head, :] hold the matching K values.  With K a multiple of 8 a lane owns NT chunks of 8
+// consecutive slots of one query (16-byte loads of entries and of bias); otherwise NT single entries.
+template <int NT, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
-  __shared__ __align__(16) bf16_t scratch_all[4][kSlotCap * 256];
+  __shared__ __align__(16) bf16_t scratch_all[4][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int g = lane >> 4, r = lane & 15;
   // Consecutive strips share K/V rows; workgroups are dealt round-robin to the 8 XCDs (one L2
   // each), so give every XCD a contiguous range of strips.
-  const int nblk = gridDim.x;
-  const int per_xcd = (nblk + 7) >> 3;
+  const int per_xcd = gridDim.x >> 3;
   const int blk = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   const int sg = blk * 4 + wave;
   if (sg >= p.strips) return;  // wave-uniform; the kernel has no workgroup barrier
@@ -59,44 +61,99 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const long long img_base = (long long)b * p.N;
   const long long tok0 = (long long)sg * 16;
   const int C = p.H * kD;
-  const int nent = 16 * p.K;
+  const int K = p.K;
 
   const uint16_t* sl = p.slots + (size_t)sg * p.slot_stride;
-  const int ntiles = min((int)__builtin_amdgcn_readfirstlane((int)sl[0]), kMaxSlots);
+  const int cnt_raw = sl[0];
   const int my_tile = (lane < p.slot_stride - 1) ? (int)sl[1 + lane] : 0;
 
+  // plan entries of this lane (kept for all heads) and where the matching bias values sit
+  constexpr int EW = VEC ? 4 : 1;  // 32-bit words per item
+  uint32_t ent[NT][EW];
+  uint32_t bias_off[NT];  // element offset of the item's first bias value within head 0's rows
+  const int items = VEC ? 2 * K : 16 * K;  // chunks of 8, or single entries
+  const int chunks_per_query = K >> 3;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int i = t * kWave + lane;
+    const bool live = i < items;
+    const int ii = live ? i : 0;
+    if (VEC) {
+      const uint4 w = *reinterpret_cast<const uint4*>(p.entries + (size_t)sg * 16 * K + (size_t)ii * 8);
+      ent[t][0] = live ? w.x : 0xffffffffu;
+      ent[t][EW > 1 ? 1 : 0] = live ? w.y : 0xffffffffu;
+      ent[t][EW > 2 ? 2 : 0] = live ? w.z : 0xffffffffu;
+      ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
+      const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
+      bias_off[t] = (uint32_t)(qi * p.H * K + j0);
+    } else {
+      ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
+      const int qi = fast_div(ii, p.k_magic);
+      bias_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
+    }
+  }
+  const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
   Frag8 idf[2];  // identity operand, one per 16-channel half: lane (column r, rows 8g..8g+7)
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int i = 0; i < 8; ++i) idf[dt].h[i] = (8 * g + i == r + 16 * dt) ? 0x3f80u : 0u;
-  const uint16_t* ent_ptr = p.entries + (size_t)sg * nent + lane;
+  // K/V rows of a token tile: uniform tile base + this lane's (row r, channels 8g..8g+7) byte offset
+  const char* kimg = reinterpret_cast<const char*>(p.k + (size_t)img_base * C);
+  const char* vimg = reinterpret_cast<const char*>(p.v + (size_t)img_base * C);
+  const uint32_t lane_off = (uint32_t)(r * C + g * 8) * 2u;
+  const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
+  const bf16_t* bias_strip = p.bias ? p.bias + (size_t)tok0 * p.H * K : nullptr;
+
+  // loads of one head: the Q^T operand (lane (query r, channels 8g..8g+7)) and the bias of the items
+  auto load_head = [&](int h, Frag8& qf, uint32_t (&bw)[NT][EW]) {
+    qf.u4 = *reinterpret_cast<const uint4*>(p.q + (tok0 + r) * C + h * kD + g * 8);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (VEC) {
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (bias_strip) w = *reinterpret_cast<const uint4*>(bias_strip + bias_off[t] + (size_t)h * K);
+        bw[t][0] = w.x;
+        bw[t][EW > 1 ? 1 : 0] = w.y;
+        bw[t][EW > 2 ? 2 : 0] = w.z;
+        bw[t][EW > 3 ? 3 : 0] = w.w;
+      } else {
+        bw[t][0] = bias_strip ? (uint32_t)bias_strip[bias_off[t] + (size_t)h * K] : 0u;
+      }
+    }
+  };
+  Frag8 qf_next;
+  uint32_t bw_next[NT][EW];
+  load_head(0, qf_next, bw_next);
 
   for (int h = 0; h < p.H; ++h) {
-    Frag8 qf;  // Q^T operand: lane (query r, channels 8g..8g+7)
-    qf.u4 = *reinterpret_cast<const uint4*>(p.q + (tok0 + r) * C + h * kD + g * 8);
-    const bf16_t* bias_ptr = p.bias ? p.bias + ((size_t)tok0 * p.K + lane) * p.H + h : nullptr;
+    Frag8 qf = qf_next;
+    uint32_t bw[NT][EW];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int e = 0; e < EW; ++e) bw[t][e] = bw_next[t][e];
+    if (h + 1 < p.H) load_head(h + 1, qf_next, bw_next);  // flies during this head's tiles
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
     for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCap) {
       const int nsl = min(kSlotCap, ntiles - slot0);
       // bias tile: -inf everywhere, then the bias of the real (query, neighbour) pairs
-      uint32_t ent[ENT];  // low half: plan entry, high half: bias bits
-#pragma unroll
-      for (int t = 0; t < ENT; ++t) {
-        const bool live = t * kWave + lane < nent;
-        ent[t] = live ? (uint32_t)ent_ptr[t * kWave] : kNoEntry;
-        if (live && bias_ptr) ent[t] |= (uint32_t)bias_ptr[(size_t)t * kWave * p.H] << 16;
-      }
       for (int s = 0; s < nsl; ++s)
         *reinterpret_cast<uint2*>(scratch + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
       wave_lds_sync();
+      const uint32_t lo = (uint32_t)slot0 * 256u, span = (uint32_t)nsl * 256u;
 #pragma unroll
-      for (int t = 0; t < ENT; ++t) {
-        const uint32_t off = ent[t] & 0xffffu;
-        const uint32_t rel = off - (uint32_t)slot0 * 256u;
-        if (off != kNoEntry && rel < (uint32_t)nsl * 256u) scratch[rel] = (bf16_t)(ent[t] >> 16);
+      for (int t = 0; t < NT; ++t) {
+#pragma unroll
+        for (int e = 0; e < (VEC ? 8 : 1); ++e) {
+          // entries of other passes, kNoEntry and dead items fall outside [0, span): they go to the spare cell
+          const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
+          const uint32_t bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
+          const uint32_t rel = off - lo;
+          scratch[rel < span ? rel : (uint32_t)kSlotCap * 256u] = (bf16_t)bits;
+        }
       }
       wave_lds_sync();
 
@@ -105,10 +162,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const int s = min(2 * pr + tt, nsl - 1);
-          const int tile = __builtin_amdgcn_readlane(my_tile, slot0 + s);
-          const size_t row = ((size_t)(img_base + (long long)tile * 16 + r)) * C + h * kD + g * 8;
-          kf[tt].u4 = *reinterpret_cast<const uint4*>(p.k + row);
-          vf[tt].u4 = *reinterpret_cast<const uint4*>(p.v + row);
+          const uint32_t tile = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + s);
+          const size_t tbase = (size_t)tile * tile_bytes + (size_t)(h * kD * 2);
+          kf[tt].u4 = *reinterpret_cast<const uint4*>(kimg + tbase + lane_off);
+          vf[tt].u4 = *reinterpret_cast<const uint4*>(vimg + tbase + lane_off);
         }
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
@@ -130,8 +187,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
           }
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = group_max(mx);
         const float m_new = fmaxf(m_run, mx);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * kLog2e);
@@ -182,8 +238,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
     // The probabilities that entered the MFMAs were rounded to bf16; the
     // denominator uses the unrounded ones, as the definition does.
-    float l_tot = l_run + __shfl_xor(l_run, 16);
-    l_tot += __shfl_xor(l_tot, 32);
+    float l_tot = group_sum(l_run);
     float m_fin = m_run;
     if (p.k_blank) {
       Frag8 kb;
@@ -191,8 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
       float part = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) part = fmaf(bf16_to_f32(qf.h[i]), bf16_to_f32(kb.h[i]), part);
-      part += __shfl_xor(part, 16);
-      part += __shfl_xor(part, 32);
+      part = group_sum(part);
       const float sb = p.scale * part;
       m_fin = fmaxf(m_run, sb);
       const float alpha = __expf(m_run - m_fin);
@@ -240,17 +294,23 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride;
   p.scale = a.scale;
   p.out = (bf16_t*)a.out; p.lse = a.lse;
-  // the XCD-contiguous remap needs a grid that is a multiple of 8; surplus waves exit at once
+  p.k_magic = div_magic(a.K);
+  p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
+  // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
   const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);
-  const int ent = (16 * a.K + kWave - 1) / kWave;
-  if (ent <= 4)
-    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<4>, grid, dim3(256), 0, stream, p);
-  else if (ent <= 8)
-    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<8>, grid, dim3(256), 0, stream, p);
-  else if (ent <= 12)
-    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<12>, grid, dim3(256), 0, stream, p);
-  else
-    AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, pla_fwd_cluster_kernel<16>, grid, dim3(256), 0, stream, p);
+  const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);
+#define AFFMAE_FWD(NT, VEC) \
+  AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (pla_fwd_cluster_kernel<NT, VEC>), grid, dim3(256), 0, stream, p)
+  if (vec) {
+    if (2 * a.K <= kWave) AFFMAE_FWD(1, true); else AFFMAE_FWD(2, true);
+  } else {
+    const int ent = (16 * a.K + kWave - 1) / kWave;
+    if (ent <= 4) AFFMAE_FWD(4, false);
+    else if (ent <= 8) AFFMAE_FWD(8, false);
+    else if (ent <= 12) AFFMAE_FWD(12, false);
+    else AFFMAE_FWD(16, false);
+  }
+#undef AFFMAE_FWD
   return hipGetLastError();
 }
 

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void pla_fwd_general_kernel(
       if (lane < K) {
         const T* krow = k + ((img_base + nb[lane]) * H + h) * D;
         s = scale * dot_row<T, D>(qr, krow);
-        if (bias) s += Elem<T>::load(bias + (tok * K + lane) * H + h);
+        if (bias) s += Elem<T>::load(bias + (tok * H + h) * K + lane);
       }
       float sb = -INFINITY;
       if (k_blank) sb = scale * dot_row<T, D>(qr, k_blank + (size_t)h * D);
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void pla_bwd_general_kernel(
       if (lane < K) {
         const long long row = ((img_base + nb[lane]) * H + h) * D;
         float s = scale * dot_row<T, D>(qr, k + row);
-        if (bias) s += Elem<T>::load(bias + (tok * K + lane) * H + h);
+        if (bias) s += Elem<T>::load(bias + (tok * H + h) * K + lane);
         p = expf(s - l);
         dP = dot_row<T, D>(gr, v + row);
       }
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void pla_bwd_general_kernel(
       if (lane < K) {
         P[h * Kp + lane] = p;
         dS[h * Kp + lane] = ds;
-        if (dbias) Elem<T>::store(dbias + (tok * K + lane) * H + h, ds);
+        if (dbias) Elem<T>::store(dbias + (tok * H + h) * K + lane, ds);
       }
       if (lane == 0) {
         P[h * Kp + K] = pb;

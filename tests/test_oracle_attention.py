@@ -37,7 +37,7 @@ def _dense_masked_attention_torch(q, k, v, bias, nbr, scale, k_blank=None, v_bla
     dense_bias = torch.zeros((B, H, N, N), dtype=q.dtype)
     for h in range(H):
         mask[bi, h, ii, nn] = 0.0
-        dense_bias = dense_bias.index_put((bi, torch.full_like(bi, h), ii, nn), bias[:, :, :, h])
+        dense_bias = dense_bias.index_put((bi, torch.full_like(bi, h), ii, nn), bias[:, :, h, :])
     logits = logits + dense_bias + mask
     vals = v.permute(0, 2, 1, 3)  # [B,H,N,d]
     if k_blank is not None:
@@ -132,7 +132,7 @@ def test_probabilities_sum_to_one_and_identities():
     assert np.all(prob[..., -1] == 0.0)  # no blank column
     g = oracle.pla_bwd(c["q"], c["k"], c["v"], c["bias"], c["nbr"], c["dout"], SCALE)
     # softmax rows sum to one => bias gradients of a row sum to zero
-    np.testing.assert_allclose(g["dbias"].sum(axis=2), 0.0, atol=1e-13)
+    np.testing.assert_allclose(g["dbias"].sum(axis=3), 0.0, atol=1e-13)
     # every probability row sums to one => the v-gradient conserves dout per head
     np.testing.assert_allclose(g["dv"].sum(axis=1), c["dout"].sum(axis=1), atol=1e-11)
 
@@ -145,7 +145,7 @@ def test_single_neighbour_copies_value_row():
     np.testing.assert_allclose(out, want, atol=1e-15)
     # lse of a single logit is the logit itself
     s = SCALE * np.einsum("bihd,bihd->bih", c["q"], np.stack([c["k"][b, c["nbr"][b, :, 0]] for b in range(B)]))
-    np.testing.assert_allclose(lse, s + c["bias"][:, :, 0, :], atol=1e-13)
+    np.testing.assert_allclose(lse, s + c["bias"][:, :, :, 0], atol=1e-13)
 
 
 def test_zero_query_zero_bias_gives_mean_of_value_rows():
@@ -160,11 +160,11 @@ def test_zero_query_zero_bias_gives_mean_of_value_rows():
 def test_row_shift_of_bias_changes_nothing_but_lse():
     """softmax(z) = softmax(z - const): the max-subtraction identity."""
     c = _case(seed=4)
-    shift = np.random.default_rng(0).normal(size=(2, 40, 1, 2)) * 3.0
+    shift = np.random.default_rng(0).normal(size=(2, 40, 2, 1)) * 3.0
     o1, l1 = oracle.pla_fwd(c["q"], c["k"], c["v"], c["bias"], c["nbr"], SCALE)
     o2, l2 = oracle.pla_fwd(c["q"], c["k"], c["v"], c["bias"] + shift, c["nbr"], SCALE)
     np.testing.assert_allclose(o1, o2, atol=1e-13)
-    np.testing.assert_allclose(l2 - l1, shift[:, :, 0, :], atol=1e-13)
+    np.testing.assert_allclose(l2 - l1, shift[:, :, :, 0], atol=1e-13)
     g1 = oracle.pla_bwd(c["q"], c["k"], c["v"], c["bias"], c["nbr"], c["dout"], SCALE)
     g2 = oracle.pla_bwd(c["q"], c["k"], c["v"], c["bias"] + shift, c["nbr"], c["dout"], SCALE)
     for n in g1:
@@ -177,7 +177,7 @@ def test_permuting_neighbour_order_permutes_only_dbias():
     B, N, K = c["nbr"].shape
     perm = np.stack([[rng.permutation(K) for _ in range(N)] for _ in range(B)])
     nbr2 = np.take_along_axis(c["nbr"], perm, axis=2)
-    bias2 = np.take_along_axis(c["bias"], perm[..., None], axis=2)
+    bias2 = np.take_along_axis(c["bias"], perm[:, :, None, :], axis=3)
     o1, l1 = oracle.pla_fwd(c["q"], c["k"], c["v"], c["bias"], c["nbr"], SCALE)
     o2, l2 = oracle.pla_fwd(c["q"], c["k"], c["v"], bias2, nbr2, SCALE)
     np.testing.assert_allclose(o1, o2, atol=1e-13)
@@ -186,7 +186,7 @@ def test_permuting_neighbour_order_permutes_only_dbias():
     g2 = oracle.pla_bwd(c["q"], c["k"], c["v"], bias2, nbr2, c["dout"], SCALE)
     for n in ("dq", "dk", "dv"):
         np.testing.assert_allclose(g1[n], g2[n], atol=1e-12)
-    np.testing.assert_allclose(np.take_along_axis(g1["dbias"], perm[..., None], axis=2), g2["dbias"], atol=1e-13)
+    np.testing.assert_allclose(np.take_along_axis(g1["dbias"], perm[:, :, None, :], axis=3), g2["dbias"], atol=1e-13)
 
 
 def test_blank_token_is_one_more_shared_neighbour():
@@ -205,8 +205,8 @@ def test_blank_token_is_one_more_shared_neighbour():
     dout2 = ext(c["dout"], np.zeros((H, d)))  # the extra token's own output carries no loss
     nbr2 = np.concatenate([np.concatenate([c["nbr"], np.full((B, N, 1), N, np.int32)], axis=2),
                            np.full((B, 1, K + 1), N, np.int32)], axis=1)
-    bias2 = np.zeros((B, N + 1, K + 1, H))
-    bias2[:, :N, :K] = c["bias"]
+    bias2 = np.zeros((B, N + 1, H, K + 1))
+    bias2[:, :N, :, :K] = c["bias"]
     o1, l1 = oracle.pla_fwd(c["q"], c["k"], c["v"], c["bias"], c["nbr"], SCALE, c["k_blank"], c["v_blank"])
     o2, l2 = oracle.pla_fwd(q2, k2, v2, bias2, nbr2, SCALE)
     np.testing.assert_allclose(o1, o2[:, :N], atol=1e-13)
@@ -215,7 +215,7 @@ def test_blank_token_is_one_more_shared_neighbour():
     g2 = oracle.pla_bwd(q2, k2, v2, bias2, nbr2, dout2, SCALE)
     for n in ("dq", "dk", "dv"):
         np.testing.assert_allclose(g1[n], g2[n][:, :N], atol=1e-12)
-    np.testing.assert_allclose(g1["dbias"], g2["dbias"][:, :N, :K], atol=1e-13)
+    np.testing.assert_allclose(g1["dbias"], g2["dbias"][:, :N, :, :K], atol=1e-13)
     # with q = 0 and dout = 0 for the extra token, its row collects exactly the blank gradients
     np.testing.assert_allclose(g1["dk_blank"], g2["dk"][:, N].sum(axis=0), atol=1e-12)
     np.testing.assert_allclose(g1["dv_blank"], g2["dv"][:, N].sum(axis=0), atol=1e-12)

@@ -148,13 +148,13 @@ def make_coords(recipe: str, B: int, N: int, frame: float, rng: np.random.Genera
 
 def make_features(B: int, N: int, H: int, d: int, K: int, dtype: str,
                   rng: np.random.Generator, blank: bool = False) -> Dict[str, np.ndarray]:
-    """q,k,v,dout ~ N(0,1) [B,N,H,d]; bias ~ N(0, 0.1) [B,N,K,H]; all returned as
+    """q,k,v,dout ~ N(0,1) [B,N,H,d]; bias ~ N(0, 0.1) [B,N,H,K]; all returned as
     fp32 arrays whose values are exactly representable in `dtype`."""
     cast = bf16_round if dtype == "bf16" else (lambda a: np.ascontiguousarray(a, dtype=np.float32))
     out = {}
     for name in ("q", "k", "v", "dout"):
         out[name] = cast(rng.standard_normal((B, N, H, d), dtype=np.float32))
-    out["bias"] = cast((0.1 * rng.standard_normal((B, N, K, H), dtype=np.float32)).astype(np.float32))
+    out["bias"] = cast((0.1 * rng.standard_normal((B, N, H, K), dtype=np.float32)).astype(np.float32))
     if blank:
         out["k_blank"] = cast(rng.standard_normal((H, d), dtype=np.float32))
         out["v_blank"] = cast(rng.standard_normal((H, d), dtype=np.float32))
