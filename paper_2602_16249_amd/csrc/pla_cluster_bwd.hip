@@ -8,7 +8,7 @@
 //    scores, forms dP = V dO^T with MFMAs, dS = p (dP - D) with D = <dout, out>,
 //    accumulates dQ^T = K^T dS^T (K transposed by an MFMA against the identity),
 //    and leaves p and dS of the real (query, neighbour) pairs in compact
-//    [token, head, slot] arrays: dS is dbias, p goes to the workspace;
+//    [token, head, slot] arrays: dS is dbias, (p, dS) pairs go to the workspace;
 //
 //  key-stationary (one wave per tile of 16 tokens): walks the sorted list of
 //    strips that touch the tile, gathers their p and dS for the tile's tokens
@@ -36,8 +36,8 @@ struct BwdParams {
   uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
   float scale;
   bf16_t *dq, *dk, *dv;
-  bf16_t* ds;  // [B,N,H,K] dS: the caller's dbias, or workspace
-  bf16_t* pc;  // [B,N,H,K] p, workspace
+  bf16_t* ds;    // [B,N,H,K] dS = dbias, or nullptr when the caller does not want it
+  uint32_t* pd;  // [B,N,H,K] workspace: p in the low half, dS in the high half (bf16 bits)
 };
 
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
@@ -255,18 +255,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
       }
       wave_lds_sync();
     }
-    // compact arrays [token, head, slot]: whole 16-byte pieces when K is a multiple of 8
+    // compact arrays [token, head, slot]: dbias, and (p, dS) pairs for the key-stationary kernel;
+    // whole 16-byte pieces when K is a multiple of 8
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       if (item_live[t]) {
         if (VEC) {
-          *reinterpret_cast<uint4*>(p.ds + head_rows + item_off[t]) =
-              make_uint4(dacc[t][0], dacc[t][EW > 1 ? 1 : 0], dacc[t][EW > 2 ? 2 : 0], dacc[t][EW > 3 ? 3 : 0]);
-          *reinterpret_cast<uint4*>(p.pc + head_rows + item_off[t]) =
-              make_uint4(pacc[t][0], pacc[t][EW > 1 ? 1 : 0], pacc[t][EW > 2 ? 2 : 0], pacc[t][EW > 3 ? 3 : 0]);
+          if (p.ds)
+            *reinterpret_cast<uint4*>(p.ds + head_rows + item_off[t]) =
+                make_uint4(dacc[t][0], dacc[t][EW > 1 ? 1 : 0], dacc[t][EW > 2 ? 2 : 0], dacc[t][EW > 3 ? 3 : 0]);
+          uint32_t w[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            w[e] = ((pacc[t][(EW > 1 ? e >> 1 : 0)] >> (16 * (e & 1))) & 0xffffu) |
+                   ((dacc[t][(EW > 1 ? e >> 1 : 0)] >> (16 * (e & 1))) << 16);
+          uint4* dst = reinterpret_cast<uint4*>(p.pd + head_rows + item_off[t]);
+          dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+          dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
         } else {
-          p.ds[head_rows + item_off[t]] = (bf16_t)dacc[t][0];
-          p.pc[head_rows + item_off[t]] = (bf16_t)pacc[t][0];
+          if (p.ds) p.ds[head_rows + item_off[t]] = (bf16_t)dacc[t][0];
+          p.pd[head_rows + item_off[t]] = (pacc[t][0] & 0xffffu) | (dacc[t][0] << 16);
         }
       }
     }
@@ -284,8 +292,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 // key-stationary kernel
 struct KeyItem {
   Frag8 qf, gf;      // strip's q and dout rows: lane (query r, channels 8g..8g+7)
-  uint16_t pv[4];    // p[query 4g+i][token r] (bf16 bits, 0 where the query does not list the token)
-  uint16_t dsv[4];   // dS likewise
+  uint32_t pd[4];    // (p, dS)[query 4g+i][token r] as bf16 bits, 0 where the query does not list the token
 };
 
 template <int HG>  // heads handled per sweep over the tile's list
@@ -340,17 +347,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
           const uint32_t j = (jm >> (8 * i)) & 255u;
           const bool hit = j != 255u;
           const size_t idx = ((tokq0 + 4 * g + i) * p.H + h) * p.K + (hit ? j : 0u);
-          const uint16_t pvv = p.pc[idx], dvv = p.ds[idx];
-          it.pv[i] = hit ? pvv : (uint16_t)0;
-          it.dsv[i] = hit ? dvv : (uint16_t)0;
+          const uint32_t both = p.pd[idx];
+          it.pd[i] = hit ? both : 0u;
         }
       };
       auto compute = [&](const KeyItem& it, f32x4(&dkh)[2], f32x4(&dvh)[2]) {
         Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
-        pf.u[0] = (uint32_t)it.pv[0] | ((uint32_t)it.pv[1] << 16);
-        pf.u[1] = (uint32_t)it.pv[2] | ((uint32_t)it.pv[3] << 16);
-        df.u[0] = (uint32_t)it.dsv[0] | ((uint32_t)it.dsv[1] << 16);
-        df.u[1] = (uint32_t)it.dsv[2] | ((uint32_t)it.dsv[3] << 16);
+        pf.u[0] = (it.pd[0] & 0xffffu) | (it.pd[1] << 16);
+        pf.u[1] = (it.pd[2] & 0xffffu) | (it.pd[3] << 16);
+        df.u[0] = (it.pd[0] >> 16) | (it.pd[1] & 0xffff0000u);
+        df.u[1] = (it.pd[2] >> 16) | (it.pd[3] & 0xffff0000u);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
           const f32x4 z = {0.f, 0.f, 0.f, 0.f};
@@ -401,9 +407,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
 }  // namespace
 
-size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, bool need_ds) {
-  const size_t one = plan_align((size_t)B * N * K * H * sizeof(bf16_t));
-  return need_ds ? 2 * one : one;
+size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K) {
+  return plan_align((size_t)B * N * K * H * sizeof(uint32_t));
 }
 
 hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* workspace, hipStream_t stream) {
@@ -421,16 +426,14 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
   p.scale = a.scale;
   p.dq = (bf16_t*)a.dq; p.dk = (bf16_t*)a.dk; p.dv = (bf16_t*)a.dv;
-  char* ws = static_cast<char*>(workspace);
-  const size_t one = plan_align((size_t)a.B * a.N * a.K * a.H * sizeof(bf16_t));
-  p.pc = reinterpret_cast<bf16_t*>(ws);
-  p.ds = a.dbias ? (bf16_t*)a.dbias : reinterpret_cast<bf16_t*>(ws + one);
+  p.pd = static_cast<uint32_t*>(workspace);
+  p.ds = (bf16_t*)a.dbias;
 
   const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);  // multiple of 8 for the XCD-contiguous mapping
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0) &&
-                   reinterpret_cast<uintptr_t>(p.ds) % 16 == 0;
+                   (!p.ds || reinterpret_cast<uintptr_t>(p.ds) % 16 == 0);
 #define AFFMAE_BWDQ(NT, VEC) \
   AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (pla_bwd_query_kernel<NT, VEC>), grid, dim3(256), 0, stream, p)
   if (vec) {
