@@ -48,7 +48,7 @@ template <int NT, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
   __shared__ __align__(16) bf16_t scratch_all[4][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
   // Consecutive strips share K/V rows; workgroups are dealt round-robin to the 8 XCDs (one L2
   // each), so give every XCD a contiguous range of strips.
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
   // loads of one head: the Q^T operand (lane (query r, channels 8g..8g+7)) and the bias of the items
   auto load_head = [&](int h, Frag8& qf, uint32_t (&bw)[NT][EW]) {
-    qf.u4 = *reinterpret_cast<const uint4*>(p.q + (tok0 + r) * C + h * kD + g * 8);
+    qf.u4 = *reinterpret_cast<const uint4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(r * C + g * 8));
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       if (VEC) {
@@ -264,9 +264,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
       uint2 o;
       o.x = pack_bf16x2(acc[dt][0] * inv, acc[dt][1] * inv);
       o.y = pack_bf16x2(acc[dt][2] * inv, acc[dt][3] * inv);
-      *reinterpret_cast<uint2*>(p.out + (tok0 + r) * C + h * kD + dt * 16 + g * 4) = o;
+      *reinterpret_cast<uint2*>(p.out + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(r * C + dt * 16 + g * 4)) = o;
     }
-    if (g == 0) p.lse[(tok0 + r) * p.H + h] = m_fin + __logf(l_tot);
+    if (g == 0) (p.lse + (size_t)tok0 * p.H + h)[(uint32_t)(r * p.H)] = m_fin + __logf(l_tot);
   }
 }
 

@@ -43,7 +43,7 @@ constexpr int kJmatPass = 16;  // slots whose 16x16 slot-index tiles are assembl
 __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   __shared__ __align__(16) uint8_t jm_all[4][kJmatPass * 256];
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int sg = blockIdx.x * (blockDim.x / kWave) + wave;
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier below
   uint8_t* jm = jm_all[wave];
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(const int32_t* __restri
 // Every strip appends itself to the list of each token tile it touches.
 __global__ __launch_bounds__(256) void plan_fill_kernel(PlanParams p) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int sg = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int sg = blockIdx.x * (blockDim.x / kWave) + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (sg >= p.strips) return;
   const int b = sg / p.strips_per_image;
   const int strip_in_image = sg - b * p.strips_per_image;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanParams p) {
 // Sort every token tile's list ascending: rank by counting (lists are short).
 __global__ __launch_bounds__(256) void plan_sort_kernel(PlanParams p) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int kt = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int kt = blockIdx.x * (blockDim.x / kWave) + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (kt >= p.strips) return;
   const int lo = p.rev_offset[kt], n = p.rev_offset[kt + 1] - lo;
   uint32_t* list = p.rev_list + lo;
