@@ -65,7 +65,7 @@ __device__ __forceinline__ int xcd_contiguous_block() {
 // query-stationary kernel
 // Items per lane as in the forward kernel: NT chunks of 8 slots (K % 8 == 0) or NT single entries.
 template <int NT, bool VEC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pla_bwd_query_kernel(BwdParams p) {
+__device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
   const int lane = threadIdx.x & (kWave - 1);
@@ -288,6 +288,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   }
 }
 
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pla_bwd_query_kernel(BwdParams p) {
+  pla_bwd_query_body<NT, true>(p);
+}
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void pla_bwd_query_scalar_kernel(BwdParams p) {
+  pla_bwd_query_body<NT, false>(p);
+}
+
 // ------------------------------------------------------------------------------------------------
 // key-stationary kernel
 struct KeyItem {
@@ -434,16 +443,16 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0) &&
                    (!p.ds || reinterpret_cast<uintptr_t>(p.ds) % 16 == 0);
-#define AFFMAE_BWDQ(NT, VEC) \
-  AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (pla_bwd_query_kernel<NT, VEC>), grid, dim3(256), 0, stream, p)
+#define AFFMAE_BWDQ(KERNEL, NT) \
+  AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (KERNEL<NT>), grid, dim3(256), 0, stream, p)
   if (vec) {
-    if (2 * a.K <= kWave) AFFMAE_BWDQ(1, true); else AFFMAE_BWDQ(2, true);
+    if (2 * a.K <= kWave) AFFMAE_BWDQ(pla_bwd_query_kernel, 1); else AFFMAE_BWDQ(pla_bwd_query_kernel, 2);
   } else {
     const int ent = (16 * a.K + kWave - 1) / kWave;
-    if (ent <= 4) AFFMAE_BWDQ(4, false);
-    else if (ent <= 8) AFFMAE_BWDQ(8, false);
-    else if (ent <= 12) AFFMAE_BWDQ(12, false);
-    else AFFMAE_BWDQ(16, false);
+    if (ent <= 4) AFFMAE_BWDQ(pla_bwd_query_scalar_kernel, 4);
+    else if (ent <= 8) AFFMAE_BWDQ(pla_bwd_query_scalar_kernel, 8);
+    else if (ent <= 12) AFFMAE_BWDQ(pla_bwd_query_scalar_kernel, 12);
+    else AFFMAE_BWDQ(pla_bwd_query_scalar_kernel, 16);
   }
 #undef AFFMAE_BWDQ
   if (a.H % 2 == 0)

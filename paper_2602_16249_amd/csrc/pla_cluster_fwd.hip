@@ -45,7 +45,7 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
 // [token, head, :] hold the matching K values.  With K a multiple of 8 a lane owns NT chunks of 8
 // consecutive slots of one query (16-byte loads of entries and of bias); otherwise NT single entries.
 template <int NT, bool VEC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
+__device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   __shared__ __align__(16) bf16_t scratch_all[4][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
@@ -270,6 +270,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   }
 }
 
+// The 16-byte path keeps four waves per SIMD; the single-entry path (K not a multiple of 8) holds more
+// per-lane state and is built for two.
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
+  pla_fwd_cluster_body<NT, true>(p);
+}
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void pla_fwd_cluster_scalar_kernel(FwdParams p) {
+  pla_fwd_cluster_body<NT, false>(p);
+}
+
 }  // namespace
 
 bool pla_cluster_supported(const PlaArgs& a) {
@@ -299,16 +310,16 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
   const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);
-#define AFFMAE_FWD(NT, VEC) \
-  AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (pla_fwd_cluster_kernel<NT, VEC>), grid, dim3(256), 0, stream, p)
+#define AFFMAE_FWD(KERNEL, NT) \
+  AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT>), grid, dim3(256), 0, stream, p)
   if (vec) {
-    if (2 * a.K <= kWave) AFFMAE_FWD(1, true); else AFFMAE_FWD(2, true);
+    if (2 * a.K <= kWave) AFFMAE_FWD(pla_fwd_cluster_kernel, 1); else AFFMAE_FWD(pla_fwd_cluster_kernel, 2);
   } else {
     const int ent = (16 * a.K + kWave - 1) / kWave;
-    if (ent <= 4) AFFMAE_FWD(4, false);
-    else if (ent <= 8) AFFMAE_FWD(8, false);
-    else if (ent <= 12) AFFMAE_FWD(12, false);
-    else AFFMAE_FWD(16, false);
+    if (ent <= 4) AFFMAE_FWD(pla_fwd_cluster_scalar_kernel, 4);
+    else if (ent <= 8) AFFMAE_FWD(pla_fwd_cluster_scalar_kernel, 8);
+    else if (ent <= 12) AFFMAE_FWD(pla_fwd_cluster_scalar_kernel, 12);
+    else AFFMAE_FWD(pla_fwd_cluster_scalar_kernel, 16);
   }
 #undef AFFMAE_FWD
   return hipGetLastError();
