@@ -6,7 +6,7 @@
 // lies in one of its cluster's M near clusters (the table affmae_knn builds), bf16
 // storage, d = 32, S a multiple of 16.  Driven by the plan of pla_plan.hip.
 //
-// One wave per strip of 16 queries, no workgroup-level cooperation.  The strip's
+// One wave per (strip of 16 queries, head), no workgroup-level cooperation.  The strip's
 // neighbours live in a few token tiles (16 consecutive tokens each).  Per pair of
 // such tiles the scores of all 16 x 32 (query, token) pairs come from two MFMAs
 // whose operands are row-major 16-byte loads of K rows and of the strip's Q rows;
@@ -54,7 +54,10 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   // each), so give every XCD a contiguous range of strips.
   const int per_xcd = gridDim.x >> 3;
   const int blk = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  const int sg = blk * 4 + wave;
+  // one wave per (strip, head): the heads of a strip sit in neighbouring waves and share cache lines
+  const int unit = blk * 4 + wave;
+  const int sg = unit / p.H;
+  const int h = unit - sg * p.H;
   if (sg >= p.strips) return;  // wave-uniform; the kernel has no workgroup barrier
   bf16_t* scratch = scratch_all[wave];
   const int b = sg / p.strips_per_image;
@@ -122,18 +125,10 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       }
     }
   };
-  Frag8 qf_next;
-  uint32_t bw_next[NT][EW];
-  load_head(0, qf_next, bw_next);
-
-  for (int h = 0; h < p.H; ++h) {
-    Frag8 qf = qf_next;
+  {
+    Frag8 qf;
     uint32_t bw[NT][EW];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int e = 0; e < EW; ++e) bw[t][e] = bw_next[t][e];
-    if (h + 1 < p.H) load_head(h + 1, qf_next, bw_next);  // flies during this head's tiles
+    load_head(h, qf, bw);
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
@@ -308,7 +303,7 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
-  const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);
+  const dim3 grid((((long long)L.strips * a.H + 3) / 4 + 7) / 8 * 8);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);
 #define AFFMAE_FWD(KERNEL, NT) \
   AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT>), grid, dim3(256), 0, stream, p)
