@@ -37,7 +37,8 @@ struct BwdParams {
   float scale;
   bf16_t *dq, *dk, *dv;
   bf16_t* ds;    // [B,N,H,K] dS = dbias, or nullptr when the caller does not want it
-  uint32_t* pd;  // [B,N,H,K] workspace: p in the low half, dS in the high half (bf16 bits)
+  uint32_t* pd;  // workspace [B,N,H/PS,K,PS] with PS = 2 heads side by side when H is even, else 1;
+                 // one word per (token, head, slot): p in the low half, dS in the high half (bf16 bits)
 };
 
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
@@ -69,7 +70,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
   const int sg = xcd_contiguous_block() * 4 + wave;
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier in this kernel
@@ -87,6 +88,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   constexpr int EW = VEC ? 4 : 1;  // 32-bit words per item
   uint32_t ent[NT][EW];
   uint32_t item_off[NT];  // element offset of the item's first value within head 0's [token, head, :] rows
+  uint32_t pair_off[NT];  // the same within head pair 0's [token, pair, slot, 2] rows of the (p, dS) words
   bool item_live[NT];
   const int items = VEC ? 2 * K : 16 * K;
   const int chunks_per_query = K >> 3;
@@ -104,10 +106,12 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
       const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
       item_off[t] = (uint32_t)(qi * p.H * K + j0);
+      pair_off[t] = (uint32_t)(qi * p.H * K + 2 * j0);
     } else {
       ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
       const int qi = fast_div(ii, p.k_magic);
       item_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
+      pair_off[t] = (uint32_t)(qi * p.H * K + 2 * (ii - qi * K));
     }
   }
   const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
@@ -119,6 +123,8 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
   const size_t strip_rows = (size_t)tok0 * p.H * K;  // first element of the strip's [token, head, :] rows
 
+  const int PS = (p.H & 1) ? 1 : 2;  // heads stored side by side in the (p, dS) workspace
+  uint32_t keep[NT][VEC ? 8 : 1];    // the even head's words until the odd head is done
   for (int h = 0; h < p.H; ++h) {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
     const size_t qrow = (size_t)(tok0 + r) * C + h * kD + g * 8;
@@ -255,11 +261,13 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       }
       wave_lds_sync();
     }
-    // compact arrays [token, head, slot]: dbias, and (p, dS) pairs for the key-stationary kernel;
-    // whole 16-byte pieces when K is a multiple of 8
+    // compact arrays: dbias [token, head, slot], and the (p, dS) words for the key-stationary kernel
+    // (two heads side by side when H is even); whole 16-byte pieces when K is a multiple of 8
+    const bool pair_lo = PS == 2 && !(h & 1);  // first head of a pair: only remember the words
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       if (item_live[t]) {
+        uint32_t* pair_dst = p.pd + strip_rows + (size_t)(h >> 1) * K * 2 + pair_off[t];
         if (VEC) {
           if (p.ds)
             *reinterpret_cast<uint4*>(p.ds + head_rows + item_off[t]) =
@@ -269,12 +277,30 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
           for (int e = 0; e < 8; ++e)
             w[e] = ((pacc[t][(EW > 1 ? e >> 1 : 0)] >> (16 * (e & 1))) & 0xffffu) |
                    ((dacc[t][(EW > 1 ? e >> 1 : 0)] >> (16 * (e & 1))) << 16);
-          uint4* dst = reinterpret_cast<uint4*>(p.pd + head_rows + item_off[t]);
-          dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-          dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+          if (PS == 1) {
+            uint4* dst = reinterpret_cast<uint4*>(p.pd + head_rows + item_off[t]);
+            dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+          } else if (pair_lo) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) keep[t][VEC ? e : 0] = w[e];
+          } else {
+            uint4* dst = reinterpret_cast<uint4*>(pair_dst);
+            dst[0] = make_uint4(keep[t][0], w[0], keep[t][VEC ? 1 : 0], w[1]);
+            dst[1] = make_uint4(keep[t][VEC ? 2 : 0], w[2], keep[t][VEC ? 3 : 0], w[3]);
+            dst[2] = make_uint4(keep[t][VEC ? 4 : 0], w[4], keep[t][VEC ? 5 : 0], w[5]);
+            dst[3] = make_uint4(keep[t][VEC ? 6 : 0], w[6], keep[t][VEC ? 7 : 0], w[7]);
+          }
         } else {
           if (p.ds) p.ds[head_rows + item_off[t]] = (bf16_t)dacc[t][0];
-          p.pd[head_rows + item_off[t]] = (pacc[t][0] & 0xffffu) | (dacc[t][0] << 16);
+          const uint32_t w0 = (pacc[t][0] & 0xffffu) | (dacc[t][0] << 16);
+          if (PS == 1) {
+            p.pd[head_rows + item_off[t]] = w0;
+          } else if (pair_lo) {
+            keep[t][0] = w0;
+          } else {
+            *reinterpret_cast<uint2*>(pair_dst) = make_uint2(keep[t][0], w0);
+          }
         }
       }
     }
@@ -289,7 +315,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
 }
 
 template <int NT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pla_bwd_query_kernel(BwdParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) void pla_bwd_query_kernel(BwdParams p) {
   pla_bwd_query_body<NT, true>(p);
 }
 template <int NT>
@@ -299,25 +325,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 // ------------------------------------------------------------------------------------------------
 // key-stationary kernel
+template <int HG>
 struct KeyItem {
-  Frag8 qf, gf;      // strip's q and dout rows: lane (query r, channels 8g..8g+7)
-  uint32_t pd[4];    // (p, dS)[query 4g+i][token r] as bf16 bits, 0 where the query does not list the token
+  Frag8 qf[HG], gf[HG];  // strip's q and dout rows per head: lane (query r, channels 8g..8g+7)
+  uint32_t pd[4][HG];    // (p, dS)[query 4g+i][token r] per head, 0 where the query does not list the token
 };
 
-template <int HG>  // heads handled per sweep over the tile's list
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_bwd_key_kernel(BwdParams p) {
+// HG = heads handled per sweep over the tile's list (2 when H is even: their (p, dS) words sit side by
+// side, so one 8-byte gather serves both).
+template <int HG>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
   const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
   if (kt >= p.strips) return;
   const int b = kt / p.strips_per_image;
   const int C = p.H * kD;
+  const int K = p.K;
   const size_t strip_base = (size_t)b * p.strips_per_image;
-  const int lo = p.rev_offset[kt];
-  const int n = p.rev_offset[kt + 1] - lo;
+  const int lo = __builtin_amdgcn_readfirstlane(p.rev_offset[kt]);
+  const int n = __builtin_amdgcn_readfirstlane(p.rev_offset[kt + 1]) - lo;
   Frag8 idf[2];
   make_identity(idf, g, r);
+  // per-lane parts of the addresses (elements); the per-item parts are uniform and stay in SGPRs
+  const uint32_t q_lane = (uint32_t)(r * C + g * 8);
+  const uint32_t jm_lane = (uint32_t)(r * 16 + g * 4);
+  uint32_t pd_lane[4];  // word offset of query 4g+i's row within the strip's rows of one head group
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pd_lane[i] = (uint32_t)((4 * g + i) * (p.H / HG) * K * HG);
 
   for (int hg = 0; hg < p.H; hg += HG) {
     f32x4 dk[HG][2], dv[HG][2];
@@ -331,84 +367,93 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     for (int base = 0; base < n; base += kWave) {
       const int nb = min(kWave, n - base);
       const uint32_t mine = (lane < nb) ? p.rev_list[lo + base + lane] : 0u;
-      const int nw = nb * HG;  // work items: (incidence, head of the group)
-      auto item_strip = [&](int w, int& slot, int& h) -> size_t {
-        const int i = (HG == 2) ? (w >> 1) : w;
-        h = hg + ((HG == 2) ? (w & 1) : 0);
+      auto item_strip = [&](int i, int& slot) -> size_t {
         const uint32_t inc = __builtin_amdgcn_readlane(mine, i);
         slot = (int)(inc & 255u);
         return strip_base + (inc >> 8);
       };
-      auto fetch_jm = [&](int w) -> uint32_t {
-        int slot, h;
-        const size_t sgq = item_strip(w, slot, h);
-        return *reinterpret_cast<const uint32_t*>(p.jmat + (sgq * p.max_slots + slot) * 256 + r * 16 + g * 4);
+      auto fetch_jm = [&](int i) -> uint32_t {
+        int slot;
+        const size_t sgq = item_strip(i, slot);
+        const uint8_t* jb = p.jmat + (sgq * p.max_slots + slot) * 256;
+        return *reinterpret_cast<const uint32_t*>(jb + jm_lane);
       };
-      auto fetch_rest = [&](int w, uint32_t jm, KeyItem& it) {
-        int slot, h;
-        const size_t sgq = item_strip(w, slot, h);
-        const size_t tokq0 = sgq * 16;
-        const size_t qrow = (tokq0 + r) * C + h * kD + g * 8;
-        it.qf.u4 = *reinterpret_cast<const uint4*>(p.q + qrow);
-        it.gf.u4 = *reinterpret_cast<const uint4*>(p.dout + qrow);
+      auto fetch_rest = [&](int i, uint32_t jm, KeyItem<HG>& it) {
+        int slot;
+        const size_t sgq = item_strip(i, slot);
+        const size_t qbase = sgq * 16 * C + (size_t)(hg * kD);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const uint32_t j = (jm >> (8 * i)) & 255u;
+        for (int hh = 0; hh < HG; ++hh) {
+          it.qf[hh].u4 = *reinterpret_cast<const uint4*>(p.q + qbase + hh * kD + q_lane);
+          it.gf[hh].u4 = *reinterpret_cast<const uint4*>(p.dout + qbase + hh * kD + q_lane);
+        }
+        // words of the strip's rows for this head group: [token][group][slot][HG]
+        const uint32_t* pdb = p.pd + (sgq * 16 * (p.H / HG) + hg / HG) * (size_t)K * HG;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const uint32_t j = (jm >> (8 * i4)) & 255u;
           const bool hit = j != 255u;
-          const size_t idx = ((tokq0 + 4 * g + i) * p.H + h) * p.K + (hit ? j : 0u);
-          const uint32_t both = p.pd[idx];
-          it.pd[i] = hit ? both : 0u;
+          const uint32_t at = pd_lane[i4] + (hit ? j : 0u) * HG;
+          if (HG == 2) {
+            const uint2 both = *reinterpret_cast<const uint2*>(pdb + at);
+            it.pd[i4][0] = hit ? both.x : 0u;
+            it.pd[i4][HG - 1] = hit ? both.y : 0u;
+          } else {
+            const uint32_t one = pdb[at];
+            it.pd[i4][0] = hit ? one : 0u;
+          }
         }
       };
-      auto compute = [&](const KeyItem& it, f32x4(&dkh)[2], f32x4(&dvh)[2]) {
-        Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
-        pf.u[0] = (it.pd[0] & 0xffffu) | (it.pd[1] << 16);
-        pf.u[1] = (it.pd[2] & 0xffffu) | (it.pd[3] << 16);
-        df.u[0] = (it.pd[0] >> 16) | (it.pd[1] & 0xffff0000u);
-        df.u[1] = (it.pd[2] >> 16) | (it.pd[3] & 0xffff0000u);
+      auto compute = [&](const KeyItem<HG>& it) {
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-          const f32x4 cq = mfma32(it.qf, idf[dt], z);  // q[query 4g+i][channel 16dt + r]
-          const f32x4 cg = mfma32(it.gf, idf[dt], z);  // dout likewise
-          Frag4 qT, gT;  // operand A: lane (channel 16dt + r, queries 4g..4g+3)
-          qT.u[0] = pack_bf16x2(cq[0], cq[1]);
-          qT.u[1] = pack_bf16x2(cq[2], cq[3]);
-          gT.u[0] = pack_bf16x2(cg[0], cg[1]);
-          gT.u[1] = pack_bf16x2(cg[2], cg[3]);
-          dkh[dt] = mfma16(qT, df, dkh[dt]);  // dk^T[channel 16dt + 4g+i][token r]
-          dvh[dt] = mfma16(gT, pf, dvh[dt]);
+        for (int hh = 0; hh < HG; ++hh) {
+          Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
+          pf.u[0] = (it.pd[0][hh] & 0xffffu) | (it.pd[1][hh] << 16);
+          pf.u[1] = (it.pd[2][hh] & 0xffffu) | (it.pd[3][hh] << 16);
+          df.u[0] = (it.pd[0][hh] >> 16) | (it.pd[1][hh] & 0xffff0000u);
+          df.u[1] = (it.pd[2][hh] >> 16) | (it.pd[3][hh] & 0xffff0000u);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) {
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            const f32x4 cq = mfma32(it.qf[hh], idf[dt], z);  // q[query 4g+i][channel 16dt + r]
+            const f32x4 cg = mfma32(it.gf[hh], idf[dt], z);  // dout likewise
+            Frag4 qT, gT;  // operand A: lane (channel 16dt + r, queries 4g..4g+3)
+            qT.u[0] = pack_bf16x2(cq[0], cq[1]);
+            qT.u[1] = pack_bf16x2(cq[2], cq[3]);
+            gT.u[0] = pack_bf16x2(cg[0], cg[1]);
+            gT.u[1] = pack_bf16x2(cg[2], cg[3]);
+            dk[hh][dt] = mfma16(qT, df, dk[hh][dt]);  // dk^T[channel 16dt + 4g+i][token r]
+            dv[hh][dt] = mfma16(gT, pf, dv[hh][dt]);
+          }
         }
       };
-      KeyItem A, B;
-      uint32_t jm_a = fetch_jm(0), jm_b = (nw > 1) ? fetch_jm(1) : 0u;
+      KeyItem<HG> A, B;
+      uint32_t jm_a = fetch_jm(0), jm_b = (nb > 1) ? fetch_jm(1) : 0u;
       fetch_rest(0, jm_a, A);
-      for (int w = 0; w < nw; w += 2) {
-        if (w + 1 < nw) fetch_rest(w + 1, jm_b, B);
-        if (w + 2 < nw) jm_a = fetch_jm(w + 2);
-        compute(A, dk[0], dv[0]);
-        if (w + 1 < nw) {
-          if (w + 2 < nw) fetch_rest(w + 2, jm_a, A);
-          if (w + 3 < nw) jm_b = fetch_jm(w + 3);
-          compute(B, dk[HG - 1], dv[HG - 1]);
+      for (int i = 0; i < nb; i += 2) {
+        if (i + 1 < nb) fetch_rest(i + 1, jm_b, B);
+        if (i + 2 < nb) jm_a = fetch_jm(i + 2);
+        compute(A);
+        if (i + 1 < nb) {
+          if (i + 2 < nb) fetch_rest(i + 2, jm_a, A);
+          if (i + 3 < nb) jm_b = fetch_jm(i + 3);
+          compute(B);
         }
       }
     }
 #pragma unroll
     for (int hh = 0; hh < HG; ++hh) {
       const int h = hg + hh;
-      if (h < p.H) {
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          const size_t at = ((size_t)kt * 16 + r) * C + h * kD + dt * 16 + g * 4;
-          uint2 o;
-          o.x = pack_bf16x2(dk[hh][dt][0] * p.scale, dk[hh][dt][1] * p.scale);
-          o.y = pack_bf16x2(dk[hh][dt][2] * p.scale, dk[hh][dt][3] * p.scale);
-          *reinterpret_cast<uint2*>(p.dk + at) = o;
-          o.x = pack_bf16x2(dv[hh][dt][0], dv[hh][dt][1]);
-          o.y = pack_bf16x2(dv[hh][dt][2], dv[hh][dt][3]);
-          *reinterpret_cast<uint2*>(p.dv + at) = o;
-        }
+      for (int dt = 0; dt < 2; ++dt) {
+        const size_t at = ((size_t)kt * 16 + r) * C + h * kD + dt * 16 + g * 4;
+        uint2 o;
+        o.x = pack_bf16x2(dk[hh][dt][0] * p.scale, dk[hh][dt][1] * p.scale);
+        o.y = pack_bf16x2(dk[hh][dt][2] * p.scale, dk[hh][dt][3] * p.scale);
+        *reinterpret_cast<uint2*>(p.dk + at) = o;
+        o.x = pack_bf16x2(dv[hh][dt][0], dv[hh][dt][1]);
+        o.y = pack_bf16x2(dv[hh][dt][2], dv[hh][dt][3]);
+        *reinterpret_cast<uint2*>(p.dv + at) = o;
       }
     }
   }
