@@ -32,12 +32,6 @@ __device__ __forceinline__ key_t make_key(float d2, int idx) {
   return ((key_t)__float_as_uint(d2) << 32) | (key_t)(uint32_t)idx;
 }
 
-__device__ __forceinline__ key_t shfl_key_xor(key_t k, int mask) {
-  uint32_t lo = (uint32_t)k, hi = (uint32_t)(k >> 32);
-  lo = __shfl_xor(lo, mask);
-  hi = __shfl_xor(hi, mask);
-  return ((key_t)hi << 32) | lo;
-}
 __device__ __forceinline__ key_t shfl_key(key_t k, int src) {
   uint32_t lo = (uint32_t)k, hi = (uint32_t)(k >> 32);
   lo = __shfl(lo, src);
@@ -45,33 +39,67 @@ __device__ __forceinline__ key_t shfl_key(key_t k, int src) {
   return ((key_t)hi << 32) | lo;
 }
 
+// The key held by lane (lane ^ J), J a power of two, moved on the VALU: DPP lane
+// patterns inside a row of 16 lanes, the gfx950 row / half swaps across rows.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor_u32(uint32_t x, int lane) {
+  typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+  if constexpr (J == 1) {
+    return dpp_mov<0xB1>(x);  // quad_perm [1,0,3,2]
+  } else if constexpr (J == 2) {
+    return dpp_mov<0x4E>(x);  // quad_perm [2,3,0,1]
+  } else if constexpr (J == 4) {
+    return dpp_mov<0x1B>(dpp_mov<0x141>(x));  // reverse 8 lanes, then reverse each quad: i -> i ^ 7 ^ 3
+  } else if constexpr (J == 8) {
+    return dpp_mov<0x128>(x);  // rotate the row by 8
+  } else if constexpr (J == 16) {
+    const u32x2 t = __builtin_amdgcn_permlane16_swap(x, x, false, false);  // [0]: even rows doubled, [1]: odd rows
+    return (lane & 16) ? t[0] : t[1];
+  } else {
+    const u32x2 t = __builtin_amdgcn_permlane32_swap(x, x, false, false);  // [0]: low half doubled, [1]: high half
+    return (lane & 32) ? t[0] : t[1];
+  }
+}
+template <int J>
+__device__ __forceinline__ key_t lane_xor_key(key_t k, int lane) {
+  const uint32_t lo = lane_xor_u32<J>((uint32_t)k, lane);
+  const uint32_t hi = lane_xor_u32<J>((uint32_t)(k >> 32), lane);
+  return ((key_t)hi << 32) | lo;
+}
+
+// One compare-exchange step of a bitonic network: partner lane ^ J; the lane keeps
+// the smaller key when keep_min.
+template <int J>
+__device__ __forceinline__ key_t exchange(key_t key, int lane, bool keep_min) {
+  const key_t other = lane_xor_key<J>(key, lane);
+  return ((key < other) == keep_min) ? key : other;
+}
+template <int K2, int J>
+__device__ __forceinline__ key_t sort_stage(key_t key, int lane) {
+  // blocks of K2 lanes alternate ascending / descending; within a block the lower lane of a pair keeps the minimum
+  key = exchange<J>(key, lane, ((lane & K2) == 0) == ((lane & J) == 0));
+  if constexpr (J > 1) key = sort_stage<K2, J / 2>(key, lane);
+  return key;
+}
+
 // Sort one key per lane ascending across the 64 lanes of the wave.
 __device__ __forceinline__ key_t wave_sort(key_t key, int lane) {
-#pragma unroll
-  for (int k = 2; k <= kWave; k <<= 1) {
-#pragma unroll
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      key_t other = shfl_key_xor(key, j);
-      bool up = (lane & k) == 0;
-      bool lower = (lane & j) == 0;
-      key_t lo = key < other ? key : other;
-      key_t hi = key < other ? other : key;
-      key = (lower == up) ? lo : hi;
-    }
-  }
+  key = sort_stage<2, 1>(key, lane);
+  key = sort_stage<4, 2>(key, lane);
+  key = sort_stage<8, 4>(key, lane);
+  key = sort_stage<16, 8>(key, lane);
+  key = sort_stage<32, 16>(key, lane);
+  key = sort_stage<64, 32>(key, lane);  // lane & 64 == 0 everywhere: ascending
   return key;
 }
 
 // Input: bitonic across lanes.  Output: ascending across lanes.
 __device__ __forceinline__ key_t wave_bitonic_merge(key_t key, int lane) {
-#pragma unroll
-  for (int j = kWave / 2; j > 0; j >>= 1) {
-    key_t other = shfl_key_xor(key, j);
-    key_t lo = key < other ? key : other;
-    key_t hi = key < other ? other : key;
-    key = ((lane & j) == 0) ? lo : hi;
-  }
-  return key;
+  return sort_stage<64, 32>(key, lane);
 }
 
 // Keeps the 64 smallest keys seen so far, ascending across lanes.  `row` holds 64
@@ -159,12 +187,19 @@ __global__ __launch_bounds__(256) void near_kernel(const float* __restrict__ cen
 
 // One workgroup per cluster.  The coordinates and token ids of the M*S candidate
 // tokens are staged in LDS once; each wave then serves the cluster's tokens in
-// turn: 64 candidates at a time, one per lane, pushed into a running top-64.
-__global__ __launch_bounds__(256) void knn_kernel(const float* __restrict__ coords,
-                                                 const int32_t* __restrict__ members,
-                                                 const int32_t* __restrict__ near, int N, int S, int M, int K,
-                                                 int G, int32_t* __restrict__ nbr_idx) {
+// turn.  The first 64 candidates (the nearest cluster's) are sorted to give a
+// first bound on the K-th key; later candidates are compared against the
+// current bound, 64 at a time, and only those below it are queued (compacted in
+// a per-wave LDS buffer).  Whenever 64 are queued they are merged into the
+// running top-64, which tightens the bound for what follows.  A candidate is
+// dropped only when K smaller keys are already known, so the result is exact.
+constexpr int kKnnWaves = 4;
+__global__ __launch_bounds__(kKnnWaves* kWave) void knn_kernel(const float* __restrict__ coords,
+                                                              const int32_t* __restrict__ members,
+                                                              const int32_t* __restrict__ near, int N, int S, int M,
+                                                              int K, int G, int32_t* __restrict__ nbr_idx) {
   extern __shared__ float4 cand[];  // x, y, token id (bits), unused
+  __shared__ key_t pend_all[kKnnWaves][2 * kWave];
   const int b = blockIdx.x / G, c = blockIdx.x % G;
   const int Cn = M * S;
   const float* xy = coords + (size_t)b * N * 2;
@@ -179,20 +214,175 @@ __global__ __launch_bounds__(256) void knn_kernel(const float* __restrict__ coor
   }
   __syncthreads();
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave, nwaves = blockDim.x / kWave;
-  for (int r = wave; r < S; r += nwaves) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  key_t* pend = pend_all[wave];
+  auto cand_key = [&](int p, float qx, float qy) -> key_t {
+    if (p >= Cn) return kKeyMax;
+    const float4 cp = cand[p];
+    return make_key(dist2(qx, qy, cp.x, cp.y), __float_as_int(cp.z));
+  };
+  for (int r = wave; r < S; r += kKnnWaves) {
     int qtok = c * S + r;
     if (mem) qtok = min(max(mem[qtok], 0), N - 1);
     const float qx = xy[2 * (size_t)qtok], qy = xy[2 * (size_t)qtok + 1];
-    key_t best = kKeyMax;
-    for (int base = 0; base < Cn; base += kWave) {
-      const int p = base + lane;
-      key_t key = kKeyMax;
-      if (p < Cn) {
-        const float4 cp = cand[p];
-        key = make_key(dist2(qx, qy, cp.x, cp.y), __float_as_int(cp.z));
+    key_t best = wave_sort(cand_key(lane, qx, qy), lane);
+    key_t bound = shfl_key(best, K - 1);
+    int fill = 0;  // queued keys, wave-uniform, always < 64 between rows
+    for (int base = kWave; base < Cn; base += kWave) {
+      const key_t key = cand_key(base + lane, qx, qy);
+      const bool in = key < bound;
+      const unsigned long long mask = __ballot(in);
+      if (mask == 0ull) continue;  // wave-uniform
+      const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+      if (in) pend[fill + rank] = key;
+      fill += __popcll(mask);
+      if (fill >= kWave) {
+        wave_lds_sync();
+        const key_t row = pend[lane];
+        const key_t rest = pend[kWave + lane];
+        wave_lds_sync();
+        fill -= kWave;
+        if (lane < fill) pend[lane] = rest;
+        best = topk_push(best, row, lane, K - 1);
+        bound = shfl_key(best, K - 1);
       }
-      best = topk_push(best, key, lane, K - 1);
+    }
+    if (fill > 0) {
+      wave_lds_sync();
+      const key_t row = (lane < fill) ? pend[lane] : kKeyMax;
+      best = topk_push(best, row, lane, K - 1);
+    }
+    wave_lds_sync();  // the next token's queue starts after this one's reads
+    if (lane < K) nbr_idx[((size_t)b * N + qtok) * K + lane] = (int32_t)(uint32_t)best;
+  }
+}
+
+// At most 512 candidates: each lane keeps its 8 candidates in registers for all of the
+// cluster's tokens.  Per token the wave looks for a distance threshold T with
+// K <= #{candidates with d2 <= T} <= 64 by counting (ballots), starting from the previous
+// token's threshold and scaling it by the ratio of the wanted to the found count (the count grows
+// like the area, i.e. like d2), then by bisection on the bit pattern.  Everything at or below T is
+// closer than everything above it, so the K nearest are among the counted candidates: they are
+// compacted into one row and sorted once by (d2, index).  When no such T exists (more than
+// 64 - K + 1 candidates at one distance) the token takes the queue-and-merge route of the
+// general kernel.  Either way the result is the exact, unique answer.
+constexpr int kFastRows = 8;
+__global__ __launch_bounds__(kKnnWaves* kWave) void knn_fast_kernel(const float* __restrict__ coords,
+                                                                   const int32_t* __restrict__ members,
+                                                                   const int32_t* __restrict__ near, int N, int S,
+                                                                   int M, int K, int G,
+                                                                   int32_t* __restrict__ nbr_idx) {
+  __shared__ key_t pend_all[kKnnWaves][2 * kWave];
+  const int b = blockIdx.x / G, c = blockIdx.x % G;
+  const int Cn = M * S;
+  const float* xy = coords + (size_t)b * N * 2;
+  const int32_t* mem = members ? members + (size_t)b * N : nullptr;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  key_t* pend = pend_all[wave];
+  float cx[kFastRows], cy[kFastRows];
+  uint32_t cid[kFastRows];
+  bool cok[kFastRows];
+#pragma unroll
+  for (int row = 0; row < kFastRows; ++row) {
+    const int p = row * kWave + lane;
+    cok[row] = p < Cn;
+    const int pp = cok[row] ? p : 0;
+    const int m = pp / S, r = pp - m * S;
+    int e = near[((size_t)b * G + c) * M + m];
+    e = min(max(e, 0), G - 1);
+    int tok = e * S + r;
+    if (mem) tok = min(max(mem[tok], 0), N - 1);
+    cx[row] = xy[2 * (size_t)tok];
+    cy[row] = xy[2 * (size_t)tok + 1];
+    cid[row] = (uint32_t)tok;
+  }
+  const uint32_t kInfBits = 0x7f800000u;
+  uint32_t guess = 0u;  // threshold that worked for the previous token (0: none yet)
+  for (int r = wave; r < S; r += kKnnWaves) {
+    int qtok = c * S + r;
+    if (mem) qtok = min(max(mem[qtok], 0), N - 1);
+    const float qx = xy[2 * (size_t)qtok], qy = xy[2 * (size_t)qtok + 1];
+    uint32_t d2[kFastRows];  // bit pattern of the squared distance: ordered like the value (d2 >= +0)
+#pragma unroll
+    for (int row = 0; row < kFastRows; ++row)
+      d2[row] = cok[row] ? __float_as_uint(dist2(qx, qy, cx[row], cy[row])) : 0xffffffffu;
+    auto count_le = [&](uint32_t t) -> int {
+      int n = 0;
+#pragma unroll
+      for (int row = 0; row < kFastRows; ++row) n += __popcll(__ballot(d2[row] <= t));
+      return n;
+    };
+    // invariant: count(lo) < K (lo = -1: nothing known), count(hi) > 64 or hi = +inf bits
+    long long lo = -1, hi = (long long)kInfBits;
+    uint32_t t = guess;
+    if (t == 0u) {  // first token of the wave: the farthest of the first 64 candidates, so the count is not 0
+      t = min(d2[0], kInfBits);
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) t = max(t, (uint32_t)__shfl_xor((int)t, o));
+      t = __builtin_amdgcn_readfirstlane(t);
+    }
+    bool found = false;
+    for (int it = 0; it < 48; ++it) {
+      const int n = count_le(t);
+      if (n >= K && n <= kWave) { found = true; break; }
+      if (n < K) lo = t; else hi = t;
+      if (hi - lo <= 1) break;  // neighbouring bit patterns straddle the window
+      long long next = -1;
+      if (it < 4 && n > 0) {
+        const float scaled = __uint_as_float(t) * ((float)(K + kWave) * 0.5f / (float)n);
+        next = (long long)__float_as_uint(scaled);
+      }
+      if (next <= lo || next >= hi) next = lo + (hi - lo) / 2;
+      t = (uint32_t)next;
+    }
+    key_t best;
+    if (found) {
+      guess = t;
+      int fill = 0;
+#pragma unroll
+      for (int row = 0; row < kFastRows; ++row) {
+        const bool in = d2[row] <= t;
+        const unsigned long long mask = __ballot(in);
+        const int rank =
+            __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (in) pend[fill + rank] = ((key_t)d2[row] << 32) | cid[row];
+        fill += __popcll(mask);
+      }
+      wave_lds_sync();
+      best = wave_sort((lane < fill) ? pend[lane] : kKeyMax, lane);
+      wave_lds_sync();
+    } else {
+      best = wave_sort(((key_t)d2[0] << 32) | (cok[0] ? cid[0] : 0xffffffffu), lane);
+      key_t bound = shfl_key(best, K - 1);
+      int fill = 0;
+#pragma unroll
+      for (int row = 1; row < kFastRows; ++row) {
+        const key_t key = ((key_t)d2[row] << 32) | (cok[row] ? cid[row] : 0xffffffffu);
+        const bool in = key < bound;
+        const unsigned long long mask = __ballot(in);
+        if (mask != 0ull) {
+          const int rank =
+              __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+          if (in) pend[fill + rank] = key;
+          fill += __popcll(mask);
+          if (fill >= kWave) {
+            wave_lds_sync();
+            const key_t full = pend[lane];
+            const key_t rest = pend[kWave + lane];
+            wave_lds_sync();
+            fill -= kWave;
+            if (lane < fill) pend[lane] = rest;
+            best = topk_push(best, full, lane, K - 1);
+            bound = shfl_key(best, K - 1);
+          }
+        }
+      }
+      if (fill > 0) {
+        wave_lds_sync();
+        best = topk_push(best, (lane < fill) ? pend[lane] : kKeyMax, lane, K - 1);
+      }
+      wave_lds_sync();
     }
     if (lane < K) nbr_idx[((size_t)b * N + qtok) * K + lane] = (int32_t)(uint32_t)best;
   }
@@ -211,9 +401,14 @@ hipError_t launch_knn(const KnnArgs& a, hipStream_t stream) {
                      a.S, a.G, a.centroid);
   AFFMAE_LAUNCH("near_kernel", stream, near_kernel, dim3((BG + 3) / 4), dim3(256), 0, stream, a.centroid, a.B, a.G, a.M,
                      a.near_clusters);
-  const size_t lds = (size_t)a.M * a.S * sizeof(float4);
-  AFFMAE_LAUNCH("knn_kernel", stream, knn_kernel, dim3(BG), dim3(256), lds, stream, a.coords, members, a.near_clusters, a.N, a.S,
-                     a.M, a.K, a.G, a.nbr_idx);
+  if (a.M * a.S <= kFastRows * kWave) {
+    AFFMAE_LAUNCH("knn_kernel", stream, knn_fast_kernel, dim3(BG), dim3(kKnnWaves * kWave), 0, stream, a.coords, members,
+                  a.near_clusters, a.N, a.S, a.M, a.K, a.G, a.nbr_idx);
+  } else {
+    const size_t lds = (size_t)a.M * a.S * sizeof(float4);
+    AFFMAE_LAUNCH("knn_kernel", stream, knn_kernel, dim3(BG), dim3(kKnnWaves * kWave), lds, stream, a.coords, members,
+                  a.near_clusters, a.N, a.S, a.M, a.K, a.G, a.nbr_idx);
+  }
   return hipGetLastError();
 }
 

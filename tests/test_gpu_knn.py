@@ -30,6 +30,8 @@ SMALL = [
     ("knn_scale", 2, 2048, 64, 8, 64),         # K at the limit
     ("knn_scale", 2, 512, 8, 3, 1),            # K = 1: every token is its own nearest
     ("knn_scale", 1, 640, 10, 64, 64),         # M at the limit, odd S
+    ("knn_scale", 1, 4096, 64, 64, 64),        # the most candidates the library takes (4096)
+    ("tiny_f32", 2, 1024, 128, 8, 48),         # 1024 candidates: the general kernel
 ]
 
 
@@ -62,6 +64,17 @@ def test_knn_coincident_points_and_integer_grid():
     rng = np.random.default_rng(6)
     B, N, S, M, K = 1, 512, 32, 16, 48
     coords = rng.integers(0, 5, size=(B, N, 2)).astype(np.float32)
+    nbr, near = _gpu_knn(coords, None, S, M, K)
+    rnbr, rnear = oracle.knn(coords, None, S, M, K)
+    assert np.array_equal(near, rnear)
+    assert np.array_equal(nbr, rnbr)
+
+
+@pytest.mark.parametrize("S,M,K", [(64, 8, 48), (64, 8, 64), (16, 4, 1), (128, 8, 48)])
+def test_knn_all_points_identical(S, M, K):
+    """Every distance is 0: no distance threshold separates K candidates, the index decides everything."""
+    B, N = 2, 1024
+    coords = np.full((B, N, 2), 3.25, dtype=np.float32)
     nbr, near = _gpu_knn(coords, None, S, M, K)
     rnbr, rnear = oracle.knn(coords, None, S, M, K)
     assert np.array_equal(near, rnear)
