@@ -328,7 +328,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 template <int HG>
 struct KeyItem {
   Frag8 qf[HG], gf[HG];  // strip's q and dout rows per head: lane (query r, channels 8g..8g+7)
-  uint32_t pd[4][HG];    // (p, dS)[query 4g+i][token r] per head, 0 where the query does not list the token
+  uint32_t pd[4][HG];    // gathered (p, dS)[query 4g+i][token r] per head (slot 0's where the query does not list the token)
+  uint32_t jm;           // the four slot indices that were gathered, 255 = the query does not list the token
 };
 
 // HG = heads handled per sweep over the tile's list (2 when H is even: their (p, dS) words sit side by
@@ -378,6 +379,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         const uint8_t* jb = p.jmat + (sgq * p.max_slots + slot) * 256;
         return *reinterpret_cast<const uint32_t*>(jb + jm_lane);
       };
+      // all loads of one item, nothing else: what is done with the words waits until compute(), so that
+      // no use of a loaded value sits between the loads of one item and the math of the previous one
       auto fetch_rest = [&](int i, uint32_t jm, KeyItem<HG>& it) {
         int slot;
         const size_t sgq = item_strip(i, slot);
@@ -389,29 +392,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         }
         // words of the strip's rows for this head group: [token][group][slot][HG]
         const uint32_t* pdb = p.pd + (sgq * 16 * (p.H / HG) + hg / HG) * (size_t)K * HG;
+        it.jm = jm;
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
           const uint32_t j = (jm >> (8 * i4)) & 255u;
-          const bool hit = j != 255u;
-          const uint32_t at = pd_lane[i4] + (hit ? j : 0u) * HG;
+          const uint32_t at = pd_lane[i4] + (j != 255u ? j : 0u) * HG;
           if (HG == 2) {
             const uint2 both = *reinterpret_cast<const uint2*>(pdb + at);
-            it.pd[i4][0] = hit ? both.x : 0u;
-            it.pd[i4][HG - 1] = hit ? both.y : 0u;
+            it.pd[i4][0] = both.x;
+            it.pd[i4][HG - 1] = both.y;
           } else {
-            const uint32_t one = pdb[at];
-            it.pd[i4][0] = hit ? one : 0u;
+            it.pd[i4][0] = pdb[at];
           }
         }
       };
       auto compute = [&](const KeyItem<HG>& it) {
+        uint32_t keep[4];  // all ones where the query lists the token
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) keep[i4] = (((it.jm >> (8 * i4)) & 255u) != 255u) ? 0xffffffffu : 0u;
 #pragma unroll
         for (int hh = 0; hh < HG; ++hh) {
+          const uint32_t w0 = it.pd[0][hh] & keep[0], w1 = it.pd[1][hh] & keep[1];
+          const uint32_t w2 = it.pd[2][hh] & keep[2], w3 = it.pd[3][hh] & keep[3];
           Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
-          pf.u[0] = (it.pd[0][hh] & 0xffffu) | (it.pd[1][hh] << 16);
-          pf.u[1] = (it.pd[2][hh] & 0xffffu) | (it.pd[3][hh] << 16);
-          df.u[0] = (it.pd[0][hh] >> 16) | (it.pd[1][hh] & 0xffff0000u);
-          df.u[1] = (it.pd[2][hh] >> 16) | (it.pd[3][hh] & 0xffff0000u);
+          pf.u[0] = (w0 & 0xffffu) | (w1 << 16);
+          pf.u[1] = (w2 & 0xffffu) | (w3 << 16);
+          df.u[0] = (w0 >> 16) | (w1 & 0xffff0000u);
+          df.u[1] = (w2 >> 16) | (w3 & 0xffff0000u);
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt) {
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
@@ -427,18 +434,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
           }
         }
       };
+      // Two items in flight, the slot-index words one item further ahead.  Every load is issued
+      // unconditionally in straight-line code (indices past the end repeat the last item): a load under
+      // a condition makes the compiler wait for all outstanding loads where the paths join.
       KeyItem<HG> A, B;
-      uint32_t jm_a = fetch_jm(0), jm_b = (nb > 1) ? fetch_jm(1) : 0u;
+      uint32_t jm_a = fetch_jm(0), jm_b = fetch_jm(min(1, nb - 1));
       fetch_rest(0, jm_a, A);
-      for (int i = 0; i < nb; i += 2) {
-        if (i + 1 < nb) fetch_rest(i + 1, jm_b, B);
-        if (i + 2 < nb) jm_a = fetch_jm(i + 2);
+      int i = 0;
+      for (; i + 2 < nb; i += 2) {
+        fetch_rest(i + 1, jm_b, B);
+        jm_a = fetch_jm(i + 2);
         compute(A);
-        if (i + 1 < nb) {
-          if (i + 2 < nb) fetch_rest(i + 2, jm_a, A);
-          if (i + 3 < nb) jm_b = fetch_jm(i + 3);
-          compute(B);
-        }
+        fetch_rest(i + 2, jm_a, A);
+        jm_b = fetch_jm(min(i + 3, nb - 1));
+        compute(B);
+      }
+      if (i + 1 < nb) {
+        fetch_rest(i + 1, jm_b, B);
+        compute(A);
+        compute(B);
+      } else {
+        compute(A);
       }
     }
 #pragma unroll

@@ -44,9 +44,10 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
 // Per strip the plan holds 16*K entries, one per (query, neighbour slot), query-major; bias rows
 // [token, head, :] hold the matching K values.  With K a multiple of 8 a lane owns NT chunks of 8
 // consecutive slots of one query (16-byte loads of entries and of bias); otherwise NT single entries.
+constexpr int kFwdWaves = 4;  // waves per workgroup; they share nothing but the launch
 template <int NT, bool VEC>
 __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
-  __shared__ __align__(16) bf16_t scratch_all[4][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
+  __shared__ __align__(16) bf16_t scratch_all[kFwdWaves][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
@@ -55,7 +56,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   const int per_xcd = gridDim.x >> 3;
   const int blk = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   // one wave per (strip, head): the heads of a strip sit in neighbouring waves and share cache lines
-  const int unit = blk * 4 + wave;
+  const int unit = blk * kFwdWaves + wave;
   const int sg = unit / p.H;
   const int h = unit - sg * p.H;
   if (sg >= p.strips) return;  // wave-uniform; the kernel has no workgroup barrier
@@ -95,7 +96,6 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       bias_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
     }
   }
-  const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
   Frag8 idf[2];  // identity operand, one per 16-channel half: lane (column r, rows 8g..8g+7)
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
@@ -129,6 +129,8 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
     Frag8 qf;
     uint32_t bw[NT][EW];
     load_head(h, qf, bw);
+    // first use of a loaded value: everything the strip streams in is in flight by now
+    const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
@@ -164,22 +166,20 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         }
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
+        // a pass with an odd number of tiles repeats its last tile in the second half of the last pair;
+        // those scores are masked.  No branch here: the whole pair is one basic block.
         const bool has1 = 2 * pr + 1 < nsl;
         float s[8];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-          if (tt == 0 || has1) {
-            f32x4 st = {0.f, 0.f, 0.f, 0.f};
-            st = mfma32(kf[tt], qf, st);  // st[i] = <k[token 4g+i], q[query r]>
-            const uint2 bm = *reinterpret_cast<const uint2*>(scratch + (2 * pr + tt) * 256 + r * 16 + g * 4);
-            s[4 * tt + 0] = fmaf(st[0], p.scale, __uint_as_float(bm.x << 16));
-            s[4 * tt + 1] = fmaf(st[1], p.scale, __uint_as_float(bm.x & 0xffff0000u));
-            s[4 * tt + 2] = fmaf(st[2], p.scale, __uint_as_float(bm.y << 16));
-            s[4 * tt + 3] = fmaf(st[3], p.scale, __uint_as_float(bm.y & 0xffff0000u));
-          } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) s[4 * tt + i] = -INFINITY;
-          }
+          f32x4 st = {0.f, 0.f, 0.f, 0.f};
+          st = mfma32(kf[tt], qf, st);  // st[i] = <k[token 4g+i], q[query r]>
+          const uint2 bm = *reinterpret_cast<const uint2*>(scratch + (2 * pr + tt) * 256 + r * 16 + g * 4);
+          const bool on = tt == 0 || has1;
+          s[4 * tt + 0] = on ? fmaf(st[0], p.scale, __uint_as_float(bm.x << 16)) : -INFINITY;
+          s[4 * tt + 1] = on ? fmaf(st[1], p.scale, __uint_as_float(bm.x & 0xffff0000u)) : -INFINITY;
+          s[4 * tt + 2] = on ? fmaf(st[2], p.scale, __uint_as_float(bm.y << 16)) : -INFINITY;
+          s[4 * tt + 3] = on ? fmaf(st[3], p.scale, __uint_as_float(bm.y & 0xffff0000u)) : -INFINITY;
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
         mx = group_max(mx);
@@ -217,16 +217,24 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
           acc[dt] = mfma32(vt, pf, acc[dt]);
         }
       };
-      // two register sets in turn, so that the loads of the next pair fly during this pair's math
+      // Two register sets in turn, so that the loads of the next pair fly during this pair's math.  Every
+      // load sits in straight-line code between the computations: a load under a condition would make the
+      // compiler wait for all outstanding loads where the paths join, which undoes the overlap.
       Frag8 kA[2], vA[2], kB[2], vB[2];
       load_pair(0, kA, vA);
-      for (int pr = 0; pr < npairs; pr += 2) {
-        if (pr + 1 < npairs) load_pair(pr + 1, kB, vB);
+      int pr = 0;
+      for (; pr + 2 < npairs; pr += 2) {
+        load_pair(pr + 1, kB, vB);
         compute_pair(pr, kA, vA);
-        if (pr + 1 < npairs) {
-          if (pr + 2 < npairs) load_pair(pr + 2, kA, vA);
-          compute_pair(pr + 1, kB, vB);
-        }
+        load_pair(pr + 2, kA, vA);
+        compute_pair(pr + 1, kB, vB);
+      }
+      if (pr + 1 < npairs) {
+        load_pair(pr + 1, kB, vB);
+        compute_pair(pr, kA, vA);
+        compute_pair(pr + 1, kB, vB);
+      } else {
+        compute_pair(pr, kA, vA);
       }
       wave_lds_sync();  // the next pass overwrites the bias tile
     }
@@ -268,11 +276,11 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
 // The 16-byte path keeps four waves per SIMD; the single-entry path (K not a multiple of 8) holds more
 // per-lane state and is built for two.
 template <int NT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
+__global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
   pla_fwd_cluster_body<NT, true>(p);
 }
 template <int NT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void pla_fwd_cluster_scalar_kernel(FwdParams p) {
+__global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void pla_fwd_cluster_scalar_kernel(FwdParams p) {
   pla_fwd_cluster_body<NT, false>(p);
 }
 
@@ -303,10 +311,10 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
-  const dim3 grid((((long long)L.strips * a.H + 3) / 4 + 7) / 8 * 8);
+  const dim3 grid((((long long)L.strips * a.H + kFwdWaves - 1) / kFwdWaves + 7) / 8 * 8);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);
 #define AFFMAE_FWD(KERNEL, NT) \
-  AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT>), grid, dim3(256), 0, stream, p)
+  AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT>), grid, dim3(kFwdWaves * kWave), 0, stream, p)
   if (vec) {
     if (2 * a.K <= kWave) AFFMAE_FWD(pla_fwd_cluster_kernel, 1); else AFFMAE_FWD(pla_fwd_cluster_kernel, 2);
   } else {
