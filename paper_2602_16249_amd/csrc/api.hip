@@ -162,7 +162,7 @@ size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, 
   const size_t gather = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
   size_t tiled = 0;
   if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && N % S == 0 && tiled_shape_ok(B, N, K, S, M))
-    tiled = align_up(affmae::pla_plan_bytes(B, N, K, S, M)) + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K);
+    tiled = align_up(affmae::pla_plan_bytes(B, N, K, S, M)) + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, S, M);
   return gather > tiled ? gather : tiled;  // blank tokens send a clustered call to the gather kernels
 }
 
@@ -198,7 +198,7 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
     if (misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
     if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
     const size_t plan_bytes = plan ? 0 : align_up(affmae::pla_plan_bytes(B, N, K, S, M));
-    const size_t need = plan_bytes + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K);
+    const size_t need = plan_bytes + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, S, M);
     if (!workspace || workspace_bytes < need) return AFFMAE_ERR_WORKSPACE;
     char* ws = static_cast<char*>(workspace);
     if (!plan) {

@@ -39,21 +39,26 @@ union Frag4 {
 };
 
 // Layout of the plan buffer.  "Incidence" = (strip, slot): a strip and one of the token tiles it touches.
-// The reverse tables list, per token tile, the incidences that touch it (sorted, so that sums formed
-// along a list do not depend on scheduling); jmat gives, per incidence, for every (token of the tile,
-// query of the strip) the neighbour slot j under which the query lists that token, or 0xff.
+// Per strip the valid entries are also listed grouped by slot ("runs", ascending entry index inside a
+// run): sorted_pos holds the entry values in that order and runs[s] the start of slot s's run, so the
+// (p, dS) words that the backward pass leaves in run order can be read back per incidence as one
+// contiguous piece.  The reverse tables list, per token tile, the incidences that touch it (sorted, so
+// that sums formed along a list do not depend on scheduling), each with the place of its run.
 struct PlanLayout {
   int strips;        // B * N / 16 (also the number of token tiles)
   int max_slots;     // M * S / 16
   int slot_stride;   // uint16 per strip in the slot table: [0] = count, [1 + s] = token tile of slot s
+  int runs_stride;   // uint16 per strip in the run table: [s] = first place of slot s, [count] = places used
+  int places;        // places per strip in run order: 16 * K entries + room to start every run at an even place
   int K;
   size_t slots_off;       // uint16 [strips][slot_stride]
   size_t entries_off;     // uint16 [strips][16 * K]
+  size_t sorted_pos_off;  // uint16 [strips][places]   entry values grouped by slot; kNoEntry in unused places
+  size_t runs_off;        // uint16 [strips][runs_stride]
   size_t rev_count_off;   // int32  [strips]      incidences per token tile
   size_t rev_offset_off;  // int32  [strips + 1]  exclusive prefix sum of rev_count
   size_t rev_cursor_off;  // int32  [strips]      build-time cursors
-  size_t rev_list_off;    // uint32 [strips * max_slots]  (strip within image) << 8 | slot
-  size_t jmat_off;        // uint8  [strips][max_slots][16 tokens][16 queries]
+  size_t rev_list_off;    // uint64 [strips * max_slots]  low: (strip within image) << 8 | slot; high: run start | run length << 16
   size_t total;
 };
 
@@ -72,6 +77,12 @@ inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   off += plan_align((size_t)L.strips * L.slot_stride * sizeof(uint16_t));
   L.entries_off = off;
   off += plan_align((size_t)L.strips * 16 * K * sizeof(uint16_t));
+  L.places = 16 * K + max_slots + (max_slots & 1);  // even
+  L.sorted_pos_off = off;
+  off += plan_align((size_t)L.strips * L.places * sizeof(uint16_t));
+  L.runs_stride = max_slots + 2 + (max_slots & 1);
+  L.runs_off = off;
+  off += plan_align((size_t)L.strips * L.runs_stride * sizeof(uint16_t));
   L.rev_count_off = off;
   off += plan_align((size_t)L.strips * sizeof(int32_t));
   L.rev_offset_off = off;
@@ -79,9 +90,7 @@ inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   L.rev_cursor_off = off;
   off += plan_align((size_t)L.strips * sizeof(int32_t));
   L.rev_list_off = off;
-  off += plan_align((size_t)L.strips * max_slots * sizeof(uint32_t));
-  L.jmat_off = off;
-  off += plan_align((size_t)L.strips * max_slots * 256);
+  off += plan_align((size_t)L.strips * max_slots * sizeof(uint64_t));
   L.total = off;
   return L;
 }

@@ -47,7 +47,7 @@ size_t pla_plan_bytes(int B, int N, int K, int S, int M);
 hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, int N, int K, int S, int M, void* plan,
                            hipStream_t stream);
 hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_t stream);
-size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K);
+size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, int S, int M);
 hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* workspace, hipStream_t stream);
 
 }  // namespace affmae

@@ -7,12 +7,13 @@
 //    probabilities p from lse tile by tile exactly as the forward pass forms the
 //    scores, forms dP = V dO^T with MFMAs, dS = p (dP - D) with D = <dout, out>,
 //    accumulates dQ^T = K^T dS^T (K transposed by an MFMA against the identity),
-//    and leaves p and dS of the real (query, neighbour) pairs in compact
-//    [token, head, slot] arrays: dS is dbias, (p, dS) pairs go to the workspace;
+//    and leaves p and dS of the real (query, neighbour) pairs in compact arrays:
+//    dS in [token, head, slot] order is dbias; (p, dS) words go to the workspace
+//    in the plan's run order (grouped by token tile);
 //
 //  key-stationary (one wave per tile of 16 tokens): walks the sorted list of
-//    strips that touch the tile, gathers their p and dS for the tile's tokens
-//    from the compact arrays (the plan's slot-index tile says where), and
+//    strips that touch the tile, reads each strip's run of (p, dS) words for the
+//    tile as one contiguous piece, spreads it over a 16x16 tile in LDS, and
 //    accumulates dK^T = Q^T dS and dV^T = dO^T P in registers, so dk and dv are
 //    written once, without atomics and in a fixed summation order.
 #include "cluster_common.h"
@@ -30,15 +31,15 @@ struct BwdParams {
   const float* lse;
   const uint16_t *slots, *entries;
   const int32_t* rev_offset;
-  const uint32_t* rev_list;
-  const uint8_t* jmat;
-  int N, H, K, strips, strips_per_image, slot_stride, max_slots;
+  const unsigned long long* rev_list;
+  const uint16_t *sorted_pos, *runs;
+  int N, H, K, strips, strips_per_image, slot_stride, max_slots, runs_stride, places;
   uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
   float scale;
   bf16_t *dq, *dk, *dv;
   bf16_t* ds;    // [B,N,H,K] dS = dbias, or nullptr when the caller does not want it
-  uint32_t* pd;  // workspace [B,N,H/PS,K,PS] with PS = 2 heads side by side when H is even, else 1;
-                 // one word per (token, head, slot): p in the low half, dS in the high half (bf16 bits)
+  uint32_t* pd;  // workspace [strips][H][places]: one word per place of the plan's run order,
+                 // p in the low half, dS in the high half (bf16 bits)
 };
 
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
@@ -88,7 +89,6 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   constexpr int EW = VEC ? 4 : 1;  // 32-bit words per item
   uint32_t ent[NT][EW];
   uint32_t item_off[NT];  // element offset of the item's first value within head 0's [token, head, :] rows
-  uint32_t pair_off[NT];  // the same within head pair 0's [token, pair, slot, 2] rows of the (p, dS) words
   bool item_live[NT];
   const int items = VEC ? 2 * K : 16 * K;
   const int chunks_per_query = K >> 3;
@@ -106,12 +106,10 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
       const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
       item_off[t] = (uint32_t)(qi * p.H * K + j0);
-      pair_off[t] = (uint32_t)(qi * p.H * K + 2 * j0);
     } else {
       ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
       const int qi = fast_div(ii, p.k_magic);
       item_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
-      pair_off[t] = (uint32_t)(qi * p.H * K + 2 * (ii - qi * K));
     }
   }
   const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
@@ -123,8 +121,14 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
   const size_t strip_rows = (size_t)tok0 * p.H * K;  // first element of the strip's [token, head, :] rows
 
-  const int PS = (p.H & 1) ? 1 : 2;  // heads stored side by side in the (p, dS) workspace
-  uint32_t keep[NT][VEC ? 8 : 1];    // the even head's words until the odd head is done
+  // entry values of the strip in run order, two consecutive places per lane and round
+  constexpr int SR = VEC ? NT * 4 + 1 : NT / 2 + 1;
+  uint32_t sp[SR];
+#pragma unroll
+  for (int t = 0; t < SR; ++t) {
+    const int w = t * 2 * kWave + 2 * lane;
+    sp[t] = (w < p.places) ? *reinterpret_cast<const uint32_t*>(p.sorted_pos + (size_t)sg * p.places + w) : 0xffffffffu;
+  }
   for (int h = 0; h < p.H; ++h) {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
     const size_t qrow = (size_t)(tok0 + r) * C + h * kD + g * 8;
@@ -138,11 +142,12 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
     const float nl2 = -p.lse[(size_t)(tok0 + r) * p.H + h] * kLog2e;
     const size_t head_rows = strip_rows + (size_t)h * K;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-    uint32_t pacc[NT][EW], dacc[NT][EW];  // p and dS of this lane's items (packed bf16), gathered pass by pass
+    uint32_t dacc[NT][EW];  // dS of this lane's items (packed bf16), gathered pass by pass
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-      for (int e = 0; e < EW; ++e) pacc[t][e] = dacc[t][e] = 0u;
+      for (int e = 0; e < EW; ++e) dacc[t][e] = 0u;
+    uint32_t* pd_head = p.pd + ((size_t)sg * p.H + h) * p.places;
 
     for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCapB) {
       const int nsl = min(kSlotCapB, ntiles - slot0);
@@ -190,7 +195,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         }
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
-        const bool has1 = 2 * pr + 1 < nsl;
+        const bool has1 = 2 * pr + 1 < nsl;  // wave-uniform
         Frag8 dsf;  // dS^T operand: k-slots 0..3 = first tile's tokens 4g..4g+3, 4..7 = second tile's
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
@@ -234,73 +239,62 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
           acc[dt] = mfma32(kt, dsf, acc[dt]);  // dq^T[channel 16dt + 4g+i][query r]
         }
       };
+      // every load in straight-line code between the computations (a load under a condition makes the
+      // compiler wait for all outstanding loads where the paths join)
       Frag8 kA[2], vA[2], kB[2], vB[2];
       load_pair(0, kA, vA);
-      for (int pr = 0; pr < npairs; pr += 2) {
-        if (pr + 1 < npairs) load_pair(pr + 1, kB, vB);
+      int pr = 0;
+      for (; pr + 2 < npairs; pr += 2) {
+        load_pair(pr + 1, kB, vB);
         compute_pair(pr, kA, vA);
-        if (pr + 1 < npairs) {
-          if (pr + 2 < npairs) load_pair(pr + 2, kA, vA);
-          compute_pair(pr + 1, kB, vB);
-        }
+        load_pair(pr + 2, kA, vA);
+        compute_pair(pr + 1, kB, vB);
+      }
+      if (pr + 1 < npairs) {
+        load_pair(pr + 1, kB, vB);
+        compute_pair(pr, kA, vA);
+        compute_pair(pr + 1, kB, vB);
+      } else {
+        compute_pair(pr, kA, vA);
       }
       wave_lds_sync();
-      // collect p and dS of this pass's real (query, neighbour) pairs
+      // dS of this pass's real (query, neighbour) pairs in [token, head, slot] order (dbias)
+      if (p.ds) {
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
+        for (int t = 0; t < NT; ++t) {
 #pragma unroll
-        for (int e = 0; e < (VEC ? 8 : 1); ++e) {
-          const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
-          const uint32_t rel = off - lo;
-          const bool in = rel < span;
-          const uint32_t at = in ? rel : 0u;
-          const uint32_t dsv = dstile[at], pv = ptile[at];
-          dacc[t][e >> 1] |= (in ? dsv : 0u) << (16 * (e & 1));
-          pacc[t][e >> 1] |= (in ? pv : 0u) << (16 * (e & 1));
+          for (int e = 0; e < (VEC ? 8 : 1); ++e) {
+            const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
+            const uint32_t rel = off - lo;
+            const bool in = rel < span;
+            const uint32_t dsv = dstile[in ? rel : 0u];
+            dacc[t][e >> 1] |= (in ? dsv : 0u) << (16 * (e & 1));
+          }
         }
+      }
+      // (p, dS) words of this pass's slots in run order: consecutive places, so the stores are whole rows.
+      // Runs start at even places: a pair of places belongs to one slot, or its second place is unused.
+#pragma unroll
+      for (int t = 0; t < SR; ++t) {
+        const uint32_t rel0 = (sp[t] & 0xffffu) - lo, rel1 = (sp[t] >> 16) - lo;  // other passes and unused places
+        const bool in0 = rel0 < span, in1 = rel1 < span;                         // fall outside [0, span)
+        const uint32_t a0 = in0 ? rel0 : 0u, a1 = in1 ? rel1 : 0u;
+        const uint32_t w0 = (uint32_t)ptile[a0] | ((uint32_t)dstile[a0] << 16);
+        const uint32_t w1 = (uint32_t)ptile[a1] | ((uint32_t)dstile[a1] << 16);
+        if (in0) *reinterpret_cast<uint2*>(pd_head + t * 2 * kWave + 2 * lane) = make_uint2(w0, in1 ? w1 : 0u);
       }
       wave_lds_sync();
     }
-    // compact arrays: dbias [token, head, slot], and the (p, dS) words for the key-stationary kernel
-    // (two heads side by side when H is even); whole 16-byte pieces when K is a multiple of 8
-    const bool pair_lo = PS == 2 && !(h & 1);  // first head of a pair: only remember the words
+    // dbias [token, head, slot]; whole 16-byte pieces when K is a multiple of 8
+    if (p.ds) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      if (item_live[t]) {
-        uint32_t* pair_dst = p.pd + strip_rows + (size_t)(h >> 1) * K * 2 + pair_off[t];
-        if (VEC) {
-          if (p.ds)
+      for (int t = 0; t < NT; ++t) {
+        if (item_live[t]) {
+          if (VEC)
             *reinterpret_cast<uint4*>(p.ds + head_rows + item_off[t]) =
                 make_uint4(dacc[t][0], dacc[t][EW > 1 ? 1 : 0], dacc[t][EW > 2 ? 2 : 0], dacc[t][EW > 3 ? 3 : 0]);
-          uint32_t w[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            w[e] = ((pacc[t][(EW > 1 ? e >> 1 : 0)] >> (16 * (e & 1))) & 0xffffu) |
-                   ((dacc[t][(EW > 1 ? e >> 1 : 0)] >> (16 * (e & 1))) << 16);
-          if (PS == 1) {
-            uint4* dst = reinterpret_cast<uint4*>(p.pd + head_rows + item_off[t]);
-            dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-            dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
-          } else if (pair_lo) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) keep[t][VEC ? e : 0] = w[e];
-          } else {
-            uint4* dst = reinterpret_cast<uint4*>(pair_dst);
-            dst[0] = make_uint4(keep[t][0], w[0], keep[t][VEC ? 1 : 0], w[1]);
-            dst[1] = make_uint4(keep[t][VEC ? 2 : 0], w[2], keep[t][VEC ? 3 : 0], w[3]);
-            dst[2] = make_uint4(keep[t][VEC ? 4 : 0], w[4], keep[t][VEC ? 5 : 0], w[5]);
-            dst[3] = make_uint4(keep[t][VEC ? 6 : 0], w[6], keep[t][VEC ? 7 : 0], w[7]);
-          }
-        } else {
-          if (p.ds) p.ds[head_rows + item_off[t]] = (bf16_t)dacc[t][0];
-          const uint32_t w0 = (pacc[t][0] & 0xffffu) | (dacc[t][0] << 16);
-          if (PS == 1) {
-            p.pd[head_rows + item_off[t]] = w0;
-          } else if (pair_lo) {
-            keep[t][0] = w0;
-          } else {
-            *reinterpret_cast<uint2*>(pair_dst) = make_uint2(keep[t][0], w0);
-          }
+          else
+            p.ds[head_rows + item_off[t]] = (bf16_t)dacc[t][0];
         }
       }
     }
@@ -328,33 +322,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 template <int HG>
 struct KeyItem {
   Frag8 qf[HG], gf[HG];  // strip's q and dout rows per head: lane (query r, channels 8g..8g+7)
-  uint32_t pd[4][HG];    // gathered (p, dS)[query 4g+i][token r] per head (slot 0's where the query does not list the token)
-  uint32_t jm;           // the four slot indices that were gathered, 255 = the query does not list the token
+  uint2 w[2][HG];        // (p, dS) words of places 2*lane, 2*lane+1 (+128 in the second round) of the run
+  uint32_t code[2];      // their entry values, two 16-bit halves
+  uint32_t len;          // places in the run (wave-uniform)
 };
 
-// HG = heads handled per sweep over the tile's list (2 when H is even: their (p, dS) words sit side by
-// side, so one 8-byte gather serves both).
+// HG = heads handled per sweep over the tile's list (2 when H is even: one walk of the list, one load of
+// the entry values and one pass over the q / dout rows serve both).
 template <int HG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
+  __shared__ __align__(16) uint32_t tile_all[4][HG * 256];  // per wave and head: (p, dS)[token][query]
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
   const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
   if (kt >= p.strips) return;
+  uint32_t* tile = tile_all[wave];
   const int b = kt / p.strips_per_image;
   const int C = p.H * kD;
-  const int K = p.K;
   const size_t strip_base = (size_t)b * p.strips_per_image;
   const int lo = __builtin_amdgcn_readfirstlane(p.rev_offset[kt]);
   const int n = __builtin_amdgcn_readfirstlane(p.rev_offset[kt + 1]) - lo;
   Frag8 idf[2];
   make_identity(idf, g, r);
-  // per-lane parts of the addresses (elements); the per-item parts are uniform and stay in SGPRs
-  const uint32_t q_lane = (uint32_t)(r * C + g * 8);
-  const uint32_t jm_lane = (uint32_t)(r * 16 + g * 4);
-  uint32_t pd_lane[4];  // word offset of query 4g+i's row within the strip's rows of one head group
-#pragma unroll
-  for (int i = 0; i < 4; ++i) pd_lane[i] = (uint32_t)((4 * g + i) * (p.H / HG) * K * HG);
+  const uint32_t q_lane = (uint32_t)(r * C + g * 8);  // per-lane part of the row addresses (elements)
 
   for (int hg = 0; hg < p.H; hg += HG) {
     f32x4 dk[HG][2], dv[HG][2];
@@ -367,58 +358,61 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
       }
     for (int base = 0; base < n; base += kWave) {
       const int nb = min(kWave, n - base);
-      const uint32_t mine = (lane < nb) ? p.rev_list[lo + base + lane] : 0u;
-      auto item_strip = [&](int i, int& slot) -> size_t {
-        const uint32_t inc = __builtin_amdgcn_readlane(mine, i);
-        slot = (int)(inc & 255u);
-        return strip_base + (inc >> 8);
-      };
-      auto fetch_jm = [&](int i) -> uint32_t {
-        int slot;
-        const size_t sgq = item_strip(i, slot);
-        const uint8_t* jb = p.jmat + (sgq * p.max_slots + slot) * 256;
-        return *reinterpret_cast<const uint32_t*>(jb + jm_lane);
-      };
+      const unsigned long long mine = (lane < nb) ? p.rev_list[lo + base + lane] : 0ull;
+      const uint32_t mine_lo = (uint32_t)mine, mine_hi = (uint32_t)(mine >> 32);
       // all loads of one item, nothing else: what is done with the words waits until compute(), so that
       // no use of a loaded value sits between the loads of one item and the math of the previous one
-      auto fetch_rest = [&](int i, uint32_t jm, KeyItem<HG>& it) {
-        int slot;
-        const size_t sgq = item_strip(i, slot);
+      auto fetch = [&](int i, KeyItem<HG>& it) {
+        const uint32_t inc = __builtin_amdgcn_readlane(mine_lo, i);
+        const uint32_t run = __builtin_amdgcn_readlane(mine_hi, i);
+        const size_t sgq = strip_base + (inc >> 8);
+        const uint32_t start = run & 0xffffu;
+        it.len = run >> 16;
         const size_t qbase = sgq * 16 * C + (size_t)(hg * kD);
 #pragma unroll
         for (int hh = 0; hh < HG; ++hh) {
           it.qf[hh].u4 = *reinterpret_cast<const uint4*>(p.q + qbase + hh * kD + q_lane);
           it.gf[hh].u4 = *reinterpret_cast<const uint4*>(p.dout + qbase + hh * kD + q_lane);
         }
-        // words of the strip's rows for this head group: [token][group][slot][HG]
-        const uint32_t* pdb = p.pd + (sgq * 16 * (p.H / HG) + hg / HG) * (size_t)K * HG;
-        it.jm = jm;
+        // runs start at even places and the rows hold an even number of places: aligned pairs
+        const uint16_t* codes = p.sorted_pos + sgq * p.places + start;
+        const uint32_t* words = p.pd + (sgq * p.H + hg) * p.places + start;
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const uint32_t j = (jm >> (8 * i4)) & 255u;
-          const uint32_t at = pd_lane[i4] + (j != 255u ? j : 0u) * HG;
-          if (HG == 2) {
-            const uint2 both = *reinterpret_cast<const uint2*>(pdb + at);
-            it.pd[i4][0] = both.x;
-            it.pd[i4][HG - 1] = both.y;
-          } else {
-            it.pd[i4][0] = pdb[at];
-          }
+        for (int rr = 0; rr < 2; ++rr) {
+          const uint32_t e = (uint32_t)(rr * 2 * kWave + 2 * lane);
+          const bool on = e < it.len;
+          it.code[rr] = on ? *reinterpret_cast<const uint32_t*>(codes + e) : 0xffffffffu;
+#pragma unroll
+          for (int hh = 0; hh < HG; ++hh)
+            it.w[rr][hh] = on ? *reinterpret_cast<const uint2*>(words + (size_t)hh * p.places + e) : make_uint2(0u, 0u);
         }
       };
       auto compute = [&](const KeyItem<HG>& it) {
-        uint32_t keep[4];  // all ones where the query lists the token
+        // spread the run over the tile: cell [token][query] <- word; unlisted cells stay 0 (p = dS = 0)
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) keep[i4] = (((it.jm >> (8 * i4)) & 255u) != 255u) ? 0xffffffffu : 0u;
+        for (int hh = 0; hh < HG; ++hh) *reinterpret_cast<uint4*>(tile + hh * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const uint32_t c = (it.code[rr] >> (16 * half)) & 0xffffu;  // query * 16 + token % 16 in the low byte
+            if (c != kNoEntry) {
+              const uint32_t cell = ((c & 15u) << 4) | ((c >> 4) & 15u);
+#pragma unroll
+              for (int hh = 0; hh < HG; ++hh) tile[hh * 256 + cell] = half ? it.w[rr][hh].y : it.w[rr][hh].x;
+            }
+          }
+        }
+        wave_lds_sync();
 #pragma unroll
         for (int hh = 0; hh < HG; ++hh) {
-          const uint32_t w0 = it.pd[0][hh] & keep[0], w1 = it.pd[1][hh] & keep[1];
-          const uint32_t w2 = it.pd[2][hh] & keep[2], w3 = it.pd[3][hh] & keep[3];
+          // (p, dS)[token r][queries 4g..4g+3]
+          const uint4 w = *reinterpret_cast<const uint4*>(tile + hh * 256 + r * 16 + g * 4);
           Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
-          pf.u[0] = (w0 & 0xffffu) | (w1 << 16);
-          pf.u[1] = (w2 & 0xffffu) | (w3 << 16);
-          df.u[0] = (w0 >> 16) | (w1 & 0xffff0000u);
-          df.u[1] = (w2 >> 16) | (w3 & 0xffff0000u);
+          pf.u[0] = (w.x & 0xffffu) | (w.y << 16);
+          pf.u[1] = (w.z & 0xffffu) | (w.w << 16);
+          df.u[0] = (w.x >> 16) | (w.y & 0xffff0000u);
+          df.u[1] = (w.z >> 16) | (w.w & 0xffff0000u);
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt) {
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
@@ -433,24 +427,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
             dv[hh][dt] = mfma16(gT, pf, dv[hh][dt]);
           }
         }
+        wave_lds_sync();  // the next item clears the tile
       };
-      // Two items in flight, the slot-index words one item further ahead.  Every load is issued
-      // unconditionally in straight-line code (indices past the end repeat the last item): a load under
-      // a condition makes the compiler wait for all outstanding loads where the paths join.
+      // Two items in flight.  Every load is issued unconditionally in straight-line code (an index past
+      // the end repeats the last item): a load under a condition makes the compiler wait for all
+      // outstanding loads where the paths join.
       KeyItem<HG> A, B;
-      uint32_t jm_a = fetch_jm(0), jm_b = fetch_jm(min(1, nb - 1));
-      fetch_rest(0, jm_a, A);
+      fetch(0, A);
       int i = 0;
       for (; i + 2 < nb; i += 2) {
-        fetch_rest(i + 1, jm_b, B);
-        jm_a = fetch_jm(i + 2);
+        fetch(i + 1, B);
         compute(A);
-        fetch_rest(i + 2, jm_a, A);
-        jm_b = fetch_jm(min(i + 3, nb - 1));
+        fetch(i + 2, A);
         compute(B);
       }
       if (i + 1 < nb) {
-        fetch_rest(i + 1, jm_b, B);
+        fetch(i + 1, B);
         compute(A);
         compute(B);
       } else {
@@ -477,8 +469,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 
 }  // namespace
 
-size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K) {
-  return plan_align((size_t)B * N * K * H * sizeof(uint32_t));
+size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, int S, int M) {
+  const PlanLayout L = make_plan_layout(B, N, K, S, M);
+  return plan_align((size_t)L.strips * H * L.places * sizeof(uint32_t));
 }
 
 hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* workspace, hipStream_t stream) {
@@ -490,8 +483,10 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.slots = reinterpret_cast<const uint16_t*>(base + L.slots_off);
   p.entries = reinterpret_cast<const uint16_t*>(base + L.entries_off);
   p.rev_offset = reinterpret_cast<const int32_t*>(base + L.rev_offset_off);
-  p.rev_list = reinterpret_cast<const uint32_t*>(base + L.rev_list_off);
-  p.jmat = reinterpret_cast<const uint8_t*>(base + L.jmat_off);
+  p.rev_list = reinterpret_cast<const unsigned long long*>(base + L.rev_list_off);
+  p.sorted_pos = reinterpret_cast<const uint16_t*>(base + L.sorted_pos_off);
+  p.runs = reinterpret_cast<const uint16_t*>(base + L.runs_off);
+  p.runs_stride = L.runs_stride; p.places = L.places;
   p.N = a.N; p.H = a.H; p.K = a.K;
   p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
   p.scale = a.scale;

@@ -21,8 +21,10 @@ struct PlanParams {
   int32_t* rev_count;
   int32_t* rev_offset;
   int32_t* rev_cursor;
-  uint32_t* rev_list;
-  uint8_t* jmat;
+  unsigned long long* rev_list;
+  uint16_t* sorted_pos;  // [strips][places]
+  uint16_t* runs;        // [strips][runs_stride]
+  int runs_stride, places;
 };
 
 __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
@@ -38,15 +40,13 @@ __global__ __launch_bounds__(256) void plan_zero_kernel(int32_t* a, int32_t* b, 
   }
 }
 
-constexpr int kJmatPass = 16;  // slots whose 16x16 slot-index tiles are assembled in LDS at a time
-
 __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
-  __shared__ __align__(16) uint8_t jm_all[4][kJmatPass * 256];
+  __shared__ uint16_t sorted_all[4][kMaxEntries * kWave + kMaxSlots];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int sg = blockIdx.x * (blockDim.x / kWave) + wave;
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier below
-  uint8_t* jm = jm_all[wave];
+  uint16_t* sorted = sorted_all[wave];
   const int b = sg / p.strips_per_image;
   const int q0 = (sg - b * p.strips_per_image) * 16;  // first query, within the image
   const int c = fast_div(q0, p.s_magic);
@@ -106,26 +106,29 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   if (lane == 0) sl[0] = (uint16_t)count;
   for (int s = count + lane; s < p.slot_stride - 1; s += kWave) sl[1 + s] = (uint16_t)own_tile;
 
-  // jmat[slot][token][query] = neighbour slot j, assembled in LDS and written out in rows
-  uint8_t* jout = p.jmat + (size_t)sg * p.max_slots * 256;
-  for (int s0 = 0; s0 < count; s0 += kJmatPass) {
-    const int ns = min(kJmatPass, count - s0);
-    for (int w = lane; w < ns * 64; w += kWave) reinterpret_cast<uint32_t*>(jm)[w] = 0xffffffffu;
-    wave_lds_sync();
+  // runs: the valid entries grouped by slot, ascending entry index inside a slot, every run starting
+  // at an even place; assembled in LDS and written out in rows.  Unused places hold kNoEntry.
+  for (int w = lane; w < kMaxEntries * kWave + kMaxSlots; w += kWave) sorted[w] = (uint16_t)kNoEntry;
+  wave_lds_sync();
+  uint16_t* runs = p.runs + (size_t)sg * p.runs_stride;
+  int place = 0;  // wave-uniform
+  for (int s = 0; s < count; ++s) {
+    place = (place + 1) & ~1;
+    if (lane == 0) runs[s] = (uint16_t)place;
 #pragma unroll
     for (int t = 0; t < kMaxEntries; ++t) {
-      const uint32_t rel = off[t] - (uint32_t)s0 * 256u;
-      if (off[t] != kNoEntry && rel < (uint32_t)ns * 256u) {
-        const int e = t * kWave + lane;
-        const int qi = (off[t] >> 4) & 15, cand = off[t] & 15;
-        jm[(rel & ~255u) + cand * 16 + qi] = (uint8_t)(e - qi * p.K);
-      }
+      const bool mine = off[t] != kNoEntry && (int)(off[t] >> 8) == s;
+      const unsigned long long m = __ballot(mine);
+      if (m == 0ull) continue;  // wave-uniform
+      const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+      if (mine) sorted[place + rank] = (uint16_t)off[t];
+      place += __popcll(m);
     }
-    wave_lds_sync();
-    for (int w = lane; w < ns * 64; w += kWave)
-      reinterpret_cast<uint32_t*>(jout + (size_t)s0 * 256)[w] = reinterpret_cast<const uint32_t*>(jm)[w];
-    wave_lds_sync();
   }
+  if (lane == 0) runs[count] = (uint16_t)place;
+  wave_lds_sync();
+  uint16_t* sp = p.sorted_pos + (size_t)sg * p.places;
+  for (int w = lane; w < p.places; w += kWave) sp[w] = sorted[w];
 }
 
 // Exclusive prefix sum of rev_count (one workgroup; n is at most a few hundred thousand).
@@ -165,27 +168,31 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanParams p) {
   if (lane < count) {
     const size_t kt = (size_t)b * p.strips_per_image + sl[1 + lane];
     const int at = atomicAdd(p.rev_cursor + kt, 1);
-    p.rev_list[(size_t)p.rev_offset[kt] + at] = ((uint32_t)strip_in_image << 8) | (uint32_t)lane;
+    const uint16_t* runs = p.runs + (size_t)sg * p.runs_stride;
+    const uint32_t start = runs[lane], len = (uint32_t)runs[lane + 1] - start;  // len may count one pad place
+    p.rev_list[(size_t)p.rev_offset[kt] + at] =
+        ((unsigned long long)(start | (len << 16)) << 32) | (((uint32_t)strip_in_image << 8) | (uint32_t)lane);
   }
 }
 
-// Sort every token tile's list ascending: rank by counting (lists are short).
+// Sort every token tile's list ascending by (strip, slot): rank by counting (lists are short).
 __global__ __launch_bounds__(256) void plan_sort_kernel(PlanParams p) {
   const int lane = threadIdx.x & (kWave - 1);
   const int kt = blockIdx.x * (blockDim.x / kWave) + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (kt >= p.strips) return;
   const int lo = p.rev_offset[kt], n = p.rev_offset[kt + 1] - lo;
-  uint32_t* list = p.rev_list + lo;
+  unsigned long long* list = p.rev_list + lo;
   if (n <= kWave) {
-    const uint32_t mine = lane < n ? list[lane] : 0xffffffffu;
+    const unsigned long long mine = lane < n ? list[lane] : ~0ull;
+    const uint32_t key = (uint32_t)mine;
     int rank = 0;
-    for (int j = 0; j < n; ++j) rank += (__shfl(mine, j) < mine) ? 1 : 0;  // entries are distinct
+    for (int j = 0; j < n; ++j) rank += (__shfl(key, j) < key) ? 1 : 0;  // keys are distinct
     if (lane < n) list[rank] = mine;  // every lane has read its element before any write lands (one wave)
   } else if (lane == 0) {
     for (int i = 1; i < n; ++i) {  // insertion sort; only for unusually popular tiles
-      const uint32_t v = list[i];
+      const unsigned long long v = list[i];
       int j = i - 1;
-      while (j >= 0 && list[j] > v) {
+      while (j >= 0 && (uint32_t)list[j] > (uint32_t)v) {
         list[j + 1] = list[j];
         --j;
       }
@@ -210,8 +217,10 @@ hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, i
   p.rev_count = reinterpret_cast<int32_t*>(base + L.rev_count_off);
   p.rev_offset = reinterpret_cast<int32_t*>(base + L.rev_offset_off);
   p.rev_cursor = reinterpret_cast<int32_t*>(base + L.rev_cursor_off);
-  p.rev_list = reinterpret_cast<uint32_t*>(base + L.rev_list_off);
-  p.jmat = reinterpret_cast<uint8_t*>(base + L.jmat_off);
+  p.rev_list = reinterpret_cast<unsigned long long*>(base + L.rev_list_off);
+  p.sorted_pos = reinterpret_cast<uint16_t*>(base + L.sorted_pos_off);
+  p.runs = reinterpret_cast<uint16_t*>(base + L.runs_off);
+  p.runs_stride = L.runs_stride; p.places = L.places;
   const dim3 per_strip((L.strips + 3) / 4);
   AFFMAE_LAUNCH("plan_zero_kernel", stream, plan_zero_kernel, dim3((L.strips + 255) / 256), dim3(256), 0, stream,
                 p.rev_count, p.rev_cursor, L.strips);
