@@ -48,6 +48,7 @@ constexpr int kFwdWaves = 4;  // waves per workgroup; they share nothing but the
 template <int NT, bool VEC>
 __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   __shared__ __align__(16) bf16_t scratch_all[kFwdWaves][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
+  __shared__ __align__(16) uint4 kv_all[kFwdWaves][4 * 64];  // K and V rows of one pair of token tiles, per wave
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
@@ -101,11 +102,20 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int i = 0; i < 8; ++i) idf[dt].h[i] = (8 * g + i == r + 16 * dt) ? 0x3f80u : 0u;
-  // K/V rows of a token tile: uniform tile base + this lane's (row r, channels 8g..8g+7) byte offset
+  // K/V rows of a token tile come in through LDS.  The MFMA operand wants lane (row r, channels
+  // 8g..8g+7), which puts the four lanes of a quad on four different rows, and the memory pipeline
+  // serves one row segment per cycle: such a load costs 64 cycles against 16 for a load whose quads
+  // read 64 contiguous bytes.  So lane (row lane/4, 16-byte piece lane%4) loads, the pieces cross
+  // through a per-wave LDS tile, and each lane reads back the piece its operand needs.  The piece index
+  // is XOR-swizzled by the row so that both the writes and the reads spread over all banks.
   const char* kimg = reinterpret_cast<const char*>(p.k + (size_t)img_base * C);
   const char* vimg = reinterpret_cast<const char*>(p.v + (size_t)img_base * C);
-  const uint32_t lane_off = (uint32_t)(r * C + g * 8) * 2u;
+  const int la = lane >> 2, lc = lane & 3;
+  const uint32_t lane_off = (uint32_t)(la * C * 2 + lc * 16);
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
+  uint4* kv = kv_all[wave];
+  const int wr_chunk = la * 4 + (lc ^ (((la >> 1) & 3) ^ ((la >> 3) & 1)));
+  const int rd_chunk = r * 4 + (g ^ (((r >> 1) & 3) ^ ((r >> 3) & 1)));
   const bf16_t* bias_strip = p.bias ? p.bias + (size_t)tok0 * p.H * K : nullptr;
 
   // loads of one head: the Q^T operand (lane (query r, channels 8g..8g+7)) and the bias of the items
@@ -155,15 +165,28 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       wave_lds_sync();
 
       const int npairs = (nsl + 1) >> 1;
-      auto load_pair = [&](int pr, Frag8(&kf)[2], Frag8(&vf)[2]) {
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const int s = min(2 * pr + tt, nsl - 1);
-          const uint32_t tile = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + s);
-          const size_t tbase = (size_t)tile * tile_bytes + (size_t)(h * kD * 2);
-          kf[tt].u4 = *reinterpret_cast<const uint4*>(kimg + tbase + lane_off);
-          vf[tt].u4 = *reinterpret_cast<const uint4*>(vimg + tbase + lane_off);
-        }
+      auto load_pair = [&](int pr, uint4& k0, uint4& v0, uint4& k1, uint4& v1) {
+        const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
+        const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
+        const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
+        const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
+        k0 = *reinterpret_cast<const uint4*>(kimg + base0 + lane_off);
+        v0 = *reinterpret_cast<const uint4*>(vimg + base0 + lane_off);
+        k1 = *reinterpret_cast<const uint4*>(kimg + base1 + lane_off);
+        v1 = *reinterpret_cast<const uint4*>(vimg + base1 + lane_off);
+      };
+      // pieces as loaded -> LDS -> operand pieces
+      auto stage_pair = [&](const uint4& k0, const uint4& v0, const uint4& k1, const uint4& v1, Frag8(&kf)[2],
+                            Frag8(&vf)[2]) {
+        kv[0 * 64 + wr_chunk] = k0;
+        kv[1 * 64 + wr_chunk] = v0;
+        kv[2 * 64 + wr_chunk] = k1;
+        kv[3 * 64 + wr_chunk] = v1;
+        wave_lds_sync();
+        kf[0].u4 = kv[0 * 64 + rd_chunk];
+        vf[0].u4 = kv[1 * 64 + rd_chunk];
+        kf[1].u4 = kv[2 * 64 + rd_chunk];
+        vf[1].u4 = kv[3 * 64 + rd_chunk];
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
         // a pass with an odd number of tiles repeats its last tile in the second half of the last pair;
@@ -217,25 +240,18 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
           acc[dt] = mfma32(vt, pf, acc[dt]);
         }
       };
-      // Two register sets in turn, so that the loads of the next pair fly during this pair's math.  Every
-      // load sits in straight-line code between the computations: a load under a condition would make the
-      // compiler wait for all outstanding loads where the paths join, which undoes the overlap.
-      Frag8 kA[2], vA[2], kB[2], vB[2];
-      load_pair(0, kA, vA);
-      int pr = 0;
-      for (; pr + 2 < npairs; pr += 2) {
-        load_pair(pr + 1, kB, vB);
-        compute_pair(pr, kA, vA);
-        load_pair(pr + 2, kA, vA);
-        compute_pair(pr + 1, kB, vB);
+      // The loads of the next pair fly during this pair's math.  Every load sits in straight-line code: a
+      // load under a condition would make the compiler wait for all outstanding loads where the paths join.
+      uint4 sk0, sv0, sk1, sv1;
+      Frag8 kf[2], vf[2];
+      load_pair(0, sk0, sv0, sk1, sv1);
+      for (int pr = 0; pr + 1 < npairs; ++pr) {
+        stage_pair(sk0, sv0, sk1, sv1, kf, vf);
+        load_pair(pr + 1, sk0, sv0, sk1, sv1);
+        compute_pair(pr, kf, vf);
       }
-      if (pr + 1 < npairs) {
-        load_pair(pr + 1, kB, vB);
-        compute_pair(pr, kA, vA);
-        compute_pair(pr + 1, kB, vB);
-      } else {
-        compute_pair(pr, kA, vA);
-      }
+      stage_pair(sk0, sv0, sk1, sv1, kf, vf);
+      compute_pair(npairs - 1, kf, vf);
       wave_lds_sync();  // the next pass overwrites the bias tile
     }
 
