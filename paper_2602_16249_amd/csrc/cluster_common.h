@@ -17,6 +17,7 @@ namespace affmae {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;  // 16 bytes on their way through registers
 
 constexpr int kD = 32;                 // channels per head
 constexpr int kMaxSlots = 64;          // token tiles one strip may touch (M*S/16 <= 64)
@@ -26,6 +27,7 @@ constexpr uint32_t kNoEntry = 0xffffu;
 union Frag8 {
   bf16x8 v;
   uint4 u4;
+  u32x4 x4;
   uint2 u2[2];
   uint32_t u[4];
   uint16_t h[8];

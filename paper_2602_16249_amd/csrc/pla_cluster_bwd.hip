@@ -70,6 +70,7 @@ template <int NT, bool VEC>
 __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
+  __shared__ __align__(16) uint4 kv_all[4][4 * 64];  // K and V rows of one pair of token tiles, per wave
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
@@ -115,10 +116,18 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
   Frag8 idf[2];
   make_identity(idf, g, r);
+  // K/V rows cross through LDS: lane (row lane/4, 16-byte piece lane%4) loads 64 contiguous bytes per
+  // quad (16 memory-pipeline cycles per load instead of the 64 of a load straight into the operand
+  // layout, whose quads touch four rows), and each lane reads back the piece its operand needs; the
+  // piece index is XOR-swizzled by the row so that writes and reads spread over all banks.
   const char* kimg = reinterpret_cast<const char*>(p.k + (size_t)img_base * C);
   const char* vimg = reinterpret_cast<const char*>(p.v + (size_t)img_base * C);
-  const uint32_t lane_off = (uint32_t)(r * C + g * 8) * 2u;
+  const int la = lane >> 2, lc = lane & 3;
+  const uint32_t lane_off = (uint32_t)(la * C * 2 + lc * 16);
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
+  uint4* kv = kv_all[wave];
+  const int wr_chunk = la * 4 + (lc ^ (((la >> 1) & 3) ^ ((la >> 3) & 1)));
+  const int rd_chunk = r * 4 + (g ^ (((r >> 1) & 3) ^ ((r >> 3) & 1)));
   const size_t strip_rows = (size_t)tok0 * p.H * K;  // first element of the strip's [token, head, :] rows
 
   // entry values of the strip in run order, two consecutive places per lane and round
@@ -184,15 +193,28 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       }
 
       const int npairs = (nsl + 1) >> 1;
-      auto load_pair = [&](int pr, Frag8(&kf)[2], Frag8(&vf)[2]) {
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const int s = min(2 * pr + tt, nsl - 1);
-          const uint32_t tile = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + s);
-          const size_t tbase = (size_t)tile * tile_bytes + (size_t)(h * kD * 2);
-          kf[tt].u4 = *reinterpret_cast<const uint4*>(kimg + tbase + lane_off);
-          vf[tt].u4 = *reinterpret_cast<const uint4*>(vimg + tbase + lane_off);
-        }
+      auto load_pair = [&](int pr, uint4& k0, uint4& v0, uint4& k1, uint4& v1) {
+        const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
+        const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
+        const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
+        const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
+        k0 = *reinterpret_cast<const uint4*>(kimg + base0 + lane_off);
+        v0 = *reinterpret_cast<const uint4*>(vimg + base0 + lane_off);
+        k1 = *reinterpret_cast<const uint4*>(kimg + base1 + lane_off);
+        v1 = *reinterpret_cast<const uint4*>(vimg + base1 + lane_off);
+      };
+      // pieces as loaded -> LDS -> operand pieces
+      auto stage_pair = [&](const uint4& k0, const uint4& v0, const uint4& k1, const uint4& v1, Frag8(&kf)[2],
+                            Frag8(&vf)[2]) {
+        kv[0 * 64 + wr_chunk] = k0;
+        kv[1 * 64 + wr_chunk] = v0;
+        kv[2 * 64 + wr_chunk] = k1;
+        kv[3 * 64 + wr_chunk] = v1;
+        wave_lds_sync();
+        kf[0].u4 = kv[0 * 64 + rd_chunk];
+        vf[0].u4 = kv[1 * 64 + rd_chunk];
+        kf[1].u4 = kv[2 * 64 + rd_chunk];
+        vf[1].u4 = kv[3 * 64 + rd_chunk];
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
         const bool has1 = 2 * pr + 1 < nsl;  // wave-uniform
@@ -239,24 +261,18 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
           acc[dt] = mfma32(kt, dsf, acc[dt]);  // dq^T[channel 16dt + 4g+i][query r]
         }
       };
-      // every load in straight-line code between the computations (a load under a condition makes the
-      // compiler wait for all outstanding loads where the paths join)
-      Frag8 kA[2], vA[2], kB[2], vB[2];
-      load_pair(0, kA, vA);
-      int pr = 0;
-      for (; pr + 2 < npairs; pr += 2) {
-        load_pair(pr + 1, kB, vB);
-        compute_pair(pr, kA, vA);
-        load_pair(pr + 2, kA, vA);
-        compute_pair(pr + 1, kB, vB);
+      // The loads of the next pair fly during this pair's math; every load in straight-line code (a load
+      // under a condition makes the compiler wait for all outstanding loads where the paths join).
+      uint4 sk0, sv0, sk1, sv1;
+      Frag8 kf[2], vf[2];
+      load_pair(0, sk0, sv0, sk1, sv1);
+      for (int pr = 0; pr + 1 < npairs; ++pr) {
+        stage_pair(sk0, sv0, sk1, sv1, kf, vf);
+        load_pair(pr + 1, sk0, sv0, sk1, sv1);
+        compute_pair(pr, kf, vf);
       }
-      if (pr + 1 < npairs) {
-        load_pair(pr + 1, kB, vB);
-        compute_pair(pr, kA, vA);
-        compute_pair(pr + 1, kB, vB);
-      } else {
-        compute_pair(pr, kA, vA);
-      }
+      stage_pair(sk0, sv0, sk1, sv1, kf, vf);
+      compute_pair(npairs - 1, kf, vf);
       wave_lds_sync();
       // dS of this pass's real (query, neighbour) pairs in [token, head, slot] order (dbias)
       if (p.ds) {
@@ -321,7 +337,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // key-stationary kernel
 template <int HG>
 struct KeyItem {
-  Frag8 qf[HG], gf[HG];  // strip's q and dout rows per head: lane (query r, channels 8g..8g+7)
+  u32x4 qs[HG], gs[HG];  // strip's q and dout rows of the head group as loaded: lane (row i*16/HG + lane/(4 HG), piece lane%(4 HG))
   uint2 w[2][HG];        // (p, dS) words of places 2*lane, 2*lane+1 (+128 in the second round) of the run
   uint32_t code[2];      // their entry values, two 16-bit halves
   uint32_t len;          // places in the run (wave-uniform)
@@ -332,12 +348,14 @@ struct KeyItem {
 template <int HG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
   __shared__ __align__(16) uint32_t tile_all[4][HG * 256];  // per wave and head: (p, dS)[token][query]
+  __shared__ __align__(16) u32x4 rows_all[4][2 * HG * 64];  // per wave: the strip's q rows, then its dout rows
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
   const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
   if (kt >= p.strips) return;
   uint32_t* tile = tile_all[wave];
+  u32x4* rows = rows_all[wave];
   const int b = kt / p.strips_per_image;
   const int C = p.H * kD;
   const size_t strip_base = (size_t)b * p.strips_per_image;
@@ -345,7 +363,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   const int n = __builtin_amdgcn_readfirstlane(p.rev_offset[kt + 1]) - lo;
   Frag8 idf[2];
   make_identity(idf, g, r);
-  const uint32_t q_lane = (uint32_t)(r * C + g * 8);  // per-lane part of the row addresses (elements)
+  // q / dout rows cross through LDS: a lane loads 16 contiguous bytes of a row so that a quad reads 64
+  // contiguous bytes (a load straight into the operand layout puts a quad on four rows and costs four
+  // times the memory-pipeline cycles); each lane then reads back the piece its operand needs.  The piece
+  // index is XOR-swizzled by the row so that writes and reads spread over all banks.
+  constexpr int PR = 4 * HG;  // 16-byte pieces per row of the head group
+  const int la = lane / PR, lc = lane % PR;  // row within a load of 64 / PR rows, piece
+  const uint32_t q_lane = (uint32_t)(la * C + lc * 8);  // per-lane part of the row addresses (elements)
+  auto swz = [](int row) { return HG == 2 ? ((row & 7) ^ (row >> 3)) : (((row >> 1) & 3) ^ ((row >> 3) & 1)); };
+  int wr_chunk[HG], rd_chunk[HG];
+#pragma unroll
+  for (int i = 0; i < HG; ++i) {
+    const int row = i * (64 / PR) + la;
+    wr_chunk[i] = row * PR + (lc ^ swz(row));
+    rd_chunk[i] = r * PR + ((i * 4 + g) ^ swz(r));  // head i of the group: piece 4 i + g of row r
+  }
 
   for (int hg = 0; hg < p.H; hg += HG) {
     f32x4 dk[HG][2], dv[HG][2];
@@ -370,9 +402,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         it.len = run >> 16;
         const size_t qbase = sgq * 16 * C + (size_t)(hg * kD);
 #pragma unroll
-        for (int hh = 0; hh < HG; ++hh) {
-          it.qf[hh].u4 = *reinterpret_cast<const uint4*>(p.q + qbase + hh * kD + q_lane);
-          it.gf[hh].u4 = *reinterpret_cast<const uint4*>(p.dout + qbase + hh * kD + q_lane);
+        for (int i = 0; i < HG; ++i) {  // load i: rows i * 64 / PR onwards
+          it.qs[i] = *reinterpret_cast<const u32x4*>(p.q + qbase + (size_t)(i * (64 / PR)) * C + q_lane);
+          it.gs[i] = *reinterpret_cast<const u32x4*>(p.dout + qbase + (size_t)(i * (64 / PR)) * C + q_lane);
         }
         // runs start at even places and the rows hold an even number of places: aligned pairs
         const uint16_t* codes = p.sorted_pos + sgq * p.places + start;
@@ -388,6 +420,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         }
       };
       auto compute = [&](const KeyItem<HG>& it) {
+#pragma unroll
+        for (int i = 0; i < HG; ++i) {
+          rows[wr_chunk[i]] = it.qs[i];
+          rows[HG * 64 + wr_chunk[i]] = it.gs[i];
+        }
         // spread the run over the tile: cell [token][query] <- word; unlisted cells stay 0 (p = dS = 0)
 #pragma unroll
         for (int hh = 0; hh < HG; ++hh) *reinterpret_cast<uint4*>(tile + hh * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
@@ -408,6 +445,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         for (int hh = 0; hh < HG; ++hh) {
           // (p, dS)[token r][queries 4g..4g+3]
           const uint4 w = *reinterpret_cast<const uint4*>(tile + hh * 256 + r * 16 + g * 4);
+          Frag8 qf, gf;  // lane (query r, channels 8g..8g+7) of q and dout
+          qf.x4 = rows[rd_chunk[hh]];
+          gf.x4 = rows[HG * 64 + rd_chunk[hh]];
           Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
           pf.u[0] = (w.x & 0xffffu) | (w.y << 16);
           pf.u[1] = (w.z & 0xffffu) | (w.w << 16);
@@ -416,8 +456,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt) {
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            const f32x4 cq = mfma32(it.qf[hh], idf[dt], z);  // q[query 4g+i][channel 16dt + r]
-            const f32x4 cg = mfma32(it.gf[hh], idf[dt], z);  // dout likewise
+            const f32x4 cq = mfma32(qf, idf[dt], z);  // q[query 4g+i][channel 16dt + r]
+            const f32x4 cg = mfma32(gf, idf[dt], z);  // dout likewise
             Frag4 qT, gT;  // operand A: lane (channel 16dt + r, queries 4g..4g+3)
             qT.u[0] = pack_bf16x2(cq[0], cq[1]);
             qT.u[1] = pack_bf16x2(cq[2], cq[3]);
