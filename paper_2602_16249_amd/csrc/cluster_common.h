@@ -122,6 +122,13 @@ __device__ __forceinline__ float group_sum(float x) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+// Place, in 16-byte pieces, of piece `piece` (0..3) of row `row` (0..15) in a 1 KB LDS tile of 16 rows
+// of 64 bytes.  The XOR keeps both access patterns of the kernels free of bank conflicts: lane (row
+// lane/4, piece lane%4), and lane (row lane%16, piece lane/16).
+__device__ __forceinline__ int tile_chunk(int row, int piece) {
+  return row * 4 + (piece ^ (((row >> 1) & 3) ^ ((row >> 3) & 1)));
+}
+
 // Two fp32 -> packed bf16 (round to nearest even), low half first.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;

@@ -70,7 +70,7 @@ template <int NT, bool VEC>
 __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
-  __shared__ __align__(16) uint4 kv_all[4][4 * 64];  // K and V rows of one pair of token tiles, per wave
+  __shared__ __align__(16) u32x4 kv_all[4][4 * 64];  // K and V rows of one pair of token tiles, per wave
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
@@ -125,9 +125,9 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int la = lane >> 2, lc = lane & 3;
   const uint32_t lane_off = (uint32_t)(la * C * 2 + lc * 16);
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
-  uint4* kv = kv_all[wave];
-  const int wr_chunk = la * 4 + (lc ^ (((la >> 1) & 3) ^ ((la >> 3) & 1)));
-  const int rd_chunk = r * 4 + (g ^ (((r >> 1) & 3) ^ ((r >> 3) & 1)));
+  u32x4* kv = kv_all[wave];
+  const int wr_chunk = tile_chunk(la, lc);
+  const int rd_chunk = tile_chunk(r, g);
   const size_t strip_rows = (size_t)tok0 * p.H * K;  // first element of the strip's [token, head, :] rows
 
   // entry values of the strip in run order, two consecutive places per lane and round
@@ -140,10 +140,20 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   }
   for (int h = 0; h < p.H; ++h) {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
-    const size_t qrow = (size_t)(tok0 + r) * C + h * kD + g * 8;
-    qf.u4 = *reinterpret_cast<const uint4*>(p.q + qrow);
-    gf.u4 = *reinterpret_cast<const uint4*>(p.dout + qrow);
-    of.u4 = *reinterpret_cast<const uint4*>(p.out + qrow);
+    {  // the strip's rows cross through LDS like the K/V rows
+      const size_t qrow = (size_t)(tok0 + la) * C + h * kD + lc * 8;
+      const u32x4 qraw = *reinterpret_cast<const u32x4*>(p.q + qrow);
+      const u32x4 graw = *reinterpret_cast<const u32x4*>(p.dout + qrow);
+      const u32x4 oraw = *reinterpret_cast<const u32x4*>(p.out + qrow);
+      kv[0 * 64 + wr_chunk] = qraw;
+      kv[1 * 64 + wr_chunk] = graw;
+      kv[2 * 64 + wr_chunk] = oraw;
+      wave_lds_sync();
+      qf.x4 = kv[0 * 64 + rd_chunk];
+      gf.x4 = kv[1 * 64 + rd_chunk];
+      of.x4 = kv[2 * 64 + rd_chunk];
+      wave_lds_sync();
+    }
     float Dq = 0.f;  // D of query r
 #pragma unroll
     for (int i = 0; i < 8; ++i) Dq = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(of.h[i]), Dq);
@@ -193,28 +203,28 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       }
 
       const int npairs = (nsl + 1) >> 1;
-      auto load_pair = [&](int pr, uint4& k0, uint4& v0, uint4& k1, uint4& v1) {
+      auto load_pair = [&](int pr, u32x4& k0, u32x4& v0, u32x4& k1, u32x4& v1) {
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
         const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
         const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
-        k0 = *reinterpret_cast<const uint4*>(kimg + base0 + lane_off);
-        v0 = *reinterpret_cast<const uint4*>(vimg + base0 + lane_off);
-        k1 = *reinterpret_cast<const uint4*>(kimg + base1 + lane_off);
-        v1 = *reinterpret_cast<const uint4*>(vimg + base1 + lane_off);
+        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + lane_off);
+        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + lane_off);
+        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + lane_off);
+        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + lane_off);
       };
       // pieces as loaded -> LDS -> operand pieces
-      auto stage_pair = [&](const uint4& k0, const uint4& v0, const uint4& k1, const uint4& v1, Frag8(&kf)[2],
+      auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],
                             Frag8(&vf)[2]) {
         kv[0 * 64 + wr_chunk] = k0;
         kv[1 * 64 + wr_chunk] = v0;
         kv[2 * 64 + wr_chunk] = k1;
         kv[3 * 64 + wr_chunk] = v1;
         wave_lds_sync();
-        kf[0].u4 = kv[0 * 64 + rd_chunk];
-        vf[0].u4 = kv[1 * 64 + rd_chunk];
-        kf[1].u4 = kv[2 * 64 + rd_chunk];
-        vf[1].u4 = kv[3 * 64 + rd_chunk];
+        kf[0].x4 = kv[0 * 64 + rd_chunk];
+        vf[0].x4 = kv[1 * 64 + rd_chunk];
+        kf[1].x4 = kv[2 * 64 + rd_chunk];
+        vf[1].x4 = kv[3 * 64 + rd_chunk];
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
         const bool has1 = 2 * pr + 1 < nsl;  // wave-uniform
@@ -263,7 +273,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       };
       // The loads of the next pair fly during this pair's math; every load in straight-line code (a load
       // under a condition makes the compiler wait for all outstanding loads where the paths join).
-      uint4 sk0, sv0, sk1, sv1;
+      u32x4 sk0, sv0, sk1, sv1;
       Frag8 kf[2], vf[2];
       load_pair(0, sk0, sv0, sk1, sv1);
       for (int pr = 0; pr + 1 < npairs; ++pr) {
@@ -314,13 +324,18 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         }
       }
     }
+    // dq rows cross through LDS the other way: lane (query r, channels 16dt + 4g..+3) holds 8 bytes of
+    // 16-byte piece 2dt + g/2 of row r; lane (row lane/4, piece lane%4) stores 16 bytes
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt) {
       uint2 o;
       o.x = pack_bf16x2(acc[dt][0] * p.scale, acc[dt][1] * p.scale);
       o.y = pack_bf16x2(acc[dt][2] * p.scale, acc[dt][3] * p.scale);
-      *reinterpret_cast<uint2*>(p.dq + (size_t)(tok0 + r) * C + h * kD + dt * 16 + g * 4) = o;
+      reinterpret_cast<uint2*>(kv)[tile_chunk(r, 2 * dt + (g >> 1)) * 2 + (g & 1)] = o;
     }
+    wave_lds_sync();
+    *reinterpret_cast<u32x4*>(p.dq + (size_t)(tok0 + la) * C + h * kD + lc * 8) = kv[wr_chunk];
+    wave_lds_sync();
   }
 }
 
@@ -489,21 +504,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         compute(A);
       }
     }
+    // dk / dv rows cross through LDS the other way: lane (token r, channels 16dt + 4g..+3 of head hh)
+    // holds 8 bytes of 16-byte piece 4hh + 2dt + g/2 of row r; the loading pattern stores 16 bytes per lane
 #pragma unroll
     for (int hh = 0; hh < HG; ++hh) {
-      const int h = hg + hh;
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt) {
-        const size_t at = ((size_t)kt * 16 + r) * C + h * kD + dt * 16 + g * 4;
+        const int at = (r * PR + ((4 * hh + 2 * dt + (g >> 1)) ^ swz(r))) * 2 + (g & 1);
         uint2 o;
         o.x = pack_bf16x2(dk[hh][dt][0] * p.scale, dk[hh][dt][1] * p.scale);
         o.y = pack_bf16x2(dk[hh][dt][2] * p.scale, dk[hh][dt][3] * p.scale);
-        *reinterpret_cast<uint2*>(p.dk + at) = o;
+        reinterpret_cast<uint2*>(rows)[at] = o;
         o.x = pack_bf16x2(dv[hh][dt][0], dv[hh][dt][1]);
         o.y = pack_bf16x2(dv[hh][dt][2], dv[hh][dt][3]);
-        *reinterpret_cast<uint2*>(p.dv + at) = o;
+        reinterpret_cast<uint2*>(rows + HG * 64)[at] = o;
       }
     }
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < HG; ++i) {
+      const size_t at = ((size_t)kt * 16 + i * (64 / PR)) * C + (size_t)(hg * kD) + q_lane;
+      *reinterpret_cast<u32x4*>(p.dk + at) = rows[wr_chunk[i]];
+      *reinterpret_cast<u32x4*>(p.dv + at) = rows[HG * 64 + wr_chunk[i]];
+    }
+    wave_lds_sync();
   }
 }
 

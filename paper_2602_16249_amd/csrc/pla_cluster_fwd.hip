@@ -48,7 +48,7 @@ constexpr int kFwdWaves = 4;  // waves per workgroup; they share nothing but the
 template <int NT, bool VEC>
 __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   __shared__ __align__(16) bf16_t scratch_all[kFwdWaves][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
-  __shared__ __align__(16) uint4 kv_all[kFwdWaves][4 * 64];  // K and V rows of one pair of token tiles, per wave
+  __shared__ __align__(16) u32x4 kv_all[kFwdWaves][4 * 64];  // K and V rows of one pair of token tiles, per wave
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
@@ -113,14 +113,14 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   const int la = lane >> 2, lc = lane & 3;
   const uint32_t lane_off = (uint32_t)(la * C * 2 + lc * 16);
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
-  uint4* kv = kv_all[wave];
-  const int wr_chunk = la * 4 + (lc ^ (((la >> 1) & 3) ^ ((la >> 3) & 1)));
-  const int rd_chunk = r * 4 + (g ^ (((r >> 1) & 3) ^ ((r >> 3) & 1)));
+  u32x4* kv = kv_all[wave];
+  const int wr_chunk = tile_chunk(la, lc);
+  const int rd_chunk = tile_chunk(r, g);
   const bf16_t* bias_strip = p.bias ? p.bias + (size_t)tok0 * p.H * K : nullptr;
 
   // loads of one head: the Q^T operand (lane (query r, channels 8g..8g+7)) and the bias of the items
-  auto load_head = [&](int h, Frag8& qf, uint32_t (&bw)[NT][EW]) {
-    qf.u4 = *reinterpret_cast<const uint4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(r * C + g * 8));
+  auto load_head = [&](int h, u32x4& qraw, uint32_t (&bw)[NT][EW]) {
+    qraw = *reinterpret_cast<const u32x4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8));
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       if (VEC) {
@@ -137,10 +137,14 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   };
   {
     Frag8 qf;
+    u32x4 qraw;
     uint32_t bw[NT][EW];
-    load_head(h, qf, bw);
+    load_head(h, qraw, bw);
     // first use of a loaded value: everything the strip streams in is in flight by now
     const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
+    kv[wr_chunk] = qraw;  // the q rows cross through LDS like the K/V rows
+    wave_lds_sync();
+    qf.x4 = kv[rd_chunk];
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
@@ -165,28 +169,28 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       wave_lds_sync();
 
       const int npairs = (nsl + 1) >> 1;
-      auto load_pair = [&](int pr, uint4& k0, uint4& v0, uint4& k1, uint4& v1) {
+      auto load_pair = [&](int pr, u32x4& k0, u32x4& v0, u32x4& k1, u32x4& v1) {
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
         const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
         const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
-        k0 = *reinterpret_cast<const uint4*>(kimg + base0 + lane_off);
-        v0 = *reinterpret_cast<const uint4*>(vimg + base0 + lane_off);
-        k1 = *reinterpret_cast<const uint4*>(kimg + base1 + lane_off);
-        v1 = *reinterpret_cast<const uint4*>(vimg + base1 + lane_off);
+        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + lane_off);
+        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + lane_off);
+        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + lane_off);
+        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + lane_off);
       };
       // pieces as loaded -> LDS -> operand pieces
-      auto stage_pair = [&](const uint4& k0, const uint4& v0, const uint4& k1, const uint4& v1, Frag8(&kf)[2],
+      auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],
                             Frag8(&vf)[2]) {
         kv[0 * 64 + wr_chunk] = k0;
         kv[1 * 64 + wr_chunk] = v0;
         kv[2 * 64 + wr_chunk] = k1;
         kv[3 * 64 + wr_chunk] = v1;
         wave_lds_sync();
-        kf[0].u4 = kv[0 * 64 + rd_chunk];
-        vf[0].u4 = kv[1 * 64 + rd_chunk];
-        kf[1].u4 = kv[2 * 64 + rd_chunk];
-        vf[1].u4 = kv[3 * 64 + rd_chunk];
+        kf[0].x4 = kv[0 * 64 + rd_chunk];
+        vf[0].x4 = kv[1 * 64 + rd_chunk];
+        kf[1].x4 = kv[2 * 64 + rd_chunk];
+        vf[1].x4 = kv[3 * 64 + rd_chunk];
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
         // a pass with an odd number of tiles repeats its last tile in the second half of the last pair;
@@ -242,7 +246,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       };
       // The loads of the next pair fly during this pair's math.  Every load sits in straight-line code: a
       // load under a condition would make the compiler wait for all outstanding loads where the paths join.
-      uint4 sk0, sv0, sk1, sv1;
+      u32x4 sk0, sv0, sk1, sv1;
       Frag8 kf[2], vf[2];
       load_pair(0, sk0, sv0, sk1, sv1);
       for (int pr = 0; pr + 1 < npairs; ++pr) {
@@ -278,13 +282,18 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
           acc[dt][i] = acc[dt][i] * alpha + pb * bf16_to_f32(p.v_blank[h * kD + dt * 16 + g * 4 + i]);
     }
     const float inv = 1.f / l_tot;
+    // out rows cross through LDS the other way: lane (query r, channels 16dt + 4g..+3) holds 8 bytes of
+    // 16-byte piece 2dt + g/2 of row r; lane (row lane/4, piece lane%4) stores 16 bytes
+    wave_lds_sync();
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt) {
       uint2 o;
       o.x = pack_bf16x2(acc[dt][0] * inv, acc[dt][1] * inv);
       o.y = pack_bf16x2(acc[dt][2] * inv, acc[dt][3] * inv);
-      *reinterpret_cast<uint2*>(p.out + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(r * C + dt * 16 + g * 4)) = o;
+      reinterpret_cast<uint2*>(kv)[tile_chunk(r, 2 * dt + (g >> 1)) * 2 + (g & 1)] = o;
     }
+    wave_lds_sync();
+    *reinterpret_cast<u32x4*>(p.out + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8)) = kv[wr_chunk];
     if (g == 0) (p.lse + (size_t)tok0 * p.H + h)[(uint32_t)(r * p.H)] = m_fin + __logf(l_tot);
   }
 }
