@@ -23,7 +23,7 @@
 namespace affmae {
 namespace {
 
-constexpr int kSlotCapB = 12;  // token tiles resident per wave: two bf16 tiles each (12 KB)
+constexpr int kSlotCapB = 10;  // token tiles resident per wave: two bf16 tiles each (10 KB); three workgroups per CU
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct BwdParams {
@@ -70,7 +70,7 @@ template <int NT, bool VEC>
 __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
-  __shared__ __align__(16) u32x4 kv_all[4][4 * 64];  // K and V rows of one pair of token tiles, per wave
+  __shared__ __align__(16) u32x4 kv_all[4][3 * 64];  // per wave: rows of two token tiles (K, then V), or the strip's q, dout, out
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
@@ -217,14 +217,16 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],
                             Frag8(&vf)[2]) {
         kv[0 * 64 + wr_chunk] = k0;
-        kv[1 * 64 + wr_chunk] = v0;
-        kv[2 * 64 + wr_chunk] = k1;
-        kv[3 * 64 + wr_chunk] = v1;
+        kv[1 * 64 + wr_chunk] = k1;
         wave_lds_sync();
         kf[0].x4 = kv[0 * 64 + rd_chunk];
-        vf[0].x4 = kv[1 * 64 + rd_chunk];
-        kf[1].x4 = kv[2 * 64 + rd_chunk];
-        vf[1].x4 = kv[3 * 64 + rd_chunk];
+        kf[1].x4 = kv[1 * 64 + rd_chunk];
+        wave_lds_sync();
+        kv[0 * 64 + wr_chunk] = v0;
+        kv[1 * 64 + wr_chunk] = v1;
+        wave_lds_sync();
+        vf[0].x4 = kv[0 * 64 + rd_chunk];
+        vf[1].x4 = kv[1 * 64 + rd_chunk];
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
         const bool has1 = 2 * pr + 1 < nsl;  // wave-uniform

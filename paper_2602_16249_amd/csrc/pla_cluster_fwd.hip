@@ -24,7 +24,7 @@
 namespace affmae {
 namespace {
 
-constexpr int kSlotCap = 16;  // token tiles whose bias tile is resident per wave (8 KB)
+constexpr int kSlotCap = 10;  // token tiles whose bias tile is resident per wave (5 KB): four workgroups per CU
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct FwdParams {
