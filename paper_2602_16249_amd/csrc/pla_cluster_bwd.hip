@@ -74,7 +74,10 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
-  const int sg = xcd_contiguous_block() * 4 + wave;
+  // one wave per (strip, head): the heads of a strip sit in neighbouring waves and share cache lines
+  const int unit = xcd_contiguous_block() * 4 + wave;
+  const int sg = unit / p.H;
+  const int h = unit - sg * p.H;
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier in this kernel
   bf16_t* dstile = ds_all[wave];  // holds the bias tile first, dS after a tile has been processed
   bf16_t* ptile = p_all[wave];
@@ -138,7 +141,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
     const int w = t * 2 * kWave + 2 * lane;
     sp[t] = (w < p.places) ? *reinterpret_cast<const uint32_t*>(p.sorted_pos + (size_t)sg * p.places + w) : 0xffffffffu;
   }
-  for (int h = 0; h < p.H; ++h) {
+  {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
     {  // the strip's rows cross through LDS like the K/V rows
       const size_t qrow = (size_t)(tok0 + la) * C + h * kD + lc * 8;
@@ -363,7 +366,7 @@ struct KeyItem {
 // HG = heads handled per sweep over the tile's list (2 when H is even: one walk of the list, one load of
 // the entry values and one pass over the q / dout rows serve both).
 template <int HG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_bwd_key_kernel(BwdParams p) {
   __shared__ __align__(16) uint32_t tile_all[4][HG * 256];  // per wave and head: (p, dS)[token][query]
   __shared__ __align__(16) u32x4 rows_all[4][2 * HG * 64];  // per wave: the strip's q rows, then its dout rows
   const int lane = threadIdx.x & (kWave - 1);
@@ -561,12 +564,13 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.ds = (bf16_t*)a.dbias;
 
   const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);  // multiple of 8 for the XCD-contiguous mapping
+  const dim3 grid_q((((long long)L.strips * a.H + 3) / 4 + 7) / 8 * 8);  // one wave per (strip, head)
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0) &&
                    (!p.ds || reinterpret_cast<uintptr_t>(p.ds) % 16 == 0);
 #define AFFMAE_BWDQ(KERNEL, NT) \
-  AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (KERNEL<NT>), grid, dim3(256), 0, stream, p)
+  AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (KERNEL<NT>), grid_q, dim3(256), 0, stream, p)
   if (vec) {
     if (2 * a.K <= kWave) AFFMAE_BWDQ(pla_bwd_query_kernel, 1); else AFFMAE_BWDQ(pla_bwd_query_kernel, 2);
   } else {

@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_e
   pla_fwd_cluster_body<NT, true>(p);
 }
 template <int NT>
-__global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void pla_fwd_cluster_scalar_kernel(FwdParams p) {
+__global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_fwd_cluster_scalar_kernel(FwdParams p) {
   pla_fwd_cluster_body<NT, false>(p);
 }
 
