@@ -45,8 +45,7 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=4, help="rotating copies of all tensors (defeats the 256 MB cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-promise", action="store_true", help="do not pass near_clusters (gather kernels)")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one 256 MiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3)")
+    ap.add_argument("--copy-probe", action="store_true", help="accepted for compatibility: the copy probe always runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over images with no exchange "
@@ -117,13 +116,20 @@ def main() -> int:
     for i in range(args.warmup):
         step(sets[i % len(sets)])
     torch.cuda.synchronize()
-    if args.copy_probe:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
-        dst = torch.empty_like(src)
+    # a plain 256 MiB device copy: the practical ceiling of this machine's HBM path (read + written bytes per
+    # second), and the dispatch of known size that calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    copy_ms = []
+    for _ in range(4):
+        c0, c1 = ev(), ev()
+        c0.record()
+        dst.copy_(src)
+        c1.record()
         torch.cuda.synchronize()
-        dst.copy_(src)  # 256 MiB read + 256 MiB written by a plain copy kernel
-        torch.cuda.synchronize()
-        del src, dst
+        copy_ms.append(c0.elapsed_time(c1))
+    copy_gbs = 2 * src.numel() / (min(copy_ms[1:]) * 1e-3) / 1e9
+    del src, dst
 
     # timed region: exactly `steps` steps, phase boundaries marked by events on the launch stream
     rec = []
@@ -197,6 +203,10 @@ def main() -> int:
         "algorithmic_bytes_per_token": {"fwd": fwd_b, "bwd": bwd_b},
         "attn_algorithmic_GBs": (fwd_b + bwd_b) * tokens / (attn_ms * 1e-3) / 1e9,
         "attn_frac_of_hbm_peak": (fwd_b + bwd_b) * tokens / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "copy_probe_GBs": copy_gbs,
+        "attn_counter_GBs": (sum(traffic_all[n] for n in attn_kernels) /
+                             (sum(v["avg_us"] for v in attn_kernels.values()) * 1e-6) / 1e9
+                             if attn_kernels and all(n in traffic_all for n in attn_kernels) else None),
         "kernels": kernels,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
