@@ -24,6 +24,7 @@ namespace affmae {
 namespace {
 
 constexpr int kSlotCapB = 10;  // token tiles resident per wave: two bf16 tiles each (10 KB); three workgroups per CU
+static_assert(kSlotCapB % 2 == 0, "an odd pass uses one more tile for the second half of its last pair");
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct BwdParams {
@@ -189,7 +190,8 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             bw[t][0] = (p.bias && item_live[t]) ? (uint32_t)p.bias[head_rows + item_off[t]] : 0u;
           }
         }
-        for (int s = 0; s < nsl; ++s)
+        // (an odd pass gets one more tile of -inf: the second half of its last pair, which repeats a tile)
+        for (int s = 0; s < nsl + (nsl & 1); ++s)
           *reinterpret_cast<uint2*>(dstile + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
         wave_lds_sync();
 #pragma unroll
@@ -232,11 +234,12 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         vf[1].x4 = kv[1 * 64 + rd_chunk];
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
-        const bool has1 = 2 * pr + 1 < nsl;  // wave-uniform
+        // A pass with an odd number of tiles repeats its last tile in the second half of the last pair, under
+        // a bias tile of -inf: p and dS come out 0 without a test.  The whole pair is one basic block.
         Frag8 dsf;  // dS^T operand: k-slots 0..3 = first tile's tokens 4g..4g+3, 4..7 = second tile's
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-          if (tt == 0 || has1) {
+          {
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             const f32x4 st = mfma32(kf[tt], qf, z);   // <k[token 4g+i], q[query r]>
             const f32x4 dpt = mfma32(vf[tt], gf, z);  // <v[token 4g+i], dout[query r]>
@@ -258,9 +261,6 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             *reinterpret_cast<uint2*>(cell) = dw;  // the bias of these cells is no longer needed
             dsf.u[2 * tt + 0] = dw.x;
             dsf.u[2 * tt + 1] = dw.y;
-          } else {
-            dsf.u[2 * tt + 0] = 0u;
-            dsf.u[2 * tt + 1] = 0u;
           }
         }
 #pragma unroll

@@ -25,6 +25,7 @@ namespace affmae {
 namespace {
 
 constexpr int kSlotCap = 10;  // token tiles whose bias tile is resident per wave (5 KB): four workgroups per CU
+static_assert(kSlotCap % 2 == 0, "an odd pass uses one more tile for the second half of its last pair");
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct FwdParams {
@@ -151,7 +152,8 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
     for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCap) {
       const int nsl = min(kSlotCap, ntiles - slot0);
       // bias tile: -inf everywhere, then the bias of the real (query, neighbour) pairs
-      for (int s = 0; s < nsl; ++s)
+      // (an odd pass gets one more tile of -inf: the second half of its last pair, which repeats a tile)
+      for (int s = 0; s < nsl + (nsl & 1); ++s)
         *reinterpret_cast<uint2*>(scratch + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
       wave_lds_sync();
       const uint32_t lo = (uint32_t)slot0 * 256u, span = (uint32_t)nsl * 256u;
@@ -193,20 +195,18 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         vf[1].x4 = kv[3 * 64 + rd_chunk];
       };
       auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
-        // a pass with an odd number of tiles repeats its last tile in the second half of the last pair;
-        // those scores are masked.  No branch here: the whole pair is one basic block.
-        const bool has1 = 2 * pr + 1 < nsl;
+        // a pass with an odd number of tiles repeats its last tile in the second half of the last pair, under
+        // a bias tile of -inf: its scores are -inf without a test.  The whole pair is one basic block.
         float s[8];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           f32x4 st = {0.f, 0.f, 0.f, 0.f};
           st = mfma32(kf[tt], qf, st);  // st[i] = <k[token 4g+i], q[query r]>
           const uint2 bm = *reinterpret_cast<const uint2*>(scratch + (2 * pr + tt) * 256 + r * 16 + g * 4);
-          const bool on = tt == 0 || has1;
-          s[4 * tt + 0] = on ? fmaf(st[0], p.scale, __uint_as_float(bm.x << 16)) : -INFINITY;
-          s[4 * tt + 1] = on ? fmaf(st[1], p.scale, __uint_as_float(bm.x & 0xffff0000u)) : -INFINITY;
-          s[4 * tt + 2] = on ? fmaf(st[2], p.scale, __uint_as_float(bm.y << 16)) : -INFINITY;
-          s[4 * tt + 3] = on ? fmaf(st[3], p.scale, __uint_as_float(bm.y & 0xffff0000u)) : -INFINITY;
+          s[4 * tt + 0] = fmaf(st[0], p.scale, __uint_as_float(bm.x << 16));
+          s[4 * tt + 1] = fmaf(st[1], p.scale, __uint_as_float(bm.x & 0xffff0000u));
+          s[4 * tt + 2] = fmaf(st[2], p.scale, __uint_as_float(bm.y << 16));
+          s[4 * tt + 3] = fmaf(st[3], p.scale, __uint_as_float(bm.y & 0xffff0000u));
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
         mx = group_max(mx);
