@@ -147,23 +147,35 @@ __global__ __launch_bounds__(256) void members_kernel(const int32_t* __restrict_
   }
 }
 
-// One thread per cluster: sequential double-precision sum in member order.
+// One wave per cluster: the lanes fetch the members' coordinates 64 at a time (coalesced), then every
+// lane forms the same sequential double-precision sum in member order from lane broadcasts.
 __global__ __launch_bounds__(256) void centroid_kernel(const float* __restrict__ coords,
                                                       const int32_t* __restrict__ members, int B, int N, int S,
                                                       int G, float* __restrict__ centroid) {
-  const int gc = blockIdx.x * blockDim.x + threadIdx.x;
-  if (gc >= B * G) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int gc = blockIdx.x * (blockDim.x / kWave) + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  if (gc >= B * G) return;  // wave-uniform
   const int b = gc / G, c = gc % G;
   const float* xy = coords + (size_t)b * N * 2;
   double sx = 0.0, sy = 0.0;
-  for (int r = 0; r < S; ++r) {
-    int tok = c * S + r;
-    if (members) tok = min(max(members[(size_t)b * N + tok], 0), N - 1);
-    sx += (double)xy[2 * (size_t)tok + 0];
-    sy += (double)xy[2 * (size_t)tok + 1];
+  for (int base = 0; base < S; base += kWave) {
+    const int n = min(kWave, S - base);
+    float x = 0.f, y = 0.f;
+    if (lane < n) {
+      int tok = c * S + base + lane;
+      if (members) tok = min(max(members[(size_t)b * N + tok], 0), N - 1);
+      x = xy[2 * (size_t)tok];
+      y = xy[2 * (size_t)tok + 1];
+    }
+    for (int r = 0; r < n; ++r) {
+      sx += (double)__uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), r));
+      sy += (double)__uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(y), r));
+    }
   }
-  centroid[2 * (size_t)gc + 0] = (float)(sx / (double)S);
-  centroid[2 * (size_t)gc + 1] = (float)(sy / (double)S);
+  if (lane == 0) {
+    centroid[2 * (size_t)gc + 0] = (float)(sx / (double)S);
+    centroid[2 * (size_t)gc + 1] = (float)(sy / (double)S);
+  }
 }
 
 // One wave per cluster: the M nearest centroids of the image, ascending.
@@ -397,7 +409,7 @@ hipError_t launch_knn(const KnnArgs& a, hipStream_t stream) {
     members = a.members;
   }
   const int BG = a.B * a.G;
-  AFFMAE_LAUNCH("centroid_kernel", stream, centroid_kernel, dim3((BG + 255) / 256), dim3(256), 0, stream, a.coords, members, a.B, a.N,
+  AFFMAE_LAUNCH("centroid_kernel", stream, centroid_kernel, dim3((BG + 3) / 4), dim3(256), 0, stream, a.coords, members, a.B, a.N,
                      a.S, a.G, a.centroid);
   AFFMAE_LAUNCH("near_kernel", stream, near_kernel, dim3((BG + 3) / 4), dim3(256), 0, stream, a.centroid, a.B, a.G, a.M,
                      a.near_clusters);

@@ -131,29 +131,47 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   for (int w = lane; w < p.places; w += kWave) sp[w] = sorted[w];
 }
 
-// Exclusive prefix sum of rev_count (one workgroup; n is at most a few hundred thousand).
-__global__ __launch_bounds__(1024) void plan_scan_kernel(const int32_t* __restrict__ count, int32_t* __restrict__ offset,
-                                                        int n) {
-  __shared__ int32_t part[1024];
-  const int tid = threadIdx.x;
-  const int per = (n + 1023) / 1024;
-  const int lo = min(tid * per, n), hi = min(lo + per, n);
-  int sum = 0;
-  for (int i = lo; i < hi; ++i) sum += count[i];
-  part[tid] = sum;
+// Exclusive prefix sum of rev_count.  Workgroup j owns elements [1024 j, 1024 j + 1024): it first adds up
+// everything before them (coalesced reads of a few hundred KB at most, all from L2), then scans its own.
+// No workgroup waits for another.
+__global__ __launch_bounds__(256) void plan_scan_kernel(const int32_t* __restrict__ count, int32_t* __restrict__ offset,
+                                                       int n) {
+  __shared__ int32_t part[4];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int first = blockIdx.x * 1024;
+  int before = 0;
+  for (int i = tid * 4; i < first; i += 1024) {  // first is a multiple of 1024: whole 16-byte pieces
+    const int4 v = *reinterpret_cast<const int4*>(count + i);
+    before += v.x + v.y + v.z + v.w;
+  }
+  // this thread's four elements
+  const int at = first + tid * 4;
+  int c[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) c[i] = (at + i < n) ? count[at + i] : 0;
+  const int mine = c[0] + c[1] + c[2] + c[3];
+  // wave-inclusive scan of (mine) and wave sum of (before)
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
+  if (lane == kWave - 1) part[wave] = incl;
+  __shared__ int32_t before_all[4];
+  if (lane == 0) before_all[wave] = before;
   __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    int v = (tid >= o) ? part[tid - o] : 0;
-    __syncthreads();
-    part[tid] += v;
-    __syncthreads();
+  int base = before_all[0] + before_all[1] + before_all[2] + before_all[3];
+  for (int w = 0; w < wave; ++w) base += part[w];
+  int run = base + incl - mine;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (at + i < n) offset[at + i] = run;
+    run += c[i];
   }
-  int run = part[tid] - sum;
-  for (int i = lo; i < hi; ++i) {
-    offset[i] = run;
-    run += count[i];
-  }
-  if (tid == 1023) offset[n] = part[1023];
+  if (at <= n - 1 && n - 1 < at + 4) offset[n] = run;  // the thread that owns the last element: run is the total
 }
 
 // Every strip appends itself to the list of each token tile it touches.
@@ -225,8 +243,8 @@ hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, i
   AFFMAE_LAUNCH("plan_zero_kernel", stream, plan_zero_kernel, dim3((L.strips + 255) / 256), dim3(256), 0, stream,
                 p.rev_count, p.rev_cursor, L.strips);
   AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel, per_strip, dim3(256), 0, stream, p);
-  AFFMAE_LAUNCH("plan_scan_kernel", stream, plan_scan_kernel, dim3(1), dim3(1024), 0, stream, p.rev_count,
-                p.rev_offset, L.strips);
+  AFFMAE_LAUNCH("plan_scan_kernel", stream, plan_scan_kernel, dim3((L.strips + 1023) / 1024), dim3(256), 0, stream,
+                p.rev_count, p.rev_offset, L.strips);
   AFFMAE_LAUNCH("plan_fill_kernel", stream, plan_fill_kernel, per_strip, dim3(256), 0, stream, p);
   AFFMAE_LAUNCH("plan_sort_kernel", stream, plan_sort_kernel, per_strip, dim3(256), 0, stream, p);
   return hipGetLastError();
