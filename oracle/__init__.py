@@ -38,7 +38,7 @@ def _load():
     if _lib is None:
         build()
         _lib = ctypes.CDLL(_LIB)
-        for name in ("oracle_centroids", "oracle_knn", "oracle_knn_bruteforce",
+        for name in ("oracle_centroids", "oracle_knn", "oracle_knn_bruteforce", "oracle_cluster",
                      "oracle_pla_fwd", "oracle_pla_bwd", "oracle_num_threads"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_set_num_threads.restype = None
@@ -69,6 +69,20 @@ def num_threads() -> int:
 
 def set_num_threads(n: int) -> None:
     _load().oracle_set_num_threads(ctypes.c_int(int(n)))
+
+
+def cluster(coords: np.ndarray, S: int, frame: Tuple[float, float, float, float]) -> Tuple[np.ndarray, np.ndarray]:
+    """Balanced clustering along the Z-order curve of `frame` = (x0, y0, w, h)
+    -> (order [B,N]: token at each place of the curve, cluster_id [B,N]: place // S per token)."""
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    B, N, two = coords.shape
+    assert two == 2
+    x0, y0, w, h = (float(t) for t in frame)
+    order = np.empty((B, N), dtype=np.int32)
+    cid = np.empty((B, N), dtype=np.int32)
+    _check(_load().oracle_cluster(_p(coords), B, N, int(S), ctypes.c_double(x0), ctypes.c_double(y0),
+                                  ctypes.c_double(w), ctypes.c_double(h), _p(order), _p(cid)), "oracle_cluster")
+    return order, cid
 
 
 def centroids(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int) -> np.ndarray:

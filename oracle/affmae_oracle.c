@@ -26,7 +26,12 @@
  *     being the fp32 rounding of the double-precision mean of the members taken
  *     in ascending token order; the cluster itself is included;
  *   - a token is a candidate for its own neighbourhood;
- *   - an explicit logit scale multiplies Q K^T; the blank column has no bias.
+ *   - an explicit logit scale multiplies Q K^T; the blank column has no bias;
+ *   - balanced clustering (oracle_cluster): the paper groups tokens into
+ *     equal-size clusters with a space-filling curve it does not name; reading:
+ *     Z-order (Morton) curve over coordinates quantised to 16 bits per axis of a
+ *     caller-given frame, x in the even key bits, ties by token index, clusters
+ *     = consecutive runs of S tokens along the curve (the last may be short).
  *
  * Parity pins (tests/test_oracle_*.py): brute force over all pairs with a
  * library sort, hand-derived grid fixtures, exact integer arithmetic on integer
@@ -147,6 +152,68 @@ int oracle_centroids(const float *coords, const int32_t *cluster_id, int B, int 
   }
   free(members);
   return rc;
+}
+
+/*
+ * oracle_cluster: balanced clustering along a Z-order curve (Sec.
+ * "AutoFocusFormer": tokens are grouped into equal-size clusters by a
+ * space-filling-curve procedure).
+ *   coords [B,N,2] fp32; frame = [x0, x0 + w) x [y0, y0 + h), w, h > 0.
+ *   A coordinate is quantised in double precision to
+ *       floor((x - x0) / w * 65536), clamped to 0..65535,
+ *   the key of a token takes bit i of the quantised x as bit 2i and bit i of the
+ *   quantised y as bit 2i + 1, and tokens are ordered by (key, token index).
+ *   order [B,N]:      order[b][p] = the token at place p along the curve;
+ *   cluster_id [B,N]: cluster_id[b][order[b][p]] = p / S  (may be NULL).
+ */
+typedef struct {
+  uint32_t key;
+  int32_t idx;
+} curve_t;
+
+static int curve_less(const void *pa, const void *pb) {
+  const curve_t *a = (const curve_t *)pa, *b = (const curve_t *)pb;
+  if (a->key != b->key) return a->key < b->key ? -1 : 1;
+  if (a->idx != b->idx) return a->idx < b->idx ? -1 : 1;
+  return 0;
+}
+
+static uint32_t quantise16(double x, double x0, double w) {
+  double q = floor((x - x0) / w * 65536.0);
+  if (q < 0.0) q = 0.0;
+  if (q > 65535.0) q = 65535.0;
+  return (uint32_t)q;
+}
+
+int oracle_cluster(const float *coords, int B, int N, int S, double x0, double y0, double w, double h,
+                   int32_t *order, int32_t *cluster_id) {
+  if (!coords || !order || B < 0 || N <= 0 || S <= 0 || !(w > 0.0) || !(h > 0.0)) return ORACLE_ERR_ARG;
+  int status = ORACLE_OK;
+  for (int b = 0; b < B; ++b) {
+    curve_t *c = (curve_t *)malloc((size_t)N * sizeof(curve_t));
+    if (!c) {
+      status = ORACLE_ERR_ALLOC;
+      break;
+    }
+    for (int i = 0; i < N; ++i) {
+      const uint32_t qx = quantise16((double)coords[((size_t)b * N + i) * 2 + 0], x0, w);
+      const uint32_t qy = quantise16((double)coords[((size_t)b * N + i) * 2 + 1], y0, h);
+      uint32_t key = 0;
+      for (int bit = 0; bit < 16; ++bit) {
+        key |= ((qx >> bit) & 1u) << (2 * bit);
+        key |= ((qy >> bit) & 1u) << (2 * bit + 1);
+      }
+      c[i].key = key;
+      c[i].idx = i;
+    }
+    qsort(c, (size_t)N, sizeof(curve_t), curve_less);
+    for (int p = 0; p < N; ++p) {
+      order[(size_t)b * N + p] = c[p].idx;
+      if (cluster_id) cluster_id[(size_t)b * N + c[p].idx] = p / S;
+    }
+    free(c);
+  }
+  return status;
 }
 
 /*
