@@ -2,8 +2,8 @@
 """Benchmark of the neighbourhood-attention hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic tokens that are
-already resident in HBM: affmae_knn (neighbour table) -> affmae_pla_fwd ->
-affmae_pla_bwd.  The headline value is attention forward+backward tokens/s (the
+already resident in HBM: affmae_cluster (curve order and clusters) -> affmae_knn
+(neighbour table) -> affmae_pla_plan -> affmae_pla_fwd -> affmae_pla_bwd.  The headline value is attention forward+backward tokens/s (the
 table is built once per encoder stage and reused by every block, so the search
 is also reported on its own).  Prints ONE JSON line.
 
@@ -80,12 +80,16 @@ def main() -> int:
         s["out"] = torch.empty_like(s["q"])
         s["lse"] = torch.empty((cfg.B, cfg.N, cfg.H), dtype=torch.float32, device=dev)
         s["plan"] = None
+        s["order"] = torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=dev)
+        s["cid"] = torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=dev)
         s["grads"] = {"dq": torch.empty_like(s["q"]), "dk": torch.empty_like(s["q"]), "dv": torch.empty_like(s["q"]),
                       "dbias": torch.empty_like(s["bias"])}
         sets.append(s)
     lib = aff.load_library()
     code = 1 if cfg.dtype == "bf16" else 0
-    ws_bytes = max(lib.affmae_knn_workspace_bytes(cfg.B, cfg.N, cfg.S, cfg.M, cfg.K),
+    frame = (0.0, 0.0, float(cfg.frame), float(cfg.frame))
+    ws_bytes = max(lib.affmae_cluster_workspace_bytes(cfg.B, cfg.N),
+                   lib.affmae_knn_workspace_bytes(cfg.B, cfg.N, cfg.S, cfg.M, cfg.K),
                    lib.affmae_pla_fwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
                    lib.affmae_pla_bwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
                    256)
@@ -96,7 +100,11 @@ def main() -> int:
         return torch.cuda.Event(enable_timing=True)
 
     def step(s, rec=None):
-        e = [ev() for _ in range(4)] if rec is not None else None
+        e = [ev() for _ in range(5)] if rec is not None else None
+        if e: e[4].record()
+        # the generator hands the tokens over in curve order already: the clustering returns the identity
+        # (its sorting network does the same work for any input), so nothing has to be gathered here
+        aff.affmae_cluster(s["coords"], cfg.S, frame, order=s["order"], cluster_id=s["cid"], workspace=s["ws"])
         if e: e[0].record()
         aff.affmae_knn(s["coords"], None, cfg.S, cfg.M, cfg.K, nbr_idx=s["nbr"], near_clusters=s["near"],
                        workspace=s["ws"])
@@ -139,6 +147,7 @@ def main() -> int:
         step(sets[i % len(sets)], rec)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    cluster_ms = float(np.mean([e[4].elapsed_time(e[0]) for e in rec]))
     knn_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in rec]))
     fwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in rec]))
     bwd_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in rec]))
@@ -196,8 +205,10 @@ def main() -> int:
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "N": cfg.N, "C": cfg.C, "H": cfg.H, "K": cfg.K, "S": cfg.S,
                    "M": cfg.M, "coords": cfg.coords, "cluster_promise": promise, "rotating_sets": len(sets),
-                   "step": "affmae_knn + affmae_pla_plan + affmae_pla_fwd + affmae_pla_bwd; value counts fwd+bwd only"},
-        "phases_ms": {"knn": knn_ms, "fwd": fwd_ms, "bwd": bwd_ms},
+                   "step": "affmae_cluster + affmae_knn + affmae_pla_plan + affmae_pla_fwd + affmae_pla_bwd; "
+                           "value counts fwd+bwd only"},
+        "phases_ms": {"cluster": cluster_ms, "knn": knn_ms, "fwd": fwd_ms, "bwd": bwd_ms},
+        "cluster_tokens_per_s": tokens / (cluster_ms * 1e-3),
         "knn_tokens_per_s": tokens / (knn_ms * 1e-3),
         "step_tokens_per_s": tokens / (wall / args.steps),
         "algorithmic_bytes_per_token": {"fwd": fwd_b, "bwd": bwd_b},

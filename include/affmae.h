@@ -2,9 +2,10 @@
  * affmae.h - C ABI of the MI355X (gfx950) neighbourhood-attention library.
  *
  * The library implements the data-parallel hot path of AFFMAE's off-grid
- * hierarchical backbone: the batched neighbour search that builds fixed-size
- * neighbourhoods over irregular 2-D token coordinates, and local attention,
- * forward and backward, over each token's K neighbours.
+ * hierarchical backbone: balanced clustering of the tokens along a space-filling
+ * curve, the batched neighbour search that builds fixed-size neighbourhoods over
+ * irregular 2-D token coordinates, and local attention, forward and backward,
+ * over each token's K neighbours.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library
@@ -58,6 +59,36 @@ const char* affmae_status_string(int status);
 
 /* Library version as major*10000 + minor*100 + patch. */
 int affmae_version(void);
+
+/*
+ * affmae_cluster - balanced clustering (paper, Sec. "AutoFocusFormer": tokens
+ * are grouped into equal-size clusters by a space-filling-curve procedure).
+ * The paper does not name the curve; this library orders the tokens of an image
+ * along the Z-order (Morton) curve of a caller-given frame and cuts the order
+ * into consecutive clusters of S tokens (the last one is smaller when S does
+ * not divide N).  A coordinate is quantised in double precision to
+ * floor((x - x0) / w * 65536) clamped to 0..65535 (likewise y with y0, h); the
+ * key of a token interleaves the two 16-bit values, x in the even bits; tokens
+ * are ordered by (key, token index), so the result is unique.
+ *
+ *   coords      in  [B,N,2] fp32 (x, y), finite
+ *   x0,y0,w,h   the frame [x0, x0+w) x [y0, y0+h), w, h > 0; points outside it
+ *               fall into its border cells
+ *   order       out [B,N] int32: order[b][p] = the token at place p of the curve.
+ *               Gathering every per-token tensor with it puts the tokens in
+ *               cluster order, the layout affmae_knn takes with cluster_id = NULL
+ *               and the tiled attention kernels need.
+ *   cluster_id  out [B,N] int32 or NULL: the cluster of every token of the
+ *               original order (its place / S); usable as affmae_knn's
+ *               cluster_id when S divides N.
+ *   workspace   affmae_cluster_workspace_bytes(B, N) bytes
+ *
+ * Errors: AFFMAE_ERR_NULL (coords, order), AFFMAE_ERR_SHAPE (B, N, S < 1; empty
+ * or non-finite frame), AFFMAE_ERR_UNSUPPORTED (N > 2^24), AFFMAE_ERR_WORKSPACE.
+ */
+size_t affmae_cluster_workspace_bytes(int B, int N);
+int affmae_cluster(const float* coords, int B, int N, int S, double x0, double y0, double w, double h,
+                   int32_t* order, int32_t* cluster_id, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * affmae_knn - neighbourhood construction (paper, Sec. "AutoFocusFormer":

@@ -7,6 +7,7 @@ PyTorch fallback: without the built library every call raises.
 """
 from .binding import (  # noqa: F401
     AffmaeError,
+    affmae_cluster,
     affmae_knn,
     affmae_pla_bwd,
     affmae_pla_fwd,
@@ -19,5 +20,5 @@ from .binding import (  # noqa: F401
     timing_reset,
 )
 
-__all__ = ["AffmaeError", "affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd", "affmae_pla_plan", "library_path", "load_library",
+__all__ = ["AffmaeError", "affmae_cluster", "affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd", "affmae_pla_plan", "library_path", "load_library",
            "status_string"]

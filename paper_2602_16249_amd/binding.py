@@ -47,6 +47,11 @@ def load_library():
     lib.affmae_status_string.restype = ctypes.c_char_p
     lib.affmae_status_string.argtypes = [_c_int]
     lib.affmae_version.restype = _c_int
+    lib.affmae_cluster_workspace_bytes.restype = _c_size_t
+    lib.affmae_cluster_workspace_bytes.argtypes = [_c_int] * 2
+    lib.affmae_cluster.restype = _c_int
+    lib.affmae_cluster.argtypes = ([_c_void_p] + [_c_int] * 3 + [ctypes.c_double] * 4
+                                   + [_c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p])
     lib.affmae_knn_workspace_bytes.restype = _c_size_t
     lib.affmae_knn_workspace_bytes.argtypes = [_c_int] * 5
     lib.affmae_knn.restype = _c_int
@@ -106,6 +111,33 @@ def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.bfloat16:
         return AFFMAE_BF16
     raise ValueError(f"unsupported storage dtype {t.dtype}")
+
+
+def affmae_cluster(coords: torch.Tensor, S: int, frame: Tuple[float, float, float, float],
+                   order: Optional[torch.Tensor] = None, cluster_id: Optional[torch.Tensor] = None,
+                   workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """coords [B,N,2] fp32, frame (x0, y0, w, h) -> (order [B,N]: token at each place of the Z-order curve,
+    cluster_id [B,N]: place // S of every token)."""
+    lib = load_library()
+    _dev(coords, "coords", torch.float32)
+    B, N, two = coords.shape
+    if two != 2:
+        raise ValueError("coords must be [B,N,2]")
+    if order is None:
+        order = torch.empty((B, N), dtype=torch.int32, device=coords.device)
+    if cluster_id is None:
+        cluster_id = torch.empty((B, N), dtype=torch.int32, device=coords.device)
+    _dev(order, "order", torch.int32, (B, N))
+    _dev(cluster_id, "cluster_id", torch.int32, (B, N))
+    need = lib.affmae_cluster_workspace_bytes(B, N)
+    if workspace is None:
+        workspace = _workspace(max(need, 256), coords.device)
+    x0, y0, w, h = (float(t) for t in frame)
+    rc = lib.affmae_cluster(_ptr(coords), B, N, int(S), x0, y0, w, h, _ptr(order), _ptr(cluster_id),
+                            _ptr(workspace), workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_cluster", rc)
+    return order, cluster_id
 
 
 def affmae_knn(coords: torch.Tensor, cluster_id: Optional[torch.Tensor], S: int, M: int, K: int,

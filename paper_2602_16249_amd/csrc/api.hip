@@ -78,6 +78,27 @@ const char* affmae_status_string(int status) {
 
 int affmae_version(void) { return 100; }
 
+size_t affmae_cluster_workspace_bytes(int B, int N) {
+  if (B < 1 || N < 1 || N > (1 << 24)) return 0;
+  return align_up(affmae::cluster_workspace_bytes(B, N));
+}
+
+int affmae_cluster(const float* coords, int B, int N, int S, double x0, double y0, double w, double h,
+                   int32_t* order, int32_t* cluster_id, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!coords || !order) return AFFMAE_ERR_NULL;
+  if (B < 1 || N < 1 || S < 1) return AFFMAE_ERR_SHAPE;
+  if (!(w > 0.0) || !(h > 0.0) || !(w < 1e300) || !(h < 1e300) || !(x0 > -1e300 && x0 < 1e300) ||
+      !(y0 > -1e300 && y0 < 1e300))
+    return AFFMAE_ERR_SHAPE;  // the frame must be finite and non-empty
+  if (N > (1 << 24)) return AFFMAE_ERR_UNSUPPORTED;
+  const size_t need = align_up(affmae::cluster_workspace_bytes(B, N));
+  if (!workspace || workspace_bytes < need || misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
+  return affmae::launch_cluster(coords, B, N, S, x0, y0, w, h, order, cluster_id, workspace,
+                                static_cast<hipStream_t>(stream)) == hipSuccess
+             ? AFFMAE_OK
+             : AFFMAE_ERR_DEVICE;
+}
+
 size_t affmae_knn_workspace_bytes(int B, int N, int S, int M, int K) {
   if (check_knn_shape(B, N, S, M, K) != AFFMAE_OK) return 0;
   return knn_plan(B, N, S, M).total;

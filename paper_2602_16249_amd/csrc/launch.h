@@ -20,6 +20,11 @@ struct KnnArgs {
 };
 hipError_t launch_knn(const KnnArgs& a, hipStream_t stream);
 
+// Balanced clustering along a Z-order curve.
+size_t cluster_workspace_bytes(int B, int N);
+hipError_t launch_cluster(const float* coords, int B, int N, int S, double x0, double y0, double w, double h,
+                          int32_t* order, int32_t* cluster_id, void* workspace, hipStream_t stream);
+
 struct PlaArgs {
   const void *q, *k, *v, *bias;
   const int32_t* nbr_idx;

@@ -46,6 +46,26 @@ def test_knn_rejects_bad_arguments_on_host():
     assert lib.affmae_knn_workspace_bytes(1, 65, 8, 2, 4) == 0
 
 
+def test_cluster_rejects_bad_arguments_on_host():
+    lib = aff.load_library()
+    lib.affmae_cluster.argtypes = ([ctypes.c_void_p] + [ctypes.c_int] * 3 + [ctypes.c_double] * 4 +
+                                   [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p])
+    one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    big = 1 << 20
+    assert lib.affmae_cluster(None, 1, 64, 8, 0.0, 0.0, 1.0, 1.0, one, None, one, big, None) == -1
+    assert lib.affmae_cluster(one, 1, 64, 8, 0.0, 0.0, 1.0, 1.0, None, None, one, big, None) == -1
+    assert lib.affmae_cluster(one, 1, 0, 8, 0.0, 0.0, 1.0, 1.0, one, None, one, big, None) == -2
+    assert lib.affmae_cluster(one, 1, 64, 0, 0.0, 0.0, 1.0, 1.0, one, None, one, big, None) == -2
+    assert lib.affmae_cluster(one, 1, 64, 8, 0.0, 0.0, 0.0, 1.0, one, None, one, big, None) == -2     # empty frame
+    assert lib.affmae_cluster(one, 1, 64, 8, 0.0, 0.0, 1.0, float("nan"), one, None, one, big, None) == -2
+    assert lib.affmae_cluster(one, 1, 64, 8, float("inf"), 0.0, 1.0, 1.0, one, None, one, big, None) == -2
+    assert lib.affmae_cluster(one, 1, (1 << 24) + 1, 8, 0.0, 0.0, 1.0, 1.0, one, None, one, big, None) == -5
+    assert lib.affmae_cluster(one, 1, 64, 8, 0.0, 0.0, 1.0, 1.0, one, None, None, 0, None) == -4
+    assert lib.affmae_cluster(one, 1, 64, 8, 0.0, 0.0, 1.0, 1.0, one, None, one, 16, None) == -4
+    assert lib.affmae_cluster_workspace_bytes(2, 100) == 2 * 128 * 8
+    assert lib.affmae_cluster_workspace_bytes(0, 100) == 0
+
+
 def test_attention_rejects_bad_arguments_on_host():
     lib = aff.load_library()
     p = ctypes.c_void_p(4096)
