@@ -54,20 +54,50 @@ __device__ __forceinline__ word_t token_word(const ClusterParams& p, int b, int 
   return ((word_t)key << 32) | (word_t)(uint32_t)i;
 }
 
-// One compare-exchange step (k, j) of the bitonic network on a chunk held in LDS.  `first` is the global
-// position of the chunk's first word (it decides the direction of every pair).
-__device__ __forceinline__ void lds_step(word_t* buf, int n, int first, int k, int j) {
-  for (int t = threadIdx.x; t < n / 2; t += blockDim.x) {
-    const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-    const int partner = i | j;
-    const word_t a = buf[i], c = buf[partner];
-    const bool ascending = ((first + i) & k) == 0;
-    if ((a > c) == ascending) {
-      buf[i] = c;
-      buf[partner] = a;
+// R consecutive compare-exchange steps (k, J), (k, J/2), ... of the bitonic network on a chunk held in LDS, in one
+// trip through LDS: a thread takes the 2^R words that these steps connect (strides J .. J >> (R-1)), exchanges
+// them in registers and writes them back.  `first` is the global position of the chunk's first word (it
+// decides the direction, which is the same for all words of a group because k > J).
+// Place of word w in the LDS chunk: the XOR spreads every access pattern of the passes below over all
+// banks (a thread's 2^R words with stride 1, 2 or 4 would otherwise fall on a few banks).
+__device__ __forceinline__ int lds_place(int w) { return w ^ ((w >> 3) & 31); }
+
+template <int R>
+__device__ __forceinline__ void lds_pass(word_t* buf, int n, int first, int k, int J) {
+  const int low = J >> (R - 1);
+  for (int t = threadIdx.x; t < (n >> R); t += blockDim.x) {
+    const int i0 = ((t & ~(low - 1)) << R) | (t & (low - 1));
+    word_t v[1 << R];
+#pragma unroll
+    for (int m = 0; m < (1 << R); ++m) v[m] = buf[lds_place(i0 + m * low)];
+    const bool ascending = ((first + i0) & k) == 0;
+#pragma unroll
+    for (int bit = R - 1; bit >= 0; --bit) {
+#pragma unroll
+      for (int m = 0; m < (1 << R); ++m) {
+        if (!((m >> bit) & 1)) {
+          const word_t a = v[m], c = v[m | (1 << bit)];
+          const bool swap = (a > c) == ascending;
+          v[m] = swap ? c : a;
+          v[m | (1 << bit)] = swap ? a : c;
+        }
+      }
     }
+#pragma unroll
+    for (int m = 0; m < (1 << R); ++m) buf[lds_place(i0 + m * low)] = v[m];
   }
   __syncthreads();
+}
+
+// The steps j = J, J/2, ..., 1 of stage k, three at a time.
+__device__ __forceinline__ void lds_steps(word_t* buf, int n, int first, int k, int J) {
+  int j = J;
+  while (j >= 4) {
+    lds_pass<3>(buf, n, first, k, j);
+    j >>= 3;
+  }
+  if (j == 2) lds_pass<2>(buf, n, first, k, 2);
+  else if (j == 1) lds_pass<1>(buf, n, first, k, 1);
 }
 
 // Builds the words of one chunk and sorts it: all steps with k <= chunk size.
@@ -76,12 +106,11 @@ __global__ __launch_bounds__(kSortThreads) void cluster_sort_chunk_kernel(Cluste
   const int chunks_per_image = p.npad / chunk;
   const int b = blockIdx.x / chunks_per_image, c = blockIdx.x % chunks_per_image;
   const int first = c * chunk;
-  for (int t = threadIdx.x; t < chunk; t += blockDim.x) buf[t] = token_word(p, b, first + t);
+  for (int t = threadIdx.x; t < chunk; t += blockDim.x) buf[lds_place(t)] = token_word(p, b, first + t);
   __syncthreads();
-  for (int k = 2; k <= chunk; k <<= 1)
-    for (int j = k >> 1; j > 0; j >>= 1) lds_step(buf, chunk, first, k, j);
+  for (int k = 2; k <= chunk; k <<= 1) lds_steps(buf, chunk, first, k, k >> 1);
   word_t* out = p.words + (size_t)b * p.npad + first;
-  for (int t = threadIdx.x; t < chunk; t += blockDim.x) out[t] = buf[t];
+  for (int t = threadIdx.x; t < chunk; t += blockDim.x) out[t] = buf[lds_place(t)];
 }
 
 // Step (k, j) with j >= chunk size: partners sit in different chunks.
@@ -108,10 +137,10 @@ __global__ __launch_bounds__(kSortThreads) void cluster_merge_chunk_kernel(Clust
   const int b = blockIdx.x / chunks_per_image, c = blockIdx.x % chunks_per_image;
   const int first = c * chunk;
   word_t* io = p.words + (size_t)b * p.npad + first;
-  for (int t = threadIdx.x; t < chunk; t += blockDim.x) buf[t] = io[t];
+  for (int t = threadIdx.x; t < chunk; t += blockDim.x) buf[lds_place(t)] = io[t];
   __syncthreads();
-  for (int j = chunk >> 1; j > 0; j >>= 1) lds_step(buf, chunk, first, k, j);
-  for (int t = threadIdx.x; t < chunk; t += blockDim.x) io[t] = buf[t];
+  lds_steps(buf, chunk, first, k, chunk >> 1);
+  for (int t = threadIdx.x; t < chunk; t += blockDim.x) io[t] = buf[lds_place(t)];
 }
 
 __global__ __launch_bounds__(256) void cluster_emit_kernel(ClusterParams p) {
