@@ -38,7 +38,7 @@ def _load():
     if _lib is None:
         build()
         _lib = ctypes.CDLL(_LIB)
-        for name in ("oracle_centroids", "oracle_knn", "oracle_knn_bruteforce", "oracle_cluster",
+        for name in ("oracle_centroids", "oracle_knn", "oracle_knn_bruteforce", "oracle_cluster", "oracle_vts_table", "oracle_vts_fwd", "oracle_vts_bwd",
                      "oracle_pla_fwd", "oracle_pla_bwd", "oracle_num_threads"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_set_num_threads.restype = None
@@ -83,6 +83,58 @@ def cluster(coords: np.ndarray, S: int, frame: Tuple[float, float, float, float]
     _check(_load().oracle_cluster(_p(coords), B, N, int(S), ctypes.c_double(x0), ctypes.c_double(y0),
                                   ctypes.c_double(w), ctypes.c_double(h), _p(order), _p(cid)), "oracle_cluster")
     return order, cid
+
+
+def _grid_args(grid):
+    Hg, Wg, x0, y0, cell = grid
+    return int(Hg), int(Wg), ctypes.c_float(x0), ctypes.c_float(y0), ctypes.c_float(cell)
+
+
+def vts_table(vis_xy: np.ndarray, grid, Kt: int) -> np.ndarray:
+    """Nearest-visible-token table of the patch grid `grid` = (Hg, Wg, x0, y0, cell) -> [B,Hg,Wg,Kt] int32."""
+    vis_xy = np.ascontiguousarray(vis_xy, dtype=np.float32)
+    B, Nv, _ = vis_xy.shape
+    Hg, Wg, x0, y0, cell = _grid_args(grid)
+    table = np.empty((B, Hg, Wg, Kt), dtype=np.int32)
+    _check(_load().oracle_vts_table(_p(vis_xy), B, Nv, Hg, Wg, x0, y0, cell, int(Kt), _p(table)), "oracle_vts_table")
+    return table
+
+
+def vts_fwd(query_xy, vis_xy, feat, table, grid, p: float, eps: float, want_weights: bool = False):
+    """Virtual sampled tokens -> out [B,Mq,C] (and the weights [B,Mq,Kt])."""
+    query_xy = np.ascontiguousarray(query_xy, dtype=np.float32)
+    vis_xy = np.ascontiguousarray(vis_xy, dtype=np.float32)
+    feat = _f64(feat)
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    B, Mq, _ = query_xy.shape
+    _, Nv, C = feat.shape
+    Kt = table.shape[-1]
+    Hg, Wg, x0, y0, cell = _grid_args(grid)
+    out = np.empty((B, Mq, C), dtype=np.float64)
+    w = np.empty((B, Mq, Kt), dtype=np.float64) if want_weights else None
+    _check(_load().oracle_vts_fwd(_p(query_xy), _p(vis_xy), _p(feat), _p(table), B, Mq, Nv, C, Hg, Wg, x0, y0, cell,
+                                  Kt, ctypes.c_double(p), ctypes.c_double(eps), _p(out), _p(w)), "oracle_vts_fwd")
+    return (out, w) if want_weights else out
+
+
+def vts_bwd(query_xy, vis_xy, feat, table, dout, grid, p: float, eps: float):
+    """Backward of vts_fwd -> dict(dfeat [B,Nv,C], dquery [B,Mq,2], dp float)."""
+    query_xy = np.ascontiguousarray(query_xy, dtype=np.float32)
+    vis_xy = np.ascontiguousarray(vis_xy, dtype=np.float32)
+    feat = _f64(feat)
+    dout = _f64(dout)
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    B, Mq, _ = query_xy.shape
+    _, Nv, C = feat.shape
+    Kt = table.shape[-1]
+    Hg, Wg, x0, y0, cell = _grid_args(grid)
+    dfeat = np.empty((B, Nv, C), dtype=np.float64)
+    dq = np.empty((B, Mq, 2), dtype=np.float64)
+    dp = ctypes.c_double(0.0)
+    _check(_load().oracle_vts_bwd(_p(query_xy), _p(vis_xy), _p(feat), _p(table), _p(dout), B, Mq, Nv, C, Hg, Wg, x0, y0,
+                                  cell, Kt, ctypes.c_double(p), ctypes.c_double(eps), _p(dfeat), _p(dq),
+                                  ctypes.byref(dp)), "oracle_vts_bwd")
+    return {"dfeat": dfeat, "dquery": dq, "dp": float(dp.value)}
 
 
 def centroids(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int) -> np.ndarray:

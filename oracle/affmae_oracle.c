@@ -27,6 +27,17 @@
  *     in ascending token order; the cluster itself is included;
  *   - a token is a candidate for its own neighbourhood;
  *   - an explicit logit scale multiplies Q K^T; the blank column has no bias;
+ *   - virtual sampled tokens of the point decoder (oracle_vts_*): Sec.
+ *     "AFFMAE" (the exponential distance kernel softmax_i(-p d_i), d_i =
+ *     |q - x_i| + eps, and the weighted sum of the K nearest visible tokens'
+ *     features) and Sec. "Flash-style Cluster Attention and Fast Decoder KNN" /
+ *     supplement "Point-based decoder" (a cached table over the dense patch grid
+ *     holds, per grid point, the nearest visible tokens; a query is rounded to
+ *     its nearest grid point and takes that entry).  Readings: grid points are
+ *     the patch centres x0 + (ix + 1/2) cell evaluated in fp32; "nearest grid
+ *     point" = the cell that contains the query, floor((qx - x0) / cell) in
+ *     fp32, clamped to the grid; the table orders by (fp32 squared distance,
+ *     token index) like the neighbour search; the table stores indices only;
  *   - balanced clustering (oracle_cluster): the paper groups tokens into
  *     equal-size clusters with a space-filling curve it does not name; reading:
  *     Z-order (Morton) curve over coordinates quantised to 16 bits per axis of a
@@ -152,6 +163,160 @@ int oracle_centroids(const float *coords, const int32_t *cluster_id, int B, int 
   }
   free(members);
   return rc;
+}
+
+/*
+ * oracle_vts_table: for every point of the Hg x Wg patch grid the Kt nearest
+ * visible tokens, ascending (fp32 squared distance, token index).
+ *   vis_xy [B,Nv,2] fp32; table [B,Hg,Wg,Kt] int32; 1 <= Kt <= Nv.
+ */
+int oracle_vts_table(const float *vis_xy, int B, int Nv, int Hg, int Wg, float x0, float y0, float cell, int Kt,
+                     int32_t *table) {
+  if (!vis_xy || !table || B < 0 || Nv <= 0 || Hg <= 0 || Wg <= 0 || Kt < 1 || Kt > Nv || !(cell > 0.f))
+    return ORACLE_ERR_ARG;
+  int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b) {
+    cand_t *cand = (cand_t *)malloc((size_t)Nv * sizeof(cand_t));
+    if (!cand) {
+#pragma omp critical
+      status = ORACLE_ERR_ALLOC;
+      continue;
+    }
+    const float *xy = vis_xy + (size_t)b * Nv * 2;
+    for (int iy = 0; iy < Hg; ++iy) {
+      for (int ix = 0; ix < Wg; ++ix) {
+        const float hx = (float)ix + 0.5f, hy = (float)iy + 0.5f;
+        const float sx = hx * cell, sy = hy * cell;
+        const float gx = x0 + sx, gy = y0 + sy;
+        for (int i = 0; i < Nv; ++i) {
+          cand[i].d2 = dist2_f32(gx, gy, xy[2 * i], xy[2 * i + 1]);
+          cand[i].idx = i;
+        }
+        qsort(cand, (size_t)Nv, sizeof(cand_t), cand_less);
+        int32_t *row = table + (((size_t)b * Hg + iy) * Wg + ix) * Kt;
+        for (int t = 0; t < Kt; ++t) row[t] = cand[t].idx;
+      }
+    }
+    free(cand);
+  }
+  return status;
+}
+
+/* Grid cell of a query coordinate: floor((q - x0) / cell) in fp32, clamped to 0..n-1. */
+static int vts_cell(float q, float x0, float cell, int n) {
+  const float t = q - x0;
+  const float u = t / cell;
+  const float f = floorf(u);
+  if (!(f >= 0.f)) return 0;
+  if (f > (float)(n - 1)) return n - 1;
+  return (int)f;
+}
+
+/*
+ * oracle_vts_fwd: virtual sampled tokens.
+ *   query_xy [B,Mq,2] fp32; vis_xy [B,Nv,2] fp32; feat [B,Nv,C] double;
+ *   table [B,Hg,Wg,Kt].  For every query: the table entry of its grid cell,
+ *   d_i = |q - x_i| + eps, w = softmax_i(-p d_i), out = sum_i w_i feat_i.
+ *   out [B,Mq,C]; weights [B,Mq,Kt] may be NULL.
+ */
+int oracle_vts_fwd(const float *query_xy, const float *vis_xy, const double *feat, const int32_t *table, int B,
+                   int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell, int Kt, double p,
+                   double eps, double *out, double *weights) {
+  if (!query_xy || !vis_xy || !feat || !table || !out) return ORACLE_ERR_ARG;
+  if (B < 0 || Mq <= 0 || Nv <= 0 || C <= 0 || Hg <= 0 || Wg <= 0 || Kt < 1 || !(cell > 0.f)) return ORACLE_ERR_ARG;
+  for (size_t t = 0; t < (size_t)B * Hg * Wg * Kt; ++t)
+    if (table[t] < 0 || table[t] >= Nv) return ORACLE_ERR_ARG;
+  for (int b = 0; b < B; ++b) {
+    for (int m = 0; m < Mq; ++m) {
+      const float qx = query_xy[((size_t)b * Mq + m) * 2], qy = query_xy[((size_t)b * Mq + m) * 2 + 1];
+      const int ix = vts_cell(qx, x0, cell, Wg), iy = vts_cell(qy, y0, cell, Hg);
+      const int32_t *row = table + (((size_t)b * Hg + iy) * Wg + ix) * Kt;
+      double z[64], zmax = -INFINITY, sum = 0.0;
+      if (Kt > 64) return ORACLE_ERR_ARG;
+      for (int i = 0; i < Kt; ++i) {
+        const double dx = (double)qx - (double)vis_xy[((size_t)b * Nv + row[i]) * 2];
+        const double dy = (double)qy - (double)vis_xy[((size_t)b * Nv + row[i]) * 2 + 1];
+        z[i] = -p * (sqrt(dx * dx + dy * dy) + eps);
+        if (z[i] > zmax) zmax = z[i];
+      }
+      for (int i = 0; i < Kt; ++i) {
+        z[i] = exp(z[i] - zmax);
+        sum += z[i];
+      }
+      double *o = out + ((size_t)b * Mq + m) * C;
+      for (int c = 0; c < C; ++c) o[c] = 0.0;
+      for (int i = 0; i < Kt; ++i) {
+        const double w = z[i] / sum;
+        if (weights) weights[((size_t)b * Mq + m) * Kt + i] = w;
+        const double *f = feat + ((size_t)b * Nv + row[i]) * C;
+        for (int c = 0; c < C; ++c) o[c] += w * f[c];
+      }
+    }
+  }
+  return ORACLE_OK;
+}
+
+/*
+ * oracle_vts_bwd: chain rule on oracle_vts_fwd for L = sum(dout * out).
+ *   dfeat [B,Nv,C] += w_i dout;  with g_i = <dout, feat_i>, dz_i = w_i (g_i - sum_j w_j g_j):
+ *   dquery [B,Mq,2] = sum_i dz_i (-p) (q - x_i) / |q - x_i|   (0 where q = x_i),
+ *   dp (scalar, summed over all queries) = sum_i dz_i (-(|q - x_i| + eps)).
+ */
+int oracle_vts_bwd(const float *query_xy, const float *vis_xy, const double *feat, const int32_t *table,
+                   const double *dout, int B, int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell,
+                   int Kt, double p, double eps, double *dfeat, double *dquery, double *dp) {
+  if (!query_xy || !vis_xy || !feat || !table || !dout || !dfeat || !dquery) return ORACLE_ERR_ARG;
+  if (B < 0 || Mq <= 0 || Nv <= 0 || C <= 0 || Hg <= 0 || Wg <= 0 || Kt < 1 || Kt > 64 || !(cell > 0.f))
+    return ORACLE_ERR_ARG;
+  for (size_t t = 0; t < (size_t)B * Hg * Wg * Kt; ++t)
+    if (table[t] < 0 || table[t] >= Nv) return ORACLE_ERR_ARG;
+  for (size_t t = 0; t < (size_t)B * Nv * C; ++t) dfeat[t] = 0.0;
+  double dp_sum = 0.0;
+  for (int b = 0; b < B; ++b) {
+    for (int m = 0; m < Mq; ++m) {
+      const float qx = query_xy[((size_t)b * Mq + m) * 2], qy = query_xy[((size_t)b * Mq + m) * 2 + 1];
+      const int ix = vts_cell(qx, x0, cell, Wg), iy = vts_cell(qy, y0, cell, Hg);
+      const int32_t *row = table + (((size_t)b * Hg + iy) * Wg + ix) * Kt;
+      const double *go = dout + ((size_t)b * Mq + m) * C;
+      double w[64], dist[64], dxs[64], dys[64], g[64], zmax = -INFINITY, sum = 0.0, gbar = 0.0;
+      for (int i = 0; i < Kt; ++i) {
+        dxs[i] = (double)qx - (double)vis_xy[((size_t)b * Nv + row[i]) * 2];
+        dys[i] = (double)qy - (double)vis_xy[((size_t)b * Nv + row[i]) * 2 + 1];
+        dist[i] = sqrt(dxs[i] * dxs[i] + dys[i] * dys[i]);
+        w[i] = -p * (dist[i] + eps);
+        if (w[i] > zmax) zmax = w[i];
+      }
+      for (int i = 0; i < Kt; ++i) {
+        w[i] = exp(w[i] - zmax);
+        sum += w[i];
+      }
+      for (int i = 0; i < Kt; ++i) {
+        w[i] /= sum;
+        const double *f = feat + ((size_t)b * Nv + row[i]) * C;
+        double *df = dfeat + ((size_t)b * Nv + row[i]) * C;
+        g[i] = 0.0;
+        for (int c = 0; c < C; ++c) {
+          g[i] += go[c] * f[c];
+          df[c] += w[i] * go[c];
+        }
+        gbar += w[i] * g[i];
+      }
+      double dqx = 0.0, dqy = 0.0;
+      for (int i = 0; i < Kt; ++i) {
+        const double dz = w[i] * (g[i] - gbar);
+        if (dist[i] > 0.0) {
+          dqx += dz * (-p) * dxs[i] / dist[i];
+          dqy += dz * (-p) * dys[i] / dist[i];
+        }
+        dp_sum += dz * (-(dist[i] + eps));
+      }
+      dquery[((size_t)b * Mq + m) * 2] = dqx;
+      dquery[((size_t)b * Mq + m) * 2 + 1] = dqy;
+    }
+  }
+  if (dp) *dp = dp_sum;
+  return ORACLE_OK;
 }
 
 /*
