@@ -36,6 +36,50 @@ def algorithmic_bytes_per_token(C: int, H: int, K: int, elt: int = 2):
     return fwd, bwd
 
 
+def bench_virtual_tokens(aff, torch, np, dev, reps: int = 20):
+    """The point decoder's virtual sampled tokens at the shape of the paper's decoder timing (batch 48, 2048 mask
+    tokens x 4 sample points, 4 nearest visible tokens; 512px images at 25 % visible, stage-1 width 128, bf16):
+    table build, fused lookup + weights + sum forward, backward.  Times are HIP-event means."""
+    rng = np.random.default_rng(2602016249 + 100)
+    B, Nv, Mq, C, Hg, Wg, Kt, cell, p, eps = 48, 1024, 8192, 128, 64, 64, 4, 8.0, 0.5, 1e-6
+    grid = (Hg, Wg, 0.0, 0.0, cell)
+    vis = np.empty((B, Nv, 2), dtype=np.float32)
+    for b in range(B):
+        keep = np.sort(rng.permutation(Hg * Wg)[:Nv])
+        vis[b, :, 0] = (keep % Wg + 0.5) * cell
+        vis[b, :, 1] = (keep // Wg + 0.5) * cell
+    q = torch.from_numpy(rng.uniform(0, Wg * cell, size=(B, Mq, 2)).astype(np.float32)).to(dev)
+    vis = torch.from_numpy(vis).to(dev)
+    feat = torch.randn((B, Nv, C), device=dev).bfloat16()
+    dout = torch.randn((B, Mq, C), device=dev).bfloat16()
+    table = aff.affmae_vts_table(vis, grid, Kt)
+    out = aff.affmae_vts_fwd(q, vis, feat, table, grid, p, eps)
+    ws = torch.empty(aff.load_library().affmae_vts_bwd_workspace_bytes(B, Mq, Nv, Kt), dtype=torch.uint8, device=dev)
+    aff.affmae_vts_bwd(q, vis, feat, table, dout, grid, p, eps, workspace=ws)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    t = [0.0, 0.0, 0.0]
+    for _ in range(reps):
+        ev[0].record()
+        aff.affmae_vts_table(vis, grid, Kt, table=table)
+        ev[1].record()
+        aff.affmae_vts_fwd(q, vis, feat, table, grid, p, eps, out=out)
+        ev[2].record()
+        aff.affmae_vts_bwd(q, vis, feat, table, dout, grid, p, eps, workspace=ws)
+        ev[3].record()
+        torch.cuda.synchronize()
+        for i in range(3):
+            t[i] += ev[i].elapsed_time(ev[i + 1]) / reps
+    samples = B * Mq
+    # algorithmic bytes: every tensor element once (bf16 features; the gathered rows counted once, as stored)
+    fwd_bytes = samples * (8 + 4 * Kt + 2 * C) + B * Nv * (8 + 2 * C)
+    bwd_bytes = samples * (8 + 4 * Kt + 2 * C + 8) + B * Nv * (8 + 2 * C + 2 * C)
+    return {"workload": "point decoder, batch 48 x 2048 mask tokens x 4 sample points, Nv=1024 of 64x64, C=128, Kt=4, bf16",
+            "table_ms": t[0], "fwd_ms": t[1], "bwd_ms": t[2],
+            "sample_points_per_s_fwd_bwd": samples / ((t[1] + t[2]) * 1e-3),
+            "fwd_algorithmic_GBs": fwd_bytes / (t[1] * 1e-3) / 1e9, "bwd_algorithmic_GBs": bwd_bytes / (t[2] * 1e-3) / 1e9}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,6 +268,8 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_us": dom_us},
         "rooflines_all_kernels": rooflines,
     }
+
+    result["virtual_tokens"] = bench_virtual_tokens(aff, torch, np, dev)
 
     if not args.no_cpu_baseline:
         import oracle

@@ -91,6 +91,60 @@ int affmae_cluster(const float* coords, int B, int N, int S, double x0, double y
                    int32_t* order, int32_t* cluster_id, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Virtual sampled tokens of the point decoder (paper, Sec. "AFFMAE": a decoder
+ * query location q gathers the K nearest visible tokens and aggregates their
+ * features with the exponential distance kernel
+ *     d_i = |q - x_i| + eps,  w_i = softmax_i(-p d_i),  out = sum_i w_i feat_i;
+ * Sec. "Flash-style Cluster Attention and Fast Decoder KNN" and supplement
+ * "Point-based decoder": the nearest visible tokens are not searched per query
+ * but read from a table cached over the dense Hg x Wg patch grid, the query
+ * being rounded to its nearest grid point; lookup, distances, weights and the
+ * weighted sum are one kernel).
+ *
+ * Grid: point (ix, iy) is the patch centre (x0 + (ix + 1/2) cell, y0 + (iy + 1/2)
+ * cell), evaluated in fp32 one operation at a time; the nearest grid point of q
+ * is the cell that contains it, floor((q.x - x0) / cell) in fp32 clamped to
+ * 0..Wg-1 (likewise y), so queries outside the grid use its border cells.
+ *
+ * affmae_vts_table  table[b][iy][ix][0..Kt-1] = the Kt visible tokens of image b
+ *                   nearest to grid point (ix, iy), ascending (fp32 squared
+ *                   distance evaluated as in affmae_knn, token index).  Built once
+ *                   per mask and reused by every decoder block.
+ *   vis_xy  in  [B,Nv,2] fp32, finite       table  out [B,Hg,Wg,Kt] int32
+ *
+ * affmae_vts_fwd
+ *   query_xy in [B,Mq,2] fp32   feat in [B,Nv,C] dtype   out [B,Mq,C] dtype
+ *   (several sample points per decoder query are simply more rows of query_xy)
+ *
+ * affmae_vts_bwd    gradients of L = <dout, out>:
+ *   dfeat   out [B,Nv,C] dtype, fully overwritten (summed in fp32 per token over
+ *           the queries that use it; the order of the additions, hence the last
+ *           bits, may vary run to run)
+ *   dquery  out [B,Mq,2] fp32: sum_i dz_i (-p) (q - x_i) / |q - x_i| with
+ *           dz_i = w_i (<dout, feat_i> - sum_j w_j <dout, feat_j>); a candidate
+ *           that coincides with q contributes no direction
+ *   dp      out device scalar fp32 or NULL: sum over all queries of
+ *           sum_i dz_i (-(|q - x_i| + eps))
+ *   workspace  affmae_vts_bwd_workspace_bytes(B, Mq, Nv, Kt) bytes
+ *
+ * Limits: 1 <= Kt <= min(Nv, AFFMAE_MAX_K); C even; feat, out, dout, dfeat
+ * 4-byte aligned.  Table entries outside 0..Nv-1 are clamped.
+ * Errors: AFFMAE_ERR_NULL, AFFMAE_ERR_SHAPE (sizes < 1, Kt > Nv, empty or
+ * non-finite grid, misaligned tensor), AFFMAE_ERR_DTYPE, AFFMAE_ERR_UNSUPPORTED,
+ * AFFMAE_ERR_WORKSPACE.
+ */
+int affmae_vts_table(const float* vis_xy, int B, int Nv, int Hg, int Wg, float x0, float y0, float cell, int Kt,
+                     int32_t* table, void* stream);
+int affmae_vts_fwd(const float* query_xy, const float* vis_xy, const void* feat, const int32_t* table, int B, int Mq,
+                   int Nv, int C, int Hg, int Wg, float x0, float y0, float cell, int Kt, float p, float eps,
+                   int dtype, void* out, void* stream);
+size_t affmae_vts_bwd_workspace_bytes(int B, int Mq, int Nv, int Kt);
+int affmae_vts_bwd(const float* query_xy, const float* vis_xy, const void* feat, const int32_t* table,
+                   const void* dout, int B, int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell,
+                   int Kt, float p, float eps, int dtype, void* dfeat, float* dquery, float* dp, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
+/*
  * affmae_knn - neighbourhood construction (paper, Sec. "AutoFocusFormer":
  * tokens are grouped into equal-size clusters and every token gets a
  * fixed-size neighbourhood by nearest-neighbour search over 2-D coordinates;

@@ -52,6 +52,16 @@ def load_library():
     lib.affmae_cluster.restype = _c_int
     lib.affmae_cluster.argtypes = ([_c_void_p] + [_c_int] * 3 + [ctypes.c_double] * 4
                                    + [_c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p])
+    lib.affmae_vts_table.restype = _c_int
+    lib.affmae_vts_table.argtypes = [_c_void_p] + [_c_int] * 4 + [_c_float] * 3 + [_c_int, _c_void_p, _c_void_p]
+    lib.affmae_vts_fwd.restype = _c_int
+    lib.affmae_vts_fwd.argtypes = ([_c_void_p] * 4 + [_c_int] * 6 + [_c_float] * 3 + [_c_int] + [_c_float] * 2 + [_c_int]
+                                   + [_c_void_p, _c_void_p])
+    lib.affmae_vts_bwd_workspace_bytes.restype = _c_size_t
+    lib.affmae_vts_bwd_workspace_bytes.argtypes = [_c_int] * 4
+    lib.affmae_vts_bwd.restype = _c_int
+    lib.affmae_vts_bwd.argtypes = ([_c_void_p] * 5 + [_c_int] * 6 + [_c_float] * 3 + [_c_int] + [_c_float] * 2 + [_c_int]
+                                   + [_c_void_p] * 4 + [_c_size_t, _c_void_p])
     lib.affmae_knn_workspace_bytes.restype = _c_size_t
     lib.affmae_knn_workspace_bytes.argtypes = [_c_int] * 5
     lib.affmae_knn.restype = _c_int
@@ -138,6 +148,85 @@ def affmae_cluster(coords: torch.Tensor, S: int, frame: Tuple[float, float, floa
     if rc != 0:
         raise AffmaeError("affmae_cluster", rc)
     return order, cluster_id
+
+
+def _grid(grid):
+    Hg, Wg, x0, y0, cell = grid
+    return int(Hg), int(Wg), float(x0), float(y0), float(cell)
+
+
+def affmae_vts_table(vis_xy: torch.Tensor, grid, Kt: int, table: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """vis_xy [B,Nv,2] fp32, grid (Hg, Wg, x0, y0, cell) -> table [B,Hg,Wg,Kt] int32: nearest visible tokens of
+    every patch centre."""
+    lib = load_library()
+    _dev(vis_xy, "vis_xy", torch.float32)
+    B, Nv, two = vis_xy.shape
+    if two != 2:
+        raise ValueError("vis_xy must be [B,Nv,2]")
+    Hg, Wg, x0, y0, cell = _grid(grid)
+    if table is None:
+        table = torch.empty((B, Hg, Wg, int(Kt)), dtype=torch.int32, device=vis_xy.device)
+    _dev(table, "table", torch.int32, (B, Hg, Wg, int(Kt)))
+    rc = lib.affmae_vts_table(_ptr(vis_xy), B, Nv, Hg, Wg, x0, y0, cell, int(Kt), _ptr(table), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_vts_table", rc)
+    return table
+
+
+def affmae_vts_fwd(query_xy: torch.Tensor, vis_xy: torch.Tensor, feat: torch.Tensor, table: torch.Tensor, grid,
+                   p: float, eps: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Virtual sampled tokens: query_xy [B,Mq,2] fp32, feat [B,Nv,C] -> out [B,Mq,C] in feat's dtype."""
+    lib = load_library()
+    _dev(query_xy, "query_xy", torch.float32)
+    B, Mq, _ = query_xy.shape
+    _dev(feat, "feat")
+    _, Nv, C = feat.shape
+    _dev(vis_xy, "vis_xy", torch.float32, (B, Nv, 2))
+    Hg, Wg, x0, y0, cell = _grid(grid)
+    _dev(table, "table", torch.int32)
+    Kt = table.shape[-1]
+    if tuple(table.shape) != (B, Hg, Wg, Kt):
+        raise ValueError("table must be [B,Hg,Wg,Kt]")
+    if out is None:
+        out = torch.empty((B, Mq, C), dtype=feat.dtype, device=feat.device)
+    _dev(out, "out", feat.dtype, (B, Mq, C))
+    rc = lib.affmae_vts_fwd(_ptr(query_xy), _ptr(vis_xy), _ptr(feat), _ptr(table), B, Mq, Nv, C, Hg, Wg, x0, y0, cell,
+                            Kt, float(p), float(eps), _dtype_code(feat), _ptr(out), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_vts_fwd", rc)
+    return out
+
+
+def affmae_vts_bwd(query_xy: torch.Tensor, vis_xy: torch.Tensor, feat: torch.Tensor, table: torch.Tensor,
+                   dout: torch.Tensor, grid, p: float, eps: float, want_dp: bool = True,
+                   workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """Backward of affmae_vts_fwd -> dict(dfeat [B,Nv,C], dquery [B,Mq,2] fp32, dp [1] fp32 when asked for)."""
+    lib = load_library()
+    _dev(query_xy, "query_xy", torch.float32)
+    B, Mq, _ = query_xy.shape
+    _dev(feat, "feat")
+    _, Nv, C = feat.shape
+    _dev(vis_xy, "vis_xy", torch.float32, (B, Nv, 2))
+    _dev(dout, "dout", feat.dtype, (B, Mq, C))
+    Hg, Wg, x0, y0, cell = _grid(grid)
+    _dev(table, "table", torch.int32)
+    Kt = table.shape[-1]
+    code = _dtype_code(feat)
+    dfeat = torch.empty_like(feat)
+    dquery = torch.empty((B, Mq, 2), dtype=torch.float32, device=feat.device)
+    dp = torch.empty((1,), dtype=torch.float32, device=feat.device) if want_dp else None
+    need = lib.affmae_vts_bwd_workspace_bytes(B, Mq, Nv, Kt)
+    if workspace is None:
+        workspace = _workspace(need, feat.device)
+    rc = lib.affmae_vts_bwd(_ptr(query_xy), _ptr(vis_xy), _ptr(feat), _ptr(table), _ptr(dout), B, Mq, Nv, C, Hg, Wg,
+                            x0, y0, cell, Kt, float(p), float(eps), code, _ptr(dfeat), _ptr(dquery), _ptr(dp),
+                            _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_vts_bwd", rc)
+    g = {"dfeat": dfeat, "dquery": dquery}
+    if want_dp:
+        g["dp"] = dp
+    return g
 
 
 def affmae_knn(coords: torch.Tensor, cluster_id: Optional[torch.Tensor], S: int, M: int, K: int,

@@ -22,6 +22,7 @@ COMMON = ["--offload-arch=" + ARCH, "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno
 # per-file extra flags
 EXTRA = {
     "knn.hip": ["-ffp-contract=off"],  # distances must not be fused
+    "vts.hip": ["-ffp-contract=off"],  # likewise (grid points and table distances)
 }
 
 

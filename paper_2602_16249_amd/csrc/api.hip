@@ -99,6 +99,81 @@ int affmae_cluster(const float* coords, int B, int N, int S, double x0, double y
              : AFFMAE_ERR_DEVICE;
 }
 
+}  // extern "C"
+
+namespace {
+
+int check_vts_shape(int B, int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell, int Kt) {
+  if (B < 1 || Mq < 1 || Nv < 1 || C < 1 || Hg < 1 || Wg < 1 || Kt < 1) return AFFMAE_ERR_SHAPE;
+  if (Kt > Nv) return AFFMAE_ERR_SHAPE;
+  if (!(cell > 0.f) || !(cell < 3e38f) || !(x0 > -3e38f && x0 < 3e38f) || !(y0 > -3e38f && y0 < 3e38f))
+    return AFFMAE_ERR_SHAPE;  // the grid must be finite and non-empty
+  if (Kt > AFFMAE_MAX_K) return AFFMAE_ERR_UNSUPPORTED;
+  if (C % 2) return AFFMAE_ERR_UNSUPPORTED;  // the kernels move two channels per lane
+  if ((long long)B * Hg * Wg > (1ll << 31) - 8 || (long long)B * Mq > (1ll << 31) - 8) return AFFMAE_ERR_UNSUPPORTED;
+  return AFFMAE_OK;
+}
+
+affmae::VtsArgs vts_args(const float* query_xy, const float* vis_xy, const void* feat, const int32_t* table, int B,
+                         int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell, int Kt, float p,
+                         float eps, int dtype) {
+  affmae::VtsArgs a = {};
+  a.query_xy = query_xy; a.vis_xy = vis_xy; a.feat = feat; a.table = table;
+  a.B = B; a.Mq = Mq; a.Nv = Nv; a.C = C; a.Hg = Hg; a.Wg = Wg; a.Kt = Kt; a.dtype = dtype;
+  a.x0 = x0; a.y0 = y0; a.cell = cell; a.p = p; a.eps = eps;
+  return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+int affmae_vts_table(const float* vis_xy, int B, int Nv, int Hg, int Wg, float x0, float y0, float cell, int Kt,
+                     int32_t* table, void* stream) {
+  if (!vis_xy || !table) return AFFMAE_ERR_NULL;
+  const int rc = check_vts_shape(B, 1, Nv, 2, Hg, Wg, x0, y0, cell, Kt);
+  if (rc != AFFMAE_OK) return rc;
+  affmae::VtsArgs a = vts_args(nullptr, vis_xy, nullptr, nullptr, B, 1, Nv, 2, Hg, Wg, x0, y0, cell, Kt, 0.f, 0.f, 0);
+  a.table_out = table;
+  return affmae::launch_vts_table(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+
+int affmae_vts_fwd(const float* query_xy, const float* vis_xy, const void* feat, const int32_t* table, int B, int Mq,
+                   int Nv, int C, int Hg, int Wg, float x0, float y0, float cell, int Kt, float p, float eps,
+                   int dtype, void* out, void* stream) {
+  if (!query_xy || !vis_xy || !feat || !table || !out) return AFFMAE_ERR_NULL;
+  if (dtype != AFFMAE_F32 && dtype != AFFMAE_BF16) return AFFMAE_ERR_DTYPE;
+  const int rc = check_vts_shape(B, Mq, Nv, C, Hg, Wg, x0, y0, cell, Kt);
+  if (rc != AFFMAE_OK) return rc;
+  if (misaligned(feat, 4) || misaligned(out, 4)) return AFFMAE_ERR_SHAPE;
+  affmae::VtsArgs a = vts_args(query_xy, vis_xy, feat, table, B, Mq, Nv, C, Hg, Wg, x0, y0, cell, Kt, p, eps, dtype);
+  a.out = out;
+  return affmae::launch_vts_fwd(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+
+size_t affmae_vts_bwd_workspace_bytes(int B, int Mq, int Nv, int Kt) {
+  if (B < 1 || Mq < 1 || Nv < 1 || Kt < 1 || Kt > AFFMAE_MAX_K) return 0;
+  if ((long long)B * Mq * Kt > (1ll << 31) - 8 || (long long)B * Nv > (1ll << 31) - 8) return 0;
+  return align_up(affmae::vts_bwd_workspace_bytes(B, Mq, Nv, Kt));
+}
+
+int affmae_vts_bwd(const float* query_xy, const float* vis_xy, const void* feat, const int32_t* table,
+                   const void* dout, int B, int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell,
+                   int Kt, float p, float eps, int dtype, void* dfeat, float* dquery, float* dp, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  if (!query_xy || !vis_xy || !feat || !table || !dout || !dfeat || !dquery) return AFFMAE_ERR_NULL;
+  if (dtype != AFFMAE_F32 && dtype != AFFMAE_BF16) return AFFMAE_ERR_DTYPE;
+  const int rc = check_vts_shape(B, Mq, Nv, C, Hg, Wg, x0, y0, cell, Kt);
+  if (rc != AFFMAE_OK) return rc;
+  if (misaligned(feat, 4) || misaligned(dout, 4) || misaligned(dfeat, 4)) return AFFMAE_ERR_SHAPE;
+  if ((long long)B * Mq * Kt > (1ll << 31) - 8) return AFFMAE_ERR_UNSUPPORTED;  // pairs are indexed with int32
+  const size_t need = align_up(affmae::vts_bwd_workspace_bytes(B, Mq, Nv, Kt));
+  if (!workspace || workspace_bytes < need || misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
+  affmae::VtsArgs a = vts_args(query_xy, vis_xy, feat, table, B, Mq, Nv, C, Hg, Wg, x0, y0, cell, Kt, p, eps, dtype);
+  a.dout = dout; a.dfeat = dfeat; a.dquery = dquery; a.dp = dp; a.workspace = workspace;
+  return affmae::launch_vts_bwd(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+
 size_t affmae_knn_workspace_bytes(int B, int N, int S, int M, int K) {
   if (check_knn_shape(B, N, S, M, K) != AFFMAE_OK) return 0;
   return knn_plan(B, N, S, M).total;

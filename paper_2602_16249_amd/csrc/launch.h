@@ -25,6 +25,28 @@ size_t cluster_workspace_bytes(int B, int N);
 hipError_t launch_cluster(const float* coords, int B, int N, int S, double x0, double y0, double w, double h,
                           int32_t* order, int32_t* cluster_id, void* workspace, hipStream_t stream);
 
+// Virtual sampled tokens of the point decoder: nearest-visible-token table over the patch grid, and the
+// fused lookup / distance / softmax(-p d) / weighted feature sum, forward and backward.
+struct VtsArgs {
+  const float* query_xy;  // [B,Mq,2]
+  const float* vis_xy;    // [B,Nv,2]
+  const void* feat;       // [B,Nv,C]
+  const int32_t* table;   // [B,Hg,Wg,Kt]
+  const void* dout;       // [B,Mq,C]
+  int B, Mq, Nv, C, Hg, Wg, Kt, dtype;
+  float x0, y0, cell, p, eps;
+  int32_t* table_out;     // table kernel only
+  void* out;              // [B,Mq,C]
+  void* dfeat;            // [B,Nv,C]
+  float* dquery;          // [B,Mq,2]
+  float* dp;              // device scalar or nullptr
+  void* workspace;
+};
+hipError_t launch_vts_table(const VtsArgs& a, hipStream_t stream);
+hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream);
+size_t vts_bwd_workspace_bytes(int B, int Mq, int Nv, int Kt);
+hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream);
+
 struct PlaArgs {
   const void *q, *k, *v, *bias;
   const int32_t* nbr_idx;

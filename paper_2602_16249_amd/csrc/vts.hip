@@ -1,0 +1,601 @@
+// Virtual sampled tokens of the point decoder (paper, Sec. "AFFMAE": a decoder query gathers the nearest
+// visible tokens and aggregates their features with the exponential distance kernel softmax_i(-p d_i),
+// d_i = |q - x_i| + eps; Sec. "Flash-style Cluster Attention and Fast Decoder KNN" and supplement
+// "Point-based decoder": the nearest visible tokens come from a table cached over the dense patch grid,
+// the query is rounded to its nearest grid point, and lookup, distances, weights and the weighted sum
+// are one kernel).
+//
+//   table   : one wave per grid point; the image's visible tokens stream past 64 at a time; the first 64
+//             are sorted, later ones are queued only when they beat the current Kt-th key and merged 64
+//             at a time.  Keys = (fp32 squared distance bits, token index): exact and unique.
+//   forward : one wave per query; lanes 0..Kt-1 hold one candidate each (index, distance, weight), then
+//             lanes <-> channels for the weighted sum of the gathered feature rows.
+//   backward: one wave per query: g_i = <dout, feat_i> by wave reductions, dz_i = w_i (g_i - sum w g),
+//             dquery and a per-query part of dp (added up in a fixed order by one workgroup afterwards) from
+//             the lanes that hold candidates; the weights are kept and
+//             every (query, candidate) pair is counted at its token.  dfeat is then gathered, not
+//             scattered: prefix sum of the counts, the pairs filed per token, and one wave per visible
+//             token adds up w * dout over its pairs (no floating-point atomics; the order inside a
+//             token's list, hence the last bits of dfeat, follows the filing order of the run).
+// This file is compiled with -ffp-contract=off (grid points and table distances are defined unfused).
+#include "device_util.h"
+#include "launch.h"
+#include "select_util.h"
+#include "timing.h"
+
+namespace affmae {
+namespace {
+
+struct Grid {
+  int Hg, Wg;
+  float x0, y0, cell;
+};
+
+__global__ __launch_bounds__(256) void vts_table_kernel(const float* __restrict__ vis_xy, int B, int Nv, Grid gr, int Kt,
+                                                       int32_t* __restrict__ table) {
+  __shared__ key_t pend_all[4][2 * kWave];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const long long cells = (long long)B * gr.Hg * gr.Wg;
+  const long long gcell = (long long)blockIdx.x * 4 + wave;
+  if (gcell >= cells) return;  // wave-uniform; no workgroup barrier below
+  key_t* pend = pend_all[wave];
+  const int per_image = gr.Hg * gr.Wg;
+  const int b = (int)(gcell / per_image);
+  const int c = (int)(gcell - (long long)b * per_image);
+  const int iy = c / gr.Wg, ix = c - iy * gr.Wg;
+  // patch centre, each operation rounded separately
+  const float hx = (float)ix + 0.5f, hy = (float)iy + 0.5f;
+  const float sx = hx * gr.cell, sy = hy * gr.cell;
+  const float gx = gr.x0 + sx, gy = gr.y0 + sy;
+  const float* xy = vis_xy + (size_t)b * Nv * 2;
+  auto key_of = [&](int i) -> key_t {
+    if (i >= Nv) return kKeyMax;
+    return make_key(dist2(gx, gy, xy[2 * (size_t)i], xy[2 * (size_t)i + 1]), i);
+  };
+  key_t best = wave_sort(key_of(lane), lane);
+  key_t bound = shfl_key(best, Kt - 1);
+  int fill = 0;  // queued keys, wave-uniform, always < 64 between rows
+  for (int base = kWave; base < Nv; base += kWave) {
+    const key_t key = key_of(base + lane);
+    const bool in = key < bound;
+    const unsigned long long mask = __ballot(in);
+    if (mask == 0ull) continue;  // wave-uniform
+    const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+    if (in) pend[fill + rank] = key;
+    fill += __popcll(mask);
+    if (fill >= kWave) {
+      wave_lds_sync();
+      const key_t row = pend[lane];
+      const key_t rest = pend[kWave + lane];
+      wave_lds_sync();
+      fill -= kWave;
+      if (lane < fill) pend[lane] = rest;
+      best = topk_push(best, row, lane, Kt - 1);
+      bound = shfl_key(best, Kt - 1);
+    }
+  }
+  if (fill > 0) {
+    wave_lds_sync();
+    best = topk_push(best, (lane < fill) ? pend[lane] : kKeyMax, lane, Kt - 1);
+  }
+  if (lane < Kt) table[(size_t)gcell * Kt + lane] = (int32_t)(uint32_t)best;
+}
+
+// Grid cell of a query coordinate: floor((q - x0) / cell), clamped to 0..n-1 (NaN goes to 0).
+__device__ __forceinline__ int cell_of(float q, float x0, float cell, int n) {
+  const float t = q - x0;
+  const float u = t / cell;
+  const float f = floorf(u);
+  if (!(f >= 0.f)) return 0;
+  if (f > (float)(n - 1)) return n - 1;
+  return (int)f;
+}
+
+// Two consecutive channels (even channel index, 4-byte aligned rows): one 32-bit access for bf16.
+__device__ __forceinline__ void load2(const float* p, float& a, float& b) {
+  a = p[0];
+  b = p[1];
+}
+__device__ __forceinline__ void load2(const bf16_t* p, float& a, float& b) {
+  const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+  a = __uint_as_float(w << 16);
+  b = __uint_as_float(w & 0xffff0000u);
+}
+__device__ __forceinline__ void store2(float* p, float a, float b) {
+  p[0] = a;
+  p[1] = b;
+}
+__device__ __forceinline__ void store2(bf16_t* p, float a, float b) {
+  *reinterpret_cast<uint32_t*>(p) = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+
+struct Cand {
+  int idx;       // visible token of this lane (lanes >= Kt: token 0, weight 0)
+  float dx, dy;  // q - x_i
+  float dist;    // |q - x_i|
+  float w;       // softmax_i(-p (dist + eps))
+};
+
+__device__ __forceinline__ Cand load_candidate(const float* __restrict__ query_xy, const float* __restrict__ vis_xy,
+                                               const int32_t* __restrict__ table, int b, long long gq, int Nv,
+                                               const Grid& gr, int Kt, float p, float eps, int lane) {
+  const float qx = query_xy[2 * (size_t)gq], qy = query_xy[2 * (size_t)gq + 1];
+  const int ix = cell_of(qx, gr.x0, gr.cell, gr.Wg), iy = cell_of(qy, gr.y0, gr.cell, gr.Hg);
+  const int32_t* row = table + (((size_t)b * gr.Hg + iy) * gr.Wg + ix) * Kt;
+  Cand c;
+  const bool on = lane < Kt;
+  c.idx = on ? min(max(row[lane], 0), Nv - 1) : 0;
+  const float* x = vis_xy + ((size_t)b * Nv + c.idx) * 2;
+  c.dx = qx - x[0];
+  c.dy = qy - x[1];
+  c.dist = sqrtf(c.dx * c.dx + c.dy * c.dy);
+  const float z = on ? -p * (c.dist + eps) : -INFINITY;
+  const float zmax = wave_max(z);
+  const float e = on ? __expf(z - zmax) : 0.f;
+  c.w = e / wave_sum(e);
+  // the weights and indices are broadcast from their lanes later: pin their values here, where every lane is
+  // active, so that no part of their computation moves under a lane predicate
+  asm volatile("" : "+v"(c.w), "+v"(c.idx));
+  return c;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void vts_fwd_kernel(const float* __restrict__ query_xy, const float* __restrict__ vis_xy,
+                                                     const T* __restrict__ feat, const int32_t* __restrict__ table,
+                                                     int B, int Mq, int Nv, int C, Grid gr, int Kt, float p, float eps,
+                                                     T* __restrict__ out) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const long long gq = (long long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  if (gq >= (long long)B * Mq) return;  // wave-uniform
+  const int b = (int)(gq / Mq);
+  const Cand cd = load_candidate(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, lane);
+  // C is even: two channels per lane and trip.  The trip loop is wave-uniform and only the memory accesses
+  // are predicated, so that the lane broadcasts below always run with every lane active.
+  for (int base = 0; base < C; base += 2 * kWave) {
+    const int c0 = base + 2 * lane;
+    const bool on = c0 < C;
+    float a0 = 0.f, a1 = 0.f;
+    for (int i = 0; i < Kt; ++i) {
+      const float w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(cd.w), i));
+      const int idx = __builtin_amdgcn_readlane(cd.idx, i);
+      const T* f = feat + ((size_t)b * Nv + idx) * C + c0;
+      if (on) {
+        float f0, f1;
+        load2(f, f0, f1);
+        a0 = fmaf(w, f0, a0);
+        a1 = fmaf(w, f1, a1);
+      }
+    }
+    if (on) store2(out + (size_t)gq * C + c0, a0, a1);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void vts_bwd_kernel(const float* __restrict__ query_xy, const float* __restrict__ vis_xy,
+                                                     const T* __restrict__ feat, const int32_t* __restrict__ table,
+                                                     const T* __restrict__ dout, int B, int Mq, int Nv, int C, Grid gr,
+                                                     int Kt, float p, float eps, float* __restrict__ weights,
+                                                     int32_t* __restrict__ pair_token, int32_t* __restrict__ count,
+                                                     float* __restrict__ dquery, float* __restrict__ dp_part) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const long long gq = (long long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  if (gq >= (long long)B * Mq) return;  // wave-uniform
+  const int b = (int)(gq / Mq);
+  const Cand cd = load_candidate(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, lane);
+  // g_i = <dout, feat_i>: lanes <-> channels, then one wave reduction per candidate; lane i keeps g_i
+  float g_mine = 0.f;
+  for (int i = 0; i < Kt; ++i) {
+    const int idx = __builtin_amdgcn_readlane(cd.idx, i);
+    const T* f = feat + ((size_t)b * Nv + idx) * C;
+    float part = 0.f;
+    for (int c0 = 2 * lane; c0 < C; c0 += 2 * kWave) {
+      float g0, g1, f0, f1;
+      load2(dout + (size_t)gq * C + c0, g0, g1);
+      load2(f + c0, f0, f1);
+      part = fmaf(g0, f0, part);
+      part = fmaf(g1, f1, part);
+    }
+    const float gi = wave_sum(part);
+    if (lane == i) g_mine = gi;
+  }
+  const float gbar = wave_sum(cd.w * g_mine);  // lanes >= Kt hold weight 0
+  const float dz = cd.w * (g_mine - gbar);
+  const float inv = cd.dist > 0.f ? 1.f / cd.dist : 0.f;
+  const float qx = wave_sum(dz * (-p) * cd.dx * inv);
+  const float qy = wave_sum(dz * (-p) * cd.dy * inv);
+  const float dpv = wave_sum(lane < Kt ? dz * (-(cd.dist + eps)) : 0.f);
+  if (lane < Kt) {
+    weights[(size_t)gq * Kt + lane] = cd.w;
+    pair_token[(size_t)gq * Kt + lane] = b * Nv + cd.idx;
+    atomicAdd(count + (size_t)b * Nv + cd.idx, 1);
+  }
+  if (lane == 0) {
+    dquery[2 * (size_t)gq] = qx;
+    dquery[2 * (size_t)gq + 1] = qy;
+    if (dp_part) dp_part[gq] = dpv;
+  }
+}
+
+// ---- four queries per wave -----------------------------------------------------------------------------------
+// A row of C channels is moved 16 bytes per lane; when Kt <= 16 a group of 16 lanes serves one query (lane l of
+// the group holds candidate l), so a wave carries four independent chains of dependent loads (query -> table
+// row -> token coordinates -> feature rows) instead of one.  Needs rows that are whole 16-byte pieces.
+template <typename T>
+struct Piece;  // 16 bytes of channels
+template <>
+struct Piece<float> {
+  static constexpr int kCh = 4;
+  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+    const float4 x = *reinterpret_cast<const float4*>(p);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <>
+struct Piece<bf16_t> {
+  static constexpr int kCh = 8;
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __uint_as_float(w[e] << 16);
+      v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    uint4 x;
+    x.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+    x.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    x.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+    x.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = x;
+  }
+};
+
+__device__ __forceinline__ float group16_max(float x) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float group16_sum(float x) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// Candidate of lane (lane % 16) for the group's query; every lane of the wave runs this (queries past the end
+// repeat the last one and are not stored).
+__device__ __forceinline__ Cand load_candidate16(const float* __restrict__ query_xy, const float* __restrict__ vis_xy,
+                                                 const int32_t* __restrict__ table, int b, long long gq, int Nv,
+                                                 const Grid& gr, int Kt, float p, float eps, int sub) {
+  const float qx = query_xy[2 * (size_t)gq], qy = query_xy[2 * (size_t)gq + 1];
+  const int ix = cell_of(qx, gr.x0, gr.cell, gr.Wg), iy = cell_of(qy, gr.y0, gr.cell, gr.Hg);
+  const int32_t* row = table + (((size_t)b * gr.Hg + iy) * gr.Wg + ix) * Kt;
+  Cand c;
+  const bool on = sub < Kt;
+  c.idx = on ? min(max(row[sub], 0), Nv - 1) : 0;
+  const float* x = vis_xy + ((size_t)b * Nv + c.idx) * 2;
+  c.dx = qx - x[0];
+  c.dy = qy - x[1];
+  c.dist = sqrtf(c.dx * c.dx + c.dy * c.dy);
+  const float z = on ? -p * (c.dist + eps) : -INFINITY;
+  const float zmax = group16_max(z);
+  const float e = on ? __expf(z - zmax) : 0.f;
+  c.w = e / group16_sum(e);
+  return c;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void vts_fwd16_kernel(const float* __restrict__ query_xy,
+                                                       const float* __restrict__ vis_xy, const T* __restrict__ feat,
+                                                       const int32_t* __restrict__ table, int B, int Mq, int Nv, int C,
+                                                       Grid gr, int Kt, float p, float eps, T* __restrict__ out) {
+  constexpr int CH = Piece<T>::kCh;
+  const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
+  const long long total = (long long)B * Mq;
+  const long long want = ((long long)blockIdx.x * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
+  const bool live = want < total;
+  const long long gq = live ? want : total - 1;
+  const int b = (int)(gq / Mq);
+  const Cand cd = load_candidate16(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, sub);
+  const int group = lane & 48;
+  for (int base = 0; base < C; base += 16 * CH) {  // wave-uniform trips
+    const int c0 = base + sub * CH;
+    const bool on = live && c0 < C;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < Kt; ++i) {
+      const float w = __shfl(cd.w, group | i);
+      const int idx = __shfl(cd.idx, group | i);
+      if (on) {
+        float f[8];
+        Piece<T>::load(feat + ((size_t)b * Nv + idx) * C + c0, f);
+#pragma unroll
+        for (int e = 0; e < CH; ++e) acc[e] = fmaf(w, f[e], acc[e]);
+      }
+    }
+    if (on) Piece<T>::store(out + (size_t)gq * C + c0, acc);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void vts_bwd16_kernel(const float* __restrict__ query_xy,
+                                                       const float* __restrict__ vis_xy, const T* __restrict__ feat,
+                                                       const int32_t* __restrict__ table, const T* __restrict__ dout,
+                                                       int B, int Mq, int Nv, int C, Grid gr, int Kt, float p, float eps,
+                                                       float* __restrict__ weights, int32_t* __restrict__ pair_token,
+                                                       int32_t* __restrict__ count, float* __restrict__ dquery,
+                                                       float* __restrict__ dp_part) {
+  constexpr int CH = Piece<T>::kCh;
+  const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
+  const long long total = (long long)B * Mq;
+  const long long want = ((long long)blockIdx.x * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
+  const bool live = want < total;
+  const long long gq = live ? want : total - 1;
+  const int b = (int)(gq / Mq);
+  const Cand cd = load_candidate16(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, sub);
+  const int group = lane & 48;
+  float g_mine = 0.f;
+  for (int i = 0; i < Kt; ++i) {
+    const int idx = __shfl(cd.idx, group | i);
+    float part = 0.f;
+    for (int base = 0; base < C; base += 16 * CH) {
+      const int c0 = base + sub * CH;
+      if (c0 < C) {
+        float g[8], f[8];
+        Piece<T>::load(dout + (size_t)gq * C + c0, g);
+        Piece<T>::load(feat + ((size_t)b * Nv + idx) * C + c0, f);
+#pragma unroll
+        for (int e = 0; e < CH; ++e) part = fmaf(g[e], f[e], part);
+      }
+    }
+    const float gi = group16_sum(part);
+    if (sub == i) g_mine = gi;
+  }
+  const float gbar = group16_sum(cd.w * g_mine);  // lanes past Kt hold weight 0
+  const float dz = cd.w * (g_mine - gbar);
+  const float inv = cd.dist > 0.f ? 1.f / cd.dist : 0.f;
+  const float qx = group16_sum(dz * (-p) * cd.dx * inv);
+  const float qy = group16_sum(dz * (-p) * cd.dy * inv);
+  const float dpv = group16_sum(sub < Kt ? dz * (-(cd.dist + eps)) : 0.f);
+  if (live && sub < Kt) {
+    weights[(size_t)gq * Kt + sub] = cd.w;
+    pair_token[(size_t)gq * Kt + sub] = b * Nv + cd.idx;
+    atomicAdd(count + (size_t)b * Nv + cd.idx, 1);
+  }
+  if (live && sub == 0) {
+    dquery[2 * (size_t)gq] = qx;
+    dquery[2 * (size_t)gq + 1] = qy;
+    if (dp_part) dp_part[gq] = dpv;
+  }
+}
+
+__global__ __launch_bounds__(256) void vts_zero_kernel(int32_t* __restrict__ a, int32_t* __restrict__ c, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    a[i] = 0;
+    c[i] = 0;
+  }
+}
+
+// dp = sum of the per-query parts, in a fixed order (one workgroup).
+__global__ __launch_bounds__(1024) void vts_dp_kernel(const float* __restrict__ part, size_t n, float* __restrict__ dp) {
+  __shared__ float acc[16];
+  float s = 0.f;
+  const size_t n4 = n / 4;  // the workspace slot is 256-byte aligned: whole 16-byte pieces first
+  for (size_t i = threadIdx.x; i < n4; i += blockDim.x) {
+    const float4 v = reinterpret_cast<const float4*>(part)[i];
+    s += (v.x + v.y) + (v.z + v.w);
+  }
+  for (size_t i = n4 * 4 + threadIdx.x; i < n; i += blockDim.x) s += part[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & (kWave - 1)) == 0) acc[threadIdx.x / kWave] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < 16; ++w) t += acc[w];
+    *dp = t;
+  }
+}
+
+// Exclusive prefix sum.  Workgroup j owns elements [1024 j, 1024 j + 1024): it first adds up everything before
+// them (coalesced, from L2), then scans its own.  No workgroup waits for another.
+__global__ __launch_bounds__(256) void vts_scan_kernel(const int32_t* __restrict__ count, int32_t* __restrict__ offset,
+                                                      int n) {
+  __shared__ int32_t part[4], before_all[4];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int first = blockIdx.x * 1024;
+  int before = 0;
+  for (int i = tid * 4; i < first; i += 1024) {
+    const int4 v = *reinterpret_cast<const int4*>(count + i);
+    before += v.x + v.y + v.z + v.w;
+  }
+  const int at = first + tid * 4;
+  int c[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) c[i] = (at + i < n) ? count[at + i] : 0;
+  const int mine = c[0] + c[1] + c[2] + c[3];
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
+  if (lane == kWave - 1) part[wave] = incl;
+  if (lane == 0) before_all[wave] = before;
+  __syncthreads();
+  int base = before_all[0] + before_all[1] + before_all[2] + before_all[3];
+  for (int w = 0; w < wave; ++w) base += part[w];
+  int run = base + incl - mine;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (at + i < n) offset[at + i] = run;
+    run += c[i];
+  }
+  if (at <= n - 1 && n - 1 < at + 4) offset[n] = run;
+}
+
+// Files every (query, candidate) pair in the list of its token.
+__global__ __launch_bounds__(256) void vts_fill_kernel(const int32_t* __restrict__ pair_token,
+                                                      const int32_t* __restrict__ offset, int32_t* __restrict__ cursor,
+                                                      int32_t* __restrict__ list, size_t pairs) {
+  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= pairs) return;
+  const int tok = pair_token[e];
+  list[offset[tok] + atomicAdd(cursor + tok, 1)] = (int32_t)e;
+}
+
+// One wave per visible token: dfeat = sum over the token's pairs of w * dout[query].
+template <typename T>
+__global__ __launch_bounds__(256) void vts_dfeat_kernel(const T* __restrict__ dout, const float* __restrict__ weights,
+                                                       const int32_t* __restrict__ offset,
+                                                       const int32_t* __restrict__ list, int tokens, int C, int Kt,
+                                                       T* __restrict__ dfeat) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int tok = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  if (tok >= tokens) return;  // wave-uniform
+  const int lo = offset[tok], n = offset[tok + 1] - lo;
+  for (int base = 0; base < C; base += 2 * kWave) {  // wave-uniform trips; only the memory accesses are predicated
+    const int c0 = base + 2 * lane;
+    const bool on = c0 < C;
+    float a0 = 0.f, a1 = 0.f;
+    for (int chunk = 0; chunk < n; chunk += kWave) {
+      const int m = min(kWave, n - chunk);
+      const int mine = lane < m ? list[lo + chunk + lane] : 0;
+      float wmine = lane < m ? weights[mine] : 0.f;
+      int qmine = mine / Kt;
+      asm volatile("" : "+v"(wmine), "+v"(qmine));  // broadcast below: computed here with every lane active
+      for (int i = 0; i < m; ++i) {
+        const float w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wmine), i));
+        const int q = __builtin_amdgcn_readlane(qmine, i);
+        if (on) {
+          float g0, g1;
+          load2(dout + (size_t)q * C + c0, g0, g1);
+          a0 = fmaf(w, g0, a0);
+          a1 = fmaf(w, g1, a1);
+        }
+      }
+    }
+    if (on) store2(dfeat + (size_t)tok * C + c0, a0, a1);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_vts_table(const VtsArgs& a, hipStream_t stream) {
+  const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
+  const long long cells = (long long)a.B * a.Hg * a.Wg;
+  AFFMAE_LAUNCH("vts_table_kernel", stream, vts_table_kernel, dim3((unsigned)((cells + 3) / 4)), dim3(256), 0, stream,
+                a.vis_xy, a.B, a.Nv, gr, a.Kt, a.table_out);
+  return hipGetLastError();
+}
+
+// Four queries per wave when a group of 16 lanes can hold the candidates and the rows are whole 16-byte pieces.
+static bool vts_grouped(const VtsArgs& a, const void* t0, const void* t1, const void* t2) {
+  const size_t row = (size_t)a.C * (a.dtype == 1 ? 2 : 4);
+  auto al = [](const void* p) { return p == nullptr || reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+  return a.Kt <= 16 && row % 16 == 0 && al(t0) && al(t1) && al(t2);
+}
+
+hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream) {
+  const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
+  if (vts_grouped(a, a.feat, a.out, nullptr)) {
+    const dim3 grid16((unsigned)(((long long)a.B * a.Mq + 15) / 16));
+    if (a.dtype == 1)
+      AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd16_kernel<bf16_t>, grid16, dim3(256), 0, stream, a.query_xy,
+                    a.vis_xy, (const bf16_t*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
+                    (bf16_t*)a.out);
+    else
+      AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd16_kernel<float>, grid16, dim3(256), 0, stream, a.query_xy,
+                    a.vis_xy, (const float*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, (float*)a.out);
+    return hipGetLastError();
+  }
+  const dim3 grid((unsigned)(((long long)a.B * a.Mq + 3) / 4));
+  if (a.dtype == 1)
+    AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd_kernel<bf16_t>, grid, dim3(256), 0, stream, a.query_xy, a.vis_xy,
+                  (const bf16_t*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, (bf16_t*)a.out);
+  else
+    AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd_kernel<float>, grid, dim3(256), 0, stream, a.query_xy, a.vis_xy,
+                  (const float*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, (float*)a.out);
+  return hipGetLastError();
+}
+
+namespace {
+struct VtsBwdLayout {
+  size_t weights_off, pair_off, count_off, offset_off, cursor_off, list_off, dp_off, total;
+};
+size_t vts_align(size_t n) { return (n + 255) / 256 * 256; }
+VtsBwdLayout vts_bwd_layout(int B, int Mq, int Nv, int Kt) {
+  VtsBwdLayout L;
+  const size_t pairs = (size_t)B * Mq * Kt, tokens = (size_t)B * Nv;
+  size_t off = 0;
+  L.weights_off = off; off += vts_align(pairs * sizeof(float));
+  L.pair_off = off;    off += vts_align(pairs * sizeof(int32_t));
+  L.count_off = off;   off += vts_align(tokens * sizeof(int32_t));
+  L.offset_off = off;  off += vts_align((tokens + 1) * sizeof(int32_t));
+  L.cursor_off = off;  off += vts_align(tokens * sizeof(int32_t));
+  L.list_off = off;    off += vts_align(pairs * sizeof(int32_t));
+  L.dp_off = off;      off += vts_align((size_t)B * Mq * sizeof(float));
+  L.total = off;
+  return L;
+}
+}  // namespace
+
+size_t vts_bwd_workspace_bytes(int B, int Mq, int Nv, int Kt) { return vts_bwd_layout(B, Mq, Nv, Kt).total; }
+
+hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
+  const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
+  const dim3 grid((unsigned)(((long long)a.B * a.Mq + 3) / 4));
+  const VtsBwdLayout L = vts_bwd_layout(a.B, a.Mq, a.Nv, a.Kt);
+  char* ws = static_cast<char*>(a.workspace);
+  float* weights = reinterpret_cast<float*>(ws + L.weights_off);
+  int32_t* pair_token = reinterpret_cast<int32_t*>(ws + L.pair_off);
+  int32_t* count = reinterpret_cast<int32_t*>(ws + L.count_off);
+  int32_t* offset = reinterpret_cast<int32_t*>(ws + L.offset_off);
+  int32_t* cursor = reinterpret_cast<int32_t*>(ws + L.cursor_off);
+  int32_t* list = reinterpret_cast<int32_t*>(ws + L.list_off);
+  float* dp_part = a.dp ? reinterpret_cast<float*>(ws + L.dp_off) : nullptr;
+  const size_t tokens = (size_t)a.B * a.Nv, pairs = (size_t)a.B * a.Mq * a.Kt;
+  AFFMAE_LAUNCH("vts_zero_kernel", stream, vts_zero_kernel, dim3((unsigned)((tokens + 255) / 256)), dim3(256), 0, stream,
+                count, cursor, tokens);
+  const bool grouped = vts_grouped(a, a.feat, a.dout, nullptr);
+  const dim3 grid16((unsigned)(((long long)a.B * a.Mq + 15) / 16));
+  if (grouped && a.dtype == 1)
+    AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd16_kernel<bf16_t>, grid16, dim3(256), 0, stream, a.query_xy, a.vis_xy,
+                  (const bf16_t*)a.feat, a.table, (const bf16_t*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
+                  weights, pair_token, count, a.dquery, dp_part);
+  else if (grouped)
+    AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd16_kernel<float>, grid16, dim3(256), 0, stream, a.query_xy, a.vis_xy,
+                  (const float*)a.feat, a.table, (const float*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
+                  weights, pair_token, count, a.dquery, dp_part);
+  else if (a.dtype == 1)
+    AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd_kernel<bf16_t>, grid, dim3(256), 0, stream, a.query_xy, a.vis_xy,
+                  (const bf16_t*)a.feat, a.table, (const bf16_t*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
+                  weights, pair_token, count, a.dquery, dp_part);
+  else
+    AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd_kernel<float>, grid, dim3(256), 0, stream, a.query_xy, a.vis_xy,
+                  (const float*)a.feat, a.table, (const float*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
+                  weights, pair_token, count, a.dquery, dp_part);
+  if (a.dp)
+    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part,
+                  (size_t)a.B * a.Mq, a.dp);
+  AFFMAE_LAUNCH("vts_scan_kernel", stream, vts_scan_kernel, dim3((unsigned)((tokens + 1023) / 1024)), dim3(256), 0, stream,
+                count, offset, (int)tokens);
+  AFFMAE_LAUNCH("vts_fill_kernel", stream, vts_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, stream,
+                pair_token, offset, cursor, list, pairs);
+  const dim3 per_token((unsigned)((tokens + 3) / 4));
+  if (a.dtype == 1)
+    AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<bf16_t>, per_token, dim3(256), 0, stream,
+                  (const bf16_t*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (bf16_t*)a.dfeat);
+  else
+    AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<float>, per_token, dim3(256), 0, stream,
+                  (const float*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (float*)a.dfeat);
+  return hipGetLastError();
+}
+
+}  // namespace affmae

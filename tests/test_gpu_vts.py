@@ -1,0 +1,132 @@
+"""GPU parity: virtual sampled tokens (table, forward, backward) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_16249_amd as aff
+from workloads import bf16_round
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _visible(rng, B, Nv, Hg, Wg, cell, jitter):
+    """Nv of the Hg*Wg patch centres per image (a random mask), optionally moved off the grid."""
+    xy = np.empty((B, Nv, 2), dtype=np.float32)
+    for b in range(B):
+        keep = np.sort(rng.permutation(Hg * Wg)[:Nv])
+        xy[b, :, 0] = (keep % Wg + 0.5) * cell
+        xy[b, :, 1] = (keep // Wg + 0.5) * cell
+    if jitter:
+        xy += rng.uniform(-jitter, jitter, size=xy.shape).astype(np.float32)
+    return xy
+
+
+TABLE_CASES = [
+    # B, Nv, Hg, Wg, cell, Kt, jitter
+    (1, 5, 3, 3, 4.0, 5, 0.0),           # Kt == Nv, fewer than 64 tokens
+    (2, 64, 8, 8, 8.0, 4, 0.0),          # every centre visible: ties everywhere
+    (2, 100, 16, 16, 8.0, 4, 0.0),       # on-grid mask, ragged last row of candidates
+    (3, 1024, 64, 64, 8.0, 4, 0.0),      # a 512px image at 25 % visible
+    (1, 1024, 64, 64, 8.0, 64, 2.0),     # Kt at the limit
+    (2, 577, 20, 30, 5.0, 9, 1.5),
+]
+
+
+@pytest.mark.parametrize("B,Nv,Hg,Wg,cell,Kt,jitter", TABLE_CASES)
+def test_table_matches_oracle(B, Nv, Hg, Wg, cell, Kt, jitter):
+    print(f"case table B={B} Nv={Nv} grid={Hg}x{Wg} Kt={Kt}", flush=True)
+    rng = np.random.default_rng(Nv + Kt)
+    vis = _visible(rng, B, Nv, Hg, Wg, cell, jitter)
+    grid = (Hg, Wg, 0.0, 0.0, cell)
+    table = aff.affmae_vts_table(torch.from_numpy(vis).cuda(), grid, Kt)
+    torch.cuda.synchronize()
+    assert np.array_equal(table.cpu().numpy(), oracle.vts_table(vis, grid, Kt))
+
+
+def test_table_all_tokens_coincide():
+    vis = np.full((2, 200, 2), 17.0, dtype=np.float32)
+    grid = (6, 6, 0.0, 0.0, 8.0)
+    table = aff.affmae_vts_table(torch.from_numpy(vis).cuda(), grid, 7).cpu().numpy()
+    assert np.array_equal(table, np.broadcast_to(np.arange(7, dtype=np.int32), (2, 6, 6, 7)))
+
+
+SAMPLE_CASES = [
+    # dtype, B, Mq, Nv, C, Hg, Wg, Kt, p
+    ("f32", 1, 7, 9, 2, 3, 3, 1, 1.0),         # one candidate: a copy
+    ("f32", 2, 300, 100, 6, 16, 16, 4, 0.5),
+    ("f32", 2, 257, 256, 130, 32, 32, 4, 2.0),   # more than 128 channels: several trips
+    ("bf16", 2, 1000, 256, 128, 32, 32, 4, 0.5),
+    ("bf16", 1, 500, 300, 384, 20, 30, 16, 0.25),
+    ("f32", 1, 200, 64, 8, 8, 8, 64, 0.1),      # Kt at the limit
+    ("f32", 2, 333, 200, 64, 16, 16, 5, 0.5),   # rows of whole 16-byte pieces, Kt <= 16: four queries per wave
+    ("f32", 1, 77, 50, 68, 8, 8, 16, 1.5),      # the same with a ragged last trip (68 channels) and Kt = 16
+    ("bf16", 3, 101, 90, 8, 10, 10, 3, 0.5),    # a single 16-byte piece per row
+]
+
+
+@pytest.mark.parametrize("dtype,B,Mq,Nv,C,Hg,Wg,Kt,p", SAMPLE_CASES)
+def test_sampling_forward_backward_match_oracle(dtype, B, Mq, Nv, C, Hg, Wg, Kt, p):
+    print(f"case vts {dtype} B={B} Mq={Mq} Nv={Nv} C={C} grid={Hg}x{Wg} Kt={Kt}", flush=True)
+    rng = np.random.default_rng(Mq + C)
+    cell, eps = 8.0, 1e-6
+    grid = (Hg, Wg, 0.0, 0.0, cell)
+    vis = _visible(rng, B, Nv, Hg, Wg, cell, 1.0)
+    # queries all over the frame and a little outside it; some exactly on a visible token
+    q = np.stack([rng.uniform(-6, Wg * cell + 6, size=(B, Mq)), rng.uniform(-6, Hg * cell + 6, size=(B, Mq))],
+                 axis=-1).astype(np.float32)
+    q[:, :3] = vis[:, :3]
+    feat = rng.normal(size=(B, Nv, C)).astype(np.float32)
+    dout = rng.normal(size=(B, Mq, C)).astype(np.float32)
+    tdt = torch.float32
+    if dtype == "bf16":
+        feat, dout, tdt = bf16_round(feat), bf16_round(dout), torch.bfloat16
+    rtable = oracle.vts_table(vis, grid, Kt)
+    dq, dvis = torch.from_numpy(q).cuda(), torch.from_numpy(vis).cuda()
+    dfeat, ddout = torch.from_numpy(feat).cuda().to(tdt), torch.from_numpy(dout).cuda().to(tdt)
+    table = aff.affmae_vts_table(dvis, grid, Kt)
+    out = aff.affmae_vts_fwd(dq, dvis, dfeat, table, grid, p, eps)
+    g = aff.affmae_vts_bwd(dq, dvis, dfeat, table, ddout, grid, p, eps)
+    torch.cuda.synchronize()
+    assert np.array_equal(table.cpu().numpy(), rtable)
+    rout = oracle.vts_fwd(q, vis, feat, rtable, grid, p, eps)
+    rg = oracle.vts_bwd(q, vis, feat, rtable, dout, grid, p, eps)
+
+    def err(a, ref):
+        a = a.float().cpu().numpy().astype(np.float64)
+        return float(np.abs(a - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+    tol = TOL[dtype]
+    assert err(out, rout) <= tol
+    assert err(g["dfeat"], rg["dfeat"]) <= tol
+    # dquery and dp are fp32 outputs formed from fp32 sums of products of the stored inputs
+    assert err(g["dquery"], rg["dquery"]) <= (1e-4 if dtype == "f32" else tol)
+    assert abs(float(g["dp"].cpu()) - rg["dp"]) <= (1e-4 if dtype == "f32" else tol) * max(abs(rg["dp"]), np.abs(rg["dquery"]).sum())
+
+
+def test_decoder_shape_of_the_supplement():
+    """Batch of 512px images at 25 % visible, 2048 mask tokens x 4 sample points, Kt = 4 (supplement,
+    'Point-based decoder'), bf16: outputs sampled against the oracle on the first two images."""
+    rng = np.random.default_rng(48)
+    B, Nv, Mq, C, Hg, Wg, Kt, cell, p, eps = 48, 1024, 8192, 128, 64, 64, 4, 8.0, 0.5, 1e-6
+    grid = (Hg, Wg, 0.0, 0.0, cell)
+    vis = _visible(rng, B, Nv, Hg, Wg, cell, 0.0)
+    q = rng.uniform(0, Wg * cell, size=(B, Mq, 2)).astype(np.float32)
+    feat = bf16_round(rng.normal(size=(B, Nv, C)).astype(np.float32))
+    dout = bf16_round(rng.normal(size=(B, Mq, C)).astype(np.float32))
+    dq, dvis = torch.from_numpy(q).cuda(), torch.from_numpy(vis).cuda()
+    dfeat, ddout = torch.from_numpy(feat).cuda().bfloat16(), torch.from_numpy(dout).cuda().bfloat16()
+    table = aff.affmae_vts_table(dvis, grid, Kt)
+    out = aff.affmae_vts_fwd(dq, dvis, dfeat, table, grid, p, eps)
+    g = aff.affmae_vts_bwd(dq, dvis, dfeat, table, ddout, grid, p, eps, want_dp=False)
+    torch.cuda.synchronize()
+    nb = 2
+    rtable = oracle.vts_table(vis[:nb], grid, Kt)
+    assert np.array_equal(table[:nb].cpu().numpy(), rtable)
+    rout = oracle.vts_fwd(q[:nb], vis[:nb], feat[:nb], rtable, grid, p, eps)
+    rg = oracle.vts_bwd(q[:nb], vis[:nb], feat[:nb], rtable, dout[:nb], grid, p, eps)
+    for a, ref in ((out[:nb], rout), (g["dfeat"][:nb], rg["dfeat"]), (g["dquery"][:nb], rg["dquery"])):
+        a = a.float().cpu().numpy().astype(np.float64)
+        assert np.abs(a - ref).max() / np.abs(ref).max() <= 2e-2
