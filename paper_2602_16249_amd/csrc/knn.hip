@@ -209,9 +209,8 @@ __global__ __launch_bounds__(kKnnWaves* kWave) void knn_fast_kernel(const float*
     if (mem) tok = min(max(mem[tok], 0), N - 1);
     cx[row] = xy[2 * (size_t)tok];
     cy[row] = xy[2 * (size_t)tok + 1];
-    cid[row] = (uint32_t)tok;
+    cid[row] = cok[row] ? (uint32_t)tok : 0xffffffffu;
   }
-  const uint32_t kInfBits = 0x7f800000u;
   uint32_t guess = 0u;  // threshold that worked for the previous token (0: none yet)
   for (int r = wave; r < S; r += kKnnWaves) {
     int qtok = c * S + r;
@@ -221,83 +220,7 @@ __global__ __launch_bounds__(kKnnWaves* kWave) void knn_fast_kernel(const float*
 #pragma unroll
     for (int row = 0; row < kFastRows; ++row)
       d2[row] = cok[row] ? __float_as_uint(dist2(qx, qy, cx[row], cy[row])) : 0xffffffffu;
-    auto count_le = [&](uint32_t t) -> int {
-      int n = 0;
-#pragma unroll
-      for (int row = 0; row < kFastRows; ++row) n += __popcll(__ballot(d2[row] <= t));
-      return n;
-    };
-    // invariant: count(lo) < K (lo = -1: nothing known), count(hi) > 64 or hi = +inf bits
-    long long lo = -1, hi = (long long)kInfBits;
-    uint32_t t = guess;
-    if (t == 0u) {  // first token of the wave: the farthest of the first 64 candidates, so the count is not 0
-      t = min(d2[0], kInfBits);
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) t = max(t, (uint32_t)__shfl_xor((int)t, o));
-      t = __builtin_amdgcn_readfirstlane(t);
-    }
-    bool found = false;
-    for (int it = 0; it < 48; ++it) {
-      const int n = count_le(t);
-      if (n >= K && n <= kWave) { found = true; break; }
-      if (n < K) lo = t; else hi = t;
-      if (hi - lo <= 1) break;  // neighbouring bit patterns straddle the window
-      long long next = -1;
-      if (it < 4 && n > 0) {
-        const float scaled = __uint_as_float(t) * ((float)(K + kWave) * 0.5f / (float)n);
-        next = (long long)__float_as_uint(scaled);
-      }
-      if (next <= lo || next >= hi) next = lo + (hi - lo) / 2;
-      t = (uint32_t)next;
-    }
-    key_t best;
-    if (found) {
-      guess = t;
-      int fill = 0;
-#pragma unroll
-      for (int row = 0; row < kFastRows; ++row) {
-        const bool in = d2[row] <= t;
-        const unsigned long long mask = __ballot(in);
-        const int rank =
-            __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-        if (in) pend[fill + rank] = ((key_t)d2[row] << 32) | cid[row];
-        fill += __popcll(mask);
-      }
-      wave_lds_sync();
-      best = wave_sort((lane < fill) ? pend[lane] : kKeyMax, lane);
-      wave_lds_sync();
-    } else {
-      best = wave_sort(((key_t)d2[0] << 32) | (cok[0] ? cid[0] : 0xffffffffu), lane);
-      key_t bound = shfl_key(best, K - 1);
-      int fill = 0;
-#pragma unroll
-      for (int row = 1; row < kFastRows; ++row) {
-        const key_t key = ((key_t)d2[row] << 32) | (cok[row] ? cid[row] : 0xffffffffu);
-        const bool in = key < bound;
-        const unsigned long long mask = __ballot(in);
-        if (mask != 0ull) {
-          const int rank =
-              __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-          if (in) pend[fill + rank] = key;
-          fill += __popcll(mask);
-          if (fill >= kWave) {
-            wave_lds_sync();
-            const key_t full = pend[lane];
-            const key_t rest = pend[kWave + lane];
-            wave_lds_sync();
-            fill -= kWave;
-            if (lane < fill) pend[lane] = rest;
-            best = topk_push(best, full, lane, K - 1);
-            bound = shfl_key(best, K - 1);
-          }
-        }
-      }
-      if (fill > 0) {
-        wave_lds_sync();
-        best = topk_push(best, (lane < fill) ? pend[lane] : kKeyMax, lane, K - 1);
-      }
-      wave_lds_sync();
-    }
+    const key_t best = select_nearest<kFastRows>(d2, cid, K, guess, pend, lane);
     if (lane < K) nbr_idx[((size_t)b * N + qtok) * K + lane] = (int32_t)(uint32_t)best;
   }
 }

@@ -107,4 +107,99 @@ __device__ __forceinline__ key_t topk_push(key_t best, key_t row, int lane, int 
   return wave_bitonic_merge(best, lane);
 }
 
+// The K nearest of up to 64 * ROWS candidates held one per lane and row: d2[row] = bit pattern of the lane's
+// squared distance (ordered like the value, since d2 >= +0; all ones where the lane has no candidate), id[row] =
+// its index (all ones likewise).  Returns the keys ascending across the lanes (the first K are the answer).
+//
+// The wave looks for a distance threshold T with K <= #{d2 <= T} <= 64 by counting with ballots: it starts from
+// `guess` (the threshold that worked for the previous, nearby query; 0 = none), scales it by wanted / found (the
+// count grows like the area, i.e. like d2), then bisects on the bit pattern.  Everything at or below T is nearer
+// than everything above it, so the K nearest are among the counted candidates: they are compacted into one row
+// (through `pend`, 128 keys of LDS owned by the wave) and sorted once.  When no such T exists (more than
+// 64 - K + 1 candidates at one distance) the first row is sorted and later candidates that beat the current K-th
+// key are queued and merged 64 at a time.  Either way the result is exact.
+template <int ROWS>
+__device__ __forceinline__ key_t select_nearest(const uint32_t (&d2)[ROWS], const uint32_t (&id)[ROWS], int K,
+                                                uint32_t& guess, key_t* pend, int lane) {
+  const uint32_t kInfBits = 0x7f800000u;
+  auto count_le = [&](uint32_t t) -> int {
+    int n = 0;
+#pragma unroll
+    for (int row = 0; row < ROWS; ++row) n += __popcll(__ballot(d2[row] <= t));
+    return n;
+  };
+  // invariant: count(lo) < K (lo = -1: nothing known), count(hi) > 64 or hi = +inf bits
+  long long lo = -1, hi = (long long)kInfBits;
+  uint32_t t = guess;
+  if (t == 0u) {  // first token of the wave: the farthest of the first 64 candidates, so the count is not 0
+    t = min(d2[0], kInfBits);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) t = max(t, (uint32_t)__shfl_xor((int)t, o));
+    t = __builtin_amdgcn_readfirstlane(t);
+  }
+  bool found = false;
+  for (int it = 0; it < 48; ++it) {
+    const int n = count_le(t);
+    if (n >= K && n <= kWave) { found = true; break; }
+    if (n < K) lo = t; else hi = t;
+    if (hi - lo <= 1) break;  // neighbouring bit patterns straddle the window
+    long long next = -1;
+    if (it < 4 && n > 0) {
+      const float scaled = __uint_as_float(t) * ((float)(K + kWave) * 0.5f / (float)n);
+      next = (long long)__float_as_uint(scaled);
+    }
+    if (next <= lo || next >= hi) next = lo + (hi - lo) / 2;
+    t = (uint32_t)next;
+  }
+  key_t best;
+  if (found) {
+    guess = t;
+    int fill = 0;
+#pragma unroll
+    for (int row = 0; row < ROWS; ++row) {
+      const bool in = d2[row] <= t;
+      const unsigned long long mask = __ballot(in);
+      const int rank =
+          __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+      if (in) pend[fill + rank] = ((key_t)d2[row] << 32) | id[row];
+      fill += __popcll(mask);
+    }
+    wave_lds_sync();
+    best = wave_sort((lane < fill) ? pend[lane] : kKeyMax, lane);
+    wave_lds_sync();
+  } else {
+    best = wave_sort(((key_t)d2[0] << 32) | id[0], lane);
+    key_t bound = shfl_key(best, K - 1);
+    int fill = 0;
+#pragma unroll
+    for (int row = 1; row < ROWS; ++row) {
+      const key_t key = ((key_t)d2[row] << 32) | id[row];
+      const bool in = key < bound;
+      const unsigned long long mask = __ballot(in);
+      if (mask != 0ull) {
+        const int rank =
+            __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (in) pend[fill + rank] = key;
+        fill += __popcll(mask);
+        if (fill >= kWave) {
+          wave_lds_sync();
+          const key_t full = pend[lane];
+          const key_t rest = pend[kWave + lane];
+          wave_lds_sync();
+          fill -= kWave;
+          if (lane < fill) pend[lane] = rest;
+          best = topk_push(best, full, lane, K - 1);
+          bound = shfl_key(best, K - 1);
+        }
+      }
+    }
+    if (fill > 0) {
+      wave_lds_sync();
+      best = topk_push(best, (lane < fill) ? pend[lane] : kKeyMax, lane, K - 1);
+    }
+    wave_lds_sync();
+  }
+  return best;
+}
+
 }  // namespace affmae

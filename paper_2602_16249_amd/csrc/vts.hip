@@ -82,6 +82,50 @@ __global__ __launch_bounds__(256) void vts_table_kernel(const float* __restrict_
   if (lane < Kt) table[(size_t)gcell * Kt + lane] = (int32_t)(uint32_t)best;
 }
 
+// At most 1024 visible tokens per image: every lane keeps its 16 tokens in registers and the wave serves a run
+// of consecutive grid points of one image, each by a counted distance threshold and a single sort (the
+// threshold of one grid point is the first guess for the next).
+constexpr int kTableRows = 16;
+constexpr int kTableRun = 16;  // grid points per wave
+__global__ __launch_bounds__(256) void vts_table_fast_kernel(const float* __restrict__ vis_xy, int B, int Nv, Grid gr,
+                                                            int Kt, int32_t* __restrict__ table) {
+  __shared__ key_t pend_all[4][2 * kWave];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int per_image = gr.Hg * gr.Wg;
+  const int runs_per_image = (per_image + kTableRun - 1) / kTableRun;
+  const long long grun = (long long)blockIdx.x * 4 + wave;
+  if (grun >= (long long)B * runs_per_image) return;  // wave-uniform; no workgroup barrier below
+  key_t* pend = pend_all[wave];
+  const int b = (int)(grun / runs_per_image);
+  const int first = (int)(grun - (long long)b * runs_per_image) * kTableRun;
+  const float* xy = vis_xy + (size_t)b * Nv * 2;
+  float cx[kTableRows], cy[kTableRows];
+  uint32_t cid[kTableRows];
+#pragma unroll
+  for (int row = 0; row < kTableRows; ++row) {
+    const int i = row * kWave + lane;
+    const bool ok = i < Nv;
+    cx[row] = ok ? xy[2 * (size_t)i] : 0.f;
+    cy[row] = ok ? xy[2 * (size_t)i + 1] : 0.f;
+    cid[row] = ok ? (uint32_t)i : 0xffffffffu;
+  }
+  uint32_t guess = 0u;
+  for (int c = first; c < min(first + kTableRun, per_image); ++c) {
+    const int iy = c / gr.Wg, ix = c - iy * gr.Wg;
+    // patch centre, each operation rounded separately
+    const float hx = (float)ix + 0.5f, hy = (float)iy + 0.5f;
+    const float sx = hx * gr.cell, sy = hy * gr.cell;
+    const float gx = gr.x0 + sx, gy = gr.y0 + sy;
+    uint32_t d2[kTableRows];
+#pragma unroll
+    for (int row = 0; row < kTableRows; ++row)
+      d2[row] = cid[row] != 0xffffffffu ? __float_as_uint(dist2(gx, gy, cx[row], cy[row])) : 0xffffffffu;
+    const key_t best = select_nearest<kTableRows>(d2, cid, Kt, guess, pend, lane);
+    if (lane < Kt) table[((size_t)b * per_image + c) * Kt + lane] = (int32_t)(uint32_t)best;
+  }
+}
+
 // Grid cell of a query coordinate: floor((q - x0) / cell), clamped to 0..n-1 (NaN goes to 0).
 __device__ __forceinline__ int cell_of(float q, float x0, float cell, int n) {
   const float t = q - x0;
@@ -490,6 +534,12 @@ __global__ __launch_bounds__(256) void vts_dfeat_kernel(const T* __restrict__ do
 hipError_t launch_vts_table(const VtsArgs& a, hipStream_t stream) {
   const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
   const long long cells = (long long)a.B * a.Hg * a.Wg;
+  if (a.Nv <= kTableRows * kWave) {
+    const long long runs = (long long)a.B * ((a.Hg * a.Wg + kTableRun - 1) / kTableRun);
+    AFFMAE_LAUNCH("vts_table_kernel", stream, vts_table_fast_kernel, dim3((unsigned)((runs + 3) / 4)), dim3(256), 0,
+                  stream, a.vis_xy, a.B, a.Nv, gr, a.Kt, a.table_out);
+    return hipGetLastError();
+  }
   AFFMAE_LAUNCH("vts_table_kernel", stream, vts_table_kernel, dim3((unsigned)((cells + 3) / 4)), dim3(256), 0, stream,
                 a.vis_xy, a.B, a.Nv, gr, a.Kt, a.table_out);
   return hipGetLastError();

@@ -66,6 +66,38 @@ def test_cluster_rejects_bad_arguments_on_host():
     assert lib.affmae_cluster_workspace_bytes(0, 100) == 0
 
 
+def test_virtual_tokens_reject_bad_arguments_on_host():
+    lib = aff.load_library()
+    f, i, v = ctypes.c_float, ctypes.c_int, ctypes.c_void_p
+    lib.affmae_vts_table.argtypes = [v] + [i] * 4 + [f] * 3 + [i, v, v]
+    lib.affmae_vts_fwd.argtypes = [v] * 4 + [i] * 6 + [f] * 3 + [i] + [f] * 2 + [i] + [v, v]
+    lib.affmae_vts_bwd.argtypes = [v] * 5 + [i] * 6 + [f] * 3 + [i] + [f] * 2 + [i] + [v] * 4 + [ctypes.c_size_t, v]
+    p = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
+    assert lib.affmae_vts_table(None, 1, 16, 4, 4, 0.0, 0.0, 8.0, 4, p, None) == -1
+    assert lib.affmae_vts_table(p, 1, 16, 4, 4, 0.0, 0.0, 8.0, 17, p, None) == -2          # Kt > Nv
+    assert lib.affmae_vts_table(p, 1, 16, 0, 4, 0.0, 0.0, 8.0, 4, p, None) == -2
+    assert lib.affmae_vts_table(p, 1, 16, 4, 4, 0.0, 0.0, 0.0, 4, p, None) == -2           # empty cell
+    assert lib.affmae_vts_table(p, 1, 100, 4, 4, 0.0, 0.0, 8.0, 65, p, None) == -5         # Kt beyond the limit
+
+    def fwd(q=p, feat=p, out=p, C=8, dtype=1, Kt=4):
+        return lib.affmae_vts_fwd(q, p, feat, p, 1, 10, 16, C, 4, 4, 0.0, 0.0, 8.0, Kt, 0.5, 1e-6, dtype, out, None)
+
+    assert fwd(q=None) == -1 and fwd(out=None) == -1
+    assert fwd(dtype=7) == -3
+    assert fwd(C=7) == -5                                                                 # odd channel count
+    assert fwd(feat=ctypes.c_void_p(4098)) == -2                                          # misaligned rows
+    assert fwd(Kt=17) == -2
+
+    def bwd(ws=p, nbytes=1 << 20, dq=p):
+        return lib.affmae_vts_bwd(p, p, p, p, p, 1, 10, 16, 8, 4, 4, 0.0, 0.0, 8.0, 4, 0.5, 1e-6, 1, p, dq, None, ws,
+                                  nbytes, None)
+
+    assert bwd(dq=None) == -1
+    assert bwd(ws=None, nbytes=0) == -4 and bwd(nbytes=16) == -4
+    assert lib.affmae_vts_bwd_workspace_bytes(1, 10, 16, 4) > 0
+    assert lib.affmae_vts_bwd_workspace_bytes(1, 10, 16, 65) == 0
+
+
 def test_attention_rejects_bad_arguments_on_host():
     lib = aff.load_library()
     p = ctypes.c_void_p(4096)

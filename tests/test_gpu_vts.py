@@ -32,6 +32,8 @@ TABLE_CASES = [
     (3, 1024, 64, 64, 8.0, 4, 0.0),      # a 512px image at 25 % visible
     (1, 1024, 64, 64, 8.0, 64, 2.0),     # Kt at the limit
     (2, 577, 20, 30, 5.0, 9, 1.5),
+    (2, 1500, 48, 48, 8.0, 4, 0.5),      # more than 1024 visible tokens: the streaming kernel
+    (1, 2304, 48, 48, 8.0, 7, 0.0),      # every centre visible, streaming kernel
 ]
 
 
