@@ -93,7 +93,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over images with no exchange "
-              "(see DESIGN.md), and no multi-GPU figure is produced. Use --gpus 1.", file=sys.stderr)
+              "(images of a batch are independent), and no multi-GPU figure is produced. Use --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
@@ -211,7 +211,7 @@ def main() -> int:
     fwd_b, bwd_b = algorithmic_bytes_per_token(cfg.C, cfg.H, cfg.K, elt)
     # Algorithmic bytes per token of each kernel: the tensors it is the first (and, by the method, only
     # necessary) reader or writer of.  The backward is split in two kernels: the key-stationary one owns
-    # dk and dv; everything else of the backward belongs to the query-stationary one (see DESIGN.md).
+    # dk and dv; everything else of the backward belongs to the query-stationary one.
     own = {}
     for n in attn_kernels:
         if "fwd" in n:

@@ -27,6 +27,7 @@ namespace {
 constexpr int kSlotCap = 10;  // token tiles whose bias tile is resident per wave (5 KB): four workgroups per CU
 static_assert(kSlotCap % 2 == 0, "an odd pass uses one more tile for the second half of its last pair");
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazy = 6.f;  // the softmax reference follows the running maximum in steps of at least this much
 
 struct FwdParams {
   const bf16_t *q, *k, *v, *bias, *k_blank, *v_blank;
@@ -210,22 +211,28 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
         mx = group_max(mx);
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * kLog2e);
-        const float shift = -m_safe * kLog2e;
+        // Online softmax with a lazily moved reference: m_run only follows the maximum when it rose by more than
+        // kLazy, and only then are the sums rescaled (wave-uniform test).  Probabilities are relative to m_run
+        // and may reach e^kLazy; the fp32 sums and the bf16 operand keep their relative precision at that size.
+        const bool move = mx > m_run + kLazy;  // also the first finite maximum after -inf
+        if (__ballot(move) != 0ull) {
+          const float m_new = move ? mx : m_run;
+          const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e) : 1.f;  // exp2(-inf) = 0
+          l_run *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[dt][i] *= alpha;
+          m_run = m_new;
+        }
+        const float shift = (m_run == -INFINITY) ? 0.f : -m_run * kLog2e;
         float pr8[8], psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           pr8[i] = __builtin_amdgcn_exp2f(fmaf(s[i], kLog2e, shift));
           psum += pr8[i];
         }
-        l_run = fmaf(l_run, alpha, psum);
-        m_run = m_new;
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) acc[dt][i] *= alpha;
+        l_run += psum;
         Frag8 pf;  // P^T operand: k-slots 0..3 = first tile's tokens 4g..4g+3, 4..7 = second tile's
         pf.u[0] = pack_bf16x2(pr8[0], pr8[1]);
         pf.u[1] = pack_bf16x2(pr8[2], pr8[3]);

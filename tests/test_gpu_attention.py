@@ -79,6 +79,18 @@ def test_clustered_tables(name, B, N, C, H, K, S, M, blank, promise):
                     blank=blank, use_plan=promise == "plan")
 
 
+@pytest.mark.parametrize("scale", [1.5, 4.0])
+@pytest.mark.parametrize("blank", [False, True])
+def test_wide_range_of_scores(scale, blank):
+    """Logits with a standard deviation of 8 to 20: the running maximum of the streaming softmax rises many
+    times along the tiles and most probabilities underflow next to the largest ones."""
+    print(f"case wide scores scale={scale} blank={blank}", flush=True)
+    cfg = CONFIGS["mae_pt_s1_1024"].scaled(B=2, N=1024, dtype="bf16")
+    w = make_workload(cfg, blank=blank)
+    nbr, near = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
+    check_attention(w, nbr, cfg.dtype, scale, near=near, S=cfg.S, M=cfg.M, blank=blank, use_plan=True)
+
+
 @pytest.mark.parametrize("name", ["mae_pt_s1_1024", "ft_s1_1024", "merged_stage", "knn_scale"])
 def test_full_size_configs(name):
     """The benchmark's configurations at full size in the launch configuration
