@@ -259,7 +259,7 @@ size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, 
   size_t tiled = 0;
   if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && N % S == 0 && tiled_shape_ok(B, N, K, S, M))
     tiled = align_up(affmae::pla_plan_bytes(B, N, K, S, M)) + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, S, M);
-  return gather > tiled ? gather : tiled;  // blank tokens send a clustered call to the gather kernels
+  return gather > tiled ? gather : tiled;
 }
 
 int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
@@ -288,8 +288,7 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
   a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias; a.dk_blank = dk_blank; a.dv_blank = dv_blank;
   a.workspace = workspace;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  // The tiled kernels do not form the blank-row gradients; such calls take the gather kernels.
-  if (affmae::pla_cluster_supported(a) && !k_blank) {
+  if (affmae::pla_cluster_supported(a)) {
     if (!out) return AFFMAE_ERR_NULL;
     if (misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
     if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;

@@ -9,7 +9,9 @@
 //    accumulates dQ^T = K^T dS^T (K transposed by an MFMA against the identity),
 //    and leaves p and dS of the real (query, neighbour) pairs in compact arrays:
 //    dS in [token, head, slot] order is dbias; (p, dS) words go to the workspace
-//    in the plan's run order (grouped by token tile);
+//    in the plan's run order (grouped by token tile).  With blank tokens the blank column joins
+//    every query's softmax: its dS feeds dq, and the strip's sums for dk_blank / dv_blank go to
+//    the workspace, to be added up over the strips in a fixed order by a last kernel;
 //
 //  key-stationary (one wave per tile of 16 tokens): walks the sorted list of
 //    strips that touch the tile, reads each strip's run of (p, dS) words for the
@@ -41,6 +43,8 @@ struct BwdParams {
   bf16_t* ds;    // [B,N,H,K] dS = dbias, or nullptr when the caller does not want it
   uint32_t* pd;  // workspace [strips][H][places]: one word per place of the plan's run order,
                  // p in the low half, dS in the high half (bf16 bits)
+  const bf16_t *k_blank, *v_blank;  // [H,32] or nullptr
+  float* blank_part;                // workspace [strips][H][2][32]: the strip's parts of dk_blank, dv_blank; or nullptr
 };
 
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
@@ -165,6 +169,49 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
     const float nl2 = -p.lse[(size_t)(tok0 + r) * p.H + h] * kLog2e;
     const size_t head_rows = strip_rows + (size_t)h * K;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    if (p.k_blank) {
+      // the blank column of query r: s = scale <q, k_blank>, p = exp(s - lse), dP = <dout, v_blank>, dS = p (dP - D)
+      Frag8 kb, vb;  // channels 8g..8g+7 of the head's blank rows
+      kb.u4 = *reinterpret_cast<const uint4*>(p.k_blank + h * kD + g * 8);
+      vb.u4 = *reinterpret_cast<const uint4*>(p.v_blank + h * kD + g * 8);
+      float sq = 0.f, gv = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        sq = fmaf(bf16_to_f32(qf.h[i]), bf16_to_f32(kb.h[i]), sq);
+        gv = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(vb.h[i]), gv);
+      }
+      sq = group_sum(sq);
+      gv = group_sum(gv);
+      const float pb = __builtin_amdgcn_exp2f(fmaf(p.scale * sq, kLog2e, nl2));
+      const float dsb = pb * (gv - Dq);
+      // dq^T[channel 16dt + 4g + i][query r] += dS k_blank (the scale is applied when dq is written)
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[dt][i] = fmaf(dsb, bf16_to_f32(p.k_blank[h * kD + dt * 16 + g * 4 + i]), acc[dt][i]);
+      if (p.blank_part) {
+        // the strip's parts: dk_blank[c] = scale sum_r dS_r q[r][c], dv_blank[c] = sum_r p_r dout[r][c]; lane (r, g)
+        // holds channels 8g..8g+7 of query r, so the sum over r runs over the 16 lanes of a row of the wave
+        float pk[8], pv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          pk[i] = p.scale * dsb * bf16_to_f32(qf.h[i]);
+          pv[i] = pb * bf16_to_f32(gf.h[i]);
+#pragma unroll
+          for (int o = 8; o > 0; o >>= 1) {
+            pk[i] += __shfl_xor(pk[i], o);
+            pv[i] += __shfl_xor(pv[i], o);
+          }
+        }
+        if (r == 0) {
+          float* dst = p.blank_part + ((size_t)sg * p.H + h) * 2 * kD + g * 8;
+          *reinterpret_cast<float4*>(dst) = make_float4(pk[0], pk[1], pk[2], pk[3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(pk[4], pk[5], pk[6], pk[7]);
+          *reinterpret_cast<float4*>(dst + kD) = make_float4(pv[0], pv[1], pv[2], pv[3]);
+          *reinterpret_cast<float4*>(dst + kD + 4) = make_float4(pv[4], pv[5], pv[6], pv[7]);
+        }
+      }
+    }
     uint32_t dacc[NT][EW];  // dS of this lane's items (packed bf16), gathered pass by pass
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -536,11 +583,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   }
 }
 
+// dk_blank, dv_blank [H,32] = sum over the strips of their parts, in a fixed order.  One workgroup per
+// (head, which of the two): 32 groups of 32 lanes, group j adds strips j, j + 32, ...
+__global__ __launch_bounds__(1024) void pla_blank_reduce_kernel(const float* __restrict__ part, int strips, int H,
+                                                               float* __restrict__ dk_blank,
+                                                               float* __restrict__ dv_blank) {
+  __shared__ float acc[32][kD + 1];
+  const int h = blockIdx.x >> 1, which = blockIdx.x & 1;
+  const int c = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  float s = 0.f;
+  for (int sg = grp; sg < strips; sg += 32) s += part[(((size_t)sg * H + h) * 2 + which) * kD + c];
+  acc[grp][c] = s;
+  __syncthreads();
+  if (grp == 0) {
+    float t = 0.f;
+    for (int j = 0; j < 32; ++j) t += acc[j][c];
+    (which ? dv_blank : dk_blank)[h * kD + c] = t;
+  }
+}
+
 }  // namespace
 
 size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, int S, int M) {
   const PlanLayout L = make_plan_layout(B, N, K, S, M);
-  return plan_align((size_t)L.strips * H * L.places * sizeof(uint32_t));
+  return plan_align((size_t)L.strips * H * L.places * sizeof(uint32_t)) +  // (p, dS) words
+         plan_align((size_t)L.strips * H * 2 * kD * sizeof(float));        // parts of the blank gradients
 }
 
 hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* workspace, hipStream_t stream) {
@@ -562,6 +629,11 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.dq = (bf16_t*)a.dq; p.dk = (bf16_t*)a.dk; p.dv = (bf16_t*)a.dv;
   p.pd = static_cast<uint32_t*>(workspace);
   p.ds = (bf16_t*)a.dbias;
+  p.k_blank = (const bf16_t*)a.k_blank; p.v_blank = (const bf16_t*)a.v_blank;
+  p.blank_part = (a.k_blank && a.dk_blank)
+                     ? reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                                plan_align((size_t)L.strips * a.H * L.places * sizeof(uint32_t)))
+                     : nullptr;
 
   const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);  // multiple of 8 for the XCD-contiguous mapping
   const dim3 grid_q((((long long)L.strips * a.H + 3) / 4 + 7) / 8 * 8);  // one wave per (strip, head)
@@ -585,6 +657,9 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
     AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<2>, grid, dim3(256), 0, stream, p);
   else
     AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<1>, grid, dim3(256), 0, stream, p);
+  if (p.blank_part)
+    AFFMAE_LAUNCH("pla_blank_reduce_kernel", stream, pla_blank_reduce_kernel, dim3(2 * a.H), dim3(1024), 0, stream,
+                  p.blank_part, L.strips, a.H, a.dk_blank, a.dv_blank);
   return hipGetLastError();
 }
 

@@ -101,3 +101,15 @@ def test_full_size_configs(name):
     nbr, near = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
     errs = check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, use_plan=True)
     print(errs)
+
+
+def test_full_image_with_blank_tokens():
+    """Two full 1024px images with blank tokens: the blank column in the tiled forward and backward, and
+    the sums for dk_blank / dv_blank over 2048 strips."""
+    cfg = CONFIGS["ft_s1_1024"].scaled(B=2)
+    print("case ft_s1_1024 B=2 blank", flush=True)
+    w = make_workload(cfg, blank=True)
+    nbr, near = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
+    errs = check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, blank=True,
+                           use_plan=True)
+    print(errs)
