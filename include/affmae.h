@@ -258,8 +258,7 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
  *                     of the additions into dk/dv may differ between runs.
  *   dbias         out [B,N,H,K] of `dtype`, or NULL to skip.
  *   dk_blank,dv_blank out [H,d] fp32, or NULL (both required when blanks given
- *                     and their gradients are wanted).  Calls with blank tokens
- *                     use the gather kernels even when near_clusters is given.
+ *                     and their gradients are wanted).
  */
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
                                       int clustered);
