@@ -26,6 +26,14 @@
 namespace affmae {
 namespace {
 
+// Workgroups are dealt round-robin to the 8 XCDs (one L2 each).  Consecutive queries and tokens belong to one
+// image and share its feature rows, so every XCD gets a contiguous range.  The grid is a multiple of 8.
+__device__ __forceinline__ long long xcd_contiguous_block() {
+  const unsigned per_xcd = gridDim.x >> 3;
+  return (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+}
+inline unsigned round_up8(long long blocks) { return (unsigned)((blocks + 7) / 8 * 8); }
+
 struct Grid {
   int Hg, Wg;
   float x0, y0, cell;
@@ -190,7 +198,7 @@ __global__ __launch_bounds__(256) void vts_fwd_kernel(const float* __restrict__ 
                                                      int B, int Mq, int Nv, int C, Grid gr, int Kt, float p, float eps,
                                                      T* __restrict__ out) {
   const int lane = threadIdx.x & (kWave - 1);
-  const long long gq = (long long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const long long gq = xcd_contiguous_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (gq >= (long long)B * Mq) return;  // wave-uniform
   const int b = (int)(gq / Mq);
   const Cand cd = load_candidate(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, lane);
@@ -223,7 +231,7 @@ __global__ __launch_bounds__(256) void vts_bwd_kernel(const float* __restrict__ 
                                                      int32_t* __restrict__ pair_token, int32_t* __restrict__ count,
                                                      float* __restrict__ dquery, float* __restrict__ dp_part) {
   const int lane = threadIdx.x & (kWave - 1);
-  const long long gq = (long long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const long long gq = xcd_contiguous_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (gq >= (long long)B * Mq) return;  // wave-uniform
   const int b = (int)(gq / Mq);
   const Cand cd = load_candidate(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, lane);
@@ -341,7 +349,7 @@ __global__ __launch_bounds__(256) void vts_fwd16_kernel(const float* __restrict_
   constexpr int CH = Piece<T>::kCh;
   const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
   const long long total = (long long)B * Mq;
-  const long long want = ((long long)blockIdx.x * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
+  const long long want = (xcd_contiguous_block() * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
   const bool live = want < total;
   const long long gq = live ? want : total - 1;
   const int b = (int)(gq / Mq);
@@ -376,7 +384,7 @@ __global__ __launch_bounds__(256) void vts_bwd16_kernel(const float* __restrict_
   constexpr int CH = Piece<T>::kCh;
   const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
   const long long total = (long long)B * Mq;
-  const long long want = ((long long)blockIdx.x * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
+  const long long want = (xcd_contiguous_block() * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
   const bool live = want < total;
   const long long gq = live ? want : total - 1;
   const int b = (int)(gq / Mq);
@@ -501,7 +509,7 @@ __global__ __launch_bounds__(256) void vts_dfeat_kernel(const T* __restrict__ do
                                                        const int32_t* __restrict__ list, int tokens, int C, int Kt,
                                                        T* __restrict__ dfeat) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int tok = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const long long tok = xcd_contiguous_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (tok >= tokens) return;  // wave-uniform
   const int lo = offset[tok], n = offset[tok + 1] - lo;
   for (int base = 0; base < C; base += 2 * kWave) {  // wave-uniform trips; only the memory accesses are predicated
@@ -555,7 +563,7 @@ static bool vts_grouped(const VtsArgs& a, const void* t0, const void* t1, const 
 hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream) {
   const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
   if (vts_grouped(a, a.feat, a.out, nullptr)) {
-    const dim3 grid16((unsigned)(((long long)a.B * a.Mq + 15) / 16));
+    const dim3 grid16(round_up8(((long long)a.B * a.Mq + 15) / 16));
     if (a.dtype == 1)
       AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd16_kernel<bf16_t>, grid16, dim3(256), 0, stream, a.query_xy,
                     a.vis_xy, (const bf16_t*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
@@ -565,7 +573,7 @@ hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream) {
                     a.vis_xy, (const float*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, (float*)a.out);
     return hipGetLastError();
   }
-  const dim3 grid((unsigned)(((long long)a.B * a.Mq + 3) / 4));
+  const dim3 grid(round_up8(((long long)a.B * a.Mq + 3) / 4));
   if (a.dtype == 1)
     AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd_kernel<bf16_t>, grid, dim3(256), 0, stream, a.query_xy, a.vis_xy,
                   (const bf16_t*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, (bf16_t*)a.out);
@@ -600,7 +608,7 @@ size_t vts_bwd_workspace_bytes(int B, int Mq, int Nv, int Kt) { return vts_bwd_l
 
 hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
   const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
-  const dim3 grid((unsigned)(((long long)a.B * a.Mq + 3) / 4));
+  const dim3 grid(round_up8(((long long)a.B * a.Mq + 3) / 4));
   const VtsBwdLayout L = vts_bwd_layout(a.B, a.Mq, a.Nv, a.Kt);
   char* ws = static_cast<char*>(a.workspace);
   float* weights = reinterpret_cast<float*>(ws + L.weights_off);
@@ -614,7 +622,7 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
   AFFMAE_LAUNCH("vts_zero_kernel", stream, vts_zero_kernel, dim3((unsigned)((tokens + 255) / 256)), dim3(256), 0, stream,
                 count, cursor, tokens);
   const bool grouped = vts_grouped(a, a.feat, a.dout, nullptr);
-  const dim3 grid16((unsigned)(((long long)a.B * a.Mq + 15) / 16));
+  const dim3 grid16(round_up8(((long long)a.B * a.Mq + 15) / 16));
   if (grouped && a.dtype == 1)
     AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd16_kernel<bf16_t>, grid16, dim3(256), 0, stream, a.query_xy, a.vis_xy,
                   (const bf16_t*)a.feat, a.table, (const bf16_t*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
@@ -638,7 +646,7 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
                 count, offset, (int)tokens);
   AFFMAE_LAUNCH("vts_fill_kernel", stream, vts_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, stream,
                 pair_token, offset, cursor, list, pairs);
-  const dim3 per_token((unsigned)((tokens + 3) / 4));
+  const dim3 per_token(round_up8(((long long)tokens + 3) / 4));
   if (a.dtype == 1)
     AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<bf16_t>, per_token, dim3(256), 0, stream,
                   (const bf16_t*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (bf16_t*)a.dfeat);
