@@ -391,6 +391,9 @@ __global__ __launch_bounds__(256) void vts_bwd16_kernel(const float* __restrict_
   const Cand cd = load_candidate16(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, sub);
   const int group = lane & 48;
   float g_mine = 0.f;
+  const bool one_trip = C <= 16 * CH;  // the whole dout row is one piece per lane: load it once
+  float g0[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (one_trip && sub * CH < C) Piece<T>::load(dout + (size_t)gq * C + sub * CH, g0);
   for (int i = 0; i < Kt; ++i) {
     const int idx = __shfl(cd.idx, group | i);
     float part = 0.f;
@@ -398,8 +401,13 @@ __global__ __launch_bounds__(256) void vts_bwd16_kernel(const float* __restrict_
       const int c0 = base + sub * CH;
       if (c0 < C) {
         float g[8], f[8];
-        Piece<T>::load(dout + (size_t)gq * C + c0, g);
         Piece<T>::load(feat + ((size_t)b * Nv + idx) * C + c0, f);
+        if (one_trip) {
+#pragma unroll
+          for (int e = 0; e < CH; ++e) g[e] = g0[e];
+        } else {
+          Piece<T>::load(dout + (size_t)gq * C + c0, g);
+        }
 #pragma unroll
         for (int e = 0; e < CH; ++e) part = fmaf(g[e], f[e], part);
       }
@@ -500,6 +508,48 @@ __global__ __launch_bounds__(256) void vts_fill_kernel(const int32_t* __restrict
   if (e >= pairs) return;
   const int tok = pair_token[e];
   list[offset[tok] + atomicAdd(cursor + tok, 1)] = (int32_t)e;
+}
+
+// Four visible tokens per wave (16 lanes each) when the rows are whole 16-byte pieces: dfeat = sum over the
+// token's pairs of w * dout[query].
+template <typename T>
+__global__ __launch_bounds__(256) void vts_dfeat16_kernel(const T* __restrict__ dout, const float* __restrict__ weights,
+                                                         const int32_t* __restrict__ offset,
+                                                         const int32_t* __restrict__ list, int tokens, int C, int Kt,
+                                                         T* __restrict__ dfeat) {
+  constexpr int CH = Piece<T>::kCh;
+  const int lane = threadIdx.x & (kWave - 1), sub = lane & 15, group = lane & 48;
+  const long long want = (xcd_contiguous_block() * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
+  const bool live = want < tokens;
+  const long long tok = live ? want : tokens - 1;
+  const int lo = offset[tok], n = live ? offset[tok + 1] - lo : 0;
+  // the longest list of the wave's four tokens sets the (wave-uniform) trip count of the pair loop
+  int nmax = n;
+  nmax = max(nmax, __shfl_xor(nmax, 16));
+  nmax = max(nmax, __shfl_xor(nmax, 32));
+  for (int base = 0; base < C; base += 16 * CH) {
+    const int c0 = base + sub * CH;
+    const bool on = live && c0 < C;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int chunk = 0; chunk < nmax; chunk += 16) {
+      const bool have = chunk + sub < n;
+      const int mine = have ? list[lo + chunk + sub] : 0;
+      const float wmine = have ? weights[mine] : 0.f;  // pairs past the end of a shorter list weigh 0
+      const int qmine = mine / Kt;
+      const int m = min(16, nmax - chunk);
+      for (int i = 0; i < m; ++i) {
+        const float w = __shfl(wmine, group | i);
+        const int q = __shfl(qmine, group | i);
+        if (on) {
+          float g[8];
+          Piece<T>::load(dout + (size_t)q * C + c0, g);
+#pragma unroll
+          for (int e = 0; e < CH; ++e) acc[e] = fmaf(w, g[e], acc[e]);
+        }
+      }
+    }
+    if (on) Piece<T>::store(dfeat + (size_t)tok * C + c0, acc);
+  }
 }
 
 // One wave per visible token: dfeat = sum over the token's pairs of w * dout[query].
@@ -646,6 +696,16 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
                 count, offset, (int)tokens);
   AFFMAE_LAUNCH("vts_fill_kernel", stream, vts_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, stream,
                 pair_token, offset, cursor, list, pairs);
+  if (vts_grouped(a, a.dout, a.dfeat, nullptr)) {  // (Kt <= 16 is not needed here, only the row shape)
+    const dim3 per4(round_up8(((long long)tokens + 15) / 16));
+    if (a.dtype == 1)
+      AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat16_kernel<bf16_t>, per4, dim3(256), 0, stream,
+                    (const bf16_t*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (bf16_t*)a.dfeat);
+    else
+      AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat16_kernel<float>, per4, dim3(256), 0, stream,
+                    (const float*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (float*)a.dfeat);
+    return hipGetLastError();
+  }
   const dim3 per_token(round_up8(((long long)tokens + 3) / 4));
   if (a.dtype == 1)
     AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<bf16_t>, per_token, dim3(256), 0, stream,
