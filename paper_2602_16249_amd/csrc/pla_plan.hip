@@ -42,11 +42,13 @@ __global__ __launch_bounds__(256) void plan_zero_kernel(int32_t* a, int32_t* b, 
 
 __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   __shared__ uint16_t sorted_all[4][kMaxEntries * kWave + kMaxSlots];
+  __shared__ int slot_count_all[4][kMaxSlots];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int sg = blockIdx.x * (blockDim.x / kWave) + wave;
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier below
   uint16_t* sorted = sorted_all[wave];
+  int* slot_count = slot_count_all[wave];
   const int b = sg / p.strips_per_image;
   const int q0 = (sg - b * p.strips_per_image) * 16;  // first query, within the image
   const int c = fast_div(q0, p.s_magic);
@@ -56,25 +58,33 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   const int32_t* nbr = p.nbr_idx + ((size_t)b * p.N + q0) * p.K;
 
   // candidate-list tile of every (query, slot): m * (S/16) + (token % S) / 16
-  int ct[kMaxEntries], tok[kMaxEntries];
+  const int near_v = (lane < p.M) ? near_c[lane] : -1;  // lane m: the m-th near cluster (M <= 64)
+  int ct[kMaxEntries], tok[kMaxEntries], ecl[kMaxEntries], where[kMaxEntries];
+  bool inr[kMaxEntries];
+#pragma unroll
+  for (int t = 0; t < kMaxEntries; ++t) {
+    const int e = t * kWave + lane;
+    const int n = (e < nent) ? nbr[e] : -1;
+    const int nn = min(max(n, 0), p.N - 1);
+    inr[t] = e < nent && n == nn;
+    tok[t] = nn;
+    ecl[t] = fast_div(nn, p.s_magic);
+    where[t] = -1;
+  }
+  for (int m = 0; m < p.M; ++m) {  // the last match wins, as a scan of the list would have it
+    const int cl = __builtin_amdgcn_readlane(near_v, m);
+#pragma unroll
+    for (int t = 0; t < kMaxEntries; ++t) where[t] = (ecl[t] == cl) ? m : where[t];
+  }
   unsigned long long mask = 0;
 #pragma unroll
   for (int t = 0; t < kMaxEntries; ++t) {
     ct[t] = -1;
-    tok[t] = 0;
-    const int e = t * kWave + lane;
-    if (e < nent) {
-      const int n = nbr[e];
-      const int nn = min(max(n, 0), p.N - 1);
-      const int ecl = fast_div(nn, p.s_magic);
-      int where = -1;
-      for (int m = 0; m < p.M; ++m)
-        if (near_c[m] == ecl) where = m;
-      if (where >= 0 && n == nn) {
-        ct[t] = where * tiles_per_cluster + ((nn - ecl * p.S) >> 4);
-        tok[t] = nn;
-        mask |= 1ull << ct[t];
-      }
+    if (inr[t] && where[t] >= 0) {
+      ct[t] = where[t] * tiles_per_cluster + ((tok[t] - ecl[t] * p.S) >> 4);
+      mask |= 1ull << ct[t];
+    } else {
+      tok[t] = 0;
     }
   }
   mask = wave_or64(mask);
@@ -106,25 +116,40 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   if (lane == 0) sl[0] = (uint16_t)count;
   for (int s = count + lane; s < p.slot_stride - 1; s += kWave) sl[1 + s] = (uint16_t)own_tile;
 
-  // runs: the valid entries grouped by slot, ascending entry index inside a slot, every run starting
-  // at an even place; assembled in LDS and written out in rows.  Unused places hold kNoEntry.
+  // runs: the valid entries grouped by slot, every run starting at an even place; assembled in LDS and written
+  // out in rows.  Unused places hold kNoEntry.  Two sweeps over the lane's entries with LDS counters per slot:
+  // count, then claim a place (the order inside a run is the order in which the wave's LDS atomics are served;
+  // any order gives the same results downstream, where every entry is addressed by its own value).
   for (int w = lane; w < kMaxEntries * kWave + kMaxSlots; w += kWave) sorted[w] = (uint16_t)kNoEntry;
+  if (lane < kMaxSlots) slot_count[lane] = 0;
+  wave_lds_sync();
+#pragma unroll
+  for (int t = 0; t < kMaxEntries; ++t)
+    if (off[t] != kNoEntry) atomicAdd(&slot_count[off[t] >> 8], 1);
   wave_lds_sync();
   uint16_t* runs = p.runs + (size_t)sg * p.runs_stride;
-  int place = 0;  // wave-uniform
-  for (int s = 0; s < count; ++s) {
-    place = (place + 1) & ~1;
-    if (lane == 0) runs[s] = (uint16_t)place;
+  // exclusive prefix over the slots, every start rounded up to an even place (lane s: slot s)
+  int mine = (lane < count) ? slot_count[lane] : 0;
+  mine = (mine + 1) & ~1;
+  int incl = mine;
 #pragma unroll
-    for (int t = 0; t < kMaxEntries; ++t) {
-      const bool mine = off[t] != kNoEntry && (int)(off[t] >> 8) == s;
-      const unsigned long long m = __ballot(mine);
-      if (m == 0ull) continue;  // wave-uniform
-      const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-      if (mine) sorted[place + rank] = (uint16_t)off[t];
-      place += __popcll(m);
-    }
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
   }
+  const int start = incl - mine;
+  const int last_count = __shfl((lane < count) ? slot_count[lane] : 0, max(count - 1, 0));
+  const int last_start = __shfl(start, max(count - 1, 0));
+  int place = count > 0 ? last_start + last_count : 0;  // places used: the last run is not padded
+  wave_lds_sync();
+  if (lane < count) {
+    runs[lane] = (uint16_t)start;
+    slot_count[lane] = start;  // becomes the cursor of the slot
+  }
+  wave_lds_sync();
+#pragma unroll
+  for (int t = 0; t < kMaxEntries; ++t)
+    if (off[t] != kNoEntry) sorted[atomicAdd(&slot_count[off[t] >> 8], 1)] = (uint16_t)off[t];
   if (lane == 0) runs[count] = (uint16_t)place;
   wave_lds_sync();
   uint16_t* sp = p.sorted_pos + (size_t)sg * p.places;
