@@ -97,8 +97,12 @@ inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   return L;
 }
 
-__device__ __forceinline__ int fast_div(int n, uint32_t magic) { return (int)__umulhi((uint32_t)n, magic); }
-inline uint32_t div_magic(int d) { return (uint32_t)((1ull << 32) / (uint32_t)d) + 1u; }
+// Division of a non-negative int by a small run-time constant through a 32-bit reciprocal (exact for the
+// ranges used here: n * d < 2^31).  The reciprocal of 1 does not fit 32 bits: magic 0 stands for it.
+__device__ __forceinline__ int fast_div(int n, uint32_t magic) {
+  return magic ? (int)__umulhi((uint32_t)n, magic) : n;
+}
+inline uint32_t div_magic(int d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / (uint32_t)d) + 1u; }
 
 __device__ __forceinline__ uint32_t wave_or32(uint32_t x) {
 #pragma unroll

@@ -62,6 +62,8 @@ CLUSTER_CASES = [
     ("knn_scale", 1, 960, 96, 3, 20, 48, 5, True),     # ragged: S=48, M=5, H=3
     ("merged_stage", 2, 512, 64, 2, 64, 16, 32, False),  # 32 candidate tiles per strip: two passes of the bias tile
     ("tiny_f32", 1, 256, 64, 2, 16, 256, 1, False),    # one cluster per image (exact kNN), bf16 storage here
+    ("merged_stage", 2, 224, 96, 3, 8, 32, 3, True),   # K = 8: one 16-byte chunk of slots per query
+    ("merged_stage", 2, 64, 64, 2, 1, 16, 2, False),   # K = 1: every token attends to itself only
 ]
 
 
