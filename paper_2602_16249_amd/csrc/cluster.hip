@@ -6,9 +6,10 @@
 // Per image the tokens are sorted by the 64-bit word (curve key << 32 | token
 // index): unique words, so the order is exact and ties go to the lower index.
 // The sort is a bitonic network over the image's words padded to a power of two
-// (pads are all ones and end up last): chunks of up to 8192 words are sorted and
-// merged in LDS by one workgroup; the compare-exchange steps whose partner lies
-// in another chunk run over global memory.  A last kernel writes the order and
+// (pads are all ones and end up last): chunks of up to 2048 words are sorted and
+// merged in LDS by one workgroup (many workgroups per image); the compare-exchange
+// steps whose partner lies in another chunk run over global memory, up to three
+// per pass.  A last kernel writes the order and
 // each token's cluster (place along the curve / S).
 #include "device_util.h"
 #include "launch.h"
@@ -18,8 +19,8 @@ namespace affmae {
 namespace {
 
 typedef unsigned long long word_t;
-constexpr int kChunk = 8192;       // words sorted in LDS by one workgroup (64 KB)
-constexpr int kSortThreads = 1024;
+constexpr int kChunk = 2048;       // words sorted in LDS by one workgroup (16 KB): many workgroups per image
+constexpr int kSortThreads = 256;
 
 struct ClusterParams {
   const float* coords;  // [B,N,2]
@@ -113,21 +114,35 @@ __global__ __launch_bounds__(kSortThreads) void cluster_sort_chunk_kernel(Cluste
   for (int t = threadIdx.x; t < chunk; t += blockDim.x) out[t] = buf[lds_place(t)];
 }
 
-// Step (k, j) with j >= chunk size: partners sit in different chunks.
-__global__ __launch_bounds__(256) void cluster_global_step_kernel(ClusterParams p, int k, int j) {
-  const int pairs = p.npad / 2;
+// R consecutive steps (k, J), (k, J/2), ... whose strides are all at least the chunk size: partners sit in
+// different chunks, so the 2^R words a thread connects come from and go back to global memory.
+template <int R>
+__global__ __launch_bounds__(256) void cluster_global_pass_kernel(ClusterParams p, int k, int J) {
+  const int groups = p.npad >> R;
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int b = blockIdx.y;
-  if (t >= pairs) return;
-  const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-  const int partner = i | j;
+  if (t >= groups) return;
+  const int low = J >> (R - 1);
+  const int i0 = ((t & ~(low - 1)) << R) | (t & (low - 1));
   word_t* w = p.words + (size_t)b * p.npad;
-  const word_t a = w[i], c = w[partner];
-  const bool ascending = (i & k) == 0;
-  if ((a > c) == ascending) {
-    w[i] = c;
-    w[partner] = a;
+  word_t v[1 << R];
+#pragma unroll
+  for (int m = 0; m < (1 << R); ++m) v[m] = w[i0 + m * low];
+  const bool ascending = (i0 & k) == 0;
+#pragma unroll
+  for (int bit = R - 1; bit >= 0; --bit) {
+#pragma unroll
+    for (int m = 0; m < (1 << R); ++m) {
+      if (!((m >> bit) & 1)) {
+        const word_t a = v[m], c = v[m | (1 << bit)];
+        const bool swap = (a > c) == ascending;
+        v[m] = swap ? c : a;
+        v[m | (1 << bit)] = swap ? a : c;
+      }
+    }
   }
+#pragma unroll
+  for (int m = 0; m < (1 << R); ++m) w[i0 + m * low] = v[m];
 }
 
 // The steps j = chunk/2 .. 1 of stage k (k > chunk size), in LDS.
@@ -176,9 +191,19 @@ hipError_t launch_cluster(const float* coords, int B, int N, int S, double x0, d
   AFFMAE_LAUNCH("cluster_sort_chunk_kernel", stream, cluster_sort_chunk_kernel, per_chunk, dim3(threads), lds, stream, p,
                 chunk);
   for (int k = chunk * 2; k <= p.npad; k <<= 1) {
-    for (int j = k >> 1; j >= chunk; j >>= 1)
-      AFFMAE_LAUNCH("cluster_global_step_kernel", stream, cluster_global_step_kernel,
-                    dim3((p.npad / 2 + 255) / 256, B), dim3(256), 0, stream, p, k, j);
+    int j = k >> 1;
+    while (j >= chunk) {  // up to three steps per pass over global memory
+      int steps = 0;
+      for (int jj = j; jj >= chunk && steps < 3; jj >>= 1) ++steps;
+      const dim3 grid(((p.npad >> steps) + 255) / 256, B);
+      if (steps == 3)
+        AFFMAE_LAUNCH("cluster_global_pass_kernel", stream, cluster_global_pass_kernel<3>, grid, dim3(256), 0, stream, p, k, j);
+      else if (steps == 2)
+        AFFMAE_LAUNCH("cluster_global_pass_kernel", stream, cluster_global_pass_kernel<2>, grid, dim3(256), 0, stream, p, k, j);
+      else
+        AFFMAE_LAUNCH("cluster_global_pass_kernel", stream, cluster_global_pass_kernel<1>, grid, dim3(256), 0, stream, p, k, j);
+      j >>= steps;
+    }
     AFFMAE_LAUNCH("cluster_merge_chunk_kernel", stream, cluster_merge_chunk_kernel, per_chunk, dim3(threads), lds, stream,
                   p, chunk, k);
   }
