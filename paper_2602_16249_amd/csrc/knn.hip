@@ -5,6 +5,8 @@
 //   centroid : double-precision mean of each cluster's coordinates -> fp32
 //   near     : per cluster the M clusters with nearest centroids
 //   knn      : per token the K nearest among the members of those M clusters
+//              (up to 512 candidates: kept in registers, selected by a counted
+//              distance threshold and one sort; more: staged in LDS and merged)
 // Selection is exact and unique: 64-bit keys (fp32 distance bits, index) compared
 // as integers; distances are evaluated without fused multiply-add.  This file is
 // compiled with -ffp-contract=off.

@@ -9,14 +9,15 @@
 // One wave per (strip of 16 queries, head), no workgroup-level cooperation.  The strip's
 // neighbours live in a few token tiles (16 consecutive tokens each).  Per pair of
 // such tiles the scores of all 16 x 32 (query, token) pairs come from two MFMAs
-// whose operands are row-major 16-byte loads of K rows and of the strip's Q rows;
-// they are computed transposed (tokens x queries) so that the probabilities leave
-// the softmax already in the operand layout of the P.V MFMAs.  A query attends
-// only to its K neighbours: their bias values are scattered into a per-wave LDS
-// tile that holds -inf everywhere else and is added to the scores.  The V rows
-// are loaded row-major as well and turned into the transposed operand P.V needs
-// by an MFMA against an identity matrix (exact in bf16), so no staging pass and
-// no barrier is needed; overlapping neighbourhoods share rows through L2.
+// on K rows and the strip's Q rows; they are computed transposed (tokens x
+// queries) so that the probabilities leave the softmax already in the operand
+// layout of the P.V MFMAs.  A query attends only to its K neighbours: their bias
+// values are scattered into a per-wave LDS tile that holds -inf everywhere else
+// and is added to the scores.  Rows are loaded 64 contiguous bytes per quad and
+// cross a per-wave LDS tile into the operand layout (see below); the V rows are
+// then turned into the transposed operand P.V needs by an MFMA against an
+// identity matrix (exact in bf16).  No workgroup barrier anywhere; overlapping
+// neighbourhoods share rows through L2.
 #include "cluster_common.h"
 #include "launch.h"
 #include "timing.h"
