@@ -187,8 +187,8 @@ int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int
  *                               bytes, 256-byte aligned; opaque.
  * affmae_pla_plan_bytes returns 0, and affmae_pla_plan AFFMAE_ERR_UNSUPPORTED,
  * when the shapes are outside what the tiled kernels take (they need S % 16 == 0,
- * M*S <= 1024, N <= 2^20); the attention calls then use the gather kernels and
- * ignore `plan`.
+ * M*S <= 1024, N < 2^20 and N*S < 2^31); the attention calls then use the gather
+ * kernels and ignore `plan`.
  */
 size_t affmae_pla_plan_bytes(int B, int N, int K, int S, int M);
 int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B, int N, int K, int S,

@@ -110,7 +110,9 @@ int check_vts_shape(int B, int Mq, int Nv, int C, int Hg, int Wg, float x0, floa
     return AFFMAE_ERR_SHAPE;  // the grid must be finite and non-empty
   if (Kt > AFFMAE_MAX_K) return AFFMAE_ERR_UNSUPPORTED;
   if (C % 2) return AFFMAE_ERR_UNSUPPORTED;  // the kernels move two channels per lane
-  if ((long long)B * Hg * Wg > (1ll << 31) - 8 || (long long)B * Mq > (1ll << 31) - 8) return AFFMAE_ERR_UNSUPPORTED;
+  if ((long long)B * Hg * Wg > (1ll << 31) - 8 || (long long)B * Mq > (1ll << 31) - 8 ||
+      (long long)B * Nv > (1ll << 31) - 8)
+    return AFFMAE_ERR_UNSUPPORTED;  // cells, queries and tokens are indexed with int32
   return AFFMAE_OK;
 }
 
@@ -166,7 +168,8 @@ int affmae_vts_bwd(const float* query_xy, const float* vis_xy, const void* feat,
   const int rc = check_vts_shape(B, Mq, Nv, C, Hg, Wg, x0, y0, cell, Kt);
   if (rc != AFFMAE_OK) return rc;
   if (misaligned(feat, 4) || misaligned(dout, 4) || misaligned(dfeat, 4)) return AFFMAE_ERR_SHAPE;
-  if ((long long)B * Mq * Kt > (1ll << 31) - 8) return AFFMAE_ERR_UNSUPPORTED;  // pairs are indexed with int32
+  if ((long long)B * Mq * Kt > (1ll << 31) - 8 || (long long)B * Nv > (1ll << 31) - 8)
+    return AFFMAE_ERR_UNSUPPORTED;  // pairs and tokens are indexed with int32
   const size_t need = align_up(affmae::vts_bwd_workspace_bytes(B, Mq, Nv, Kt));
   if (!workspace || workspace_bytes < need || misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
   affmae::VtsArgs a = vts_args(query_xy, vis_xy, feat, table, B, Mq, Nv, C, Hg, Wg, x0, y0, cell, Kt, p, eps, dtype);

@@ -18,6 +18,8 @@
 //             token adds up w * dout over its pairs (no floating-point atomics; the order inside a
 //             token's list, hence the last bits of dfeat, follows the filing order of the run).
 // This file is compiled with -ffp-contract=off (grid points and table distances are defined unfused).
+#include <algorithm>
+
 #include "device_util.h"
 #include "launch.h"
 #include "select_util.h"
@@ -228,8 +230,8 @@ __global__ __launch_bounds__(256) void vts_bwd_kernel(const float* __restrict__ 
                                                      const T* __restrict__ feat, const int32_t* __restrict__ table,
                                                      const T* __restrict__ dout, int B, int Mq, int Nv, int C, Grid gr,
                                                      int Kt, float p, float eps, float* __restrict__ weights,
-                                                     int32_t* __restrict__ pair_token, int32_t* __restrict__ count,
-                                                     float* __restrict__ dquery, float* __restrict__ dp_part) {
+                                                     int32_t* __restrict__ pair_token, float* __restrict__ dquery,
+                                                     float* __restrict__ dp_part) {
   const int lane = threadIdx.x & (kWave - 1);
   const long long gq = xcd_contiguous_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (gq >= (long long)B * Mq) return;  // wave-uniform
@@ -260,7 +262,6 @@ __global__ __launch_bounds__(256) void vts_bwd_kernel(const float* __restrict__ 
   if (lane < Kt) {
     weights[(size_t)gq * Kt + lane] = cd.w;
     pair_token[(size_t)gq * Kt + lane] = b * Nv + cd.idx;
-    atomicAdd(count + (size_t)b * Nv + cd.idx, 1);
   }
   if (lane == 0) {
     dquery[2 * (size_t)gq] = qx;
@@ -273,6 +274,12 @@ __global__ __launch_bounds__(256) void vts_bwd_kernel(const float* __restrict__ 
 // A row of C channels is moved 16 bytes per lane; when Kt <= 16 a group of 16 lanes serves one query (lane l of
 // the group holds candidate l), so a wave carries four independent chains of dependent loads (query -> table
 // row -> token coordinates -> feature rows) instead of one.  Needs rows that are whole 16-byte pieces.
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  const f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
 template <typename T>
 struct Piece;  // 16 bytes of channels
 template <>
@@ -299,184 +306,282 @@ struct Piece<bf16_t> {
     }
   }
   static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
-    uint4 x;
-    x.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-    x.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-    x.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
-    x.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+    uint4 x;  // round to nearest even, two values per conversion instruction
+    x.x = pack2_bf16(v[0], v[1]);
+    x.y = pack2_bf16(v[2], v[3]);
+    x.z = pack2_bf16(v[4], v[5]);
+    x.w = pack2_bf16(v[6], v[7]);
     *reinterpret_cast<uint4*>(p) = x;
   }
 };
 
-__device__ __forceinline__ float group16_max(float x) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
+// A group of G lanes (4 or 16) serves one query: lane l of the group holds candidate l and moves every G-th
+// 16-byte piece of a row, so the lanes of a group read G x 16 contiguous bytes per load.  Reductions and
+// broadcasts inside a group run on the VALU (DPP), not through LDS.
+template <int CTRL>
+__device__ __forceinline__ float dpp_movf(float x) {
+  return __uint_as_float(dpp_mov<CTRL>(__float_as_uint(x)));
 }
-__device__ __forceinline__ float group16_sum(float x) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
+template <int G>
+struct Group;
+template <>
+struct Group<16> {  // a DPP row: rotating it by 8, 4, 2 and 1 lanes leaves every lane with the reduction of all 16
+  static __device__ __forceinline__ float max(float x) {
+    x = fmaxf(x, dpp_movf<0x128>(x));  // row_ror:8
+    x = fmaxf(x, dpp_movf<0x124>(x));  // row_ror:4
+    x = fmaxf(x, dpp_movf<0x122>(x));  // row_ror:2
+    x = fmaxf(x, dpp_movf<0x121>(x));  // row_ror:1
+    return x;
+  }
+  static __device__ __forceinline__ float sum(float x) {
+    x += dpp_movf<0x128>(x);
+    x += dpp_movf<0x124>(x);
+    x += dpp_movf<0x122>(x);
+    x += dpp_movf<0x121>(x);
+    return x;
+  }
+  template <int I0>
+  static __device__ __forceinline__ void bcast4_at(uint32_t x, uint32_t (&out)[4]) {
+    out[0] = dpp_mov<0x150 + I0 + 0>(x);  // row_newbcast: one lane of the row to all of them
+    out[1] = dpp_mov<0x150 + I0 + 1>(x);
+    out[2] = dpp_mov<0x150 + I0 + 2>(x);
+    out[3] = dpp_mov<0x150 + I0 + 3>(x);
+  }
+  // out[u] = the value that lane i0 + u of the group holds, u = 0..3, i0 in {0, 4, 8, 12} (wave-uniform)
+  static __device__ __forceinline__ void bcast4(uint32_t x, int i0, uint32_t (&out)[4]) {
+    if (i0 == 0) bcast4_at<0>(x, out);
+    else if (i0 == 4) bcast4_at<4>(x, out);
+    else if (i0 == 8) bcast4_at<8>(x, out);
+    else bcast4_at<12>(x, out);
+  }
+};
+template <>
+struct Group<4> {  // a DPP quad
+  static __device__ __forceinline__ float max(float x) {
+    x = fmaxf(x, dpp_movf<0xB1>(x));  // quad_perm [1,0,3,2]
+    x = fmaxf(x, dpp_movf<0x4E>(x));  // quad_perm [2,3,0,1]
+    return x;
+  }
+  static __device__ __forceinline__ float sum(float x) {
+    x += dpp_movf<0xB1>(x);
+    x += dpp_movf<0x4E>(x);
+    return x;
+  }
+  static __device__ __forceinline__ void bcast4(uint32_t x, int, uint32_t (&out)[4]) {  // i0 is always 0
+    out[0] = dpp_mov<0x00>(x);
+    out[1] = dpp_mov<0x55>(x);
+    out[2] = dpp_mov<0xAA>(x);
+    out[3] = dpp_mov<0xFF>(x);
+  }
+};
 
-// Candidate of lane (lane % 16) for the group's query; every lane of the wave runs this (queries past the end
+// Candidate of lane (lane % G) for the group's query; every lane of the wave runs this (queries past the end
 // repeat the last one and are not stored).
-__device__ __forceinline__ Cand load_candidate16(const float* __restrict__ query_xy, const float* __restrict__ vis_xy,
-                                                 const int32_t* __restrict__ table, int b, long long gq, int Nv,
+template <int G>
+__device__ __forceinline__ Cand load_candidate_g(const float* __restrict__ query_xy, const float* __restrict__ vis_xy,
+                                                 const int32_t* __restrict__ table, int b, int gq, int Nv,
                                                  const Grid& gr, int Kt, float p, float eps, int sub) {
-  const float qx = query_xy[2 * (size_t)gq], qy = query_xy[2 * (size_t)gq + 1];
+  const float2 qxy = *reinterpret_cast<const float2*>(query_xy + 2 * (size_t)gq);
+  const float qx = qxy.x, qy = qxy.y;
   const int ix = cell_of(qx, gr.x0, gr.cell, gr.Wg), iy = cell_of(qy, gr.y0, gr.cell, gr.Hg);
-  const int32_t* row = table + (((size_t)b * gr.Hg + iy) * gr.Wg + ix) * Kt;
+  const int cell = (b * gr.Hg + iy) * gr.Wg + ix;  // < 2^31 cells
+  const int32_t* row = table + (size_t)cell * Kt;
   Cand c;
   const bool on = sub < Kt;
   c.idx = on ? min(max(row[sub], 0), Nv - 1) : 0;
-  const float* x = vis_xy + ((size_t)b * Nv + c.idx) * 2;
-  c.dx = qx - x[0];
-  c.dy = qy - x[1];
-  c.dist = sqrtf(c.dx * c.dx + c.dy * c.dy);
+  const float2 x = *reinterpret_cast<const float2*>(vis_xy + 2 * (size_t)(b * Nv + c.idx));
+  c.dx = qx - x.x;
+  c.dy = qy - x.y;
+  c.dist = __builtin_amdgcn_sqrtf(c.dx * c.dx + c.dy * c.dy);  // 1 ulp
   const float z = on ? -p * (c.dist + eps) : -INFINITY;
-  const float zmax = group16_max(z);
+  const float zmax = Group<G>::max(z);
   const float e = on ? __expf(z - zmax) : 0.f;
-  c.w = e / group16_sum(e);
+  c.w = e * __builtin_amdgcn_rcpf(Group<G>::sum(e));  // the sum is in [1, Kt]
   return c;
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void vts_fwd16_kernel(const float* __restrict__ query_xy,
-                                                       const float* __restrict__ vis_xy, const T* __restrict__ feat,
-                                                       const int32_t* __restrict__ table, int B, int Mq, int Nv, int C,
-                                                       Grid gr, int Kt, float p, float eps, T* __restrict__ out) {
+// The query of this lane's group (clamped to the last one) and its image.  The wave's first query is divided by
+// Mq on the scalar unit; a wave spans at most 16 queries, so with Mq >= 16 the image index moves on at most once.
+struct QueryOfLane {
+  int gq, b;
+  bool live;
+};
+template <int G>
+__device__ __forceinline__ QueryOfLane query_of_lane(int B, int Mq, int lane) {
+  constexpr int QW = kWave / G;  // queries per wave
+  const int total = B * Mq;      // < 2^31
+  const long long wave_id = xcd_contiguous_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const long long wave_first = wave_id * QW;
+  QueryOfLane q;
+  q.live = wave_first + lane / G < total;
+  q.gq = q.live ? (int)wave_first + lane / G : total - 1;
+  if (Mq >= QW) {
+    const int first = (int)min(wave_first, (long long)total - 1);
+    const int b0 = first / Mq;  // wave-uniform
+    q.b = b0 + (q.gq - b0 * Mq >= Mq ? 1 : 0);
+  } else {
+    q.b = q.gq / Mq;
+  }
+  return q;
+}
+
+template <typename T, int G>
+__global__ __launch_bounds__(256) void vts_fwdg_kernel(const float* __restrict__ query_xy,
+                                                      const float* __restrict__ vis_xy, const T* __restrict__ feat,
+                                                      const int32_t* __restrict__ table, int B, int Mq, int Nv, int C,
+                                                      Grid gr, int Kt, float p, float eps, T* __restrict__ out) {
   constexpr int CH = Piece<T>::kCh;
-  const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
-  const long long total = (long long)B * Mq;
-  const long long want = (xcd_contiguous_block() * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
-  const bool live = want < total;
-  const long long gq = live ? want : total - 1;
-  const int b = (int)(gq / Mq);
-  const Cand cd = load_candidate16(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, sub);
-  const int group = lane & 48;
-  for (int base = 0; base < C; base += 16 * CH) {  // wave-uniform trips
-    const int c0 = base + sub * CH;
-    const bool on = live && c0 < C;
+  const int lane = threadIdx.x & (kWave - 1), sub = lane & (G - 1);
+  const QueryOfLane ql = query_of_lane<G>(B, Mq, lane);
+  const Cand cd = load_candidate_g<G>(query_xy, vis_xy, table, ql.b, ql.gq, Nv, gr, Kt, p, eps, sub);
+  const int pieces = C / CH;  // rows are whole 16-byte pieces
+  const T* rows = feat + (size_t)ql.b * Nv * C;
+  T* orow = out + (size_t)ql.gq * C;
+  for (int p0 = 0; p0 < pieces; p0 += G) {  // wave-uniform trips
+    const bool on = ql.live && p0 + sub < pieces;
+    const int c0 = min(p0 + sub, pieces - 1) * CH;  // lanes past the row's end repeat its last piece: all loads are valid
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int i = 0; i < Kt; ++i) {
-      const float w = __shfl(cd.w, group | i);
-      const int idx = __shfl(cd.idx, group | i);
-      if (on) {
-        float f[8];
-        Piece<T>::load(feat + ((size_t)b * Nv + idx) * C + c0, f);
+    // four candidates per trip, their rows in flight together (past Kt: the trip's first one again, at weight 0)
+    for (int i0 = 0; i0 < Kt; i0 += 4) {
+      uint32_t wb[4], ib[4];
+      Group<G>::bcast4(__float_as_uint(cd.w), i0, wb);
+      Group<G>::bcast4((uint32_t)cd.idx, i0, ib);
+      float f[4][8];
 #pragma unroll
-        for (int e = 0; e < CH; ++e) acc[e] = fmaf(w, f[e], acc[e]);
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t idx = i0 + u < Kt ? ib[u] : ib[0];
+        Piece<T>::load(rows + (size_t)(idx * (uint32_t)C) + c0, f[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float w = i0 + u < Kt ? __uint_as_float(wb[u]) : 0.f;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) acc[e] = fmaf(w, f[u][e], acc[e]);
       }
     }
-    if (on) Piece<T>::store(out + (size_t)gq * C + c0, acc);
+    if (on) Piece<T>::store(orow + c0, acc);
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void vts_bwd16_kernel(const float* __restrict__ query_xy,
-                                                       const float* __restrict__ vis_xy, const T* __restrict__ feat,
-                                                       const int32_t* __restrict__ table, const T* __restrict__ dout,
-                                                       int B, int Mq, int Nv, int C, Grid gr, int Kt, float p, float eps,
-                                                       float* __restrict__ weights, int32_t* __restrict__ pair_token,
-                                                       int32_t* __restrict__ count, float* __restrict__ dquery,
-                                                       float* __restrict__ dp_part) {
+template <typename T, int G>
+__global__ __launch_bounds__(256) void vts_bwdg_kernel(const float* __restrict__ query_xy,
+                                                      const float* __restrict__ vis_xy, const T* __restrict__ feat,
+                                                      const int32_t* __restrict__ table, const T* __restrict__ dout,
+                                                      int B, int Mq, int Nv, int C, Grid gr, int Kt, float p, float eps,
+                                                      float* __restrict__ weights, int32_t* __restrict__ pair_token,
+                                                      float* __restrict__ dquery, float* __restrict__ dp_part) {
   constexpr int CH = Piece<T>::kCh;
-  const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
-  const long long total = (long long)B * Mq;
-  const long long want = (xcd_contiguous_block() * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
-  const bool live = want < total;
-  const long long gq = live ? want : total - 1;
-  const int b = (int)(gq / Mq);
-  const Cand cd = load_candidate16(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, sub);
-  const int group = lane & 48;
+  const int lane = threadIdx.x & (kWave - 1), sub = lane & (G - 1);
+  const QueryOfLane ql = query_of_lane<G>(B, Mq, lane);
+  const int gq = ql.gq, b = ql.b;
+  const Cand cd = load_candidate_g<G>(query_xy, vis_xy, table, b, gq, Nv, gr, Kt, p, eps, sub);
+  const int pieces = C / CH;  // rows are whole 16-byte pieces
+  const T* rows = feat + (size_t)b * Nv * C;
+  const T* grow = dout + (size_t)gq * C;
   float g_mine = 0.f;
-  const bool one_trip = C <= 16 * CH;  // the whole dout row is one piece per lane: load it once
-  float g0[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (one_trip && sub * CH < C) Piece<T>::load(dout + (size_t)gq * C + sub * CH, g0);
-  for (int i = 0; i < Kt; ++i) {
-    const int idx = __shfl(cd.idx, group | i);
-    float part = 0.f;
-    for (int base = 0; base < C; base += 16 * CH) {
-      const int c0 = base + sub * CH;
-      if (c0 < C) {
-        float g[8], f[8];
-        Piece<T>::load(feat + ((size_t)b * Nv + idx) * C + c0, f);
-        if (one_trip) {
+  // four candidates per trip, their rows in flight together (past Kt: the trip's first one again, result unused)
+  for (int i0 = 0; i0 < Kt; i0 += 4) {
+    uint32_t ib[4];
+    Group<G>::bcast4((uint32_t)cd.idx, i0, ib);
+    float part[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int p0 = 0; p0 < pieces; p0 += G) {
+      const bool on = p0 + sub < pieces;
+      const int c0 = min(p0 + sub, pieces - 1) * CH;  // lanes past the row's end repeat its last piece, unused
+      float g[8], f[4][8];
+      Piece<T>::load(grow + c0, g);
 #pragma unroll
-          for (int e = 0; e < CH; ++e) g[e] = g0[e];
-        } else {
-          Piece<T>::load(dout + (size_t)gq * C + c0, g);
-        }
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t idx = i0 + u < Kt ? ib[u] : ib[0];
+        Piece<T>::load(rows + (size_t)(idx * (uint32_t)C) + c0, f[u]);
+      }
+      if (on) {
 #pragma unroll
-        for (int e = 0; e < CH; ++e) part = fmaf(g[e], f[e], part);
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int e = 0; e < CH; ++e) part[u] = fmaf(g[e], f[u][e], part[u]);
       }
     }
-    const float gi = group16_sum(part);
-    if (sub == i) g_mine = gi;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float gi = Group<G>::sum(part[u]);
+      if (sub == i0 + u && sub < Kt) g_mine = gi;
+    }
   }
-  const float gbar = group16_sum(cd.w * g_mine);  // lanes past Kt hold weight 0
+  const float gbar = Group<G>::sum(cd.w * g_mine);  // lanes past Kt hold weight 0
   const float dz = cd.w * (g_mine - gbar);
-  const float inv = cd.dist > 0.f ? 1.f / cd.dist : 0.f;
-  const float qx = group16_sum(dz * (-p) * cd.dx * inv);
-  const float qy = group16_sum(dz * (-p) * cd.dy * inv);
-  const float dpv = group16_sum(sub < Kt ? dz * (-(cd.dist + eps)) : 0.f);
-  if (live && sub < Kt) {
+  const float inv = cd.dist > 0.f ? __builtin_amdgcn_rcpf(cd.dist) : 0.f;
+  const float qx = Group<G>::sum(dz * (-p) * cd.dx * inv);
+  const float qy = Group<G>::sum(dz * (-p) * cd.dy * inv);
+  const float dpv = Group<G>::sum(sub < Kt ? dz * (-(cd.dist + eps)) : 0.f);
+  if (ql.live && sub < Kt) {
     weights[(size_t)gq * Kt + sub] = cd.w;
     pair_token[(size_t)gq * Kt + sub] = b * Nv + cd.idx;
-    atomicAdd(count + (size_t)b * Nv + cd.idx, 1);
   }
-  if (live && sub == 0) {
-    dquery[2 * (size_t)gq] = qx;
-    dquery[2 * (size_t)gq + 1] = qy;
+  if (ql.live && sub == 0) {
+    *reinterpret_cast<float2*>(dquery + 2 * (size_t)gq) = make_float2(qx, qy);
     if (dp_part) dp_part[gq] = dpv;
   }
 }
 
-__global__ __launch_bounds__(256) void vts_zero_kernel(int32_t* __restrict__ a, int32_t* __restrict__ c, size_t n) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) {
-    a[i] = 0;
-    c[i] = 0;
-  }
-}
-
-// dp = sum of the per-query parts, in a fixed order (one workgroup).
-__global__ __launch_bounds__(1024) void vts_dp_kernel(const float* __restrict__ part, size_t n, float* __restrict__ dp) {
+// dp = sum of the per-query parts in a fixed order, in two steps: workgroup j adds up parts [j per, (j + 1) per)
+// into out[j]; a second launch with one workgroup adds up those sums.
+constexpr int kDpPer = 16384;
+__global__ __launch_bounds__(1024) void vts_dp_kernel(const float* __restrict__ part, size_t n, size_t per,
+                                                      float* __restrict__ out) {
   __shared__ float acc[16];
+  const size_t lo = (size_t)blockIdx.x * per, hi = min(n, lo + per);  // per is a multiple of 4 or the only block's n
   float s = 0.f;
-  const size_t n4 = n / 4;  // the workspace slot is 256-byte aligned: whole 16-byte pieces first
+  const size_t n4 = (hi - lo) / 4;  // the workspace slots are 256-byte aligned: whole 16-byte pieces first
   for (size_t i = threadIdx.x; i < n4; i += blockDim.x) {
-    const float4 v = reinterpret_cast<const float4*>(part)[i];
+    const float4 v = reinterpret_cast<const float4*>(part + lo)[i];
     s += (v.x + v.y) + (v.z + v.w);
   }
-  for (size_t i = n4 * 4 + threadIdx.x; i < n; i += blockDim.x) s += part[i];
+  for (size_t i = lo + n4 * 4 + threadIdx.x; i < hi; i += blockDim.x) s += part[i];
   s = wave_sum(s);
   if ((threadIdx.x & (kWave - 1)) == 0) acc[threadIdx.x / kWave] = s;
   __syncthreads();
   if (threadIdx.x == 0) {
     float t = 0.f;
     for (int w = 0; w < 16; ++w) t += acc[w];
-    *dp = t;
+    out[blockIdx.x] = t;
   }
 }
 
-// Exclusive prefix sum.  Workgroup j owns elements [1024 j, 1024 j + 1024): it first adds up everything before
-// them (coalesced, from L2), then scans its own.  No workgroup waits for another.
-__global__ __launch_bounds__(256) void vts_scan_kernel(const int32_t* __restrict__ count, int32_t* __restrict__ offset,
-                                                      int n) {
-  __shared__ int32_t part[4], before_all[4];
+// Files every (query, candidate) pair in the list of its token, with no atomic on global memory.  A
+// workgroup owns a range of at most kListRange tokens of one image; it walks all pairs of that image twice
+// (they sit in L2): first it counts the pairs of each of its tokens in LDS (and the pairs of the image's earlier
+// tokens), a prefix sum turns the counts into list starts (every image holds exactly pairs_per_image pairs,
+// so the image's first list starts at a known place), then every pair takes the next free place of its list.
+constexpr int kListThreads = 1024;
+constexpr int kListRange = 4 * kListThreads;
+__global__ __launch_bounds__(kListThreads) void vts_lists_kernel(const int32_t* __restrict__ pair_token, int B, int Nv,
+                                                                 int pairs_per_image, int range, int ranges,
+                                                                 int32_t* __restrict__ offset,
+                                                                 int32_t* __restrict__ list) {
+  __shared__ int32_t cnt[kListRange];
+  __shared__ int32_t wave_total[kListThreads / kWave], wave_below[kListThreads / kWave];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int first = blockIdx.x * 1024;
-  int before = 0;
-  for (int i = tid * 4; i < first; i += 1024) {
-    const int4 v = *reinterpret_cast<const int4*>(count + i);
-    before += v.x + v.y + v.z + v.w;
+  const int b = blockIdx.x / ranges, rg = blockIdx.x - b * ranges;
+  const int t0 = rg * range;
+  const int span = min(range, Nv - t0);  // >= 1: ranges = ceil(Nv / range)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) cnt[4 * tid + i] = 0;
+  __syncthreads();
+  const int32_t* pt = pair_token + (size_t)b * pairs_per_image;
+  const int first = b * Nv + t0;
+  int below = 0;
+#pragma unroll 4
+  for (int e = tid; e < pairs_per_image; e += kListThreads) {
+    const int rel = pt[e] - first;
+    below += rel < 0 ? 1 : 0;
+    if ((unsigned)rel < (unsigned)span) atomicAdd(&cnt[rel], 1);
   }
-  const int at = first + tid * 4;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o);
+  __syncthreads();
   int c[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) c[i] = (at + i < n) ? count[at + i] : 0;
+  for (int i = 0; i < 4; ++i) c[i] = cnt[4 * tid + i];  // zero past the span
   const int mine = c[0] + c[1] + c[2] + c[3];
   int incl = mine;
 #pragma unroll
@@ -484,30 +589,24 @@ __global__ __launch_bounds__(256) void vts_scan_kernel(const int32_t* __restrict
     const int v = __shfl_up(incl, o);
     if (lane >= o) incl += v;
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
-  if (lane == kWave - 1) part[wave] = incl;
-  if (lane == 0) before_all[wave] = before;
+  if (lane == kWave - 1) wave_total[wave] = incl;
+  if (lane == 0) wave_below[wave] = below;
   __syncthreads();
-  int base = before_all[0] + before_all[1] + before_all[2] + before_all[3];
-  for (int w = 0; w < wave; ++w) base += part[w];
-  int run = base + incl - mine;
+  int run = b * pairs_per_image + incl - mine;
+  for (int w = 0; w < kListThreads / kWave; ++w) run += wave_below[w] + (w < wave ? wave_total[w] : 0);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    if (at + i < n) offset[at + i] = run;
+    if (4 * tid + i < span) offset[(size_t)first + 4 * tid + i] = run;
+    cnt[4 * tid + i] = run;  // from here on: the next free place of the token's list
     run += c[i];
   }
-  if (at <= n - 1 && n - 1 < at + 4) offset[n] = run;
-}
-
-// Files every (query, candidate) pair in the list of its token.
-__global__ __launch_bounds__(256) void vts_fill_kernel(const int32_t* __restrict__ pair_token,
-                                                      const int32_t* __restrict__ offset, int32_t* __restrict__ cursor,
-                                                      int32_t* __restrict__ list, size_t pairs) {
-  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= pairs) return;
-  const int tok = pair_token[e];
-  list[offset[tok] + atomicAdd(cursor + tok, 1)] = (int32_t)e;
+  if (blockIdx.x == gridDim.x - 1 && tid == 0) offset[(size_t)B * Nv] = B * pairs_per_image;
+  __syncthreads();
+#pragma unroll 4
+  for (int e = tid; e < pairs_per_image; e += kListThreads) {
+    const int rel = pt[e] - first;
+    if ((unsigned)rel < (unsigned)span) list[atomicAdd(&cnt[rel], 1)] = b * pairs_per_image + e;
+  }
 }
 
 // Four visible tokens per wave (16 lanes each) when the rows are whole 16-byte pieces: dfeat = sum over the
@@ -518,7 +617,7 @@ __global__ __launch_bounds__(256) void vts_dfeat16_kernel(const T* __restrict__ 
                                                          const int32_t* __restrict__ list, int tokens, int C, int Kt,
                                                          T* __restrict__ dfeat) {
   constexpr int CH = Piece<T>::kCh;
-  const int lane = threadIdx.x & (kWave - 1), sub = lane & 15, group = lane & 48;
+  const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
   const long long want = (xcd_contiguous_block() * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
   const bool live = want < tokens;
   const long long tok = live ? want : tokens - 1;
@@ -533,18 +632,33 @@ __global__ __launch_bounds__(256) void vts_dfeat16_kernel(const T* __restrict__ 
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int chunk = 0; chunk < nmax; chunk += 16) {
       const bool have = chunk + sub < n;
-      const int mine = have ? list[lo + chunk + sub] : 0;
-      const float wmine = have ? weights[mine] : 0.f;  // pairs past the end of a shorter list weigh 0
+      // places past the end of a list repeat its last pair at weight 0 (an empty list: pair 0)
+      const int mine = n > 0 ? list[lo + min(chunk + sub, n - 1)] : 0;
+      const float wmine = have ? weights[mine] : 0.f;
       const int qmine = mine / Kt;
       const int m = min(16, nmax - chunk);
-      for (int i = 0; i < m; ++i) {
-        const float w = __shfl(wmine, group | i);
-        const int q = __shfl(qmine, group | i);
-        if (on) {
-          float g[8];
-          Piece<T>::load(dout + (size_t)q * C + c0, g);
+      // four pairs per trip, their rows in flight together
+      for (int i0 = 0; i0 < m; i0 += 4) {
+        float w[4];
+        int q[4];
+        {
+          uint32_t wb[4], qb[4];
+          Group<16>::bcast4(__float_as_uint(wmine), i0, wb);
+          Group<16>::bcast4((uint32_t)qmine, i0, qb);
 #pragma unroll
-          for (int e = 0; e < CH; ++e) acc[e] = fmaf(w, g[e], acc[e]);
+          for (int u = 0; u < 4; ++u) {
+            w[u] = __uint_as_float(wb[u]);
+            q[u] = (int)qb[u];
+          }
+        }
+        if (on) {
+          float g[4][8];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) Piece<T>::load(dout + (size_t)q[u] * C + c0, g[u]);
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < CH; ++e) acc[e] = fmaf(w[u], g[u][e], acc[e]);
         }
       }
     }
@@ -607,20 +721,27 @@ hipError_t launch_vts_table(const VtsArgs& a, hipStream_t stream) {
 static bool vts_grouped(const VtsArgs& a, const void* t0, const void* t1, const void* t2) {
   const size_t row = (size_t)a.C * (a.dtype == 1 ? 2 : 4);
   auto al = [](const void* p) { return p == nullptr || reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-  return a.Kt <= 16 && row % 16 == 0 && al(t0) && al(t1) && al(t2);
+  auto al8 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 8 == 0; };  // (x, y) pairs are moved whole
+  if ((long long)a.Nv * a.C >= (1ll << 31)) return false;                             // 32-bit offsets inside an image
+  return a.Kt <= 16 && row % 16 == 0 && al(t0) && al(t1) && al8(t2) && al8(a.query_xy) && al8(a.vis_xy);
 }
 
 hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream) {
   const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
   if (vts_grouped(a, a.feat, a.out, nullptr)) {
-    const dim3 grid16(round_up8(((long long)a.B * a.Mq + 15) / 16));
-    if (a.dtype == 1)
-      AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd16_kernel<bf16_t>, grid16, dim3(256), 0, stream, a.query_xy,
-                    a.vis_xy, (const bf16_t*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
-                    (bf16_t*)a.out);
-    else
-      AFFMAE_LAUNCH("vts_fwd_kernel", stream, vts_fwd16_kernel<float>, grid16, dim3(256), 0, stream, a.query_xy,
-                    a.vis_xy, (const float*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, (float*)a.out);
+    // groups of 4 lanes (16 queries per wave) when they can hold the candidates, else groups of 16
+    const long long total = (long long)a.B * a.Mq;
+    const bool quad = a.Kt <= 4;
+    const int per_block = quad ? 64 : 16;
+    const dim3 gridg(round_up8((total + per_block - 1) / per_block));
+#define AFFMAE_VTS_FWDG(T, G)                                                                                     \
+  AFFMAE_LAUNCH("vts_fwd_kernel", stream, (vts_fwdg_kernel<T, G>), gridg, dim3(256), 0, stream, a.query_xy,       \
+                a.vis_xy, (const T*)a.feat, a.table, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, (T*)a.out)
+    if (a.dtype == 1 && quad) AFFMAE_VTS_FWDG(bf16_t, 4);
+    else if (a.dtype == 1) AFFMAE_VTS_FWDG(bf16_t, 16);
+    else if (quad) AFFMAE_VTS_FWDG(float, 4);
+    else AFFMAE_VTS_FWDG(float, 16);
+#undef AFFMAE_VTS_FWDG
     return hipGetLastError();
   }
   const dim3 grid(round_up8(((long long)a.B * a.Mq + 3) / 4));
@@ -635,20 +756,20 @@ hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream) {
 
 namespace {
 struct VtsBwdLayout {
-  size_t weights_off, pair_off, count_off, offset_off, cursor_off, list_off, dp_off, total;
+  size_t weights_off, pair_off, offset_off, list_off, dp_off, dp2_off, total;
 };
 size_t vts_align(size_t n) { return (n + 255) / 256 * 256; }
+size_t vts_dp_blocks(int B, int Mq) { return ((size_t)B * Mq + kDpPer - 1) / kDpPer; }
 VtsBwdLayout vts_bwd_layout(int B, int Mq, int Nv, int Kt) {
   VtsBwdLayout L;
   const size_t pairs = (size_t)B * Mq * Kt, tokens = (size_t)B * Nv;
   size_t off = 0;
   L.weights_off = off; off += vts_align(pairs * sizeof(float));
   L.pair_off = off;    off += vts_align(pairs * sizeof(int32_t));
-  L.count_off = off;   off += vts_align(tokens * sizeof(int32_t));
   L.offset_off = off;  off += vts_align((tokens + 1) * sizeof(int32_t));
-  L.cursor_off = off;  off += vts_align(tokens * sizeof(int32_t));
   L.list_off = off;    off += vts_align(pairs * sizeof(int32_t));
   L.dp_off = off;      off += vts_align((size_t)B * Mq * sizeof(float));
+  L.dp2_off = off;     off += vts_align(vts_dp_blocks(B, Mq) * sizeof(float));
   L.total = off;
   return L;
 }
@@ -663,39 +784,47 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
   char* ws = static_cast<char*>(a.workspace);
   float* weights = reinterpret_cast<float*>(ws + L.weights_off);
   int32_t* pair_token = reinterpret_cast<int32_t*>(ws + L.pair_off);
-  int32_t* count = reinterpret_cast<int32_t*>(ws + L.count_off);
   int32_t* offset = reinterpret_cast<int32_t*>(ws + L.offset_off);
-  int32_t* cursor = reinterpret_cast<int32_t*>(ws + L.cursor_off);
   int32_t* list = reinterpret_cast<int32_t*>(ws + L.list_off);
   float* dp_part = a.dp ? reinterpret_cast<float*>(ws + L.dp_off) : nullptr;
-  const size_t tokens = (size_t)a.B * a.Nv, pairs = (size_t)a.B * a.Mq * a.Kt;
-  AFFMAE_LAUNCH("vts_zero_kernel", stream, vts_zero_kernel, dim3((unsigned)((tokens + 255) / 256)), dim3(256), 0, stream,
-                count, cursor, tokens);
-  const bool grouped = vts_grouped(a, a.feat, a.dout, nullptr);
-  const dim3 grid16(round_up8(((long long)a.B * a.Mq + 15) / 16));
-  if (grouped && a.dtype == 1)
-    AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd16_kernel<bf16_t>, grid16, dim3(256), 0, stream, a.query_xy, a.vis_xy,
-                  (const bf16_t*)a.feat, a.table, (const bf16_t*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
-                  weights, pair_token, count, a.dquery, dp_part);
-  else if (grouped)
-    AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd16_kernel<float>, grid16, dim3(256), 0, stream, a.query_xy, a.vis_xy,
-                  (const float*)a.feat, a.table, (const float*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
-                  weights, pair_token, count, a.dquery, dp_part);
+  float* dp_part2 = reinterpret_cast<float*>(ws + L.dp2_off);
+  const size_t tokens = (size_t)a.B * a.Nv;
+  const bool grouped = vts_grouped(a, a.feat, a.dout, a.dquery);
+  const bool quad = a.Kt <= 4;
+  const int per_block = quad ? 64 : 16;
+  const dim3 gridg(round_up8(((long long)a.B * a.Mq + per_block - 1) / per_block));
+#define AFFMAE_VTS_BWDG(T, G)                                                                                      \
+  AFFMAE_LAUNCH("vts_bwd_kernel", stream, (vts_bwdg_kernel<T, G>), gridg, dim3(256), 0, stream, a.query_xy,        \
+                a.vis_xy, (const T*)a.feat, a.table, (const T*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps, \
+                weights, pair_token, a.dquery, dp_part)
+  if (grouped && a.dtype == 1 && quad) AFFMAE_VTS_BWDG(bf16_t, 4);
+  else if (grouped && a.dtype == 1) AFFMAE_VTS_BWDG(bf16_t, 16);
+  else if (grouped && quad) AFFMAE_VTS_BWDG(float, 4);
+  else if (grouped) AFFMAE_VTS_BWDG(float, 16);
+#undef AFFMAE_VTS_BWDG
   else if (a.dtype == 1)
     AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd_kernel<bf16_t>, grid, dim3(256), 0, stream, a.query_xy, a.vis_xy,
                   (const bf16_t*)a.feat, a.table, (const bf16_t*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
-                  weights, pair_token, count, a.dquery, dp_part);
+                  weights, pair_token, a.dquery, dp_part);
   else
     AFFMAE_LAUNCH("vts_bwd_kernel", stream, vts_bwd_kernel<float>, grid, dim3(256), 0, stream, a.query_xy, a.vis_xy,
                   (const float*)a.feat, a.table, (const float*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
-                  weights, pair_token, count, a.dquery, dp_part);
-  if (a.dp)
-    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part,
-                  (size_t)a.B * a.Mq, a.dp);
-  AFFMAE_LAUNCH("vts_scan_kernel", stream, vts_scan_kernel, dim3((unsigned)((tokens + 1023) / 1024)), dim3(256), 0, stream,
-                count, offset, (int)tokens);
-  AFFMAE_LAUNCH("vts_fill_kernel", stream, vts_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, stream,
-                pair_token, offset, cursor, list, pairs);
+                  weights, pair_token, a.dquery, dp_part);
+  if (a.dp) {
+    const size_t n = (size_t)a.B * a.Mq, blocks = vts_dp_blocks(a.B, a.Mq);
+    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3((unsigned)blocks), dim3(1024), 0, stream, dp_part, n,
+                  (size_t)kDpPer, dp_part2);
+    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part2, blocks, blocks, a.dp);
+  }
+  {
+    // token ranges per image: enough workgroups to fill the chip, never more tokens than the LDS counters hold
+    const int want = (256 + a.B - 1) / a.B;
+    int range = std::max(64, (a.Nv + want - 1) / want);
+    range = std::min(range, kListRange);
+    const int ranges = (a.Nv + range - 1) / range;
+    AFFMAE_LAUNCH("vts_lists_kernel", stream, vts_lists_kernel, dim3((unsigned)(a.B * ranges)), dim3(kListThreads), 0,
+                  stream, pair_token, a.B, a.Nv, a.Mq * a.Kt, range, ranges, offset, list);
+  }
   if (vts_grouped(a, a.dout, a.dfeat, nullptr)) {  // (Kt <= 16 is not needed here, only the row shape)
     const dim3 per4(round_up8(((long long)tokens + 15) / 16));
     if (a.dtype == 1)
