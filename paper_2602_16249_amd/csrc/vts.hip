@@ -8,15 +8,16 @@
 //   table   : one wave per grid point; the image's visible tokens stream past 64 at a time; the first 64
 //             are sorted, later ones are queued only when they beat the current Kt-th key and merged 64
 //             at a time.  Keys = (fp32 squared distance bits, token index): exact and unique.
-//   forward : one wave per query; lanes 0..Kt-1 hold one candidate each (index, distance, weight), then
-//             lanes <-> channels for the weighted sum of the gathered feature rows.
-//   backward: one wave per query: g_i = <dout, feat_i> by wave reductions, dz_i = w_i (g_i - sum w g),
-//             dquery and a per-query part of dp (added up in a fixed order by one workgroup afterwards) from
-//             the lanes that hold candidates; the weights are kept and
-//             every (query, candidate) pair is counted at its token.  dfeat is then gathered, not
-//             scattered: prefix sum of the counts, the pairs filed per token, and one wave per visible
-//             token adds up w * dout over its pairs (no floating-point atomics; the order inside a
-//             token's list, hence the last bits of dfeat, follows the filing order of the run).
+//   forward : a group of 4 lanes (Kt <= 4; 16 lanes up to Kt = 16, else a whole wave) per query; lane l of the
+//             group holds candidate l (index, distance, weight), then the lanes split the channels of the
+//             gathered feature rows, 16 bytes at a time, for the weighted sum.
+//   backward: the same groups: g_i = <dout, feat_i> by group reductions, dz_i = w_i (g_i - sum w g), dquery
+//             and a part of dp per wave (added up in a fixed order afterwards) from the lanes that hold
+//             candidates; the weights and the token of every (query, candidate) pair are kept.  dfeat is then
+//             gathered, not scattered: the pairs are filed per token (counted, prefix-summed and placed in LDS,
+//             one workgroup per range of tokens of an image: no atomics on global memory), and a group of
+//             lanes per visible token adds up w * dout over its pairs (no floating-point atomics; the order
+//             inside a token's list, hence the last bits of dfeat, follows the filing order of the run).
 // This file is compiled with -ffp-contract=off (grid points and table distances are defined unfused).
 #include <algorithm>
 
@@ -270,10 +271,12 @@ __global__ __launch_bounds__(256) void vts_bwd_kernel(const float* __restrict__ 
   }
 }
 
-// ---- four queries per wave -----------------------------------------------------------------------------------
-// A row of C channels is moved 16 bytes per lane; when Kt <= 16 a group of 16 lanes serves one query (lane l of
-// the group holds candidate l), so a wave carries four independent chains of dependent loads (query -> table
-// row -> token coordinates -> feature rows) instead of one.  Needs rows that are whole 16-byte pieces.
+// ---- several queries per wave --------------------------------------------------------------------------------
+// A row of C channels is moved 16 bytes per lane; when Kt <= 16 a group of 16 lanes (of 4 when Kt <= 4) serves
+// one query (lane l of the group holds candidate l), so a wave carries 4 (16) independent chains of dependent
+// loads (query -> table row -> token coordinates -> feature rows) instead of one, and the per-query arithmetic
+// (cell, distances, weights) is spread over the lanes instead of repeated by all of them.  Needs rows that are
+// whole 16-byte pieces.
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   typedef __attribute__((ext_vector_type(2))) float f32x2;
@@ -517,9 +520,11 @@ __global__ __launch_bounds__(256) void vts_bwdg_kernel(const float* __restrict__
     weights[(size_t)gq * Kt + sub] = cd.w;
     pair_token[(size_t)gq * Kt + sub] = b * Nv + cd.idx;
   }
-  if (ql.live && sub == 0) {
-    *reinterpret_cast<float2*>(dquery + 2 * (size_t)gq) = make_float2(qx, qy);
-    if (dp_part) dp_part[gq] = dpv;
+  if (ql.live && sub == 0) *reinterpret_cast<float2*>(dquery + 2 * (size_t)gq) = make_float2(qx, qy);
+  if (dp_part) {  // one part per wave (0 from a wave past the end)
+    const float wave_part = wave_sum(ql.live && sub == 0 ? dpv : 0.f);
+    const long long wave_id = xcd_contiguous_block() * 4 + threadIdx.x / kWave;
+    if (lane == 0) dp_part[wave_id] = wave_part;
   }
 }
 
@@ -554,6 +559,9 @@ __global__ __launch_bounds__(1024) void vts_dp_kernel(const float* __restrict__ 
 // so the image's first list starts at a known place), then every pair takes the next free place of its list.
 constexpr int kListThreads = 1024;
 constexpr int kListRange = 4 * kListThreads;
+// NP > 0: a thread keeps its NP 16-byte pieces of the pair array in registers between the two walks (the image's
+// pairs must fit: NP * kListThreads pieces); NP == 0: it reads them again.
+template <int NP>
 __global__ __launch_bounds__(kListThreads) void vts_lists_kernel(const int32_t* __restrict__ pair_token, int B, int Nv,
                                                                  int pairs_per_image, int range, int ranges,
                                                                  int32_t* __restrict__ offset,
@@ -564,18 +572,47 @@ __global__ __launch_bounds__(kListThreads) void vts_lists_kernel(const int32_t* 
   const int b = blockIdx.x / ranges, rg = blockIdx.x - b * ranges;
   const int t0 = rg * range;
   const int span = min(range, Nv - t0);  // >= 1: ranges = ceil(Nv / range)
+  // the image's pairs [lo, hi), read 16 bytes at a time from the aligned place at or before lo (the slot of the
+  // pair array is padded to 256 bytes, so the last piece may reach past hi but not past the slot)
+  const int lo = b * pairs_per_image, hi = lo + pairs_per_image;
+  const int a0 = lo & ~3;
+  const int pieces = (hi - a0 + 3) >> 2;
+  const int first = b * Nv + t0;
+  int4 held[NP > 0 ? NP : 1];
+  if constexpr (NP > 0) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i)  // threads past the end repeat the last piece and skip it below
+      held[i] = *reinterpret_cast<const int4*>(pair_token + a0 + 4 * min(tid + i * kListThreads, pieces - 1));
+  }
+  // fn(token, pair) for every pair of the image that this thread looks at
+  auto each_pair = [&](auto&& fn) {
+    auto piece = [&](const int4& v, int g4, bool in) {
+      const int tok[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (in && g4 + j >= lo && g4 + j < hi) fn(tok[j], g4 + j);
+    };
+    if constexpr (NP > 0) {
+#pragma unroll
+      for (int i = 0; i < NP; ++i) {
+        const int k = tid + i * kListThreads;
+        piece(held[i], a0 + 4 * k, k < pieces);
+      }
+    } else {
+#pragma unroll 2
+      for (int k = tid; k < pieces; k += kListThreads)
+        piece(*reinterpret_cast<const int4*>(pair_token + a0 + 4 * k), a0 + 4 * k, true);
+    }
+  };
 #pragma unroll
   for (int i = 0; i < 4; ++i) cnt[4 * tid + i] = 0;
   __syncthreads();
-  const int32_t* pt = pair_token + (size_t)b * pairs_per_image;
-  const int first = b * Nv + t0;
   int below = 0;
-#pragma unroll 4
-  for (int e = tid; e < pairs_per_image; e += kListThreads) {
-    const int rel = pt[e] - first;
+  each_pair([&](int tok, int) {
+    const int rel = tok - first;
     below += rel < 0 ? 1 : 0;
     if ((unsigned)rel < (unsigned)span) atomicAdd(&cnt[rel], 1);
-  }
+  });
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o);
   __syncthreads();
@@ -592,7 +629,7 @@ __global__ __launch_bounds__(kListThreads) void vts_lists_kernel(const int32_t* 
   if (lane == kWave - 1) wave_total[wave] = incl;
   if (lane == 0) wave_below[wave] = below;
   __syncthreads();
-  int run = b * pairs_per_image + incl - mine;
+  int run = lo + incl - mine;
   for (int w = 0; w < kListThreads / kWave; ++w) run += wave_below[w] + (w < wave ? wave_total[w] : 0);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -602,11 +639,10 @@ __global__ __launch_bounds__(kListThreads) void vts_lists_kernel(const int32_t* 
   }
   if (blockIdx.x == gridDim.x - 1 && tid == 0) offset[(size_t)B * Nv] = B * pairs_per_image;
   __syncthreads();
-#pragma unroll 4
-  for (int e = tid; e < pairs_per_image; e += kListThreads) {
-    const int rel = pt[e] - first;
-    if ((unsigned)rel < (unsigned)span) list[atomicAdd(&cnt[rel], 1)] = b * pairs_per_image + e;
-  }
+  each_pair([&](int tok, int pair) {
+    const int rel = tok - first;
+    if ((unsigned)rel < (unsigned)span) list[atomicAdd(&cnt[rel], 1)] = pair;
+  });
 }
 
 // Four visible tokens per wave (16 lanes each) when the rows are whole 16-byte pieces: dfeat = sum over the
@@ -768,7 +804,7 @@ VtsBwdLayout vts_bwd_layout(int B, int Mq, int Nv, int Kt) {
   L.pair_off = off;    off += vts_align(pairs * sizeof(int32_t));
   L.offset_off = off;  off += vts_align((tokens + 1) * sizeof(int32_t));
   L.list_off = off;    off += vts_align(pairs * sizeof(int32_t));
-  L.dp_off = off;      off += vts_align((size_t)B * Mq * sizeof(float));
+  L.dp_off = off;      off += vts_align(((size_t)B * Mq + 64) * sizeof(float));  // per query, or per wave (+ grid padding)
   L.dp2_off = off;     off += vts_align(vts_dp_blocks(B, Mq) * sizeof(float));
   L.total = off;
   return L;
@@ -811,19 +847,33 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
                   (const float*)a.feat, a.table, (const float*)a.dout, a.B, a.Mq, a.Nv, a.C, gr, a.Kt, a.p, a.eps,
                   weights, pair_token, a.dquery, dp_part);
   if (a.dp) {
-    const size_t n = (size_t)a.B * a.Mq, blocks = vts_dp_blocks(a.B, a.Mq);
-    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3((unsigned)blocks), dim3(1024), 0, stream, dp_part, n,
-                  (size_t)kDpPer, dp_part2);
-    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part2, blocks, blocks, a.dp);
+    // parts: one per wave of the grouped kernels, one per query otherwise
+    const size_t n = grouped ? (size_t)gridg.x * 4 : (size_t)a.B * a.Mq;
+    const size_t blocks = (n + kDpPer - 1) / kDpPer;
+    if (blocks == 1) {
+      AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part, n, n, a.dp);
+    } else {
+      AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3((unsigned)blocks), dim3(1024), 0, stream, dp_part, n,
+                    (size_t)kDpPer, dp_part2);
+      AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part2, blocks, blocks,
+                    a.dp);
+    }
   }
   {
     // token ranges per image: enough workgroups to fill the chip, never more tokens than the LDS counters hold
-    const int want = (256 + a.B - 1) / a.B;
+    const int want = (192 + a.B - 1) / a.B;
     int range = std::max(64, (a.Nv + want - 1) / want);
     range = std::min(range, kListRange);
     const int ranges = (a.Nv + range - 1) / range;
-    AFFMAE_LAUNCH("vts_lists_kernel", stream, vts_lists_kernel, dim3((unsigned)(a.B * ranges)), dim3(kListThreads), 0,
-                  stream, pair_token, a.B, a.Nv, a.Mq * a.Kt, range, ranges, offset, list);
+    const dim3 lgrid((unsigned)(a.B * ranges));
+    const int ppi = a.Mq * a.Kt, pieces_max = (ppi + 3) / 4 + 1;  // + 1: an image may start inside a piece
+#define AFFMAE_VTS_LISTS(NP)                                                                                         \
+  AFFMAE_LAUNCH("vts_lists_kernel", stream, vts_lists_kernel<NP>, lgrid, dim3(kListThreads), 0, stream, pair_token, \
+                a.B, a.Nv, ppi, range, ranges, offset, list)
+    if (pieces_max <= 4 * kListThreads) AFFMAE_VTS_LISTS(4);
+    else if (pieces_max <= 9 * kListThreads) AFFMAE_VTS_LISTS(9);
+    else AFFMAE_VTS_LISTS(0);
+#undef AFFMAE_VTS_LISTS
   }
   if (vts_grouped(a, a.dout, a.dfeat, nullptr)) {  // (Kt <= 16 is not needed here, only the row shape)
     const dim3 per4(round_up8(((long long)tokens + 15) / 16));

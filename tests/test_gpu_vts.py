@@ -66,7 +66,8 @@ SAMPLE_CASES = [
     ("f32", 2, 333, 200, 64, 16, 16, 5, 0.5),   # rows of whole 16-byte pieces, Kt <= 16: four queries per wave
     ("f32", 1, 77, 50, 68, 8, 8, 16, 1.5),      # the same with a ragged last trip (68 channels) and Kt = 16
     ("bf16", 3, 101, 90, 8, 10, 10, 3, 0.5),    # a single 16-byte piece per row
-    ("f32", 1, 40000, 2000, 8, 48, 48, 4, 0.5),  # many pairs per image: 32 token ranges, dp summed in two steps
+    ("f32", 1, 40000, 2000, 8, 48, 48, 4, 0.5),  # many pairs per image, several token ranges
+    ("f32", 1, 20000, 100, 6, 12, 12, 4, 0.5),   # rows that are no whole 16-byte pieces: dp summed in two steps
     ("bf16", 3, 21847, 500, 16, 32, 32, 4, 0.5),  # enough queries for two per lane group, ragged end (65541)
 ]
 
