@@ -28,7 +28,7 @@ namespace {
 constexpr int kSlotCap = 10;  // token tiles whose bias tile is resident per wave (5 KB): four workgroups per CU
 static_assert(kSlotCap % 2 == 0, "an odd pass uses one more tile for the second half of its last pair");
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLazy = 6.f;  // the softmax reference follows the running maximum in steps of at least this much
+constexpr float kLazy = 40.f;  // the softmax reference follows the running maximum in steps of at least this much
 
 struct FwdParams {
   const bf16_t *q, *k, *v, *bias, *k_blank, *v_blank;
@@ -178,10 +178,15 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
         const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
         const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
-        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + lane_off);
-        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + lane_off);
-        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + lane_off);
-        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + lane_off);
+        // scalar tile address + 32-bit lane offset, so that the address needs no vector arithmetic: the lane
+        // offset is made opaque here, or the compiler keeps (image + lane offset) as a 64-bit vector and adds
+        // the tile's offset to it with two vector instructions per load
+        uint32_t off = lane_off;
+        asm volatile("" : "+v"(off));
+        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + off);
+        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + off);
+        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + off);
+        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + off);
       };
       // pieces as loaded -> LDS -> operand pieces
       auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],
@@ -211,12 +216,14 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
           s[4 * tt + 3] = fmaf(st[3], p.scale, __uint_as_float(bm.y & 0xffff0000u));
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-        mx = group_max(mx);
-        // Online softmax with a lazily moved reference: m_run only follows the maximum when it rose by more than
-        // kLazy, and only then are the sums rescaled (wave-uniform test).  Probabilities are relative to m_run
-        // and may reach e^kLazy; the fp32 sums and the bf16 operand keep their relative precision at that size.
-        const bool move = mx > m_run + kLazy;  // also the first finite maximum after -inf
-        if (__ballot(move) != 0ull) {
+        // Online softmax with a lazily moved reference: m_run (one value per query, the same in the four lanes
+        // that share the query) only follows the maximum when some score rose more than kLazy above it, and only
+        // then are the maxima of the lanes combined and the sums rescaled (wave-uniform test).  Probabilities are
+        // relative to m_run and may reach e^kLazy; the fp32 sums and the bf16 operand (8 exponent bits) keep their
+        // relative precision at that size.
+        if (__ballot(mx > m_run + kLazy) != 0ull) {  // also the first finite score after -inf
+          mx = group_max(mx);
+          const bool move = mx > m_run + kLazy;
           const float m_new = move ? mx : m_run;
           const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e) : 1.f;  // exp2(-inf) = 0
           l_run *= alpha;
