@@ -260,10 +260,14 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
         const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
         const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
-        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + lane_off);
-        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + lane_off);
-        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + lane_off);
-        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + lane_off);
+        // scalar tile address + 32-bit lane offset (made opaque here, or the compiler keeps image + lane offset
+        // as a 64-bit vector and adds the tile's offset with two vector instructions per load)
+        uint32_t off = lane_off;
+        asm volatile("" : "+v"(off));
+        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + off);
+        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + off);
+        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + off);
+        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + off);
       };
       // pieces as loaded -> LDS -> operand pieces
       auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],

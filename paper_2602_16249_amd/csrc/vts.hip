@@ -147,6 +147,129 @@ __device__ __forceinline__ int cell_of(float q, float x0, float cell, int n) {
   return (int)f;
 }
 
+// Table by a search over the grid itself, for small Kt.  A workgroup bins the image's visible tokens by grid
+// cell in LDS (count, prefix sum, fill: tokens of a cell, and of consecutive cells of a grid row, end up
+// adjacent), then every thread serves one grid point: it scans the tokens of a square window of cells around the
+// point, keeping the best Kt keys in registers, and widens the window until the Kt-th key is closer than
+// anything outside the window can be.  A token binned outside a window of radius r cells is at least
+// (r + 1/2) cell widths away along one axis (tokens outside the grid are binned to border cells and are farther
+// still); the test leaves a margin of 2^-10 for the rounding of the bin and of the distances.  Same keys, hence
+// the same table, as the exhaustive kernels above.
+constexpr int kGridThreads = 1024;
+constexpr int kGridLdsBytes = 64 * 1024;
+template <int CAP>
+__global__ __launch_bounds__(kGridThreads) void vts_table_grid_kernel(const float* __restrict__ vis_xy, int B, int Nv,
+                                                                     Grid gr, int Kt, int r0, int slabs,
+                                                                     int32_t* __restrict__ table) {
+  extern __shared__ __align__(16) unsigned char grid_lds[];
+  const int cells = gr.Hg * gr.Wg;
+  int32_t* cend = reinterpret_cast<int32_t*>(grid_lds);                      // [cells] counts, then starts, then ends
+  float2* sxy = reinterpret_cast<float2*>(grid_lds + (size_t)((cells + 1) & ~1) * 4);  // [Nv] tokens in cell order
+  int32_t* sidx = reinterpret_cast<int32_t*>(sxy + Nv);                     // [Nv]
+  __shared__ int32_t wave_total[kGridThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int b = blockIdx.x / slabs, slab = blockIdx.x - b * slabs;
+  const float2* xy = reinterpret_cast<const float2*>(vis_xy) + (size_t)b * Nv;
+  auto bin_of = [&](const float2& t) { return cell_of(t.y, gr.y0, gr.cell, gr.Hg) * gr.Wg + cell_of(t.x, gr.x0, gr.cell, gr.Wg); };
+  // the first kHeld tokens of a thread stay in registers between the counting and the filing
+  constexpr int kHeld = 4;
+  float2 held[kHeld];
+  int held_bin[kHeld];
+#pragma unroll
+  for (int i = 0; i < kHeld; ++i) {
+    const int t = tid + i * kGridThreads;
+    held[i] = xy[min(t, Nv - 1)];
+  }
+  for (int c = tid; c < cells; c += kGridThreads) cend[c] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kHeld; ++i) {
+    held_bin[i] = bin_of(held[i]);
+    if (tid + i * kGridThreads < Nv) atomicAdd(&cend[held_bin[i]], 1);
+  }
+  for (int t = tid + kHeld * kGridThreads; t < Nv; t += kGridThreads) atomicAdd(&cend[bin_of(xy[t])], 1);
+  __syncthreads();
+  // exclusive prefix sum in place: thread tid owns a run of consecutive cells
+  const int per = (cells + kGridThreads - 1) / kGridThreads;
+  const int c_lo = min(tid * per, cells), c_hi = min(c_lo + per, cells);
+  int mine = 0;
+  for (int c = c_lo; c < c_hi; ++c) mine += cend[c];
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+  if (lane == kWave - 1) wave_total[wave] = incl;
+  __syncthreads();
+  int run = incl - mine;
+  for (int w = 0; w < wave; ++w) run += wave_total[w];
+  for (int c = c_lo; c < c_hi; ++c) {
+    const int n = cend[c];
+    cend[c] = run;
+    run += n;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kHeld; ++i) {
+    const int t = tid + i * kGridThreads;
+    if (t < Nv) {
+      const int pos = atomicAdd(&cend[held_bin[i]], 1);  // leaves the end of every cell behind
+      sxy[pos] = held[i];
+      sidx[pos] = t;
+    }
+  }
+  for (int t = tid + kHeld * kGridThreads; t < Nv; t += kGridThreads) {
+    const float2 v = xy[t];
+    const int pos = atomicAdd(&cend[bin_of(v)], 1);
+    sxy[pos] = v;
+    sidx[pos] = t;
+  }
+  __syncthreads();
+
+  const int c = slab * kGridThreads + tid;
+  if (c >= cells) return;  // no barrier below
+  const int iy = c / gr.Wg, ix = c - iy * gr.Wg;
+  // patch centre, each operation rounded separately
+  const float hx = (float)ix + 0.5f, hy = (float)iy + 0.5f;
+  const float sx = hx * gr.cell, sy = hy * gr.cell;
+  const float gx = gr.x0 + sx, gy = gr.y0 + sy;
+  key_t best[CAP];
+  for (int r = r0;; r += max(1, r >> 1)) {
+#pragma unroll
+    for (int i = 0; i < CAP; ++i) best[i] = kKeyMax;
+    const int x_lo = max(ix - r, 0), x_hi = min(ix + r, gr.Wg - 1);
+    const int y_lo = max(iy - r, 0), y_hi = min(iy + r, gr.Hg - 1);
+    for (int y = y_lo; y <= y_hi; ++y) {
+      const int first = y * gr.Wg + x_lo, last = y * gr.Wg + x_hi;
+      const int t_lo = first > 0 ? cend[first - 1] : 0, t_hi = cend[last];
+      for (int t = t_lo; t < t_hi; ++t) {
+        const float2 v = sxy[t];
+        const key_t key = make_key(dist2(gx, gy, v.x, v.y), sidx[t]);
+        if (key < best[CAP - 1]) {
+          best[CAP - 1] = key;
+#pragma unroll
+          for (int i = CAP - 1; i > 0; --i) {
+            const key_t a = best[i - 1], bb = best[i];
+            best[i - 1] = a < bb ? a : bb;
+            best[i] = a < bb ? bb : a;
+          }
+        }
+      }
+    }
+    if (x_lo == 0 && y_lo == 0 && x_hi == gr.Wg - 1 && y_hi == gr.Hg - 1) break;  // every token has been seen
+    key_t kth = kKeyMax;
+#pragma unroll
+    for (int i = 0; i < CAP; ++i) kth = (i == Kt - 1) ? best[i] : kth;
+    const float reach = ((float)r + 0.5f) * gr.cell;
+    const float safe = reach * reach * (1.f - 0x1p-10f);
+    if (kth != kKeyMax && __uint_as_float((uint32_t)(kth >> 32)) < safe) break;
+  }
+#pragma unroll
+  for (int i = 0; i < CAP; ++i)
+    if (i < Kt) table[((size_t)b * cells + c) * Kt + i] = (int32_t)(uint32_t)best[i];
+}
+
 // Two consecutive channels (even channel index, 4-byte aligned rows): one 32-bit access for bf16.
 __device__ __forceinline__ void load2(const float* p, float& a, float& b) {
   a = p[0];
@@ -742,6 +865,23 @@ __global__ __launch_bounds__(256) void vts_dfeat_kernel(const T* __restrict__ do
 hipError_t launch_vts_table(const VtsArgs& a, hipStream_t stream) {
   const Grid gr = {a.Hg, a.Wg, a.x0, a.y0, a.cell};
   const long long cells = (long long)a.B * a.Hg * a.Wg;
+  const size_t grid_lds = (size_t)((a.Hg * a.Wg + 1) & ~1) * 4 + (size_t)a.Nv * 12;
+  if (a.Kt <= 8 && (long long)a.Hg * a.Wg <= 16384 && grid_lds <= (size_t)kGridLdsBytes &&
+      reinterpret_cast<uintptr_t>(a.vis_xy) % 8 == 0) {
+    // first window: about twice Kt tokens expected inside at the image's mean density
+    const int per_image = a.Hg * a.Wg;
+    int r0 = 1;
+    while ((2ll * r0 + 1) * (2 * r0 + 1) * a.Nv < 2ll * a.Kt * per_image && r0 < 64) ++r0;
+    const int slabs = (per_image + kGridThreads - 1) / kGridThreads;
+    const dim3 grid((unsigned)(a.B * slabs));
+    if (a.Kt <= 4)
+      AFFMAE_LAUNCH("vts_table_kernel", stream, vts_table_grid_kernel<4>, grid, dim3(kGridThreads), grid_lds, stream,
+                    a.vis_xy, a.B, a.Nv, gr, a.Kt, r0, slabs, a.table_out);
+    else
+      AFFMAE_LAUNCH("vts_table_kernel", stream, vts_table_grid_kernel<8>, grid, dim3(kGridThreads), grid_lds, stream,
+                    a.vis_xy, a.B, a.Nv, gr, a.Kt, r0, slabs, a.table_out);
+    return hipGetLastError();
+  }
   if (a.Nv <= kTableRows * kWave) {
     const long long runs = (long long)a.B * ((a.Hg * a.Wg + kTableRun - 1) / kTableRun);
     AFFMAE_LAUNCH("vts_table_kernel", stream, vts_table_fast_kernel, dim3((unsigned)((runs + 3) / 4)), dim3(256), 0,

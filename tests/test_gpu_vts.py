@@ -32,8 +32,12 @@ TABLE_CASES = [
     (3, 1024, 64, 64, 8.0, 4, 0.0),      # a 512px image at 25 % visible
     (1, 1024, 64, 64, 8.0, 64, 2.0),     # Kt at the limit
     (2, 577, 20, 30, 5.0, 9, 1.5),
-    (2, 1500, 48, 48, 8.0, 4, 0.5),      # more than 1024 visible tokens: the streaming kernel
-    (1, 2304, 48, 48, 8.0, 7, 0.0),      # every centre visible, streaming kernel
+    (2, 1500, 48, 48, 8.0, 4, 0.5),      # more than 1024 visible tokens
+    (2, 1500, 48, 48, 8.0, 12, 0.5),     # the same with Kt > 8: the streaming kernel
+    (1, 2304, 48, 48, 8.0, 7, 0.0),      # every centre visible
+    (1, 2304, 48, 48, 8.0, 20, 0.0),     # every centre visible, streaming kernel
+    (2, 6, 32, 32, 8.0, 4, 0.0),         # very sparse: the search window grows to the whole grid
+    (1, 900, 30, 30, 8.0, 8, 3.9),       # Kt = 8, tokens almost anywhere in their cells
 ]
 
 
@@ -43,6 +47,26 @@ def test_table_matches_oracle(B, Nv, Hg, Wg, cell, Kt, jitter):
     rng = np.random.default_rng(Nv + Kt)
     vis = _visible(rng, B, Nv, Hg, Wg, cell, jitter)
     grid = (Hg, Wg, 0.0, 0.0, cell)
+    table = aff.affmae_vts_table(torch.from_numpy(vis).cuda(), grid, Kt)
+    torch.cuda.synchronize()
+    assert np.array_equal(table.cpu().numpy(), oracle.vts_table(vis, grid, Kt))
+
+
+@pytest.mark.parametrize("B,Nv,Hg,Wg,cell,Kt,x0,y0,spread", [
+    (2, 300, 4, 4, 8.0, 4, 0.0, 0.0, 1.0),       # many tokens per cell
+    (2, 200, 16, 12, 6.0, 3, -20.0, 35.0, 1.6),  # shifted origin, tokens up to 30 % outside the grid on every side
+    (1, 50, 24, 24, 4.0, 8, 5.0, 5.0, 0.3),      # all tokens in the middle third: far corners search the whole grid
+    (3, 64, 8, 8, 8.0, 1, 0.0, 0.0, 1.0),        # Kt = 1
+])
+def test_table_arbitrary_token_positions(B, Nv, Hg, Wg, cell, Kt, x0, y0, spread):
+    """Tokens anywhere (off the patch centres, several per cell, outside the grid): the table is still exact."""
+    print(f"case table free B={B} Nv={Nv} grid={Hg}x{Wg} Kt={Kt}", flush=True)
+    rng = np.random.default_rng(1000 + Nv + Kt)
+    cx, cy = x0 + 0.5 * Wg * cell, y0 + 0.5 * Hg * cell
+    vis = np.empty((B, Nv, 2), dtype=np.float32)
+    vis[..., 0] = cx + (rng.random((B, Nv)) - 0.5) * Wg * cell * spread
+    vis[..., 1] = cy + (rng.random((B, Nv)) - 0.5) * Hg * cell * spread
+    grid = (Hg, Wg, x0, y0, cell)
     table = aff.affmae_vts_table(torch.from_numpy(vis).cuda(), grid, Kt)
     torch.cuda.synchronize()
     assert np.array_equal(table.cpu().numpy(), oracle.vts_table(vis, grid, Kt))
