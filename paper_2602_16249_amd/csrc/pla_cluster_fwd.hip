@@ -40,6 +40,15 @@ struct FwdParams {
   float* lse;
 };
 
+// ds_read_b64_tr_b16: inside a group of 16 lanes, lanes 4j..4j+3 address the four 8-byte quarters of a row j of
+// 16 bf16 values (j = 0..3), and lane i of the group receives element i of rows 0..3: a 4 x 16 block read by
+// columns.  With rows = tokens and columns = channels this is the transposed operand of an MFMA.
+__device__ __forceinline__ uint2 lds_read_tr(const void* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  return __builtin_bit_cast(uint2, r);
+}
+
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
 }
@@ -75,36 +84,38 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   const int cnt_raw = sl[0];
   const int my_tile = (lane < p.slot_stride - 1) ? (int)sl[1 + lane] : 0;
 
-  // plan entries of this lane (kept for all heads) and where the matching bias values sit
+  // Plan entries of this lane and the matching bias values.  They are used only while a pass scatters its bias
+  // tile; a later pass (rare) loads them again, so that they hold no registers during the tile loop.
   constexpr int EW = VEC ? 4 : 1;  // 32-bit words per item
-  uint32_t ent[NT][EW];
-  uint32_t bias_off[NT];  // element offset of the item's first bias value within head 0's rows
   const int items = VEC ? 2 * K : 16 * K;  // chunks of 8, or single entries
   const int chunks_per_query = K >> 3;
+  const bf16_t* bias_head = p.bias ? p.bias + (size_t)tok0 * p.H * K + (size_t)h * K : nullptr;
+  auto load_items = [&](uint32_t (&ent)[NT][EW], uint32_t (&bw)[NT][EW]) {
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int i = t * kWave + lane;
-    const bool live = i < items;
-    const int ii = live ? i : 0;
-    if (VEC) {
-      const uint4 w = *reinterpret_cast<const uint4*>(p.entries + (size_t)sg * 16 * K + (size_t)ii * 8);
-      ent[t][0] = live ? w.x : 0xffffffffu;
-      ent[t][EW > 1 ? 1 : 0] = live ? w.y : 0xffffffffu;
-      ent[t][EW > 2 ? 2 : 0] = live ? w.z : 0xffffffffu;
-      ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
-      const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
-      bias_off[t] = (uint32_t)(qi * p.H * K + j0);
-    } else {
-      ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
-      const int qi = fast_div(ii, p.k_magic);
-      bias_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
+    for (int t = 0; t < NT; ++t) {
+      const int i = t * kWave + lane;
+      const bool live = i < items;
+      const int ii = live ? i : 0;
+      if (VEC) {
+        const uint4 w = *reinterpret_cast<const uint4*>(p.entries + (size_t)sg * 16 * K + (size_t)ii * 8);
+        ent[t][0] = live ? w.x : 0xffffffffu;
+        ent[t][EW > 1 ? 1 : 0] = live ? w.y : 0xffffffffu;
+        ent[t][EW > 2 ? 2 : 0] = live ? w.z : 0xffffffffu;
+        ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
+        const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
+        uint4 bv = make_uint4(0, 0, 0, 0);
+        if (bias_head) bv = *reinterpret_cast<const uint4*>(bias_head + (uint32_t)(qi * p.H * K + j0));
+        bw[t][0] = bv.x;
+        bw[t][EW > 1 ? 1 : 0] = bv.y;
+        bw[t][EW > 2 ? 2 : 0] = bv.z;
+        bw[t][EW > 3 ? 3 : 0] = bv.w;
+      } else {
+        ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
+        const int qi = fast_div(ii, p.k_magic);
+        bw[t][0] = bias_head ? (uint32_t)bias_head[(uint32_t)(qi * p.H * K + (ii - qi * K))] : 0u;
+      }
     }
-  }
-  Frag8 idf[2];  // identity operand, one per 16-channel half: lane (column r, rows 8g..8g+7)
-#pragma unroll
-  for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) idf[dt].h[i] = (8 * g + i == r + 16 * dt) ? 0x3f80u : 0u;
+  };
   // K/V rows of a token tile come in through LDS.  The MFMA operand wants lane (row r, channels
   // 8g..8g+7), which puts the four lanes of a quad on four different rows, and the memory pipeline
   // serves one row segment per cycle: such a load costs 64 cycles against 16 for a load whose quads
@@ -119,30 +130,18 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   u32x4* kv = kv_all[wave];
   const int wr_chunk = tile_chunk(la, lc);
   const int rd_chunk = tile_chunk(r, g);
-  const bf16_t* bias_strip = p.bias ? p.bias + (size_t)tok0 * p.H * K : nullptr;
-
-  // loads of one head: the Q^T operand (lane (query r, channels 8g..8g+7)) and the bias of the items
-  auto load_head = [&](int h, u32x4& qraw, uint32_t (&bw)[NT][EW]) {
-    qraw = *reinterpret_cast<const u32x4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8));
+  // V^T operand of P.V, lane (channel 16 dt + r, tokens 4g..4g+3): read from the staged row-major V tile by the
+  // transposing LDS read; this lane addresses the quarter (r % 4) of the 16 channels of token 4g + r / 4
+  int vt_off[2];  // byte offsets inside a staged tile
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      if (VEC) {
-        uint4 w = make_uint4(0, 0, 0, 0);
-        if (bias_strip) w = *reinterpret_cast<const uint4*>(bias_strip + bias_off[t] + (size_t)h * K);
-        bw[t][0] = w.x;
-        bw[t][EW > 1 ? 1 : 0] = w.y;
-        bw[t][EW > 2 ? 2 : 0] = w.z;
-        bw[t][EW > 3 ? 3 : 0] = w.w;
-      } else {
-        bw[t][0] = bias_strip ? (uint32_t)bias_strip[bias_off[t] + (size_t)h * K] : 0u;
-      }
-    }
-  };
+  for (int dt = 0; dt < 2; ++dt) vt_off[dt] = tile_chunk(4 * g + (r >> 2), 2 * dt + ((r & 3) >> 1)) * 16 + (r & 1) * 8;
   {
     Frag8 qf;
-    u32x4 qraw;
-    uint32_t bw[NT][EW];
-    load_head(h, qraw, bw);
+    uint32_t ent[NT][EW], bw[NT][EW];
+    load_items(ent, bw);
+    // the Q^T operand: lane (query r, channels 8g..8g+7)
+    const u32x4 qraw =
+        *reinterpret_cast<const u32x4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8));
     // first use of a loaded value: everything the strip streams in is in flight by now
     const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
     kv[wr_chunk] = qraw;  // the q rows cross through LDS like the K/V rows
@@ -151,7 +150,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
-    for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCap) {
+    for (int slot0 = 0; slot0 < ntiles;) {
       const int nsl = min(kSlotCap, ntiles - slot0);
       // bias tile: -inf everywhere, then the bias of the real (query, neighbour) pairs
       // (an odd pass gets one more tile of -inf: the second half of its last pair, which repeats a tile)
@@ -190,18 +189,23 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       };
       // pieces as loaded -> LDS -> operand pieces
       auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],
-                            Frag8(&vf)[2]) {
+                            Frag8(&vt)[2]) {
         kv[0 * 64 + wr_chunk] = k0;
         kv[1 * 64 + wr_chunk] = v0;
         kv[2 * 64 + wr_chunk] = k1;
         kv[3 * 64 + wr_chunk] = v1;
         wave_lds_sync();
         kf[0].x4 = kv[0 * 64 + rd_chunk];
-        vf[0].x4 = kv[1 * 64 + rd_chunk];
         kf[1].x4 = kv[2 * 64 + rd_chunk];
-        vf[1].x4 = kv[3 * 64 + rd_chunk];
+        const char* vbase = reinterpret_cast<const char*>(kv);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {  // k-slots 0..3 = first tile's tokens 4g..4g+3, 4..7 = second tile's
+          const uint2 a = lds_read_tr(vbase + 1 * 1024 + vt_off[dt]);
+          const uint2 b = lds_read_tr(vbase + 3 * 1024 + vt_off[dt]);
+          vt[dt].u[0] = a.x; vt[dt].u[1] = a.y; vt[dt].u[2] = b.x; vt[dt].u[3] = b.y;
+        }
       };
-      auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
+      auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vt)[2]) {
         // a pass with an odd number of tiles repeats its last tile in the second half of the last pair, under
         // a bias tile of -inf: its scores are -inf without a test.  The whole pair is one basic block.
         float s[8];
@@ -247,31 +251,24 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         pf.u[2] = pack_bf16x2(pr8[4], pr8[5]);
         pf.u[3] = pack_bf16x2(pr8[6], pr8[7]);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          Frag8 vt;  // V^T operand: lane (channel 16dt + r, the same tokens), via V x identity
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            f32x4 c = {0.f, 0.f, 0.f, 0.f};
-            c = mfma32(vf[tt], idf[dt], c);  // c[i] = v[token 4g+i][channel 16dt + r]
-            vt.u[2 * tt + 0] = pack_bf16x2(c[0], c[1]);
-            vt.u[2 * tt + 1] = pack_bf16x2(c[2], c[3]);
-          }
-          acc[dt] = mfma32(vt, pf, acc[dt]);
-        }
+        for (int dt = 0; dt < 2; ++dt) acc[dt] = mfma32(vt[dt], pf, acc[dt]);
       };
       // The loads of the next pair fly during this pair's math.  Every load sits in straight-line code: a
       // load under a condition would make the compiler wait for all outstanding loads where the paths join.
       u32x4 sk0, sv0, sk1, sv1;
-      Frag8 kf[2], vf[2];
+      Frag8 kf[2], vt[2];
       load_pair(0, sk0, sv0, sk1, sv1);
       for (int pr = 0; pr + 1 < npairs; ++pr) {
-        stage_pair(sk0, sv0, sk1, sv1, kf, vf);
+        stage_pair(sk0, sv0, sk1, sv1, kf, vt);
         load_pair(pr + 1, sk0, sv0, sk1, sv1);
-        compute_pair(pr, kf, vf);
+        compute_pair(pr, kf, vt);
       }
-      stage_pair(sk0, sv0, sk1, sv1, kf, vf);
-      compute_pair(npairs - 1, kf, vf);
+      stage_pair(sk0, sv0, sk1, sv1, kf, vt);
+      compute_pair(npairs - 1, kf, vt);
       wave_lds_sync();  // the next pass overwrites the bias tile
+      slot0 += kSlotCap;
+      if (slot0 >= ntiles) break;
+      load_items(ent, bw);
     }
 
     // The probabilities that entered the MFMAs were rounded to bf16; the
@@ -316,7 +313,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
 // The 16-byte path keeps four waves per SIMD; the single-entry path (K not a multiple of 8) holds more
 // per-lane state and is built for two.
 template <int NT>
-__global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
+__global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
   pla_fwd_cluster_body<NT, true>(p);
 }
 template <int NT>
