@@ -133,6 +133,22 @@ __device__ __forceinline__ int tile_chunk(int row, int piece) {
   return row * 4 + (piece ^ (((row >> 1) & 3) ^ ((row >> 3) & 1)));
 }
 
+// ds_read_b64_tr_b16: inside a group of 16 lanes, lanes 4j..4j+3 address the four 8-byte quarters of a row j of
+// 16 bf16 values (j = 0..3), and lane i of the group receives element i of rows 0..3: a 4 x 16 block read by
+// columns.  With rows = tokens and columns = channels this is the transposed operand of an MFMA.
+__device__ __forceinline__ uint2 lds_read_tr(const void* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  return __builtin_bit_cast(uint2, r);
+}
+
+// Byte offset, inside a staged 16 x 32 tile (layout of tile_chunk), that lane (r = lane % 16, g = lane / 16) gives
+// to lds_read_tr to receive, for channel 16 dt + r, the values of rows 4g..4g+3: it addresses the quarter r % 4 of
+// the 16 channels of row 4g + r / 4.
+__device__ __forceinline__ int tile_tr_offset(int g, int r, int dt) {
+  return tile_chunk(4 * g + (r >> 2), 2 * dt + ((r & 3) >> 1)) * 16 + (r & 1) * 8;
+}
+
 // Two fp32 -> packed bf16 (round to nearest even), low half first.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;

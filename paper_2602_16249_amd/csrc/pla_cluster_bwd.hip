@@ -54,13 +54,6 @@ __device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c)
   return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ void make_identity(Frag8 (&idf)[2], int g, int r) {
-#pragma unroll
-  for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) idf[dt].h[i] = (8 * g + i == r + 16 * dt) ? 0x3f80u : 0u;
-}
-
 __device__ __forceinline__ int xcd_contiguous_block() {
   // Workgroups are dealt round-robin to the 8 XCDs (one L2 each); neighbouring strips and tiles share
   // rows, so give every XCD a contiguous range.  The grid is a multiple of 8.
@@ -122,8 +115,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
     }
   }
   const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
-  Frag8 idf[2];
-  make_identity(idf, g, r);
+  const int tr_off[2] = {tile_tr_offset(g, r, 0), tile_tr_offset(g, r, 1)};
   // K/V rows cross through LDS: lane (row lane/4, 16-byte piece lane%4) loads 64 contiguous bytes per
   // quad (16 memory-pipeline cycles per load instead of the 64 of a load straight into the operand
   // layout, whose quads touch four rows), and each lane reads back the piece its operand needs; the
@@ -271,12 +263,22 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       };
       // pieces as loaded -> LDS -> operand pieces
       auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],
-                            Frag8(&vf)[2]) {
+                            Frag8(&vf)[2], Frag8(&kt)[2]) {
         kv[0 * 64 + wr_chunk] = k0;
         kv[1 * 64 + wr_chunk] = k1;
         wave_lds_sync();
         kf[0].x4 = kv[0 * 64 + rd_chunk];
         kf[1].x4 = kv[1 * 64 + rd_chunk];
+        {
+          // K^T operand, lane (channel 16dt + r, tokens 4g..4g+3 of both tiles), by the transposing LDS read
+          const char* kbase = reinterpret_cast<const char*>(kv);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) {
+            const uint2 a = lds_read_tr(kbase + 0 * 1024 + tr_off[dt]);
+            const uint2 b = lds_read_tr(kbase + 1 * 1024 + tr_off[dt]);
+            kt[dt].u[0] = a.x; kt[dt].u[1] = a.y; kt[dt].u[2] = b.x; kt[dt].u[3] = b.y;
+          }
+        }
         wave_lds_sync();
         kv[0 * 64 + wr_chunk] = v0;
         kv[1 * 64 + wr_chunk] = v1;
@@ -284,7 +286,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         vf[0].x4 = kv[0 * 64 + rd_chunk];
         vf[1].x4 = kv[1 * 64 + rd_chunk];
       };
-      auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2]) {
+      auto compute_pair = [&](int pr, const Frag8(&kf)[2], const Frag8(&vf)[2], const Frag8(&kt)[2]) {
         // A pass with an odd number of tiles repeats its last tile in the second half of the last pair, under
         // a bias tile of -inf: p and dS come out 0 without a test.  The whole pair is one basic block.
         Frag8 dsf;  // dS^T operand: k-slots 0..3 = first tile's tokens 4g..4g+3, 4..7 = second tile's
@@ -315,30 +317,20 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
           }
         }
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          Frag8 kt;  // K^T operand: lane (channel 16dt + r, the same tokens), via K x identity
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            f32x4 c = {0.f, 0.f, 0.f, 0.f};
-            c = mfma32(kf[tt], idf[dt], c);  // c[i] = k[token 4g+i][channel 16dt + r]
-            kt.u[2 * tt + 0] = pack_bf16x2(c[0], c[1]);
-            kt.u[2 * tt + 1] = pack_bf16x2(c[2], c[3]);
-          }
-          acc[dt] = mfma32(kt, dsf, acc[dt]);  // dq^T[channel 16dt + 4g+i][query r]
-        }
+        for (int dt = 0; dt < 2; ++dt) acc[dt] = mfma32(kt[dt], dsf, acc[dt]);  // dq^T[channel 16dt + 4g+i][query r]
       };
       // The loads of the next pair fly during this pair's math; every load in straight-line code (a load
       // under a condition makes the compiler wait for all outstanding loads where the paths join).
       u32x4 sk0, sv0, sk1, sv1;
-      Frag8 kf[2], vf[2];
+      Frag8 kf[2], vf[2], kt[2];
       load_pair(0, sk0, sv0, sk1, sv1);
       for (int pr = 0; pr + 1 < npairs; ++pr) {
-        stage_pair(sk0, sv0, sk1, sv1, kf, vf);
+        stage_pair(sk0, sv0, sk1, sv1, kf, vf, kt);
         load_pair(pr + 1, sk0, sv0, sk1, sv1);
-        compute_pair(pr, kf, vf);
+        compute_pair(pr, kf, vf, kt);
       }
-      stage_pair(sk0, sv0, sk1, sv1, kf, vf);
-      compute_pair(npairs - 1, kf, vf);
+      stage_pair(sk0, sv0, sk1, sv1, kf, vf, kt);
+      compute_pair(npairs - 1, kf, vf, kt);
       wave_lds_sync();
       // dS of this pass's real (query, neighbour) pairs in [token, head, slot] order (dbias)
       if (p.ds) {
@@ -432,8 +424,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const size_t strip_base = (size_t)b * p.strips_per_image;
   const int lo = __builtin_amdgcn_readfirstlane(p.rev_offset[kt]);
   const int n = __builtin_amdgcn_readfirstlane(p.rev_offset[kt + 1]) - lo;
-  Frag8 idf[2];
-  make_identity(idf, g, r);
   // q / dout rows cross through LDS: a lane loads 16 contiguous bytes of a row so that a quad reads 64
   // contiguous bytes (a load straight into the operand layout puts a quad on four rows and costs four
   // times the memory-pipeline cycles); each lane then reads back the piece its operand needs.  The piece
@@ -442,13 +432,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const int la = lane / PR, lc = lane % PR;  // row within a load of 64 / PR rows, piece
   const uint32_t q_lane = (uint32_t)(la * C + lc * 8);  // per-lane part of the row addresses (elements)
   auto swz = [](int row) { return HG == 2 ? ((row & 7) ^ (row >> 3)) : (((row >> 1) & 3) ^ ((row >> 3) & 1)); };
-  int wr_chunk[HG], rd_chunk[HG];
+  int wr_chunk[HG];
 #pragma unroll
   for (int i = 0; i < HG; ++i) {
     const int row = i * (64 / PR) + la;
     wr_chunk[i] = row * PR + (lc ^ swz(row));
-    rd_chunk[i] = r * PR + ((i * 4 + g) ^ swz(r));  // head i of the group: piece 4 i + g of row r
   }
+  // what this lane gives to lds_read_tr to receive, for channel 16dt + r of head hh, the values of rows (queries)
+  // 4g..4g+3: the quarter r % 4 of those 16 channels in row 4g + r / 4
+  int tr_off[HG][2];
+#pragma unroll
+  for (int hh = 0; hh < HG; ++hh)
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+      const int row = 4 * g + (r >> 2);
+      tr_off[hh][dt] = (row * PR + ((4 * hh + 2 * dt + ((r & 3) >> 1)) ^ swz(row))) * 16 + (r & 1) * 8;
+    }
 
   for (int hg = 0; hg < p.H; hg += HG) {
     f32x4 dk[HG][2], dv[HG][2];
@@ -516,9 +515,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         for (int hh = 0; hh < HG; ++hh) {
           // (p, dS)[token r][queries 4g..4g+3]
           const uint4 w = *reinterpret_cast<const uint4*>(tile + hh * 256 + r * 16 + g * 4);
-          Frag8 qf, gf;  // lane (query r, channels 8g..8g+7) of q and dout
-          qf.x4 = rows[rd_chunk[hh]];
-          gf.x4 = rows[HG * 64 + rd_chunk[hh]];
           Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
           pf.u[0] = (w.x & 0xffffu) | (w.y << 16);
           pf.u[1] = (w.z & 0xffffu) | (w.w << 16);
@@ -526,14 +522,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
           df.u[1] = (w.z >> 16) | (w.w & 0xffff0000u);
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt) {
-            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            const f32x4 cq = mfma32(qf, idf[dt], z);  // q[query 4g+i][channel 16dt + r]
-            const f32x4 cg = mfma32(gf, idf[dt], z);  // dout likewise
-            Frag4 qT, gT;  // operand A: lane (channel 16dt + r, queries 4g..4g+3)
-            qT.u[0] = pack_bf16x2(cq[0], cq[1]);
-            qT.u[1] = pack_bf16x2(cq[2], cq[3]);
-            gT.u[0] = pack_bf16x2(cg[0], cg[1]);
-            gT.u[1] = pack_bf16x2(cg[2], cg[3]);
+            // operand A: lane (channel 16dt + r, queries 4g..4g+3) of q and dout, by the transposing LDS read
+            const uint2 qw = lds_read_tr(reinterpret_cast<const char*>(rows) + tr_off[hh][dt]);
+            const uint2 gw = lds_read_tr(reinterpret_cast<const char*>(rows + HG * 64) + tr_off[hh][dt]);
+            Frag4 qT, gT;
+            qT.u[0] = qw.x; qT.u[1] = qw.y;
+            gT.u[0] = gw.x; gT.u[1] = gw.y;
             dk[hh][dt] = mfma16(qT, df, dk[hh][dt]);  // dk^T[channel 16dt + 4g+i][token r]
             dv[hh][dt] = mfma16(gT, pf, dv[hh][dt]);
           }

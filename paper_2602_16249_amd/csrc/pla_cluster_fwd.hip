@@ -40,15 +40,6 @@ struct FwdParams {
   float* lse;
 };
 
-// ds_read_b64_tr_b16: inside a group of 16 lanes, lanes 4j..4j+3 address the four 8-byte quarters of a row j of
-// 16 bf16 values (j = 0..3), and lane i of the group receives element i of rows 0..3: a 4 x 16 block read by
-// columns.  With rows = tokens and columns = channels this is the transposed operand of an MFMA.
-__device__ __forceinline__ uint2 lds_read_tr(const void* p) {
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
-  return __builtin_bit_cast(uint2, r);
-}
-
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
 }
@@ -134,7 +125,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   // transposing LDS read; this lane addresses the quarter (r % 4) of the 16 channels of token 4g + r / 4
   int vt_off[2];  // byte offsets inside a staged tile
 #pragma unroll
-  for (int dt = 0; dt < 2; ++dt) vt_off[dt] = tile_chunk(4 * g + (r >> 2), 2 * dt + ((r & 3) >> 1)) * 16 + (r & 1) * 8;
+  for (int dt = 0; dt < 2; ++dt) vt_off[dt] = tile_tr_offset(g, r, dt);
   {
     Frag8 qf;
     uint32_t ent[NT][EW], bw[NT][EW];
