@@ -518,7 +518,7 @@ __device__ __forceinline__ Cand load_candidate_g(const float* __restrict__ query
   const float2 x = *reinterpret_cast<const float2*>(vis_xy + 2 * (size_t)(b * Nv + c.idx));
   c.dx = qx - x.x;
   c.dy = qy - x.y;
-  c.dist = __builtin_amdgcn_sqrtf(c.dx * c.dx + c.dy * c.dy);  // 1 ulp
+  c.dist = sqrtf(c.dx * c.dx + c.dy * c.dy);  // correctly rounded: an error of d is multiplied by p in the exponent
   const float z = on ? -p * (c.dist + eps) : -INFINITY;
   const float zmax = Group<G>::max(z);
   const float e = on ? __expf(z - zmax) : 0.f;
