@@ -128,7 +128,11 @@ int affmae_cluster(const float* coords, int B, int N, int S, double x0, double y
  *   workspace  affmae_vts_bwd_workspace_bytes(B, Mq, Nv, Kt) bytes
  *
  * Limits: 1 <= Kt <= min(Nv, AFFMAE_MAX_K); C even; feat, out, dout, dfeat
- * 4-byte aligned.  Table entries outside 0..Nv-1 are clamped.
+ * 4-byte aligned; B*Hg*Wg, B*Mq, B*Nv and (backward) B*Mq*Kt below 2^31 - 8
+ * (AFFMAE_ERR_UNSUPPORTED otherwise).  Table entries outside 0..Nv-1 are clamped.
+ * The fastest kernels need rows of whole 16-byte pieces (C a multiple of 8 for
+ * bf16, of 4 for fp32), 16-byte aligned feature tensors and 8-byte aligned
+ * coordinate tensors; other shapes are served by slower kernels, same results.
  * Errors: AFFMAE_ERR_NULL, AFFMAE_ERR_SHAPE (sizes < 1, Kt > Nv, empty or
  * non-finite grid, misaligned tensor), AFFMAE_ERR_DTYPE, AFFMAE_ERR_UNSUPPORTED,
  * AFFMAE_ERR_WORKSPACE.
