@@ -4,8 +4,8 @@
  * The library implements the data-parallel hot path of AFFMAE's off-grid
  * hierarchical backbone: balanced clustering of the tokens along a space-filling
  * curve, the batched neighbour search that builds fixed-size neighbourhoods over
- * irregular 2-D token coordinates, and local attention, forward and backward,
- * over each token's K neighbours.
+ * irregular 2-D token coordinates, local attention, forward and backward, over
+ * each token's K neighbours, and the point decoder's virtual sampled tokens.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library
@@ -20,7 +20,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls validate their arguments on the host, enqueue kernels on `stream`
  *     and return without synchronising.  Calls that share a workspace must be
- *     ordered on one stream.
+ *     ordered on one stream.  No call allocates, frees or clears device memory
+ *     through the runtime: a caller may record the calls into a HIP graph.
  *   - Return value: AFFMAE_OK (0) or a negative affmae_status.  When an error
  *     is returned nothing has been enqueued.  No exception crosses the ABI.
  *   - Outputs are fully overwritten (never accumulated into).
