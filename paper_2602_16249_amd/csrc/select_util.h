@@ -36,7 +36,9 @@ __device__ __forceinline__ key_t shfl_key(key_t k, int src) {
 // patterns inside a row of 16 lanes, the gfx950 row / half swaps across rows.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_mov(uint32_t x) {
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+  // every pattern used here reads an existing lane, so no value is needed for lanes without a source: leaving it
+  // undefined saves the instruction that would otherwise set it before every move
+  return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, CTRL, 0xf, 0xf, true);
 }
 template <int J>
 __device__ __forceinline__ uint32_t lane_xor_u32(uint32_t x, int lane) {
