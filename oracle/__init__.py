@@ -39,7 +39,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         for name in ("oracle_centroids", "oracle_knn", "oracle_knn_bruteforce", "oracle_cluster", "oracle_vts_table", "oracle_vts_fwd", "oracle_vts_bwd",
-                     "oracle_pla_fwd", "oracle_pla_bwd", "oracle_num_threads"):
+                     "oracle_pla_fwd", "oracle_pla_bwd", "oracle_relpos_bias", "oracle_relpos_dtable", "oracle_num_threads"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_set_num_threads.restype = None
     return _lib
@@ -219,3 +219,46 @@ def pla_bwd(q, k, v, bias, nbr_idx, dout, scale: float, k_blank=None, v_blank=No
         res["dk_blank"] = dkb
         res["dv_blank"] = dvb
     return res
+
+
+def relpos_bias(coords, nbr_idx, table, R: int, rate: float) -> np.ndarray:
+    """Relative-position bias from a per-head table [H, 2R+1, 2R+1] over quantised offsets -> [B,N,H,K]."""
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    B, N, K = nbr_idx.shape
+    W = 2 * int(R) + 1
+    table = _f64(table)
+    H = table.shape[0]
+    assert table.shape == (H, W, W) and coords.shape == (B, N, 2)
+    bias = np.empty((B, N, H, K), dtype=np.float64)
+    _check(_load().oracle_relpos_bias(_p(coords), _p(nbr_idx), _p(table), B, N, H, K, int(R), ctypes.c_float(rate),
+                                      _p(bias)), "oracle_relpos_bias")
+    return bias
+
+
+def relpos_dtable(coords, nbr_idx, dbias, R: int, rate: float) -> np.ndarray:
+    """Gradient of the table: the bias gradients [B,N,H,K] added up per bin -> [H, 2R+1, 2R+1]."""
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    B, N, K = nbr_idx.shape
+    dbias = _f64(dbias)
+    H = dbias.shape[2]
+    assert dbias.shape == (B, N, H, K)
+    W = 2 * int(R) + 1
+    dtable = np.empty((H, W, W), dtype=np.float64)
+    _check(_load().oracle_relpos_dtable(_p(coords), _p(nbr_idx), _p(dbias), B, N, H, K, int(R), ctypes.c_float(rate),
+                                        _p(dtable)), "oracle_relpos_dtable")
+    return dtable
+
+
+def pla_fwd_relpos(q, k, v, coords, table, nbr_idx, scale: float, R: int, rate: float, k_blank=None, v_blank=None):
+    """Local attention with the bias taken from the relative-position table -> (out, lse)."""
+    return pla_fwd(q, k, v, relpos_bias(coords, nbr_idx, table, R, rate), nbr_idx, scale, k_blank, v_blank)
+
+
+def pla_bwd_relpos(q, k, v, coords, table, nbr_idx, dout, scale: float, R: int, rate: float, k_blank=None,
+                   v_blank=None):
+    """Backward of pla_fwd_relpos -> dict(dq, dk, dv, dtable[, dk_blank, dv_blank])."""
+    g = pla_bwd(q, k, v, relpos_bias(coords, nbr_idx, table, R, rate), nbr_idx, dout, scale, k_blank, v_blank)
+    g["dtable"] = relpos_dtable(coords, nbr_idx, g.pop("dbias"), R, rate)
+    return g

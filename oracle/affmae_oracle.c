@@ -38,6 +38,13 @@
  *     point" = the cell that contains the query, floor((qx - x0) / cell) in
  *     fp32, clamped to the grid; the table orders by (fp32 squared distance,
  *     token index) like the neighbour search; the table stores indices only;
+ *   - relative-position bias (oracle_relpos_bias / oracle_relpos_dtable): the
+ *     paper states that the bias of a neighbourhood is derived from the relative
+ *     positions of its tokens and gives no function; reading: a learned table
+ *     per head over quantised offsets, bias = table[h][by][bx] with bx = the
+ *     offset x_neighbour - x_query times a bin rate, rounded to the nearest
+ *     integer (ties to even) in fp32 and clamped to -R..R, plus R; by alike.
+ *     The gradient of the table adds up the bias gradients that fall in a bin;
  *   - balanced clustering (oracle_cluster): the paper groups tokens into
  *     equal-size clusters with a space-filling curve it does not name; reading:
  *     Z-order (Morton) curve over coordinates quantised to 16 bits per axis of a
@@ -514,6 +521,72 @@ static double attention_row(const double *q, const double *k, const double *bias
 static int check_nbr(const int32_t *nbr, size_t count, int N) {
   for (size_t t = 0; t < count; ++t)
     if (nbr[t] < 0 || nbr[t] >= N) return ORACLE_ERR_ARG;
+  return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* relative-position bias (Sec. "AutoFocusFormer": within a neighbourhood,    */
+/* attention uses relative position derived from the 2-D token coordinates;   */
+/* the FlashNbhdAttn equation adds it as B_n).  The function is this build's  */
+/* reading: a per-head table over quantised offsets.                          */
+
+/* Bin of one axis: offset (neighbour minus query) times the bin rate, in fp32,
+ * rounded to the nearest integer with ties to even, clamped to -R..R, plus R. */
+static int relpos_bin(float nbr, float query, float rate, int R) {
+  float d = nbr - query;
+  float t = d * rate;
+  float r = rintf(t); /* default rounding mode: to nearest, ties to even */
+  if (!(r >= (float)(-R))) return 0; /* also NaN */
+  if (r > (float)R) return 2 * R;
+  return (int)r + R;
+}
+
+/*
+ * oracle_relpos_bias: coords [B,N,2] fp32, nbr_idx [B,N,K], table [H][2R+1][2R+1]
+ * (row = y bin, column = x bin) -> bias [B,N,H,K].
+ */
+int oracle_relpos_bias(const float *coords, const int32_t *nbr_idx, const double *table, int B,
+                       int N, int H, int K, int R, float rate, double *bias) {
+  if (!coords || !nbr_idx || !table || !bias) return ORACLE_ERR_ARG;
+  if (B < 0 || N <= 0 || H <= 0 || K <= 0 || R < 0) return ORACLE_ERR_ARG;
+  int W = 2 * R + 1;
+  for (int b = 0; b < B; ++b)
+    for (int i = 0; i < N; ++i)
+      for (int j = 0; j < K; ++j) {
+        int n = nbr_idx[((size_t)b * N + i) * K + j];
+        if (n < 0 || n >= N) return ORACLE_ERR_ARG;
+        const float *ci = coords + ((size_t)b * N + i) * 2;
+        const float *cn = coords + ((size_t)b * N + n) * 2;
+        int bx = relpos_bin(cn[0], ci[0], rate, R);
+        int by = relpos_bin(cn[1], ci[1], rate, R);
+        for (int h = 0; h < H; ++h)
+          bias[(((size_t)b * N + i) * H + h) * K + j] = table[((size_t)h * W + by) * W + bx];
+      }
+  return ORACLE_OK;
+}
+
+/*
+ * oracle_relpos_dtable: the gradient of the table, dtable[h][by][bx] = sum of
+ * dbias[b,i,h,j] over every (b,i,j) whose offset falls in bin (by,bx).
+ */
+int oracle_relpos_dtable(const float *coords, const int32_t *nbr_idx, const double *dbias, int B,
+                         int N, int H, int K, int R, float rate, double *dtable) {
+  if (!coords || !nbr_idx || !dbias || !dtable) return ORACLE_ERR_ARG;
+  if (B < 0 || N <= 0 || H <= 0 || K <= 0 || R < 0) return ORACLE_ERR_ARG;
+  int W = 2 * R + 1;
+  memset(dtable, 0, (size_t)H * W * W * sizeof(double));
+  for (int b = 0; b < B; ++b)
+    for (int i = 0; i < N; ++i)
+      for (int j = 0; j < K; ++j) {
+        int n = nbr_idx[((size_t)b * N + i) * K + j];
+        if (n < 0 || n >= N) return ORACLE_ERR_ARG;
+        const float *ci = coords + ((size_t)b * N + i) * 2;
+        const float *cn = coords + ((size_t)b * N + n) * 2;
+        int bx = relpos_bin(cn[0], ci[0], rate, R);
+        int by = relpos_bin(cn[1], ci[1], rate, R);
+        for (int h = 0; h < H; ++h)
+          dtable[((size_t)h * W + by) * W + bx] += dbias[(((size_t)b * N + i) * H + h) * K + j];
+      }
   return ORACLE_OK;
 }
 
