@@ -286,6 +286,49 @@ void affmae_timing_enable(int on);
 void affmae_timing_reset(void);
 int affmae_timing_read(int index, char* name, int name_len, double* total_ms, int* count);
 
+/*
+ * affmae_pla_fwd_relpos / affmae_pla_bwd_relpos - local attention whose bias is
+ * derived inside the library from the token coordinates (paper, Sec.
+ * "AutoFocusFormer": within a neighbourhood, attention uses relative position
+ * derived directly from the 2-D token coordinates; it is the term B_n of the
+ * FlashNbhdAttn equation).  The paper gives no function for it; this library
+ * takes a learned table per head over quantised offsets:
+ *     B[b,i,h,j] = rel_table[h][by][bx],
+ *     bx = clamp(rint((x_n - x_i) * rate), -R, R) + R,  by alike with y,
+ * n = nbr_idx[b,i,j]; the offset, the product and the rounding (to nearest, ties
+ * to even) are fp32.  The blank column has no bias.  Everything else is as in
+ * affmae_pla_fwd / affmae_pla_bwd, whose argument lists these calls follow with
+ * `bias` replaced by (coords, rel_table, R, rate) and `dbias` by drel_table.
+ *
+ *   coords      in  [B,N,2] fp32, 8-byte aligned
+ *   rel_table   in  [H, 2R+1, 2R+1] in the storage type (row = y bin)
+ *   R           bins on each side of zero, 0 <= R <= 31, H*(2R+1)^2 <= 12288
+ *   rate        bins per unit of length (> 0), e.g. 1/8 for bins of one 8-px patch
+ *   drel_table  out [H, 2R+1, 2R+1] fp32: the bias gradients added up per bin
+ *               (fp32 sums; the order of the additions inside a workgroup's
+ *               share, hence the last bits, may vary run to run)
+ *   workspace   affmae_pla_fwd_relpos_workspace_bytes / affmae_pla_bwd_relpos_workspace_bytes
+ *
+ * Errors: as affmae_pla_fwd / affmae_pla_bwd, plus AFFMAE_ERR_SHAPE for a negative
+ * R or a rate that is not positive and finite, AFFMAE_ERR_UNSUPPORTED beyond the
+ * limits of R.
+ */
+size_t affmae_pla_fwd_relpos_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
+                                             int clustered);
+int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const float* coords, const void* rel_table,
+                          const int32_t* nbr_idx, const int32_t* near_clusters, const void* plan,
+                          const void* k_blank, const void* v_blank, int B, int N, int H, int d, int K, int S, int M,
+                          float scale, int R, float rate, int dtype, void* out, float* lse, void* workspace,
+                          size_t workspace_bytes, void* stream);
+size_t affmae_pla_bwd_relpos_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int R, int dtype,
+                                             int clustered);
+int affmae_pla_bwd_relpos(const void* q, const void* k, const void* v, const float* coords, const void* rel_table,
+                          const int32_t* nbr_idx, const int32_t* near_clusters, const void* plan,
+                          const void* k_blank, const void* v_blank, const void* out, const float* lse,
+                          const void* dout, int B, int N, int H, int d, int K, int S, int M, float scale, int R,
+                          float rate, int dtype, void* dq, void* dk, void* dv, float* drel_table, float* dk_blank,
+                          float* dv_blank, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

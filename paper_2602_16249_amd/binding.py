@@ -77,6 +77,16 @@ def load_library():
     lib.affmae_pla_bwd.restype = _c_int
     lib.affmae_pla_bwd.argtypes = ([_c_void_p] * 12 + [_c_int] * 7 + [_c_float, _c_int] + [_c_void_p] * 6
                                    + [_c_void_p, _c_size_t, _c_void_p])
+    lib.affmae_pla_fwd_relpos_workspace_bytes.restype = _c_size_t
+    lib.affmae_pla_fwd_relpos_workspace_bytes.argtypes = [_c_int] * 9
+    lib.affmae_pla_bwd_relpos_workspace_bytes.restype = _c_size_t
+    lib.affmae_pla_bwd_relpos_workspace_bytes.argtypes = [_c_int] * 10
+    lib.affmae_pla_fwd_relpos.restype = _c_int
+    lib.affmae_pla_fwd_relpos.argtypes = ([_c_void_p] * 10 + [_c_int] * 7 + [_c_float, _c_int, _c_float, _c_int]
+                                          + [_c_void_p, _c_void_p] + [_c_void_p, _c_size_t, _c_void_p])
+    lib.affmae_pla_bwd_relpos.restype = _c_int
+    lib.affmae_pla_bwd_relpos.argtypes = ([_c_void_p] * 13 + [_c_int] * 7 + [_c_float, _c_int, _c_float, _c_int]
+                                          + [_c_void_p] * 6 + [_c_void_p, _c_size_t, _c_void_p])
     lib.affmae_pla_plan_bytes.restype = _c_size_t
     lib.affmae_pla_plan_bytes.argtypes = [_c_int] * 5
     lib.affmae_pla_plan.restype = _c_int
@@ -367,6 +377,92 @@ def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
                             0 if workspace is None else workspace.numel(), _stream())
     if rc != 0:
         raise AffmaeError("affmae_pla_bwd", rc)
+    return g
+
+
+def affmae_pla_fwd_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, coords: torch.Tensor,
+                          rel_table: torch.Tensor, nbr_idx: torch.Tensor, scale: float, rate: float,
+                          near_clusters: Optional[torch.Tensor] = None, S: int = 0, M: int = 0,
+                          k_blank: Optional[torch.Tensor] = None, v_blank: Optional[torch.Tensor] = None,
+                          out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None, plan: Optional[torch.Tensor] = None
+                          ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Local attention forward with the bias taken from rel_table [H, 2R+1, 2R+1] at the quantised offset of
+    every (token, neighbour) pair -> (out [B,N,H,d], lse [B,N,H])."""
+    lib = load_library()
+    code = _dtype_code(q)
+    _dev(q, "q")
+    B, N, H, d = q.shape
+    _dev(k, "k", q.dtype, q.shape)
+    _dev(v, "v", q.dtype, q.shape)
+    _dev(coords, "coords", torch.float32, (B, N, 2))
+    W = rel_table.shape[-1]
+    _dev(rel_table, "rel_table", q.dtype, (H, W, W))
+    R = (W - 1) // 2
+    K = nbr_idx.shape[2]
+    _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
+    if near_clusters is not None:
+        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+    if k_blank is not None:
+        _dev(k_blank, "k_blank", q.dtype, (H, d))
+        _dev(v_blank, "v_blank", q.dtype, (H, d))
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, N, H), dtype=torch.float32, device=q.device)
+    need = lib.affmae_pla_fwd_relpos_workspace_bytes(B, N, H, d, K, S, M, code, int(near_clusters is not None))
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    rc = lib.affmae_pla_fwd_relpos(_ptr(q), _ptr(k), _ptr(v), _ptr(coords), _ptr(rel_table), _ptr(nbr_idx),
+                                   _ptr(near_clusters), _ptr(plan), _ptr(k_blank), _ptr(v_blank), B, N, H, d, K, S, M,
+                                   float(scale), R, float(rate), code, _ptr(out), _ptr(lse), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_pla_fwd_relpos", rc)
+    return out, lse
+
+
+def affmae_pla_bwd_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, coords: torch.Tensor,
+                          rel_table: torch.Tensor, nbr_idx: torch.Tensor, out: torch.Tensor, lse: torch.Tensor,
+                          dout: torch.Tensor, scale: float, rate: float,
+                          near_clusters: Optional[torch.Tensor] = None, S: int = 0, M: int = 0,
+                          k_blank: Optional[torch.Tensor] = None, v_blank: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None, plan: Optional[torch.Tensor] = None
+                          ) -> Dict[str, torch.Tensor]:
+    """Backward of affmae_pla_fwd_relpos -> dict(dq, dk, dv, drel_table [H,2R+1,2R+1] fp32[, dk_blank, dv_blank])."""
+    lib = load_library()
+    code = _dtype_code(q)
+    _dev(q, "q")
+    B, N, H, d = q.shape
+    for name, t in (("k", k), ("v", v), ("dout", dout), ("out", out)):
+        _dev(t, name, q.dtype, q.shape)
+    _dev(coords, "coords", torch.float32, (B, N, 2))
+    W = rel_table.shape[-1]
+    _dev(rel_table, "rel_table", q.dtype, (H, W, W))
+    R = (W - 1) // 2
+    K = nbr_idx.shape[2]
+    _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
+    _dev(lse, "lse", torch.float32, (B, N, H))
+    if near_clusters is not None:
+        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+    g = {name: torch.empty_like(q) for name in ("dq", "dk", "dv")}
+    g["drel_table"] = torch.empty((H, W, W), dtype=torch.float32, device=q.device)
+    if k_blank is not None:
+        _dev(k_blank, "k_blank", q.dtype, (H, d))
+        _dev(v_blank, "v_blank", q.dtype, (H, d))
+        g["dk_blank"] = torch.empty((H, d), dtype=torch.float32, device=q.device)
+        g["dv_blank"] = torch.empty((H, d), dtype=torch.float32, device=q.device)
+    need = lib.affmae_pla_bwd_relpos_workspace_bytes(B, N, H, d, K, S, M, R, code, int(near_clusters is not None))
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    rc = lib.affmae_pla_bwd_relpos(_ptr(q), _ptr(k), _ptr(v), _ptr(coords), _ptr(rel_table), _ptr(nbr_idx),
+                                   _ptr(near_clusters), _ptr(plan), _ptr(k_blank), _ptr(v_blank), _ptr(out), _ptr(lse),
+                                   _ptr(dout), B, N, H, d, K, S, M, float(scale), R, float(rate), code, _ptr(g["dq"]),
+                                   _ptr(g["dk"]), _ptr(g["dv"]), _ptr(g["drel_table"]), _ptr(g.get("dk_blank")),
+                                   _ptr(g.get("dv_blank")), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_pla_bwd_relpos", rc)
     return g
 
 

@@ -23,6 +23,7 @@ COMMON = ["--offload-arch=" + ARCH, "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno
 EXTRA = {
     "knn.hip": ["-ffp-contract=off"],  # distances must not be fused
     "vts.hip": ["-ffp-contract=off"],  # likewise (grid points and table distances)
+    "relpos.hip": ["-ffp-contract=off"],  # likewise (offset times bin rate)
 }
 
 

@@ -311,4 +311,88 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
   return affmae::launch_pla_bwd_general(a, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
 }
 
+namespace {
+// limits of the relative-position table: the gradient kernel keeps H tables in LDS
+int check_relpos(const float* coords, const void* table, int H, int R, float rate) {
+  if (!coords || !table) return AFFMAE_ERR_NULL;
+  if (R < 0 || !(rate > 0.f) || !(rate < 3e38f)) return AFFMAE_ERR_SHAPE;
+  if (R > 31 || (long long)H * (2 * R + 1) * (2 * R + 1) > 12288) return AFFMAE_ERR_UNSUPPORTED;
+  if (misaligned(coords, 8)) return AFFMAE_ERR_SHAPE;
+  return AFFMAE_OK;
+}
+size_t bias_bytes(int B, int N, int H, int K, int dtype) {
+  return align_up((size_t)B * N * H * K * (dtype == AFFMAE_BF16 ? 2 : 4));
+}
+}  // namespace
+
+size_t affmae_pla_fwd_relpos_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
+                                             int clustered) {
+  if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
+  return bias_bytes(B, N, H, K, dtype) + align_up(affmae_pla_fwd_workspace_bytes(B, N, H, d, K, S, M, dtype, clustered));
+}
+
+int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const float* coords, const void* rel_table,
+                          const int32_t* nbr_idx, const int32_t* near_clusters, const void* plan,
+                          const void* k_blank, const void* v_blank, int B, int N, int H, int d, int K, int S, int M,
+                          float scale, int R, float rate, int dtype, void* out, float* lse, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !nbr_idx || !out || !lse) return AFFMAE_ERR_NULL;
+  int rc = check_pla_shape(B, N, H, d, K, dtype);
+  if (rc != AFFMAE_OK) return rc;
+  rc = check_relpos(coords, rel_table, H, R, rate);
+  if (rc != AFFMAE_OK) return rc;
+  const size_t bb = bias_bytes(B, N, H, K, dtype);
+  if (!workspace || workspace_bytes < affmae_pla_fwd_relpos_workspace_bytes(B, N, H, d, K, S, M, dtype,
+                                                                             near_clusters != nullptr) ||
+      misaligned(workspace, kAlign))
+    return AFFMAE_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(workspace);
+  const affmae::RelposArgs r = {coords, nbr_idx, rel_table, R, rate};
+  if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, ws, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return AFFMAE_ERR_DEVICE;
+  return affmae_pla_fwd(q, k, v, ws, nbr_idx, near_clusters, plan, k_blank, v_blank, B, N, H, d, K, S, M, scale, dtype,
+                        out, lse, ws + bb, workspace_bytes - bb, stream);
+}
+
+size_t affmae_pla_bwd_relpos_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int R, int dtype,
+                                             int clustered) {
+  if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK || R < 0 || R > 31) return 0;
+  return 2 * bias_bytes(B, N, H, K, dtype) + align_up(affmae::relpos_dtable_workspace_bytes(B, N, H, K, R)) +
+         align_up(affmae_pla_bwd_workspace_bytes(B, N, H, d, K, S, M, dtype, clustered));
+}
+
+int affmae_pla_bwd_relpos(const void* q, const void* k, const void* v, const float* coords, const void* rel_table,
+                          const int32_t* nbr_idx, const int32_t* near_clusters, const void* plan,
+                          const void* k_blank, const void* v_blank, const void* out, const float* lse,
+                          const void* dout, int B, int N, int H, int d, int K, int S, int M, float scale, int R,
+                          float rate, int dtype, void* dq, void* dk, void* dv, float* drel_table, float* dk_blank,
+                          float* dv_blank, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !nbr_idx || !lse || !dout || !dq || !dk || !dv || !drel_table) return AFFMAE_ERR_NULL;
+  int rc = check_pla_shape(B, N, H, d, K, dtype);
+  if (rc != AFFMAE_OK) return rc;
+  rc = check_relpos(coords, rel_table, H, R, rate);
+  if (rc != AFFMAE_OK) return rc;
+  const size_t bb = bias_bytes(B, N, H, K, dtype);
+  const size_t tb = align_up(affmae::relpos_dtable_workspace_bytes(B, N, H, K, R));
+  if (!workspace || workspace_bytes < affmae_pla_bwd_relpos_workspace_bytes(B, N, H, d, K, S, M, R, dtype,
+                                                                             near_clusters != nullptr) ||
+      misaligned(workspace, kAlign))
+    return AFFMAE_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(workspace);
+  void* bias = ws;
+  void* dbias = ws + bb;
+  void* parts = ws + 2 * bb;
+  char* inner = ws + 2 * bb + tb;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const affmae::RelposArgs r = {coords, nbr_idx, rel_table, R, rate};
+  if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, bias, st) != hipSuccess) return AFFMAE_ERR_DEVICE;
+  rc = affmae_pla_bwd(q, k, v, bias, nbr_idx, near_clusters, plan, k_blank, v_blank, out, lse, dout, B, N, H, d, K, S,
+                      M, scale, dtype, dq, dk, dv, dbias, dk_blank, dv_blank, inner, workspace_bytes - (2 * bb + tb),
+                      stream);
+  if (rc != AFFMAE_OK) return rc;
+  return affmae::launch_relpos_dtable(r, B, N, H, K, dtype, dbias, drel_table, parts, st) == hipSuccess
+             ? AFFMAE_OK
+             : AFFMAE_ERR_DEVICE;
+}
+
 }  // extern "C"

@@ -47,6 +47,20 @@ hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream);
 size_t vts_bwd_workspace_bytes(int B, int Mq, int Nv, int Kt);
 hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream);
 
+// Relative-position bias from a per-head table over quantised offsets (relpos.hip).
+struct RelposArgs {
+  const float* coords;     // [B,N,2]
+  const int32_t* nbr_idx;  // [B,N,K]
+  const void* table;       // [H, 2R+1, 2R+1] in the storage type
+  int R;
+  float rate;              // bins per unit of length
+};
+hipError_t launch_relpos_bias(const RelposArgs& r, int B, int N, int H, int K, int dtype, void* bias,
+                              hipStream_t stream);
+size_t relpos_dtable_workspace_bytes(int B, int N, int H, int K, int R);
+hipError_t launch_relpos_dtable(const RelposArgs& r, int B, int N, int H, int K, int dtype, const void* dbias,
+                                float* dtable, void* workspace, hipStream_t stream);
+
 struct PlaArgs {
   const void *q, *k, *v, *bias;
   const int32_t* nbr_idx;

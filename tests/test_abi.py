@@ -134,3 +134,22 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         aff.affmae_knn(torch.zeros(1, 64, 2), None, 8, 2, 4)
+
+
+def test_relpos_rejects_bad_arguments_on_host():
+    lib = aff.load_library()
+    one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    f = ctypes.c_float
+
+    def fwd(coords=one, table=one, R=2, rate=0.125, ws=one, ws_bytes=1 << 30, H=2):
+        return lib.affmae_pla_fwd_relpos(one, one, one, coords, table, one, None, None, None, None, 1, 64, H, 32, 8, 0, 0,
+                                         f(0.2), R, f(rate), 0, one, one, ws, ws_bytes, None)
+
+    assert fwd(coords=None) == -1 and fwd(table=None) == -1
+    assert fwd(R=-1) == -2 and fwd(rate=0.0) == -2 and fwd(rate=float("inf")) == -2
+    assert fwd(R=32) == -5 and fwd(R=31, H=8) == -5          # beyond the table limits
+    assert fwd(ws=None) == -4 and fwd(ws_bytes=16) == -4
+    assert fwd(coords=ctypes.c_void_p(260)) == -2             # coordinates are read as 8-byte pairs
+    assert lib.affmae_pla_fwd_relpos_workspace_bytes(1, 64, 2, 32, 8, 0, 0, 0, 0) >= 64 * 2 * 8 * 4
+    assert lib.affmae_pla_bwd_relpos_workspace_bytes(1, 64, 2, 32, 8, 0, 0, 2, 0, 0) >= 2 * 64 * 2 * 8 * 4
+    assert lib.affmae_pla_bwd_relpos_workspace_bytes(1, 64, 2, 32, 8, 0, 0, 32, 0, 0) == 0
