@@ -80,6 +80,38 @@ def bench_virtual_tokens(aff, torch, np, dev, reps: int = 20):
             "fwd_algorithmic_GBs": fwd_bytes / (t[1] * 1e-3) / 1e9, "bwd_algorithmic_GBs": bwd_bytes / (t[2] * 1e-3) / 1e9}
 
 
+def bench_relpos(aff, torch, np, cfg, s, scale, promise, reps: int = 20):
+    """The same attention with the bias taken from a relative-position table (9 x 9 bins of one 8-px patch per
+    head) instead of a bias tensor: forward and backward through affmae_pla_*_relpos on the workload's first
+    tensor set.  Times are HIP-event means; the bias is written out by one kernel and the table's gradient
+    reduced by two more around the same attention kernels."""
+    dev = s["q"].device
+    R, rate = 4, 1.0 / 8.0
+    table = (0.1 * torch.randn((cfg.H, 2 * R + 1, 2 * R + 1), device=dev)).to(s["q"].dtype)
+    lib = aff.load_library()
+    code = 1 if cfg.dtype == "bf16" else 0
+    near = s["near"] if promise else None
+    ws = torch.empty(max(lib.affmae_pla_fwd_relpos_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
+                         lib.affmae_pla_bwd_relpos_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, R, code, int(promise))),
+                     dtype=torch.uint8, device=dev)
+    t = [0.0, 0.0]
+    for it in range(reps + 2):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        out, lse = aff.affmae_pla_fwd_relpos(s["q"], s["k"], s["v"], s["coords"], table, s["nbr"], scale, rate, near,
+                                             cfg.S, cfg.M, out=s["out"], lse=s["lse"], workspace=ws, plan=s["plan"])
+        e[1].record()
+        aff.affmae_pla_bwd_relpos(s["q"], s["k"], s["v"], s["coords"], table, s["nbr"], out, lse, s["dout"], scale, rate,
+                                  near, cfg.S, cfg.M, workspace=ws, plan=s["plan"])
+        e[2].record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            t[0] += e[0].elapsed_time(e[1]) / reps
+            t[1] += e[1].elapsed_time(e[2]) / reps
+    return {"table": f"{cfg.H} x {2 * R + 1} x {2 * R + 1}, bins of 8 px", "fwd_ms": t[0], "bwd_ms": t[1],
+            "tokens_per_s_fwd_bwd": cfg.B * cfg.N / ((t[0] + t[1]) * 1e-3)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -269,6 +301,7 @@ def main() -> int:
         "rooflines_all_kernels": rooflines,
     }
 
+    result["relative_position_bias"] = bench_relpos(aff, torch, np, cfg, sets[0], scale, promise)
     result["virtual_tokens"] = bench_virtual_tokens(aff, torch, np, dev)
 
     if not args.no_cpu_baseline:

@@ -313,8 +313,9 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
 
 namespace {
 // limits of the relative-position table: the gradient kernel keeps H tables in LDS
-int check_relpos(const float* coords, const void* table, int H, int R, float rate) {
+int check_relpos(const float* coords, const void* table, int B, int N, int H, int K, int R, float rate) {
   if (!coords || !table) return AFFMAE_ERR_NULL;
+  if ((long long)B * N * K > (1ll << 31) - 8) return AFFMAE_ERR_UNSUPPORTED;  // pairs are indexed with int32
   if (R < 0 || !(rate > 0.f) || !(rate < 3e38f)) return AFFMAE_ERR_SHAPE;
   if (R > 31 || (long long)H * (2 * R + 1) * (2 * R + 1) > 12288) return AFFMAE_ERR_UNSUPPORTED;
   if (misaligned(coords, 8)) return AFFMAE_ERR_SHAPE;
@@ -339,7 +340,7 @@ int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const flo
   if (!q || !k || !v || !nbr_idx || !out || !lse) return AFFMAE_ERR_NULL;
   int rc = check_pla_shape(B, N, H, d, K, dtype);
   if (rc != AFFMAE_OK) return rc;
-  rc = check_relpos(coords, rel_table, H, R, rate);
+  rc = check_relpos(coords, rel_table, B, N, H, K, R, rate);
   if (rc != AFFMAE_OK) return rc;
   const size_t bb = bias_bytes(B, N, H, K, dtype);
   if (!workspace || workspace_bytes < affmae_pla_fwd_relpos_workspace_bytes(B, N, H, d, K, S, M, dtype,
@@ -370,7 +371,7 @@ int affmae_pla_bwd_relpos(const void* q, const void* k, const void* v, const flo
   if (!q || !k || !v || !nbr_idx || !lse || !dout || !dq || !dk || !dv || !drel_table) return AFFMAE_ERR_NULL;
   int rc = check_pla_shape(B, N, H, d, K, dtype);
   if (rc != AFFMAE_OK) return rc;
-  rc = check_relpos(coords, rel_table, H, R, rate);
+  rc = check_relpos(coords, rel_table, B, N, H, K, R, rate);
   if (rc != AFFMAE_OK) return rc;
   const size_t bb = bias_bytes(B, N, H, K, dtype);
   const size_t tb = align_up(affmae::relpos_dtable_workspace_bytes(B, N, H, K, R));
