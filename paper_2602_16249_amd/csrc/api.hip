@@ -348,9 +348,30 @@ int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const flo
       misaligned(workspace, kAlign))
     return AFFMAE_ERR_WORKSPACE;
   char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (near_clusters && S >= 1 && M >= 1 && N % S == 0 && M <= N / S) {
+    // the tiled kernel looks the bias up itself: no bias tensor
+    affmae::PlaArgs a = {};
+    a.q = q; a.k = k; a.v = v; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
+    a.k_blank = k_blank; a.v_blank = v_blank;
+    a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
+    a.out = out; a.lse = lse;
+    a.rel_coords = coords; a.rel_table = rel_table; a.rel_R = R; a.rel_rate = rate;
+    if (affmae::pla_cluster_relpos_supported(a)) {
+      if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
+      if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
+      if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
+      if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
+      if (!plan) {  // the workspace holds at least a plan (checked above)
+        if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, ws, st) != hipSuccess)
+          return AFFMAE_ERR_DEVICE;
+        plan = ws;
+      }
+      return affmae::launch_pla_fwd_cluster(a, plan, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+    }
+  }
   const affmae::RelposArgs r = {coords, nbr_idx, rel_table, R, rate};
-  if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, ws, static_cast<hipStream_t>(stream)) != hipSuccess)
-    return AFFMAE_ERR_DEVICE;
+  if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, ws, st) != hipSuccess) return AFFMAE_ERR_DEVICE;
   return affmae_pla_fwd(q, k, v, ws, nbr_idx, near_clusters, plan, k_blank, v_blank, B, N, H, d, K, S, M, scale, dtype,
                         out, lse, ws + bb, workspace_bytes - bb, stream);
 }

@@ -79,4 +79,17 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
+// Bin of a relative-position table along one axis (paper, Sec. "AutoFocusFormer": relative position from the 2-D
+// token coordinates): clamp(rint((nbr - query) * rate), -R, R) + R, in fp32 one operation at a time, ties to
+// even.  Every kernel that needs a bin calls this, so that all of them take the same integer decision.
+__device__ __forceinline__ int relpos_bin(float nbr, float query, float rate, int R) {
+#pragma clang fp contract(off)
+  const float d = nbr - query;
+  const float t = d * rate;
+  const float r = __builtin_rintf(t);
+  if (!(r >= (float)(-R))) return 0;  // also NaN
+  if (r > (float)R) return 2 * R;
+  return (int)r + R;
+}
+
 }  // namespace affmae

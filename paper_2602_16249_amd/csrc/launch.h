@@ -69,6 +69,11 @@ struct PlaArgs {
   int B, N, H, d, K, S, M;
   float scale;
   int dtype;
+  // bias from a relative-position table instead of `bias` (tiled kernels only; null otherwise)
+  const float* rel_coords;  // [B,N,2]
+  const void* rel_table;    // [H, 2R+1, 2R+1] in the storage type
+  int rel_R;
+  float rel_rate;
   // forward outputs / backward inputs
   void* out;
   float* lse;
@@ -84,6 +89,7 @@ size_t pla_bwd_general_workspace_bytes(int B, int N, int H, int d, int dtype);
 
 // Cluster-tiled kernels (bf16, d = 32, cluster promise given), driven by a plan.
 bool pla_cluster_supported(const PlaArgs& a);
+bool pla_cluster_relpos_supported(const PlaArgs& a);  // ... and able to take the bias from a.rel_table themselves
 size_t pla_plan_bytes(int B, int N, int K, int S, int M);
 hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, int N, int K, int S, int M, void* plan,
                            hipStream_t stream);

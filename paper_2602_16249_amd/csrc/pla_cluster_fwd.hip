@@ -14,10 +14,10 @@
 // layout of the P.V MFMAs.  A query attends only to its K neighbours: their bias
 // values are scattered into a per-wave LDS tile that holds -inf everywhere else
 // and is added to the scores.  Rows are loaded 64 contiguous bytes per quad and
-// cross a per-wave LDS tile into the operand layout (see below); the V rows are
-// then turned into the transposed operand P.V needs by an MFMA against an
-// identity matrix (exact in bf16).  No workgroup barrier anywhere; overlapping
-// neighbourhoods share rows through L2.
+// cross a per-wave LDS tile into the operand layout (see below); the transposed
+// V operand that P.V needs is read from the same tile with the transposing LDS
+// read.  No workgroup barrier anywhere; overlapping neighbourhoods share rows
+// through L2.
 #include "cluster_common.h"
 #include "launch.h"
 #include "timing.h"
@@ -36,6 +36,11 @@ struct FwdParams {
   int N, H, K, strips, strips_per_image, slot_stride;
   uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
   float scale;
+  // bias from a relative-position table (REL kernels): token coordinates [B,N,2], table [H][2R+1][2R+1]
+  const float* coords;
+  const bf16_t* rel_table;
+  int R;
+  float rate;
   bf16_t* out;
   float* lse;
 };
@@ -48,8 +53,13 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
 // [token, head, :] hold the matching K values.  With K a multiple of 8 a lane owns NT chunks of 8
 // consecutive slots of one query (16-byte loads of entries and of bias); otherwise NT single entries.
 constexpr int kFwdWaves = 4;  // waves per workgroup; they share nothing but the launch
-template <int NT, bool VEC>
+// REL: the bias of a (query, neighbour) pair is looked up in the head's relative-position table instead of being
+// read from a tensor.  The coordinates of the pass's token tiles are staged once in the wave's K/V tile (free
+// until the first pair is staged); a lane then reads the neighbour's coordinates by the entry's (slot, token)
+// fields, takes the bin against its query's coordinates and fetches the table value through the vector cache.
+template <int NT, bool VEC, bool REL>
 __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
+  static_assert(!REL || VEC, "the table form is built for 16-byte items");
   __shared__ __align__(16) bf16_t scratch_all[kFwdWaves][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) u32x4 kv_all[kFwdWaves][4 * 64];  // K and V rows of one pair of token tiles, per wave
   const int lane = threadIdx.x & (kWave - 1);
@@ -95,7 +105,13 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
         const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
         uint4 bv = make_uint4(0, 0, 0, 0);
-        if (bias_head) bv = *reinterpret_cast<const uint4*>(bias_head + (uint32_t)(qi * p.H * K + j0));
+        if (REL) {  // the query's coordinates instead
+          const float2 c = (reinterpret_cast<const float2*>(p.coords) + tok0)[qi];
+          bv.x = __float_as_uint(c.x);
+          bv.y = __float_as_uint(c.y);
+        } else if (bias_head) {
+          bv = *reinterpret_cast<const uint4*>(bias_head + (uint32_t)(qi * p.H * K + j0));
+        }
         bw[t][0] = bv.x;
         bw[t][EW > 1 ? 1 : 0] = bv.y;
         bw[t][EW > 2 ? 2 : 0] = bv.z;
@@ -147,16 +163,35 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       // (an odd pass gets one more tile of -inf: the second half of its last pair, which repeats a tile)
       for (int s = 0; s < nsl + (nsl & 1); ++s)
         *reinterpret_cast<uint2*>(scratch + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
+      const float2* cxy = reinterpret_cast<const float2*>(kv);  // REL: [slot of the pass][token of the tile]
+      if (REL) {
+        const float2* cimg = reinterpret_cast<const float2*>(p.coords) + img_base;
+#pragma unroll
+        for (int i = 0; i < (kSlotCap * 16 + kWave - 1) / kWave; ++i) {
+          const int tile = __shfl(my_tile, slot0 + min(4 * i + g, nsl - 1));
+          reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)(tile * 16 + r)];
+        }
+      }
       wave_lds_sync();
       const uint32_t lo = (uint32_t)slot0 * 256u, span = (uint32_t)nsl * 256u;
+      const int RW = 2 * p.R + 1;
+      const bf16_t* tab = REL ? p.rel_table + h * RW * RW : nullptr;
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
 #pragma unroll
         for (int e = 0; e < (VEC ? 8 : 1); ++e) {
           // entries of other passes, kNoEntry and dead items fall outside [0, span): they go to the spare cell
           const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
-          const uint32_t bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
           const uint32_t rel = off - lo;
+          uint32_t bits;
+          if (REL) {
+            const float2 cn = cxy[rel < span ? ((rel >> 8) << 4) | (rel & 15u) : 0u];
+            const int cell = relpos_bin(cn.y, __uint_as_float(bw[t][EW > 1 ? 1 : 0]), p.rate, p.R) * RW +
+                             relpos_bin(cn.x, __uint_as_float(bw[t][0]), p.rate, p.R);
+            bits = tab[cell];
+          } else {
+            bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
+          }
           scratch[rel < span ? rel : (uint32_t)kSlotCap * 256u] = (bf16_t)bits;
         }
       }
@@ -305,14 +340,24 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
 // per-lane state and is built for two.
 template <int NT>
 __global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
-  pla_fwd_cluster_body<NT, true>(p);
+  pla_fwd_cluster_body<NT, true, false>(p);
+}
+template <int NT>
+__global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_rel_kernel(FwdParams p) {
+  pla_fwd_cluster_body<NT, true, true>(p);
 }
 template <int NT>
 __global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_fwd_cluster_scalar_kernel(FwdParams p) {
-  pla_fwd_cluster_body<NT, false>(p);
+  pla_fwd_cluster_body<NT, false, false>(p);
 }
 
 }  // namespace
+
+bool pla_cluster_relpos_supported(const PlaArgs& a) {
+  // the table form of the tiled kernels: 16-byte items, 8-byte coordinate pairs
+  return pla_cluster_supported(a) && a.K % 8 == 0 && a.rel_coords && a.rel_table &&
+         reinterpret_cast<uintptr_t>(a.rel_coords) % 8 == 0;
+}
 
 bool pla_cluster_supported(const PlaArgs& a) {
   if (!a.near_clusters || a.dtype != 1 || a.d != kD) return false;
@@ -336,6 +381,7 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride;
   p.scale = a.scale;
   p.out = (bf16_t*)a.out; p.lse = a.lse;
+  p.coords = a.rel_coords; p.rel_table = (const bf16_t*)a.rel_table; p.R = a.rel_R; p.rate = a.rel_rate;
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
@@ -343,7 +389,9 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);
 #define AFFMAE_FWD(KERNEL, NT) \
   AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT>), grid, dim3(kFwdWaves * kWave), 0, stream, p)
-  if (vec) {
+  if (a.rel_table) {  // callers check pla_cluster_relpos_supported first
+    if (2 * a.K <= kWave) AFFMAE_FWD(pla_fwd_cluster_rel_kernel, 1); else AFFMAE_FWD(pla_fwd_cluster_rel_kernel, 2);
+  } else if (vec) {
     if (2 * a.K <= kWave) AFFMAE_FWD(pla_fwd_cluster_kernel, 1); else AFFMAE_FWD(pla_fwd_cluster_kernel, 2);
   } else {
     const int ent = (16 * a.K + kWave - 1) / kWave;

@@ -15,17 +15,6 @@
 namespace affmae {
 namespace {
 
-// the same arithmetic everywhere: fp32 offset, fp32 product, round to nearest even, clamp
-__device__ __forceinline__ int relpos_bin(float nbr, float query, float rate, int R) {
-#pragma clang fp contract(off)
-  const float d = nbr - query;
-  const float t = d * rate;
-  const float r = __builtin_rintf(t);
-  if (!(r >= (float)(-R))) return 0;  // also NaN
-  if (r > (float)R) return 2 * R;
-  return (int)r + R;
-}
-
 // one thread per (token, neighbour): the bin once, then one value per head
 template <typename T>
 __global__ __launch_bounds__(256) void relpos_bias_kernel(const float* __restrict__ coords,
