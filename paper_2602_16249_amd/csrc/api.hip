@@ -324,11 +324,16 @@ int check_relpos(const float* coords, const void* table, int B, int N, int H, in
 size_t bias_bytes(int B, int N, int H, int K, int dtype) {
   return align_up((size_t)B * N * H * K * (dtype == AFFMAE_BF16 ? 2 : 4));
 }
+// Shapes for which the tiled kernels look the bias up themselves (the coordinates' alignment is checked apart).
+bool relpos_in_kernel(int B, int N, int d, int K, int S, int M, int dtype, int clustered) {
+  return clustered && dtype == AFFMAE_BF16 && d == 32 && K % 8 == 0 && tiled_shape_ok(B, N, K, S, M);
+}
 }  // namespace
 
 size_t affmae_pla_fwd_relpos_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
                                              int clustered) {
   if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
+  if (relpos_in_kernel(B, N, d, K, S, M, dtype, clustered)) return align_up(affmae::pla_plan_bytes(B, N, K, S, M));
   return bias_bytes(B, N, H, K, dtype) + align_up(affmae_pla_fwd_workspace_bytes(B, N, H, d, K, S, M, dtype, clustered));
 }
 
@@ -349,26 +354,26 @@ int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const flo
     return AFFMAE_ERR_WORKSPACE;
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (near_clusters && S >= 1 && M >= 1 && N % S == 0 && M <= N / S) {
+  if (relpos_in_kernel(B, N, d, K, S, M, dtype, near_clusters != nullptr)) {
     // the tiled kernel looks the bias up itself: no bias tensor
+    if (M > N / S) return AFFMAE_ERR_SHAPE;
     affmae::PlaArgs a = {};
     a.q = q; a.k = k; a.v = v; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
     a.k_blank = k_blank; a.v_blank = v_blank;
     a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
     a.out = out; a.lse = lse;
     a.rel_coords = coords; a.rel_table = rel_table; a.rel_R = R; a.rel_rate = rate;
-    if (affmae::pla_cluster_relpos_supported(a)) {
-      if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
-      if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
-      if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
-      if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
-      if (!plan) {  // the workspace holds at least a plan (checked above)
-        if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, ws, st) != hipSuccess)
-          return AFFMAE_ERR_DEVICE;
-        plan = ws;
-      }
-      return affmae::launch_pla_fwd_cluster(a, plan, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+    if (!affmae::pla_cluster_relpos_supported(a)) return AFFMAE_ERR_UNSUPPORTED;  // (the workspace is sized for this path)
+    if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
+    if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
+    if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
+    if (!plan) {  // the workspace holds at least a plan (checked above)
+      if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, ws, st) != hipSuccess)
+        return AFFMAE_ERR_DEVICE;
+      plan = ws;
     }
+    return affmae::launch_pla_fwd_cluster(a, plan, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
   }
   const affmae::RelposArgs r = {coords, nbr_idx, rel_table, R, rate};
   if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, ws, st) != hipSuccess) return AFFMAE_ERR_DEVICE;
@@ -379,6 +384,13 @@ int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const flo
 size_t affmae_pla_bwd_relpos_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int R, int dtype,
                                              int clustered) {
   if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK || R < 0 || R > 31) return 0;
+  if (relpos_in_kernel(B, N, d, K, S, M, dtype, clustered)) {
+    const size_t table = affmae::pla_bwd_cluster_rel_sums(R)
+                             ? align_up(affmae::pla_bwd_cluster_rel_workspace_bytes(B, N, H, R))
+                             : bias_bytes(B, N, H, K, dtype) + align_up(affmae::relpos_dtable_workspace_bytes(B, N, H, K, R));
+    return table + align_up(affmae::pla_plan_bytes(B, N, K, S, M)) +
+           align_up(affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, S, M));
+  }
   return 2 * bias_bytes(B, N, H, K, dtype) + align_up(affmae::relpos_dtable_workspace_bytes(B, N, H, K, R)) +
          align_up(affmae_pla_bwd_workspace_bytes(B, N, H, d, K, S, M, dtype, clustered));
 }
@@ -401,12 +413,55 @@ int affmae_pla_bwd_relpos(const void* q, const void* k, const void* v, const flo
       misaligned(workspace, kAlign))
     return AFFMAE_ERR_WORKSPACE;
   char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const affmae::RelposArgs r = {coords, nbr_idx, rel_table, R, rate};
+  if (relpos_in_kernel(B, N, d, K, S, M, dtype, near_clusters != nullptr)) {
+    // the tiled kernels look the bias up themselves; the table's gradient is summed in the query-stationary
+    // kernel when the table fits its LDS, else dbias goes through the workspace to the stand-alone kernel
+    if (!out) return AFFMAE_ERR_NULL;
+    if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
+    if ((dk_blank == nullptr) != (dv_blank == nullptr)) return AFFMAE_ERR_NULL;
+    if (M > N / S) return AFFMAE_ERR_SHAPE;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(dout, 16) || misaligned(dq, 16) ||
+        misaligned(dk, 16) || misaligned(dv, 16) || misaligned(out, 16))
+      return AFFMAE_ERR_SHAPE;
+    if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
+    if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
+    affmae::PlaArgs a = {};
+    a.q = q; a.k = k; a.v = v; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
+    a.k_blank = k_blank; a.v_blank = v_blank;
+    a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
+    a.out = const_cast<void*>(out); a.lse = const_cast<float*>(lse); a.dout = dout;
+    a.dq = dq; a.dk = dk; a.dv = dv; a.dk_blank = dk_blank; a.dv_blank = dv_blank;
+    a.rel_coords = coords; a.rel_table = rel_table; a.rel_R = R; a.rel_rate = rate;
+    if (!affmae::pla_cluster_relpos_supported(a)) return AFFMAE_ERR_UNSUPPORTED;  // (the workspace is sized for this path)
+    const bool sums = affmae::pla_bwd_cluster_rel_sums(R);
+    size_t off = 0;
+    void* parts = nullptr;
+    if (sums) {
+      a.rel_part = reinterpret_cast<float*>(ws);
+      a.rel_dtable = drel_table;
+      off += align_up(affmae::pla_bwd_cluster_rel_workspace_bytes(B, N, H, R));
+    } else {
+      a.dbias = ws;
+      parts = ws + bb;
+      off += bb + tb;
+    }
+    if (!plan) {
+      if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, ws + off, st) != hipSuccess)
+        return AFFMAE_ERR_DEVICE;
+      plan = ws + off;
+    }
+    off += align_up(affmae::pla_plan_bytes(B, N, K, S, M));
+    if (affmae::launch_pla_bwd_cluster(a, plan, ws + off, st) != hipSuccess) return AFFMAE_ERR_DEVICE;
+    if (!sums && affmae::launch_relpos_dtable(r, B, N, H, K, dtype, a.dbias, drel_table, parts, st) != hipSuccess)
+      return AFFMAE_ERR_DEVICE;
+    return AFFMAE_OK;
+  }
   void* bias = ws;
   void* dbias = ws + bb;
   void* parts = ws + 2 * bb;
   char* inner = ws + 2 * bb + tb;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const affmae::RelposArgs r = {coords, nbr_idx, rel_table, R, rate};
   if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, bias, st) != hipSuccess) return AFFMAE_ERR_DEVICE;
   rc = affmae_pla_bwd(q, k, v, bias, nbr_idx, near_clusters, plan, k_blank, v_blank, out, lse, dout, B, N, H, d, K, S,
                       M, scale, dtype, dq, dk, dv, dbias, dk_blank, dv_blank, inner, workspace_bytes - (2 * bb + tb),

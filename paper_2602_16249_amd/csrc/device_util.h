@@ -79,17 +79,22 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
-// Bin of a relative-position table along one axis (paper, Sec. "AutoFocusFormer": relative position from the 2-D
-// token coordinates): clamp(rint((nbr - query) * rate), -R, R) + R, in fp32 one operation at a time, ties to
-// even.  Every kernel that needs a bin calls this, so that all of them take the same integer decision.
-__device__ __forceinline__ int relpos_bin(float nbr, float query, float rate, int R) {
+// Cell of a relative-position table (paper, Sec. "AutoFocusFormer": relative position from the 2-D token
+// coordinates): along each axis clamp(rint((nbr - query) * rate), -R, R), in fp32 one operation at a time, ties
+// to even; cell = (by + R) * (2R + 1) + bx + R.  Every kernel that needs a cell calls this, so that all of them
+// take the same integer decision.  The clamped offsets are small integers held in fp32, so combining them with
+// one fused multiply-add is exact; a NaN offset lands on -R (the median instruction returns the minimum then).
+__device__ __forceinline__ float relpos_axis(float nbr, float query, float rate, float Rf) {
 #pragma clang fp contract(off)
   const float d = nbr - query;
   const float t = d * rate;
-  const float r = __builtin_rintf(t);
-  if (!(r >= (float)(-R))) return 0;  // also NaN
-  if (r > (float)R) return 2 * R;
-  return (int)r + R;
+  return __builtin_amdgcn_fmed3f(__builtin_rintf(t), -Rf, Rf);
+}
+__device__ __forceinline__ int relpos_cell(float2 nbr, float2 query, float rate, int R) {
+  const float Rf = (float)R;
+  const float c = __builtin_fmaf(relpos_axis(nbr.y, query.y, rate, Rf), (float)(2 * R + 1),
+                                 relpos_axis(nbr.x, query.x, rate, Rf));
+  return (int)c + (R * (2 * R + 1) + R);
 }
 
 }  // namespace affmae

@@ -60,6 +60,8 @@ hipError_t launch_relpos_bias(const RelposArgs& r, int B, int N, int H, int K, i
 size_t relpos_dtable_workspace_bytes(int B, int N, int H, int K, int R);
 hipError_t launch_relpos_dtable(const RelposArgs& r, int B, int N, int H, int K, int dtype, const void* dbias,
                                 float* dtable, void* workspace, hipStream_t stream);
+// dtable[i] = sum over t < tables of part[t][i], i < entries
+hipError_t launch_relpos_table_sum(const float* part, int tables, int entries, float* dtable, hipStream_t stream);
 
 struct PlaArgs {
   const void *q, *k, *v, *bias;
@@ -74,6 +76,8 @@ struct PlaArgs {
   const void* rel_table;    // [H, 2R+1, 2R+1] in the storage type
   int rel_R;
   float rel_rate;
+  float* rel_part;    // backward: workspace of pla_bwd_cluster_rel_workspace_bytes, or null (then dbias is written)
+  float* rel_dtable;  // backward, with rel_part: [H, 2R+1, 2R+1] gradient of the table
   // forward outputs / backward inputs
   void* out;
   float* lse;
@@ -95,6 +99,8 @@ hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, i
                            hipStream_t stream);
 hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_t stream);
 size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, int S, int M);
+bool pla_bwd_cluster_rel_sums(int R);  // the table is small enough for the backward kernel to sum its gradient itself
+size_t pla_bwd_cluster_rel_workspace_bytes(int B, int N, int H, int R);
 hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* workspace, hipStream_t stream);
 
 }  // namespace affmae

@@ -45,7 +45,15 @@ struct BwdParams {
                  // p in the low half, dS in the high half (bf16 bits)
   const bf16_t *k_blank, *v_blank;  // [H,32] or nullptr
   float* blank_part;                // workspace [strips][H][2][32]: the strip's parts of dk_blank, dv_blank; or nullptr
+  // bias from a relative-position table (REL kernels): token coordinates [B,N,2], table [H][2R+1][2R+1]
+  const float* coords;
+  const bf16_t* rel_table;
+  int R;
+  float rate;
+  float* rel_part;  // workspace [strips][H][(2R+1)^2]: every wave's sums of dS per bin (needs (2R+1)^2 <= kRelCells),
+                    // or nullptr: then dS goes out through `ds` for the stand-alone table-gradient kernel
 };
+constexpr int kRelCells = 128;  // bins of a wave's fp64 table: the third KB of its row tile, idle after the prologue
 
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
@@ -64,8 +72,14 @@ __device__ __forceinline__ int xcd_contiguous_block() {
 // ------------------------------------------------------------------------------------------------
 // query-stationary kernel
 // Items per lane as in the forward kernel: NT chunks of 8 slots (K % 8 == 0) or NT single entries.
-template <int NT, bool VEC>
+// REL: the bias comes from the head's relative-position table as in the forward kernel (tile coordinates staged
+// in the wave's row tile, bin per pair, value through the vector cache), and the table's gradient is summed per
+// wave: each pair's dS is added to its bin in an fp64 table in LDS (ds_add_f64 runs at the speed of an integer
+// LDS atomic on this chip; the fp32 form is several times slower) and the wave writes its table out at the end.
+template <int NT, bool VEC, bool REL, bool SUMS>
 __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
+  static_assert(!SUMS || REL, "the table's gradient belongs to the table form");
+  static_assert(!REL || VEC, "the table form is built for 16-byte items");
   __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
   __shared__ __align__(16) u32x4 kv_all[4][3 * 64];  // per wave: rows of two token tiles (K, then V), or the strip's q, dout, out
@@ -154,6 +168,17 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       of.x4 = kv[2 * 64 + rd_chunk];
       wave_lds_sync();
     }
+    double* tabw = reinterpret_cast<double*>(kv + 2 * 64);  // REL: [bin] sums of dS, this wave's
+    constexpr bool rel_sum = SUMS;  // else dS goes out through p.ds (the table does not fit)
+    if (rel_sum) kv[2 * 64 + lane] = u32x4{0u, 0u, 0u, 0u};
+    uint32_t cells[SUMS ? NT : 1][SUMS ? 2 : 1];  // bins of this lane's pairs (< kRelCells <= 256), four per word
+    if (SUMS) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) cells[t][e] = 0u;
+    }
+    const int RW = 2 * p.R + 1;
     float Dq = 0.f;  // D of query r
 #pragma unroll
     for (int i = 0; i < 8; ++i) Dq = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(of.h[i]), Dq);
@@ -220,7 +245,14 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         for (int t = 0; t < NT; ++t) {
           if (VEC) {
             uint4 w = make_uint4(0, 0, 0, 0);
-            if (p.bias && item_live[t]) w = *reinterpret_cast<const uint4*>(p.bias + head_rows + item_off[t]);
+            if (REL) {  // the query's coordinates instead
+              const int ii = item_live[t] ? t * kWave + lane : 0;
+              const float2 c = (reinterpret_cast<const float2*>(p.coords) + tok0)[fast_div(ii, p.cq_magic)];
+              w.x = __float_as_uint(c.x);
+              w.y = __float_as_uint(c.y);
+            } else if (p.bias && item_live[t]) {
+              w = *reinterpret_cast<const uint4*>(p.bias + head_rows + item_off[t]);
+            }
             bw[t][0] = w.x;
             bw[t][EW > 1 ? 1 : 0] = w.y;
             bw[t][EW > 2 ? 2 : 0] = w.z;
@@ -232,14 +264,33 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         // (an odd pass gets one more tile of -inf: the second half of its last pair, which repeats a tile)
         for (int s = 0; s < nsl + (nsl & 1); ++s)
           *reinterpret_cast<uint2*>(dstile + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
+        const float2* cxy = reinterpret_cast<const float2*>(kv);  // REL: [slot of the pass][token of the tile]
+        if (REL) {
+          const float2* cimg = reinterpret_cast<const float2*>(p.coords) + img_base;
+#pragma unroll
+          for (int i = 0; i < (kSlotCapB * 16 + kWave - 1) / kWave; ++i) {
+            const int tile = __shfl(my_tile, slot0 + min(4 * i + g, nsl - 1));
+            reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)(tile * 16 + r)];
+          }
+        }
         wave_lds_sync();
+        const bf16_t* tab = REL ? p.rel_table + h * RW * RW : nullptr;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
 #pragma unroll
           for (int e = 0; e < (VEC ? 8 : 1); ++e) {
             const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
-            const uint32_t bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
             const uint32_t rel = off - lo;  // other passes, kNoEntry and dead items fall outside [0, span)
+            uint32_t bits;
+            if (REL) {
+              // (an entry outside the pass reads some coordinate pair of the tile area: any value gives a cell of the table)
+              const float2 cn = cxy[((rel >> 4) & 0xf0u) | (rel & 0xfu)];
+              const int cell = relpos_cell(cn, make_float2(__uint_as_float(bw[t][0]), __uint_as_float(bw[t][EW > 1 ? 1 : 0])), p.rate, p.R);
+              bits = *reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(tab) + (uint32_t)cell * 2u);
+              if (SUMS) cells[SUMS ? t : 0][SUMS ? (e >> 2) : 0] |= (rel < span ? (uint32_t)cell : 0u) << (8 * (e & 3));
+            } else {
+              bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
+            }
             dstile[rel < span ? rel : (uint32_t)kSlotCapB * 256u] = (bf16_t)bits;
           }
         }
@@ -332,8 +383,23 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       stage_pair(sk0, sv0, sk1, sv1, kf, vf, kt);
       compute_pair(npairs - 1, kf, vf, kt);
       wave_lds_sync();
+      // REL: dS of this pass's real pairs, added to their bins
+      if (rel_sum) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t off = (ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu;
+            const uint32_t rel = off - lo;
+            if (rel < span) {
+              const uint32_t cell = (cells[SUMS ? t : 0][SUMS ? (e >> 2) : 0] >> (8 * (e & 3))) & 0xffu;
+              atomicAdd(&tabw[cell], (double)bf16_to_f32(dstile[rel]));
+            }
+          }
+        }
+      }
       // dS of this pass's real (query, neighbour) pairs in [token, head, slot] order (dbias)
-      if (p.ds) {
+      if (!SUMS && p.ds) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
 #pragma unroll
@@ -360,7 +426,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       wave_lds_sync();
     }
     // dbias [token, head, slot]; whole 16-byte pieces when K is a multiple of 8
-    if (p.ds) {
+    if (!SUMS && p.ds) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         if (item_live[t]) {
@@ -371,6 +437,10 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             p.ds[head_rows + item_off[t]] = (bf16_t)dacc[t][0];
         }
       }
+    }
+    if (rel_sum) {  // (the last pass ended with a wave_lds_sync)
+      float* dst = p.rel_part + ((size_t)sg * p.H + h) * (RW * RW);
+      for (int c = lane; c < RW * RW; c += kWave) dst[c] = (float)tabw[c];
     }
     // dq rows cross through LDS the other way: lane (query r, channels 16dt + 4g..+3) holds 8 bytes of
     // 16-byte piece 2dt + g/2 of row r; lane (row lane/4, piece lane%4) stores 16 bytes
@@ -389,11 +459,19 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
 
 template <int NT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) void pla_bwd_query_kernel(BwdParams p) {
-  pla_bwd_query_body<NT, true>(p);
+  pla_bwd_query_body<NT, true, false, false>(p);
+}
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pla_bwd_query_rel_kernel(BwdParams p) {
+  pla_bwd_query_body<NT, true, true, true>(p);
+}
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) void pla_bwd_query_rel_ds_kernel(BwdParams p) {
+  pla_bwd_query_body<NT, true, true, false>(p);
 }
 template <int NT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void pla_bwd_query_scalar_kernel(BwdParams p) {
-  pla_bwd_query_body<NT, false>(p);
+  pla_bwd_query_body<NT, false, false, false>(p);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -600,7 +678,37 @@ __global__ __launch_bounds__(1024) void pla_blank_reduce_kernel(const float* __r
   }
 }
 
+// First step of the sum of the waves' relative-position tables [strips][H][cells]: workgroup (head, part) adds
+// its share of the strips, thread = (bin, one of the groups that fit 256 threads), and writes one table.
+constexpr int kRelParts = 256;
+__global__ __launch_bounds__(256) void pla_rel_reduce_kernel(const float* __restrict__ part, int strips, int H,
+                                                             int cells, float* __restrict__ out) {
+  __shared__ float acc[256];
+  const int h = blockIdx.x / kRelParts, pt = blockIdx.x - h * kRelParts;
+  const int groups = 256 / cells;  // cells <= 128: at least two
+  const int c = threadIdx.x % cells, grp = threadIdx.x / cells;
+  const int per = (strips + kRelParts - 1) / kRelParts;
+  const int end = min(strips, (pt + 1) * per);
+  float s = 0.f;
+  if (grp < groups)
+    for (int sg = pt * per + grp; sg < end; sg += groups) s += part[((size_t)sg * H + h) * cells + c];
+  acc[threadIdx.x] = s;
+  __syncthreads();
+  if (threadIdx.x < cells) {
+    float t = 0.f;
+    for (int j = 0; j < groups; ++j) t += acc[j * cells + threadIdx.x];
+    out[((size_t)pt * H + h) * cells + threadIdx.x] = t;
+  }
+}
+
 }  // namespace
+
+size_t pla_bwd_cluster_rel_workspace_bytes(int B, int N, int H, int R) {
+  // tables of the waves, then the tables of pla_rel_reduce_kernel
+  const size_t cells = (size_t)(2 * R + 1) * (2 * R + 1);
+  return plan_align((size_t)B * (N / 16) * H * cells * sizeof(float)) + plan_align((size_t)kRelParts * H * cells * sizeof(float));
+}
+bool pla_bwd_cluster_rel_sums(int R) { return (2 * R + 1) * (2 * R + 1) <= kRelCells; }
 
 size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, int S, int M) {
   const PlanLayout L = make_plan_layout(B, N, K, S, M);
@@ -633,6 +741,8 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
                                                 plan_align((size_t)L.strips * a.H * L.places * sizeof(uint32_t)))
                      : nullptr;
 
+  p.coords = a.rel_coords; p.rel_table = (const bf16_t*)a.rel_table; p.R = a.rel_R; p.rate = a.rel_rate;
+  p.rel_part = a.rel_part;
   const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);  // multiple of 8 for the XCD-contiguous mapping
   const dim3 grid_q((((long long)L.strips * a.H + 3) / 4 + 7) / 8 * 8);  // one wave per (strip, head)
   p.k_magic = div_magic(a.K);
@@ -641,7 +751,11 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
                    (!p.ds || reinterpret_cast<uintptr_t>(p.ds) % 16 == 0);
 #define AFFMAE_BWDQ(KERNEL, NT) \
   AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (KERNEL<NT>), grid_q, dim3(256), 0, stream, p)
-  if (vec) {
+  if (a.rel_table && a.rel_part) {  // callers check pla_cluster_relpos_supported first
+    if (2 * a.K <= kWave) AFFMAE_BWDQ(pla_bwd_query_rel_kernel, 1); else AFFMAE_BWDQ(pla_bwd_query_rel_kernel, 2);
+  } else if (a.rel_table) {
+    if (2 * a.K <= kWave) AFFMAE_BWDQ(pla_bwd_query_rel_ds_kernel, 1); else AFFMAE_BWDQ(pla_bwd_query_rel_ds_kernel, 2);
+  } else if (vec) {
     if (2 * a.K <= kWave) AFFMAE_BWDQ(pla_bwd_query_kernel, 1); else AFFMAE_BWDQ(pla_bwd_query_kernel, 2);
   } else {
     const int ent = (16 * a.K + kWave - 1) / kWave;
@@ -655,6 +769,15 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
     AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<2>, grid, dim3(256), 0, stream, p);
   else
     AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<1>, grid, dim3(256), 0, stream, p);
+  if (a.rel_table && a.rel_part) {
+    const int cells = (2 * a.rel_R + 1) * (2 * a.rel_R + 1);
+    float* second = reinterpret_cast<float*>(reinterpret_cast<char*>(a.rel_part) +
+                                             plan_align((size_t)L.strips * a.H * cells * sizeof(float)));
+    AFFMAE_LAUNCH("pla_rel_reduce_kernel", stream, pla_rel_reduce_kernel, dim3(a.H * kRelParts), dim3(256), 0, stream,
+                  a.rel_part, L.strips, a.H, cells, second);
+    const hipError_t e = launch_relpos_table_sum(second, kRelParts, a.H * cells, a.rel_dtable, stream);
+    if (e != hipSuccess) return e;
+  }
   if (p.blank_part)
     AFFMAE_LAUNCH("pla_blank_reduce_kernel", stream, pla_blank_reduce_kernel, dim3(2 * a.H), dim3(1024), 0, stream,
                   p.blank_part, L.strips, a.H, a.dk_blank, a.dv_blank);

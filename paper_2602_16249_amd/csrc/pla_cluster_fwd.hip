@@ -185,10 +185,10 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
           const uint32_t rel = off - lo;
           uint32_t bits;
           if (REL) {
-            const float2 cn = cxy[rel < span ? ((rel >> 8) << 4) | (rel & 15u) : 0u];
-            const int cell = relpos_bin(cn.y, __uint_as_float(bw[t][EW > 1 ? 1 : 0]), p.rate, p.R) * RW +
-                             relpos_bin(cn.x, __uint_as_float(bw[t][0]), p.rate, p.R);
-            bits = tab[cell];
+            // (an entry outside the pass reads some coordinate pair of the tile area: any value gives a cell of the table)
+            const float2 cn = cxy[((rel >> 4) & 0xf0u) | (rel & 0xfu)];
+            const int cell = relpos_cell(cn, make_float2(__uint_as_float(bw[t][0]), __uint_as_float(bw[t][EW > 1 ? 1 : 0])), p.rate, p.R);
+            bits = *reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(tab) + (uint32_t)cell * 2u);
           } else {
             bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
           }

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void relpos_bias_kernel(const float* __restric
   const float2 ci = reinterpret_cast<const float2*>(coords)[tok];
   const float2 cn = reinterpret_cast<const float2*>(coords)[(long long)b * N + n];
   const int W = 2 * R + 1;
-  const int cell = relpos_bin(cn.y, ci.y, rate, R) * W + relpos_bin(cn.x, ci.x, rate, R);
+  const int cell = relpos_cell(cn, ci, rate, R);
   for (int h = 0; h < H; ++h) bias[(tok * H + h) * K + j] = table[(size_t)h * W * W + cell];
 }
 
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void relpos_bias8_kernel(const float* __restri
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const float2 cn = reinterpret_cast<const float2*>(coords)[(long long)b * N + min(max(nn[e], 0), N - 1)];
-    cell[e] = relpos_bin(cn.y, ci.y, rate, R) * W + relpos_bin(cn.x, ci.x, rate, R);
+    cell[e] = relpos_cell(cn, ci, rate, R);
   }
   for (int h = 0; h < H; ++h) {
     const bf16_t* t = table + (size_t)h * W * W;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kDtableThreads) void relpos_dtable_part_kernel(cons
     const int b = tok[i] / N;
     const float2 ci = reinterpret_cast<const float2*>(coords)[tok[i]];
     const float2 cn = reinterpret_cast<const float2*>(coords)[b * N + n[i]];
-    cell[i] = relpos_bin(cn.y, ci.y, rate, R) * W + relpos_bin(cn.x, ci.x, rate, R);
+    cell[i] = relpos_cell(cn, ci, rate, R);
   }
   for (int h = 0; h < H; ++h) {
     float g[kDtableItems];
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(kDtableThreads) void relpos_dtable_part8_kernel(con
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float2 cn = reinterpret_cast<const float2*>(coords)[b * N + min(max(nn[e], 0), N - 1)];
-      cell[u][e] = relpos_bin(cn.y, ci.y, rate, R) * W + relpos_bin(cn.x, ci.x, rate, R);
+      cell[u][e] = relpos_cell(cn, ci, rate, R);
     }
   }
   for (int h = 0; h < H; ++h) {
@@ -271,6 +271,12 @@ hipError_t launch_relpos_dtable(const RelposArgs& r, int B, int N, int H, int K,
 #undef AFFMAE_DTABLE
   AFFMAE_LAUNCH("relpos_dtable_sum_kernel", stream, relpos_dtable_sum_kernel, dim3(H * cells), dim3(256), 0, stream,
                 part, used, H * cells, dtable);
+  return hipGetLastError();
+}
+
+hipError_t launch_relpos_table_sum(const float* part, int tables, int entries, float* dtable, hipStream_t stream) {
+  AFFMAE_LAUNCH("relpos_dtable_sum_kernel", stream, relpos_dtable_sum_kernel, dim3(entries), dim3(256), 0, stream,
+                part, tables, entries, dtable);
   return hipGetLastError();
 }
 
