@@ -300,6 +300,15 @@ int affmae_timing_read(int index, char* name, int name_len, double* total_ms, in
  * affmae_pla_fwd / affmae_pla_bwd, whose argument lists these calls follow with
  * `bias` replaced by (coords, rel_table, R, rate) and `dbias` by drel_table.
  *
+ * With the cluster promise, bf16, d = 32 and K a multiple of 8 the tiled kernels
+ * compute the bias themselves (the coordinates of the token tiles a strip
+ * touches are staged in LDS, a cell per (query, neighbour) pair, the value
+ * through the cache): no bias or dbias tensor exists, and for tables of at most
+ * 128 cells per head (R <= 5) the gradient of the table is summed inside the
+ * backward kernel as well.  In every other case the bias is written into the
+ * workspace by a kernel of its own and the table's gradient is reduced from
+ * dbias by another; the results are the same.
+ *
  *   coords      in  [B,N,2] fp32, 8-byte aligned
  *   rel_table   in  [H, 2R+1, 2R+1] in the storage type (row = y bin)
  *   R           bins on each side of zero, 0 <= R <= 31, H*(2R+1)^2 <= 12288
