@@ -124,3 +124,52 @@ def test_clustering_and_sampling_replayed_from_a_graph():
         a, b = got["dfeat"].float(), ref["dfeat"].float()
         assert float((a - b).abs().max()) <= 2e-2 * float(b.abs().max()), f"replay {rep}: dfeat"
         assert abs(float(got["dp"]) - float(ref["dp"])) <= 1e-3 * max(1.0, abs(float(ref["dp"])))
+
+
+def test_relative_position_attention_replayed_from_a_graph():
+    """Forward and backward with the bias from a relative-position table, recorded once and replayed with new
+    coordinates, tables and gradients.  The table's gradient is summed with LDS atomics whose order may vary, in
+    fp64, so it is compared to 1e-6 of its largest entry; everything else bit for bit."""
+    cfg = CONFIGS["ft_s1_1024"].scaled(B=2, N=4096, C=64, H=2, K=48, S=64, M=8, dtype="bf16", frame=512.0)
+    S, M, K, scale, rate = cfg.S, cfg.M, cfg.K, 1.0 / np.sqrt(32.0), 0.125
+    w = make_workload(cfg)
+    coords = torch.from_numpy(w["coords"]).cuda()
+    q, k, v, dout = (to_dev(w[n], "bf16") for n in ("q", "k", "v", "dout"))
+    nbr, near = aff.affmae_knn(coords, None, S, M, K)
+    plan = aff.affmae_pla_plan(nbr, near, S, M)
+    gen = torch.Generator(device="cuda").manual_seed(3)
+
+    def run(c, table, g):
+        out, lse = aff.affmae_pla_fwd_relpos(q, k, v, c, table, nbr, scale, rate, near, S, M, plan=plan)
+        grads = aff.affmae_pla_bwd_relpos(q, k, v, c, table, nbr, out, lse, g, scale, rate, near, S, M, plan=plan)
+        return {"out": out, "lse": lse, **grads}
+
+    for R in (4, 7):   # the table's gradient summed inside the backward kernel / by the kernel of its own
+        s_c = coords.clone()
+        s_t = (0.3 * torch.randn((cfg.H, 2 * R + 1, 2 * R + 1), device="cuda", generator=gen)).to(torch.bfloat16)
+        s_g = dout.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run(s_c, s_t, s_g)  # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            got = run(s_c, s_t, s_g)
+        for rep in range(3):
+            # jittered coordinates (same neighbour table: any table is a valid input), a new table, rolled gradients
+            c_new = coords + 0.9 * torch.rand(coords.shape, device="cuda", generator=gen)
+            t_new = (0.3 * torch.randn(s_t.shape, device="cuda", generator=gen)).to(torch.bfloat16)
+            g_new = dout.roll(rep + 1, dims=1).contiguous()
+            ref = run(c_new, t_new, g_new)  # eager work between the replays
+            torch.cuda.synchronize()
+            s_c.copy_(c_new); s_t.copy_(t_new); s_g.copy_(g_new)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for name, t in ref.items():
+                if name == "drel_table":
+                    assert float((got[name] - t).abs().max()) <= 1e-6 * float(t.abs().max()), f"R={R} replay {rep}"
+                else:
+                    assert torch.equal(got[name], t), f"R={R} replay {rep}: {name} differs from the eager result"
