@@ -6,7 +6,7 @@
 //  query-stationary (one wave per strip of 16 queries): recomputes the
 //    probabilities p from lse tile by tile exactly as the forward pass forms the
 //    scores, forms dP = V dO^T with MFMAs, dS = p (dP - D) with D = <dout, out>,
-//    accumulates dQ^T = K^T dS^T (K transposed by an MFMA against the identity),
+//    accumulates dQ^T = K^T dS^T (K^T read from the staged rows with the transposing LDS read),
 //    and leaves p and dS of the real (query, neighbour) pairs in compact arrays:
 //    dS in [token, head, slot] order is dbias; (p, dS) words go to the workspace
 //    in the plan's run order (grouped by token tile).  With blank tokens the blank column joins
@@ -25,7 +25,7 @@
 namespace affmae {
 namespace {
 
-constexpr int kSlotCapB = 10;  // token tiles resident per wave: two bf16 tiles each (10 KB); three workgroups per CU
+constexpr int kSlotCapB = 10;  // token tiles resident per wave: one tile of (p, dS) words each (10 KB); three workgroups per CU
 static_assert(kSlotCapB % 2 == 0, "an odd pass uses one more tile for the second half of its last pair");
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -80,8 +80,9 @@ template <int NT, bool VEC, bool REL, bool SUMS>
 __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   static_assert(!SUMS || REL, "the table's gradient belongs to the table form");
   static_assert(!REL || VEC, "the table form is built for 16-byte items");
-  __shared__ __align__(16) bf16_t ds_all[4][kSlotCapB * 256 + 8];  // + a cell that absorbs skipped entries
-  __shared__ __align__(16) bf16_t p_all[4][kSlotCapB * 256];
+  // per wave and resident token tile, a 16 x 16 tile of words: the bias (low half) until the tile has been
+  // processed, then p (low half) and dS (high half), the word that the key-stationary kernel is handed
+  __shared__ __align__(16) uint32_t pd_all[4][kSlotCapB * 256 + 4];  // + a cell that absorbs skipped entries
   __shared__ __align__(16) u32x4 kv_all[4][3 * 64];  // per wave: rows of two token tiles (K, then V), or the strip's q, dout, out
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
@@ -91,8 +92,8 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int sg = unit / p.H;
   const int h = unit - sg * p.H;
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier in this kernel
-  bf16_t* dstile = ds_all[wave];  // holds the bias tile first, dS after a tile has been processed
-  bf16_t* ptile = p_all[wave];
+  uint32_t* pdtile = pd_all[wave];
+  bf16_t* halves = reinterpret_cast<bf16_t*>(pdtile);  // [2 * cell] low half, [2 * cell + 1] high half
   const int b = sg / p.strips_per_image;
   const long long img_base = (long long)b * p.N;
   const long long tok0 = (long long)sg * 16;
@@ -263,7 +264,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         }
         // (an odd pass gets one more tile of -inf: the second half of its last pair, which repeats a tile)
         for (int s = 0; s < nsl + (nsl & 1); ++s)
-          *reinterpret_cast<uint2*>(dstile + s * 256 + lane * 4) = make_uint2(0xff80ff80u, 0xff80ff80u);
+          *reinterpret_cast<uint4*>(pdtile + s * 256 + lane * 4) = make_uint4(0xff80u, 0xff80u, 0xff80u, 0xff80u);
         const float2* cxy = reinterpret_cast<const float2*>(kv);  // REL: [slot of the pass][token of the tile]
         if (REL) {
           const float2* cimg = reinterpret_cast<const float2*>(p.coords) + img_base;
@@ -291,7 +292,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             } else {
               bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
             }
-            dstile[rel < span ? rel : (uint32_t)kSlotCapB * 256u] = (bf16_t)bits;
+            halves[2u * (rel < span ? rel : (uint32_t)kSlotCapB * 256u)] = (bf16_t)bits;
           }
         }
         wave_lds_sync();
@@ -347,24 +348,20 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             const f32x4 st = mfma32(kf[tt], qf, z);   // <k[token 4g+i], q[query r]>
             const f32x4 dpt = mfma32(vf[tt], gf, z);  // <v[token 4g+i], dout[query r]>
-            bf16_t* cell = dstile + (2 * pr + tt) * 256 + r * 16 + g * 4;
-            const uint2 bm = *reinterpret_cast<const uint2*>(cell);
+            uint32_t* cell = pdtile + (2 * pr + tt) * 256 + r * 16 + g * 4;
+            const uint4 bm = *reinterpret_cast<const uint4*>(cell);
             float pv[4], dsv[4];
             pv[0] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[0], p.scale, __uint_as_float(bm.x << 16)), kLog2e, nl2));
-            pv[1] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[1], p.scale, __uint_as_float(bm.x & 0xffff0000u)), kLog2e, nl2));
-            pv[2] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[2], p.scale, __uint_as_float(bm.y << 16)), kLog2e, nl2));
-            pv[3] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[3], p.scale, __uint_as_float(bm.y & 0xffff0000u)), kLog2e, nl2));
+            pv[1] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[1], p.scale, __uint_as_float(bm.y << 16)), kLog2e, nl2));
+            pv[2] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[2], p.scale, __uint_as_float(bm.z << 16)), kLog2e, nl2));
+            pv[3] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[3], p.scale, __uint_as_float(bm.w << 16)), kLog2e, nl2));
 #pragma unroll
             for (int i = 0; i < 4; ++i) dsv[i] = pv[i] * (dpt[i] - Dq);
-            uint2 pw, dw;
-            pw.x = pack_bf16x2(pv[0], pv[1]);
-            pw.y = pack_bf16x2(pv[2], pv[3]);
-            dw.x = pack_bf16x2(dsv[0], dsv[1]);
-            dw.y = pack_bf16x2(dsv[2], dsv[3]);
-            *reinterpret_cast<uint2*>(ptile + (2 * pr + tt) * 256 + r * 16 + g * 4) = pw;
-            *reinterpret_cast<uint2*>(cell) = dw;  // the bias of these cells is no longer needed
-            dsf.u[2 * tt + 0] = dw.x;
-            dsf.u[2 * tt + 1] = dw.y;
+            // (p, dS) words replace the bias of these cells, which is no longer needed
+            *reinterpret_cast<uint4*>(cell) = make_uint4(pack_bf16x2(pv[0], dsv[0]), pack_bf16x2(pv[1], dsv[1]),
+                                                         pack_bf16x2(pv[2], dsv[2]), pack_bf16x2(pv[3], dsv[3]));
+            dsf.u[2 * tt + 0] = pack_bf16x2(dsv[0], dsv[1]);
+            dsf.u[2 * tt + 1] = pack_bf16x2(dsv[2], dsv[3]);
           }
         }
 #pragma unroll
@@ -393,7 +390,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             const uint32_t rel = off - lo;
             if (rel < span) {
               const uint32_t cell = (cells[SUMS ? t : 0][SUMS ? (e >> 2) : 0] >> (8 * (e & 3))) & 0xffu;
-              atomicAdd(&tabw[cell], (double)bf16_to_f32(dstile[rel]));
+              atomicAdd(&tabw[cell], (double)bf16_to_f32(halves[2u * rel + 1u]));
             }
           }
         }
@@ -407,7 +404,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
             const uint32_t rel = off - lo;
             const bool in = rel < span;
-            const uint32_t dsv = dstile[in ? rel : 0u];
+            const uint32_t dsv = halves[in ? 2u * rel + 1u : 1u];
             dacc[t][e >> 1] |= (in ? dsv : 0u) << (16 * (e & 1));
           }
         }
@@ -419,8 +416,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         const uint32_t rel0 = (sp[t] & 0xffffu) - lo, rel1 = (sp[t] >> 16) - lo;  // other passes and unused places
         const bool in0 = rel0 < span, in1 = rel1 < span;                         // fall outside [0, span)
         const uint32_t a0 = in0 ? rel0 : 0u, a1 = in1 ? rel1 : 0u;
-        const uint32_t w0 = (uint32_t)ptile[a0] | ((uint32_t)dstile[a0] << 16);
-        const uint32_t w1 = (uint32_t)ptile[a1] | ((uint32_t)dstile[a1] << 16);
+        const uint32_t w0 = pdtile[a0], w1 = pdtile[a1];
         if (in0) *reinterpret_cast<uint2*>(pd_head + t * 2 * kWave + 2 * lane) = make_uint2(w0, in1 ? w1 : 0u);
       }
       wave_lds_sync();
