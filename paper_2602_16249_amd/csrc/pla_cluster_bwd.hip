@@ -82,7 +82,11 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   static_assert(!REL || VEC, "the table form is built for 16-byte items");
   // per wave and resident token tile, a 16 x 16 tile of words: the bias (low half) until the tile has been
   // processed, then p (low half) and dS (high half), the word that the key-stationary kernel is handed
-  __shared__ __align__(16) uint32_t pd_all[4][kSlotCapB * 256 + 4];  // + a cell that absorbs skipped entries
+  // + a spare cell: entries that are not of the pass (other passes, no neighbour, dead items) are steered to it
+  // with one unsigned minimum - their offset relative to the pass is at least kSlotCapB * 256, wrapped around or
+  // not, because every pass but the last is full.  Skipped bias values land in its low half; its high half stays
+  // zero, which is what a skipped read of dS takes.
+  __shared__ __align__(16) uint32_t pd_all[4][kSlotCapB * 256 + 4];
   __shared__ __align__(16) u32x4 kv_all[4][3 * 64];  // per wave: rows of two token tiles (K, then V), or the strip's q, dout, out
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
@@ -94,6 +98,8 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier in this kernel
   uint32_t* pdtile = pd_all[wave];
   bf16_t* halves = reinterpret_cast<bf16_t*>(pdtile);  // [2 * cell] low half, [2 * cell + 1] high half
+  constexpr uint32_t kSpare = kSlotCapB * 256u;
+  if (lane == 0) pdtile[kSpare] = 0u;  // (ordered before its first read by the fences of the passes)
   const int b = sg / p.strips_per_image;
   const long long img_base = (long long)b * p.N;
   const long long tok0 = (long long)sg * 16;
@@ -292,7 +298,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             } else {
               bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
             }
-            halves[2u * (rel < span ? rel : (uint32_t)kSlotCapB * 256u)] = (bf16_t)bits;
+            halves[2u * min(rel, kSpare)] = (bf16_t)bits;
           }
         }
         wave_lds_sync();
@@ -403,9 +409,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
           for (int e = 0; e < (VEC ? 8 : 1); ++e) {
             const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
             const uint32_t rel = off - lo;
-            const bool in = rel < span;
-            const uint32_t dsv = halves[in ? 2u * rel + 1u : 1u];
-            dacc[t][e >> 1] |= (in ? dsv : 0u) << (16 * (e & 1));
+            dacc[t][e >> 1] |= (uint32_t)halves[2u * min(rel, kSpare) + 1u] << (16 * (e & 1));
           }
         }
       }
@@ -415,7 +419,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       for (int t = 0; t < SR; ++t) {
         const uint32_t rel0 = (sp[t] & 0xffffu) - lo, rel1 = (sp[t] >> 16) - lo;  // other passes and unused places
         const bool in0 = rel0 < span, in1 = rel1 < span;                         // fall outside [0, span)
-        const uint32_t a0 = in0 ? rel0 : 0u, a1 = in1 ? rel1 : 0u;
+        const uint32_t a0 = min(rel0, kSpare), a1 = min(rel1, kSpare);
         const uint32_t w0 = pdtile[a0], w1 = pdtile[a1];
         if (in0) *reinterpret_cast<uint2*>(pd_head + t * 2 * kWave + 2 * lane) = make_uint2(w0, in1 ? w1 : 0u);
       }
