@@ -113,6 +113,38 @@ def bench_relpos(aff, torch, np, cfg, s, scale, promise, reps: int = 20):
             "tokens_per_s_fwd_bwd": cfg.B * cfg.N / ((t[0] + t[1]) * 1e-3)}
 
 
+def bench_graphs(torch, sets, step, attn, steps: int):
+    """The same work replayed from HIP graphs (one per tensor set, recorded once): the library's calls only
+    enqueue kernels, so a caller can remove the launch gaps between the ~20 kernels of a step this way.
+    Returns mean milliseconds per replay of the whole step and of attention forward + backward alone."""
+    out = {}
+    for name, fn in (("step_ms", step), ("attn_fwd_bwd_ms", attn)):
+        side = torch.cuda.Stream()
+        graphs = []
+        for st in sets:
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                fn(st)  # warm-up outside the capture
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                fn(st)
+            graphs.append(g)
+        for g in graphs:
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            graphs[i % len(graphs)].replay()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1) / steps
+        del graphs
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -197,6 +229,13 @@ def main() -> int:
         if e:
             e[3].record()
             rec.append(e)
+
+    def attn_only(s):
+        near = s["near"] if promise else None
+        aff.affmae_pla_fwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], scale, near, cfg.S, cfg.M,
+                           out=s["out"], lse=s["lse"], workspace=s["ws"], plan=s["plan"])
+        aff.affmae_pla_bwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], s["out"], s["lse"], s["dout"], scale,
+                           near, cfg.S, cfg.M, grads=s["grads"], workspace=s["ws"], plan=s["plan"])
 
     for i in range(args.warmup):
         step(sets[i % len(sets)])
@@ -303,6 +342,10 @@ def main() -> int:
     }
 
     result["relative_position_bias"] = bench_relpos(aff, torch, np, cfg, sets[0], scale, promise)
+    g = bench_graphs(torch, sets, step, attn_only, args.steps)
+    result["hip_graph"] = {"step_ms": g["step_ms"], "attn_fwd_bwd_ms": g["attn_fwd_bwd_ms"],
+                           "attn_tokens_per_s": tokens / (g["attn_fwd_bwd_ms"] * 1e-3),
+                           "step_tokens_per_s": tokens / (g["step_ms"] * 1e-3)}
     result["virtual_tokens"] = bench_virtual_tokens(aff, torch, np, dev)
 
     if not args.no_cpu_baseline:

@@ -7,17 +7,20 @@
 //    probabilities p from lse tile by tile exactly as the forward pass forms the
 //    scores, forms dP = V dO^T with MFMAs, dS = p (dP - D) with D = <dout, out>,
 //    accumulates dQ^T = K^T dS^T (K^T read from the staged rows with the transposing LDS read),
-//    and leaves p and dS of the real (query, neighbour) pairs in compact arrays:
-//    dS in [token, head, slot] order is dbias; (p, dS) words go to the workspace
-//    in the plan's run order (grouped by token tile).  With blank tokens the blank column joins
+//    and leaves what the other kernel needs in compact arrays: dS of the real (query, neighbour)
+//    pairs in [token, head, slot] order is dbias; their p goes to the workspace in the plan's run
+//    order (grouped by token tile), with D of every query.  With blank tokens the blank column joins
 //    every query's softmax: its dS feeds dq, and the strip's sums for dk_blank / dv_blank go to
 //    the workspace, to be added up over the strips in a fixed order by a last kernel;
 //
 //  key-stationary (one wave per tile of 16 tokens): walks the sorted list of
-//    strips that touch the tile, reads each strip's run of (p, dS) words for the
-//    tile as one contiguous piece, spreads it over a 16x16 tile in LDS, and
-//    accumulates dK^T = Q^T dS and dV^T = dO^T P in registers, so dk and dv are
-//    written once, without atomics and in a fixed summation order.
+//    strips that touch the tile, reads each strip's run of p values for the
+//    tile as one contiguous piece, spreads it over a 16x16 tile in LDS, forms
+//    dS = p (dP - D) itself (one more MFMA on its own V rows: handing dS over as
+//    well would cost 2 bytes per pair written and read again, and both kernels run
+//    close to what the memory system delivers), and accumulates dK^T = Q^T dS and
+//    dV^T = dO^T P in registers, so dk and dv are written once, without atomics and
+//    in a fixed summation order.
 #include "cluster_common.h"
 #include "launch.h"
 #include "timing.h"
@@ -41,8 +44,8 @@ struct BwdParams {
   float scale;
   bf16_t *dq, *dk, *dv;
   bf16_t* ds;    // [B,N,H,K] dS = dbias, or nullptr when the caller does not want it
-  uint32_t* pd;  // workspace [strips][H][places]: one word per place of the plan's run order,
-                 // p in the low half, dS in the high half (bf16 bits)
+  bf16_t* ph;    // workspace [strips][H][places]: p of every place of the plan's run order
+  float* dsum;   // workspace [strips][H][16]: -D = -<dout, out> of the strip's queries
   const bf16_t *k_blank, *v_blank;  // [H,32] or nullptr
   float* blank_part;                // workspace [strips][H][2][32]: the strip's parts of dk_blank, dv_blank; or nullptr
   // bias from a relative-position table (REL kernels): token coordinates [B,N,2], table [H][2R+1][2R+1]
@@ -190,6 +193,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) Dq = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(of.h[i]), Dq);
     Dq = group_sum(Dq);
+    if (g == 0) p.dsum[((size_t)sg * p.H + h) * 16 + r] = -Dq;  // the key-stationary kernel forms dS with it
     const float nl2 = -p.lse[(size_t)(tok0 + r) * p.H + h] * kLog2e;
     const size_t head_rows = strip_rows + (size_t)h * K;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
@@ -241,7 +245,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int e = 0; e < EW; ++e) dacc[t][e] = 0u;
-    uint32_t* pd_head = p.pd + ((size_t)sg * p.H + h) * p.places;
+    bf16_t* ph_head = p.ph + ((size_t)sg * p.H + h) * p.places;
 
     for (int slot0 = 0; slot0 < ntiles; slot0 += kSlotCapB) {
       const int nsl = min(kSlotCapB, ntiles - slot0);
@@ -413,15 +417,15 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
           }
         }
       }
-      // (p, dS) words of this pass's slots in run order: consecutive places, so the stores are whole rows.
+      // p of this pass's slots in run order: consecutive places, so the stores are whole rows.
       // Runs start at even places: a pair of places belongs to one slot, or its second place is unused.
 #pragma unroll
       for (int t = 0; t < SR; ++t) {
         const uint32_t rel0 = (sp[t] & 0xffffu) - lo, rel1 = (sp[t] >> 16) - lo;  // other passes and unused places
         const bool in0 = rel0 < span, in1 = rel1 < span;                         // fall outside [0, span)
         const uint32_t a0 = min(rel0, kSpare), a1 = min(rel1, kSpare);
-        const uint32_t w0 = pdtile[a0], w1 = pdtile[a1];
-        if (in0) *reinterpret_cast<uint2*>(pd_head + t * 2 * kWave + 2 * lane) = make_uint2(w0, in1 ? w1 : 0u);
+        const uint32_t p0 = halves[2u * a0], p1 = halves[2u * a1];
+        if (in0) *reinterpret_cast<uint32_t*>(ph_head + t * 2 * kWave + 2 * lane) = p0 | ((in1 ? p1 : 0u) << 16);
       }
       wave_lds_sync();
     }
@@ -479,7 +483,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 template <int HG>
 struct KeyItem {
   u32x4 qs[HG], gs[HG];  // strip's q and dout rows of the head group as loaded: lane (row i*16/HG + lane/(4 HG), piece lane%(4 HG))
-  uint2 w[2][HG];        // (p, dS) words of places 2*lane, 2*lane+1 (+128 in the second round) of the run
+  uint32_t w[2][HG];     // p of places 2*lane, 2*lane+1 (+128 in the second round) of the run, two bf16 halves
   uint32_t code[2];      // their entry values, two 16-bit halves
   uint32_t len;          // places in the run (wave-uniform)
 };
@@ -487,15 +491,15 @@ struct KeyItem {
 // HG = heads handled per sweep over the tile's list (2 when H is even: one walk of the list, one load of
 // the entry values and one pass over the q / dout rows serve both).
 template <int HG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_bwd_key_kernel(BwdParams p) {
-  __shared__ __align__(16) uint32_t tile_all[4][HG * 256];  // per wave and head: (p, dS)[token][query]
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
+  __shared__ __align__(16) bf16_t tile_all[4][HG * 256];  // per wave and head: p[token][query]
   __shared__ __align__(16) u32x4 rows_all[4][2 * HG * 64];  // per wave: the strip's q rows, then its dout rows
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
   const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
   if (kt >= p.strips) return;
-  uint32_t* tile = tile_all[wave];
+  bf16_t* tile = tile_all[wave];
   u32x4* rows = rows_all[wave];
   const int b = kt / p.strips_per_image;
   const int C = p.H * kD;
@@ -527,7 +531,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
       tr_off[hh][dt] = (row * PR + ((4 * hh + 2 * dt + ((r & 3) >> 1)) ^ swz(row))) * 16 + (r & 1) * 8;
     }
 
+  // where lane (query r, channels 8g..8g+7 of head hh) finds its piece of the staged dout rows
+  int gf_chunk[HG];
+#pragma unroll
+  for (int hh = 0; hh < HG; ++hh) gf_chunk[hh] = HG * 64 + r * PR + ((4 * hh + g) ^ swz(r));
+
   for (int hg = 0; hg < p.H; hg += HG) {
+    // The hand-over carries p only: dS = p (dP - D) is formed here, with dP - D = <dout[query], v[token]> - D from one
+    // more MFMA on the tile's own V rows (operand: lane (token r, channels 8g..8g+7)) and the dout rows that
+    // are staged anyway.  It comes out as lane (token r, queries 4g..4g+3), the operand layout of dK^T = Q^T dS.
+    Frag8 vop[HG];
+#pragma unroll
+    for (int hh = 0; hh < HG; ++hh)
+      vop[hh].u4 = *reinterpret_cast<const uint4*>(p.v + ((size_t)kt * 16 + r) * C + (size_t)((hg + hh) * kD) + g * 8);
     f32x4 dk[HG][2], dv[HG][2];
 #pragma unroll
     for (int hh = 0; hh < HG; ++hh)
@@ -556,7 +572,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         }
         // runs start at even places and the rows hold an even number of places: aligned pairs
         const uint16_t* codes = p.sorted_pos + sgq * p.places + start;
-        const uint32_t* words = p.pd + (sgq * p.H + hg) * p.places + start;
+        const bf16_t* words = p.ph + (sgq * p.H + hg) * p.places + start;
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
           const uint32_t e = (uint32_t)(rr * 2 * kWave + 2 * lane);
@@ -564,18 +580,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
           it.code[rr] = on ? *reinterpret_cast<const uint32_t*>(codes + e) : 0xffffffffu;
 #pragma unroll
           for (int hh = 0; hh < HG; ++hh)
-            it.w[rr][hh] = on ? *reinterpret_cast<const uint2*>(words + (size_t)hh * p.places + e) : make_uint2(0u, 0u);
+            it.w[rr][hh] = on ? *reinterpret_cast<const uint32_t*>(words + (size_t)hh * p.places + e) : 0u;
         }
       };
-      auto compute = [&](const KeyItem<HG>& it) {
+      // -D of the queries 4g..4g+3 of item i's strip: one copy only, loaded for the next item when the current one
+      // has used its own (it is small and cached; a second copy would cost the kernel its fourth wave per SIMD)
+      float4 dsum[HG];
+      auto load_dsum = [&](int i) {
+        const uint32_t inc = __builtin_amdgcn_readlane(mine_lo, min(i, nb - 1));
+        const size_t sgq = strip_base + (inc >> 8);
+#pragma unroll
+        for (int hh = 0; hh < HG; ++hh)
+          dsum[hh] = *reinterpret_cast<const float4*>(p.dsum + (sgq * p.H + hg + hh) * 16 + g * 4);
+      };
+      auto compute = [&](const KeyItem<HG>& it, int next) {
 #pragma unroll
         for (int i = 0; i < HG; ++i) {
           rows[wr_chunk[i]] = it.qs[i];
           rows[HG * 64 + wr_chunk[i]] = it.gs[i];
         }
-        // spread the run over the tile: cell [token][query] <- word; unlisted cells stay 0 (p = dS = 0)
+        // spread the run over the tile: cell [token][query] <- p; unlisted cells stay 0 (hence dS = 0 there)
 #pragma unroll
-        for (int hh = 0; hh < HG; ++hh) *reinterpret_cast<uint4*>(tile + hh * 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+        for (int hh = 0; hh < HG; ++hh) *reinterpret_cast<uint2*>(tile + hh * 256 + lane * 4) = make_uint2(0u, 0u);
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
 #pragma unroll
@@ -584,20 +610,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             if (c != kNoEntry) {
               const uint32_t cell = ((c & 15u) << 4) | ((c >> 4) & 15u);
 #pragma unroll
-              for (int hh = 0; hh < HG; ++hh) tile[hh * 256 + cell] = half ? it.w[rr][hh].y : it.w[rr][hh].x;
+              for (int hh = 0; hh < HG; ++hh) tile[hh * 256 + cell] = (bf16_t)(half ? it.w[rr][hh] >> 16 : it.w[rr][hh] & 0xffffu);
             }
           }
         }
         wave_lds_sync();
 #pragma unroll
         for (int hh = 0; hh < HG; ++hh) {
-          // (p, dS)[token r][queries 4g..4g+3]
-          const uint4 w = *reinterpret_cast<const uint4*>(tile + hh * 256 + r * 16 + g * 4);
           Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
-          pf.u[0] = (w.x & 0xffffu) | (w.y << 16);
-          pf.u[1] = (w.z & 0xffffu) | (w.w << 16);
-          df.u[0] = (w.x >> 16) | (w.y & 0xffff0000u);
-          df.u[1] = (w.z >> 16) | (w.w & 0xffff0000u);
+          const uint2 w = *reinterpret_cast<const uint2*>(tile + hh * 256 + r * 16 + g * 4);  // p[token r][queries 4g..]
+          pf.u[0] = w.x;
+          pf.u[1] = w.y;
+          Frag8 gf;  // lane (query r, channels 8g..8g+7) of dout
+          gf.x4 = rows[gf_chunk[hh]];
+          // <dout[query 4g+i], v[token r]> - D[query 4g+i]: the accumulator starts at -D
+          const f32x4 nd = {dsum[hh].x, dsum[hh].y, dsum[hh].z, dsum[hh].w};
+          const f32x4 dp = mfma32(gf, vop[hh], nd);
+          df.u[0] = pack_bf16x2(__uint_as_float(w.x << 16) * dp[0], __uint_as_float(w.x & 0xffff0000u) * dp[1]);
+          df.u[1] = pack_bf16x2(__uint_as_float(w.y << 16) * dp[2], __uint_as_float(w.y & 0xffff0000u) * dp[3]);
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt) {
             // operand A: lane (channel 16dt + r, queries 4g..4g+3) of q and dout, by the transposing LDS read
@@ -610,26 +640,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             dv[hh][dt] = mfma16(gT, pf, dv[hh][dt]);
           }
         }
+        load_dsum(next);
         wave_lds_sync();  // the next item clears the tile
       };
       // Two items in flight.  Every load is issued unconditionally in straight-line code (an index past
       // the end repeats the last item): a load under a condition makes the compiler wait for all
       // outstanding loads where the paths join.
       KeyItem<HG> A, B;
+      load_dsum(0);
       fetch(0, A);
       int i = 0;
       for (; i + 2 < nb; i += 2) {
         fetch(i + 1, B);
-        compute(A);
+        compute(A, i + 1);
         fetch(i + 2, A);
-        compute(B);
+        compute(B, i + 2);
       }
       if (i + 1 < nb) {
         fetch(i + 1, B);
-        compute(A);
-        compute(B);
+        compute(A, i + 1);
+        compute(B, i + 2);
       } else {
-        compute(A);
+        compute(A, i + 1);
       }
     }
     // dk / dv rows cross through LDS the other way: lane (token r, channels 16dt + 4g..+3 of head hh)
@@ -712,7 +744,8 @@ bool pla_bwd_cluster_rel_sums(int R) { return (2 * R + 1) * (2 * R + 1) <= kRelC
 
 size_t pla_bwd_cluster_workspace_bytes(int B, int N, int H, int K, int S, int M) {
   const PlanLayout L = make_plan_layout(B, N, K, S, M);
-  return plan_align((size_t)L.strips * H * L.places * sizeof(uint32_t)) +  // (p, dS) words
+  return plan_align((size_t)L.strips * H * L.places * sizeof(bf16_t)) +  // p in run order
+         plan_align((size_t)L.strips * H * 16 * sizeof(float)) +         // D of every query
          plan_align((size_t)L.strips * H * 2 * kD * sizeof(float));        // parts of the blank gradients
 }
 
@@ -733,12 +766,14 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
   p.scale = a.scale;
   p.dq = (bf16_t*)a.dq; p.dk = (bf16_t*)a.dk; p.dv = (bf16_t*)a.dv;
-  p.pd = static_cast<uint32_t*>(workspace);
+  const size_t ph_bytes = plan_align((size_t)L.strips * a.H * L.places * sizeof(bf16_t));
+  const size_t dsum_bytes = plan_align((size_t)L.strips * a.H * 16 * sizeof(float));
+  p.ph = static_cast<bf16_t*>(workspace);
+  p.dsum = reinterpret_cast<float*>(static_cast<char*>(workspace) + ph_bytes);
   p.ds = (bf16_t*)a.dbias;
   p.k_blank = (const bf16_t*)a.k_blank; p.v_blank = (const bf16_t*)a.v_blank;
   p.blank_part = (a.k_blank && a.dk_blank)
-                     ? reinterpret_cast<float*>(static_cast<char*>(workspace) +
-                                                plan_align((size_t)L.strips * a.H * L.places * sizeof(uint32_t)))
+                     ? reinterpret_cast<float*>(static_cast<char*>(workspace) + ph_bytes + dsum_bytes)
                      : nullptr;
 
   p.coords = a.rel_coords; p.rel_table = (const bf16_t*)a.rel_table; p.R = a.rel_R; p.rate = a.rel_rate;
