@@ -154,14 +154,8 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int rd_chunk = tile_chunk(r, g);
   const size_t strip_rows = (size_t)tok0 * p.H * K;  // first element of the strip's [token, head, :] rows
 
-  // entry values of the strip in run order, two consecutive places per lane and round
+  // entry values of the strip in run order, two consecutive places per lane and round (loaded late in each pass)
   constexpr int SR = VEC ? NT * 4 + 1 : NT / 2 + 1;
-  uint32_t sp[SR];
-#pragma unroll
-  for (int t = 0; t < SR; ++t) {
-    const int w = t * 2 * kWave + 2 * lane;
-    sp[t] = (w < p.places) ? *reinterpret_cast<const uint32_t*>(p.sorted_pos + (size_t)sg * p.places + w) : 0xffffffffu;
-  }
   {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
     {  // the strip's rows cross through LDS like the K/V rows
@@ -388,6 +382,14 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         compute_pair(pr, kf, vf, kt);
       }
       stage_pair(sk0, sv0, sk1, sv1, kf, vf, kt);
+      // The run-order entry values are needed after the last pair only: their loads fly during its math, in
+      // the registers that the staged K/V rows have just left.
+      uint32_t sp[SR];
+#pragma unroll
+      for (int t = 0; t < SR; ++t) {
+        const int w = t * 2 * kWave + 2 * lane;
+        sp[t] = (w < p.places) ? *reinterpret_cast<const uint32_t*>(p.sorted_pos + (size_t)sg * p.places + w) : 0xffffffffu;
+      }
       compute_pair(npairs - 1, kf, vf, kt);
       wave_lds_sync();
       // REL: dS of this pass's real pairs, added to their bins
