@@ -41,6 +41,7 @@ struct BwdParams {
   const uint16_t *sorted_pos, *runs;
   int N, H, K, strips, strips_per_image, slot_stride, max_slots, runs_stride, places;
   uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
+  uint32_t h_magic, spi_magic;  // ... of H and of strips_per_image
   float scale;
   bf16_t *dq, *dk, *dv;
   bf16_t* ds;    // [B,N,H,K] dS = dbias, or nullptr when the caller does not want it
@@ -96,14 +97,14 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int g = lane >> 4, r = lane & 15;
   // one wave per (strip, head): the heads of a strip sit in neighbouring waves and share cache lines
   const int unit = xcd_contiguous_block() * 4 + wave;
-  const int sg = unit / p.H;
+  const int sg = exact_div(unit, p.H, p.h_magic);
   const int h = unit - sg * p.H;
   if (sg >= p.strips) return;  // wave-uniform; no workgroup barrier in this kernel
   uint32_t* pdtile = pd_all[wave];
   bf16_t* halves = reinterpret_cast<bf16_t*>(pdtile);  // [2 * cell] low half, [2 * cell + 1] high half
   constexpr uint32_t kSpare = kSlotCapB * 256u;
   if (lane == 0) pdtile[kSpare] = 0u;  // (ordered before its first read by the fences of the passes)
-  const int b = sg / p.strips_per_image;
+  const int b = exact_div(sg, p.strips_per_image, p.spi_magic);
   const long long img_base = (long long)b * p.N;
   const long long tok0 = (long long)sg * 16;
   const int C = p.H * kD;
@@ -503,7 +504,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   if (kt >= p.strips) return;
   bf16_t* tile = tile_all[wave];
   u32x4* rows = rows_all[wave];
-  const int b = kt / p.strips_per_image;
+  const int b = exact_div(kt, p.strips_per_image, p.spi_magic);
   const int C = p.H * kD;
   const size_t strip_base = (size_t)b * p.strips_per_image;
   const int lo = __builtin_amdgcn_readfirstlane(p.rev_offset[kt]);
@@ -784,6 +785,8 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   const dim3 grid_q((((long long)L.strips * a.H + 3) / 4 + 7) / 8 * 8);  // one wave per (strip, head)
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
+  p.h_magic = div_magic(a.H);
+  p.spi_magic = div_magic(a.N / 16);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0) &&
                    (!p.ds || reinterpret_cast<uintptr_t>(p.ds) % 16 == 0);
 #define AFFMAE_BWDQ(KERNEL, NT) \

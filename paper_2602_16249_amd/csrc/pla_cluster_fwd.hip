@@ -35,6 +35,7 @@ struct FwdParams {
   const uint16_t *slots, *entries;
   int N, H, K, strips, strips_per_image, slot_stride;
   uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
+  uint32_t h_magic, spi_magic;  // ... of H and of strips_per_image
   float scale;
   // bias from a relative-position table (REL kernels): token coordinates [B,N,2], table [H][2R+1][2R+1]
   const float* coords;
@@ -71,11 +72,11 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   const int blk = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   // one wave per (strip, head): the heads of a strip sit in neighbouring waves and share cache lines
   const int unit = blk * kFwdWaves + wave;
-  const int sg = unit / p.H;
+  const int sg = exact_div(unit, p.H, p.h_magic);
   const int h = unit - sg * p.H;
   if (sg >= p.strips) return;  // wave-uniform; the kernel has no workgroup barrier
   bf16_t* scratch = scratch_all[wave];
-  const int b = sg / p.strips_per_image;
+  const int b = exact_div(sg, p.strips_per_image, p.spi_magic);
   const long long img_base = (long long)b * p.N;
   const long long tok0 = (long long)sg * 16;
   const int C = p.H * kD;
@@ -384,6 +385,8 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   p.coords = a.rel_coords; p.rel_table = (const bf16_t*)a.rel_table; p.R = a.rel_R; p.rate = a.rel_rate;
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
+  p.h_magic = div_magic(a.H);
+  p.spi_magic = div_magic(a.N / 16);
   // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
   const dim3 grid((((long long)L.strips * a.H + kFwdWaves - 1) / kFwdWaves + 7) / 8 * 8);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);
