@@ -7,7 +7,7 @@
 // The plan (built by pla_plan.hip from the neighbour table) describes, per
 // strip, which token tiles hold at least one neighbour of one of its queries
 // ("slots", at most kMaxSlots) and, for every (query, neighbour slot j), where
-// that neighbour sits: entry = slot * 256 + query * 16 + (token % 16).
+// that neighbour sits: entry = slot * 256 + tile_cell(query, token % 16) (see tile_cell below).
 #pragma once
 
 #include "device_util.h"
@@ -95,6 +95,19 @@ inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   off += plan_align((size_t)L.strips * max_slots * sizeof(uint64_t));
   L.total = off;
   return L;
+}
+
+// Cells of a 16 x 16 (query, token) tile in LDS sit at query * 16 + (token ^ (f(query) << 2)), f(q) = ((q >> 1) & 3) ^
+// (q >> 3), and the plan's entries carry the cell in this form.  A lane of the MFMA layouts reads the four cells of
+// tokens 4g..4g+3 of query r as one piece of 8 bytes (bf16 cells) or 16 bytes (word cells), and LDS serves such
+// reads 16, respectively 8, consecutive lanes at a time: without the XOR the pieces of queries r, r + 4, r + 8, ...
+// (r, r + 2, ...) start on the same bank, a four-way conflict on every access; with it both widths are spread
+// over all 32 banks.  The XOR only permutes groups of four tokens, so a piece still holds tokens 4g'..4g'+3.
+__device__ __forceinline__ int cell_group_swizzle(int q) { return ((q >> 1) & 3) ^ (q >> 3); }  // q in 0..15
+__device__ __forceinline__ int tile_cell(int q, int tok) { return q * 16 + (tok ^ (cell_group_swizzle(q) << 2)); }
+// token of a cell value (low byte of an entry)
+__device__ __forceinline__ uint32_t cell_token(uint32_t cell) {
+  return (cell & 15u) ^ (((((cell >> 5) & 3u) ^ ((cell >> 7) & 1u))) << 2);
 }
 
 // Division of a non-negative int by a small run-time constant through a 32-bit reciprocal (exact for the

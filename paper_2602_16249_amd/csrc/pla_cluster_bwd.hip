@@ -95,6 +95,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
+  const int lane_cell = tile_cell(r, 4 * g);  // the lane's piece of a 16 x 16 tile: row r, columns 4g..4g+3
   // one wave per (strip, head): the heads of a strip sit in neighbouring waves and share cache lines
   const int unit = xcd_contiguous_block() * 4 + wave;
   const int sg = exact_div(unit, p.H, p.h_magic);
@@ -290,7 +291,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             uint32_t bits;
             if (REL) {
               // (an entry outside the pass reads some coordinate pair of the tile area: any value gives a cell of the table)
-              const float2 cn = cxy[((rel >> 4) & 0xf0u) | (rel & 0xfu)];
+              const float2 cn = cxy[((rel >> 4) & 0xf0u) | cell_token(rel)];
               const int cell = relpos_cell(cn, make_float2(__uint_as_float(bw[t][0]), __uint_as_float(bw[t][EW > 1 ? 1 : 0])), p.rate, p.R);
               bits = *reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(tab) + (uint32_t)cell * 2u);
               if (SUMS) cells[SUMS ? t : 0][SUMS ? (e >> 2) : 0] |= (rel < span ? (uint32_t)cell : 0u) << (8 * (e & 3));
@@ -353,7 +354,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             const f32x4 st = mfma32(kf[tt], qf, z);   // <k[token 4g+i], q[query r]>
             const f32x4 dpt = mfma32(vf[tt], gf, z);  // <v[token 4g+i], dout[query r]>
-            uint32_t* cell = pdtile + (2 * pr + tt) * 256 + r * 16 + g * 4;
+            uint32_t* cell = pdtile + (2 * pr + tt) * 256 + lane_cell;
             const uint4 bm = *reinterpret_cast<const uint4*>(cell);
             float pv[4], dsv[4];
             pv[0] = __builtin_amdgcn_exp2f(fmaf(fmaf(st[0], p.scale, __uint_as_float(bm.x << 16)), kLog2e, nl2));
@@ -500,6 +501,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
+  const int lane_cell = tile_cell(r, 4 * g);  // the lane's piece of a 16 x 16 tile: row r, columns 4g..4g+3
   const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
   if (kt >= p.strips) return;
   bf16_t* tile = tile_all[wave];
@@ -611,7 +613,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
           for (int half = 0; half < 2; ++half) {
             const uint32_t c = (it.code[rr] >> (16 * half)) & 0xffffu;  // query * 16 + token % 16 in the low byte
             if (c != kNoEntry) {
-              const uint32_t cell = ((c & 15u) << 4) | ((c >> 4) & 15u);
+              const uint32_t cell = (uint32_t)tile_cell((int)cell_token(c), (int)((c >> 4) & 15u));  // [token][query], same XOR
 #pragma unroll
               for (int hh = 0; hh < HG; ++hh) tile[hh * 256 + cell] = (bf16_t)(half ? it.w[rr][hh] >> 16 : it.w[rr][hh] & 0xffffu);
             }
@@ -621,7 +623,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 #pragma unroll
         for (int hh = 0; hh < HG; ++hh) {
           Frag4 pf, df;  // operand B of the 16x16x16 MFMA: lane (token r, queries 4g..4g+3)
-          const uint2 w = *reinterpret_cast<const uint2*>(tile + hh * 256 + r * 16 + g * 4);  // p[token r][queries 4g..]
+          const uint2 w = *reinterpret_cast<const uint2*>(tile + hh * 256 + lane_cell);  // p[token r][queries 4g..]
           pf.u[0] = w.x;
           pf.u[1] = w.y;
           Frag8 gf;  // lane (query r, channels 8g..8g+7) of dout

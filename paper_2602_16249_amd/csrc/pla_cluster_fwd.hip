@@ -138,6 +138,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   u32x4* kv = kv_all[wave];
   const int wr_chunk = tile_chunk(la, lc);
   const int rd_chunk = tile_chunk(r, g);
+  const int lane_cell = tile_cell(r, 4 * g);  // the lane's piece of a bias tile: query r, tokens 4g..4g+3
   // V^T operand of P.V, lane (channel 16 dt + r, tokens 4g..4g+3): read from the staged row-major V tile by the
   // transposing LDS read; this lane addresses the quarter (r % 4) of the 16 channels of token 4g + r / 4
   int vt_off[2];  // byte offsets inside a staged tile
@@ -187,7 +188,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
           uint32_t bits;
           if (REL) {
             // (an entry outside the pass reads some coordinate pair of the tile area: any value gives a cell of the table)
-            const float2 cn = cxy[((rel >> 4) & 0xf0u) | (rel & 0xfu)];
+            const float2 cn = cxy[((rel >> 4) & 0xf0u) | cell_token(rel)];
             const int cell = relpos_cell(cn, make_float2(__uint_as_float(bw[t][0]), __uint_as_float(bw[t][EW > 1 ? 1 : 0])), p.rate, p.R);
             bits = *reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(tab) + (uint32_t)cell * 2u);
           } else {
@@ -240,7 +241,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         for (int tt = 0; tt < 2; ++tt) {
           f32x4 st = {0.f, 0.f, 0.f, 0.f};
           st = mfma32(kf[tt], qf, st);  // st[i] = <k[token 4g+i], q[query r]>
-          const uint2 bm = *reinterpret_cast<const uint2*>(scratch + (2 * pr + tt) * 256 + r * 16 + g * 4);
+          const uint2 bm = *reinterpret_cast<const uint2*>(scratch + (2 * pr + tt) * 256 + lane_cell);
           s[4 * tt + 0] = fmaf(st[0], p.scale, __uint_as_float(bm.x << 16));
           s[4 * tt + 1] = fmaf(st[1], p.scale, __uint_as_float(bm.x & 0xffff0000u));
           s[4 * tt + 2] = fmaf(st[2], p.scale, __uint_as_float(bm.y << 16));

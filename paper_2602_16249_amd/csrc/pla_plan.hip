@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
     if (e < nent) {
       if (ct[t] >= 0) {
         const int slot = __popcll(mask & ((1ull << ct[t]) - 1ull));
-        off[t] = (uint32_t)(slot * 256 + fast_div(e, p.k_magic) * 16 + (tok[t] & 15));
+        off[t] = (uint32_t)(slot * 256 + tile_cell(fast_div(e, p.k_magic), tok[t] & 15));
       }
       ent[e] = (uint16_t)off[t];
     }
