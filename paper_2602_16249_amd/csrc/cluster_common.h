@@ -97,17 +97,17 @@ inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   return L;
 }
 
-// Cells of a 16 x 16 (query, token) tile in LDS sit at query * 16 + (token ^ (f(query) << 2)), f(q) = ((q >> 1) & 3) ^
-// (q >> 3), and the plan's entries carry the cell in this form.  A lane of the MFMA layouts reads the four cells of
-// tokens 4g..4g+3 of query r as one piece of 8 bytes (bf16 cells) or 16 bytes (word cells), and LDS serves such
-// reads 16, respectively 8, consecutive lanes at a time: without the XOR the pieces of queries r, r + 4, r + 8, ...
-// (r, r + 2, ...) start on the same bank, a four-way conflict on every access; with it both widths are spread
-// over all 32 banks.  The XOR only permutes groups of four tokens, so a piece still holds tokens 4g'..4g'+3.
-__device__ __forceinline__ int cell_group_swizzle(int q) { return ((q >> 1) & 3) ^ (q >> 3); }  // q in 0..15
+// Cells of a 16 x 16 (query, token) tile in LDS sit at query * 16 + (token ^ (f(query) << 2)), f(q) = (q >> 1) & 3,
+// and the plan's entries carry the cell in this form.  A lane of the MFMA layouts reads or writes the four cells of
+// tokens 4g..4g+3 of query r as one piece of 8 bytes (bf16 cells) or 16 bytes (word cells); without the XOR the
+// pieces of several queries start on the same banks (measured per 16-byte access of a wave, 16 waves per CU: write
+// 32 cycles without, 13.6 with; read 8.2 without, 5.6 with this f, 8.2 with f = ((q >> 1) & 3) ^ (q >> 3)).  The
+// XOR only permutes groups of four tokens, so a piece still holds tokens 4g'..4g'+3.
+__device__ __forceinline__ int cell_group_swizzle(int q) { return (q >> 1) & 3; }  // q in 0..15
 __device__ __forceinline__ int tile_cell(int q, int tok) { return q * 16 + (tok ^ (cell_group_swizzle(q) << 2)); }
 // token of a cell value (low byte of an entry)
 __device__ __forceinline__ uint32_t cell_token(uint32_t cell) {
-  return (cell & 15u) ^ (((((cell >> 5) & 3u) ^ ((cell >> 7) & 1u))) << 2);
+  return (cell & 15u) ^ (((cell >> 5) & 3u) << 2);
 }
 
 // Division of a non-negative int by a small run-time constant through a 32-bit reciprocal (exact for the
@@ -147,10 +147,11 @@ __device__ __forceinline__ float group_sum(float x) {
 }
 
 // Place, in 16-byte pieces, of piece `piece` (0..3) of row `row` (0..15) in a 1 KB LDS tile of 16 rows
-// of 64 bytes.  The XOR keeps both access patterns of the kernels free of bank conflicts: lane (row
-// lane/4, piece lane%4), and lane (row lane%16, piece lane/16).
+// of 64 bytes.  The XOR spreads both access patterns of the kernels over the banks: lane (row lane/4, piece
+// lane%4) writes (13.6 cycles per access whatever the XOR), lane (row lane%16, piece lane/16) reads (5.6 cycles
+// with this XOR, 8.2 without).
 __device__ __forceinline__ int tile_chunk(int row, int piece) {
-  return row * 4 + (piece ^ (((row >> 1) & 3) ^ ((row >> 3) & 1)));
+  return row * 4 + (piece ^ ((row >> 1) & 3));
 }
 
 // ds_read_b64_tr_b16: inside a group of 16 lanes, lanes 4j..4j+3 address the four 8-byte quarters of a row j of
