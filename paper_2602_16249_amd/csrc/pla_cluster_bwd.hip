@@ -486,7 +486,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // key-stationary kernel
 template <int HG>
 struct KeyItem {
-  u32x4 qs[HG], gs[HG];  // strip's q and dout rows of the head group as loaded: lane (row i*16/HG + lane/(4 HG), piece lane%(4 HG))
   uint32_t w[2][HG];     // p of places 2*lane, 2*lane+1 (+128 in the second round) of the run, two bf16 halves
   uint32_t code[2];      // their entry values, two 16-bit halves
   uint32_t len;          // places in the run (wave-uniform)
@@ -497,7 +496,10 @@ struct KeyItem {
 template <int HG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
   __shared__ __align__(16) bf16_t tile_all[4][HG * 256];  // per wave and head: p[token][query]
-  __shared__ __align__(16) u32x4 rows_all[4][2 * HG * 64];  // per wave: the strip's q rows, then its dout rows
+  // per wave, twice (two incidences in flight): the strip's q rows, then its dout rows.  They come straight from
+  // memory (global_load_lds: 16 bytes per lane, lane l's piece landing at 16 l; no registers, no LDS write
+  // instructions), so each lane fetches the piece that belongs in its place of the swizzled tile.
+  __shared__ __align__(16) u32x4 rows_all[4][2][2 * HG * 64];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
@@ -505,7 +507,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
   if (kt >= p.strips) return;
   bf16_t* tile = tile_all[wave];
-  u32x4* rows = rows_all[wave];
+  u32x4* rows0 = rows_all[wave][0];
+  u32x4* rows1 = rows_all[wave][1];
   const int b = exact_div(kt, p.strips_per_image, p.spi_magic);
   const int C = p.H * kD;
   const size_t strip_base = (size_t)b * p.strips_per_image;
@@ -524,6 +527,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   for (int i = 0; i < HG; ++i) {
     const int row = i * (64 / PR) + la;
     wr_chunk[i] = row * PR + (lc ^ swz(row));
+  }
+  // element offset, within the strip's rows, of the piece this lane fetches in load i: row i * 64 / PR + la, and
+  // the piece whose place in the tile is lc, i.e. piece lc ^ swz(row)
+  uint32_t q_dma[HG];
+#pragma unroll
+  for (int i = 0; i < HG; ++i) {
+    const int row = i * (64 / PR) + la;
+    q_dma[i] = (uint32_t)(row * C + ((lc ^ swz(row)) * 8));
   }
   // what this lane gives to lds_read_tr to receive, for channel 16dt + r of head hh, the values of rows (queries)
   // 4g..4g+3: the quarter r % 4 of those 16 channels in row 4g + r / 4
@@ -563,17 +574,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
       const uint32_t mine_lo = (uint32_t)mine, mine_hi = (uint32_t)(mine >> 32);
       // all loads of one item, nothing else: what is done with the words waits until compute(), so that
       // no use of a loaded value sits between the loads of one item and the math of the previous one
-      auto fetch = [&](int i, KeyItem<HG>& it) {
+      auto fetch = [&](int i, KeyItem<HG>& it, u32x4* rows) {
         const uint32_t inc = __builtin_amdgcn_readlane(mine_lo, i);
         const uint32_t run = __builtin_amdgcn_readlane(mine_hi, i);
         const size_t sgq = strip_base + (inc >> 8);
         const uint32_t start = run & 0xffffu;
         it.len = run >> 16;
         const size_t qbase = sgq * 16 * C + (size_t)(hg * kD);
+        typedef const __attribute__((address_space(1))) void* gptr_t;
+        typedef __attribute__((address_space(3))) void* lptr_t;
 #pragma unroll
         for (int i = 0; i < HG; ++i) {  // load i: rows i * 64 / PR onwards
-          it.qs[i] = *reinterpret_cast<const u32x4*>(p.q + qbase + (size_t)(i * (64 / PR)) * C + q_lane);
-          it.gs[i] = *reinterpret_cast<const u32x4*>(p.dout + qbase + (size_t)(i * (64 / PR)) * C + q_lane);
+          __builtin_amdgcn_global_load_lds((gptr_t)(p.q + qbase + q_dma[i]), (lptr_t)(rows + i * 64), 16, 0, 0);
+          __builtin_amdgcn_global_load_lds((gptr_t)(p.dout + qbase + q_dma[i]), (lptr_t)(rows + HG * 64 + i * 64), 16, 0, 0);
         }
         // runs start at even places and the rows hold an even number of places: aligned pairs
         const uint16_t* codes = p.sorted_pos + sgq * p.places + start;
@@ -598,12 +611,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         for (int hh = 0; hh < HG; ++hh)
           dsum[hh] = *reinterpret_cast<const float4*>(p.dsum + (sgq * p.H + hg + hh) * 16 + g * 4);
       };
-      auto compute = [&](const KeyItem<HG>& it, int next) {
-#pragma unroll
-        for (int i = 0; i < HG; ++i) {
-          rows[wr_chunk[i]] = it.qs[i];
-          rows[HG * 64 + wr_chunk[i]] = it.gs[i];
-        }
+      auto compute = [&](const KeyItem<HG>& it, const u32x4* rows, int next) {
         // spread the run over the tile: cell [token][query] <- p; unlisted cells stay 0 (hence dS = 0 there)
 #pragma unroll
         for (int hh = 0; hh < HG; ++hh) *reinterpret_cast<uint2*>(tile + hh * 256 + lane * 4) = make_uint2(0u, 0u);
@@ -646,6 +654,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
           }
         }
         load_dsum(next);
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): every read of this item's rows has returned (they may be refilled)
         wave_lds_sync();  // the next item clears the tile
       };
       // Two items in flight.  Every load is issued unconditionally in straight-line code (an index past
@@ -653,20 +662,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
       // outstanding loads where the paths join.
       KeyItem<HG> A, B;
       load_dsum(0);
-      fetch(0, A);
+      fetch(0, A, rows0);
       int i = 0;
       for (; i + 2 < nb; i += 2) {
-        fetch(i + 1, B);
-        compute(A, i + 1);
-        fetch(i + 2, A);
-        compute(B, i + 2);
+        fetch(i + 1, B, rows1);
+        compute(A, rows0, i + 1);
+        fetch(i + 2, A, rows0);  // compute(A) has consumed every read of rows0 (its MFMAs are issued)
+        compute(B, rows1, i + 2);
       }
       if (i + 1 < nb) {
-        fetch(i + 1, B);
-        compute(A, i + 1);
-        compute(B, i + 2);
+        fetch(i + 1, B, rows1);
+        compute(A, rows0, i + 1);
+        compute(B, rows1, i + 2);
       } else {
-        compute(A, i + 1);
+        compute(A, rows0, i + 1);
       }
     }
     // dk / dv rows cross through LDS the other way: lane (token r, channels 16dt + 4g..+3 of head hh)
@@ -679,18 +688,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         uint2 o;
         o.x = pack_bf16x2(dk[hh][dt][0] * p.scale, dk[hh][dt][1] * p.scale);
         o.y = pack_bf16x2(dk[hh][dt][2] * p.scale, dk[hh][dt][3] * p.scale);
-        reinterpret_cast<uint2*>(rows)[at] = o;
+        reinterpret_cast<uint2*>(rows0)[at] = o;
         o.x = pack_bf16x2(dv[hh][dt][0], dv[hh][dt][1]);
         o.y = pack_bf16x2(dv[hh][dt][2], dv[hh][dt][3]);
-        reinterpret_cast<uint2*>(rows + HG * 64)[at] = o;
+        reinterpret_cast<uint2*>(rows0 + HG * 64)[at] = o;
       }
     }
     wave_lds_sync();
 #pragma unroll
     for (int i = 0; i < HG; ++i) {
       const size_t at = ((size_t)kt * 16 + i * (64 / PR)) * C + (size_t)(hg * kD) + q_lane;
-      *reinterpret_cast<u32x4*>(p.dk + at) = rows[wr_chunk[i]];
-      *reinterpret_cast<u32x4*>(p.dv + at) = rows[HG * 64 + wr_chunk[i]];
+      *reinterpret_cast<u32x4*>(p.dk + at) = rows0[wr_chunk[i]];
+      *reinterpret_cast<u32x4*>(p.dv + at) = rows0[HG * 64 + wr_chunk[i]];
     }
     wave_lds_sync();
   }
