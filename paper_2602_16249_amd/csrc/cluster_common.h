@@ -113,14 +113,15 @@ __device__ __forceinline__ uint32_t cell_token(uint32_t cell) {
 // Division of a non-negative int by a small run-time constant through a 32-bit reciprocal (exact for the
 // ranges used here: n * d < 2^31).  The reciprocal of 1 does not fit 32 bits: magic 0 stands for it.
 __device__ __forceinline__ int fast_div(int n, uint32_t magic) {
-  return magic ? (int)__umulhi((uint32_t)n, magic) : n;
+  // (a sum, not a choice between the two: the choice on a uniform magic becomes a branch at every use)
+  return (int)(__umulhi((uint32_t)n, magic) + (magic == 0u ? (uint32_t)n : 0u));
 }
 inline uint32_t div_magic(int d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / (uint32_t)d) + 1u; }
 // The same for any non-negative n and d >= 1: the reciprocal is rounded up, so the quotient it gives is at most
 // one too large; one multiplication checks it.  (The compiler's own division by a run-time value is a chain of
 // ~30 dependent instructions through the reciprocal unit, at the head of every wave.)
 __device__ __forceinline__ int exact_div(int n, int d, uint32_t magic) {
-  const uint32_t q = magic ? __umulhi((uint32_t)n, magic) : (uint32_t)n;
+  const uint32_t q = __umulhi((uint32_t)n, magic) + (magic == 0u ? (uint32_t)n : 0u);
   return (int)(q - (q * (uint32_t)d > (uint32_t)n ? 1u : 0u));
 }
 
