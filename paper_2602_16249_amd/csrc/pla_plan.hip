@@ -40,8 +40,10 @@ __global__ __launch_bounds__(256) void plan_zero_kernel(int32_t* a, int32_t* b, 
   }
 }
 
+// NE = entries per lane: 16 K / 64 rounded up to a multiple of 4 (the loops over a lane's entries are unrolled)
+template <int NE>
 __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
-  __shared__ uint16_t sorted_all[4][kMaxEntries * kWave + kMaxSlots];
+  __shared__ uint16_t sorted_all[4][NE * kWave + kMaxSlots];
   __shared__ int slot_count_all[4][kMaxSlots];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
@@ -59,10 +61,10 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
 
   // candidate-list tile of every (query, slot): m * (S/16) + (token % S) / 16
   const int near_v = (lane < p.M) ? near_c[lane] : -1;  // lane m: the m-th near cluster (M <= 64)
-  int ct[kMaxEntries], tok[kMaxEntries], ecl[kMaxEntries], where[kMaxEntries];
-  bool inr[kMaxEntries];
+  int ct[NE], tok[NE], ecl[NE], where[NE];
+  bool inr[NE];
 #pragma unroll
-  for (int t = 0; t < kMaxEntries; ++t) {
+  for (int t = 0; t < NE; ++t) {
     const int e = t * kWave + lane;
     const int n = (e < nent) ? nbr[e] : -1;
     const int nn = min(max(n, 0), p.N - 1);
@@ -74,11 +76,11 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   for (int m = 0; m < p.M; ++m) {  // the last match wins, as a scan of the list would have it
     const int cl = __builtin_amdgcn_readlane(near_v, m);
 #pragma unroll
-    for (int t = 0; t < kMaxEntries; ++t) where[t] = (ecl[t] == cl) ? m : where[t];
+    for (int t = 0; t < NE; ++t) where[t] = (ecl[t] == cl) ? m : where[t];
   }
   unsigned long long mask = 0;
 #pragma unroll
-  for (int t = 0; t < kMaxEntries; ++t) {
+  for (int t = 0; t < NE; ++t) {
     ct[t] = -1;
     if (inr[t] && where[t] >= 0) {
       ct[t] = where[t] * tiles_per_cluster + ((tok[t] - ecl[t] * p.S) >> 4);
@@ -89,9 +91,9 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   }
   mask = wave_or64(mask);
   uint16_t* ent = p.entries + (size_t)sg * nent;
-  uint32_t off[kMaxEntries];
+  uint32_t off[NE];
 #pragma unroll
-  for (int t = 0; t < kMaxEntries; ++t) {
+  for (int t = 0; t < NE; ++t) {
     const int e = t * kWave + lane;
     off[t] = kNoEntry;
     if (e < nent) {
@@ -120,11 +122,11 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   // out in rows.  Unused places hold kNoEntry.  Two sweeps over the lane's entries with LDS counters per slot:
   // count, then claim a place (the order inside a run is the order in which the wave's LDS atomics are served;
   // any order gives the same results downstream, where every entry is addressed by its own value).
-  for (int w = lane; w < kMaxEntries * kWave + kMaxSlots; w += kWave) sorted[w] = (uint16_t)kNoEntry;
+  for (int w = lane; w < NE * kWave + kMaxSlots; w += kWave) sorted[w] = (uint16_t)kNoEntry;
   if (lane < kMaxSlots) slot_count[lane] = 0;
   wave_lds_sync();
 #pragma unroll
-  for (int t = 0; t < kMaxEntries; ++t)
+  for (int t = 0; t < NE; ++t)
     if (off[t] != kNoEntry) atomicAdd(&slot_count[off[t] >> 8], 1);
   wave_lds_sync();
   uint16_t* runs = p.runs + (size_t)sg * p.runs_stride;
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   }
   wave_lds_sync();
 #pragma unroll
-  for (int t = 0; t < kMaxEntries; ++t)
+  for (int t = 0; t < NE; ++t)
     if (off[t] != kNoEntry) sorted[atomicAdd(&slot_count[off[t] >> 8], 1)] = (uint16_t)off[t];
   if (lane == 0) runs[count] = (uint16_t)place;
   wave_lds_sync();
@@ -267,7 +269,11 @@ hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, i
   const dim3 per_strip((L.strips + 3) / 4);
   AFFMAE_LAUNCH("plan_zero_kernel", stream, plan_zero_kernel, dim3((L.strips + 255) / 256), dim3(256), 0, stream,
                 p.rev_count, p.rev_cursor, L.strips);
-  AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel, per_strip, dim3(256), 0, stream, p);
+  const int ne = (16 * K + kWave - 1) / kWave;
+  if (ne <= 4) AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel<4>, per_strip, dim3(256), 0, stream, p);
+  else if (ne <= 8) AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel<8>, per_strip, dim3(256), 0, stream, p);
+  else if (ne <= 12) AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel<12>, per_strip, dim3(256), 0, stream, p);
+  else AFFMAE_LAUNCH("pla_plan_kernel", stream, pla_plan_kernel<kMaxEntries>, per_strip, dim3(256), 0, stream, p);
   AFFMAE_LAUNCH("plan_scan_kernel", stream, plan_scan_kernel, dim3((L.strips + 1023) / 1024), dim3(256), 0, stream,
                 p.rev_count, p.rev_offset, L.strips);
   AFFMAE_LAUNCH("plan_fill_kernel", stream, plan_fill_kernel, per_strip, dim3(256), 0, stream, p);
