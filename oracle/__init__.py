@@ -118,7 +118,8 @@ def vts_fwd(query_xy, vis_xy, feat, table, grid, p: float, eps: float, want_weig
 
 
 def vts_bwd(query_xy, vis_xy, feat, table, dout, grid, p: float, eps: float):
-    """Backward of vts_fwd -> dict(dfeat [B,Nv,C], dquery [B,Mq,2], dp float)."""
+    """Backward of vts_fwd -> dict(dfeat [B,Nv,C], dquery [B,Mq,2], dp float, dp_abs float = the sum of the
+    absolute per-query contributions to dp, a scale for judging errors of dp)."""
     query_xy = np.ascontiguousarray(query_xy, dtype=np.float32)
     vis_xy = np.ascontiguousarray(vis_xy, dtype=np.float32)
     feat = _f64(feat)
@@ -131,10 +132,11 @@ def vts_bwd(query_xy, vis_xy, feat, table, dout, grid, p: float, eps: float):
     dfeat = np.empty((B, Nv, C), dtype=np.float64)
     dq = np.empty((B, Mq, 2), dtype=np.float64)
     dp = ctypes.c_double(0.0)
+    dp_abs = ctypes.c_double(0.0)
     _check(_load().oracle_vts_bwd(_p(query_xy), _p(vis_xy), _p(feat), _p(table), _p(dout), B, Mq, Nv, C, Hg, Wg, x0, y0,
                                   cell, Kt, ctypes.c_double(p), ctypes.c_double(eps), _p(dfeat), _p(dq),
-                                  ctypes.byref(dp)), "oracle_vts_bwd")
-    return {"dfeat": dfeat, "dquery": dq, "dp": float(dp.value)}
+                                  ctypes.byref(dp), ctypes.byref(dp_abs)), "oracle_vts_bwd")
+    return {"dfeat": dfeat, "dquery": dq, "dp": float(dp.value), "dp_abs": float(dp_abs.value)}
 
 
 def centroids(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int) -> np.ndarray:

@@ -269,17 +269,19 @@ int oracle_vts_fwd(const float *query_xy, const float *vis_xy, const double *fea
  *   dfeat [B,Nv,C] += w_i dout;  with g_i = <dout, feat_i>, dz_i = w_i (g_i - sum_j w_j g_j):
  *   dquery [B,Mq,2] = sum_i dz_i (-p) (q - x_i) / |q - x_i|   (0 where q = x_i),
  *   dp (scalar, summed over all queries) = sum_i dz_i (-(|q - x_i| + eps)).
+ *   dp_abs (optional, a scale for judging errors of dp, no part of the method): the sum over the queries of the
+ *   absolute value of each query's contribution to dp.
  */
 int oracle_vts_bwd(const float *query_xy, const float *vis_xy, const double *feat, const int32_t *table,
                    const double *dout, int B, int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell,
-                   int Kt, double p, double eps, double *dfeat, double *dquery, double *dp) {
+                   int Kt, double p, double eps, double *dfeat, double *dquery, double *dp, double *dp_abs) {
   if (!query_xy || !vis_xy || !feat || !table || !dout || !dfeat || !dquery) return ORACLE_ERR_ARG;
   if (B < 0 || Mq <= 0 || Nv <= 0 || C <= 0 || Hg <= 0 || Wg <= 0 || Kt < 1 || Kt > 64 || !(cell > 0.f))
     return ORACLE_ERR_ARG;
   for (size_t t = 0; t < (size_t)B * Hg * Wg * Kt; ++t)
     if (table[t] < 0 || table[t] >= Nv) return ORACLE_ERR_ARG;
   for (size_t t = 0; t < (size_t)B * Nv * C; ++t) dfeat[t] = 0.0;
-  double dp_sum = 0.0;
+  double dp_sum = 0.0, dp_abs_sum = 0.0;
   for (int b = 0; b < B; ++b) {
     for (int m = 0; m < Mq; ++m) {
       const float qx = query_xy[((size_t)b * Mq + m) * 2], qy = query_xy[((size_t)b * Mq + m) * 2 + 1];
@@ -309,20 +311,23 @@ int oracle_vts_bwd(const float *query_xy, const float *vis_xy, const double *fea
         }
         gbar += w[i] * g[i];
       }
-      double dqx = 0.0, dqy = 0.0;
+      double dqx = 0.0, dqy = 0.0, dp_query = 0.0;
       for (int i = 0; i < Kt; ++i) {
         const double dz = w[i] * (g[i] - gbar);
         if (dist[i] > 0.0) {
           dqx += dz * (-p) * dxs[i] / dist[i];
           dqy += dz * (-p) * dys[i] / dist[i];
         }
-        dp_sum += dz * (-(dist[i] + eps));
+        dp_query += dz * (-(dist[i] + eps));
       }
+      dp_sum += dp_query;
+      dp_abs_sum += fabs(dp_query);
       dquery[((size_t)b * Mq + m) * 2] = dqx;
       dquery[((size_t)b * Mq + m) * 2 + 1] = dqy;
     }
   }
   if (dp) *dp = dp_sum;
+  if (dp_abs) *dp_abs = dp_abs_sum;
   return ORACLE_OK;
 }
 

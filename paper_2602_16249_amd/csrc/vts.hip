@@ -377,12 +377,23 @@ __global__ __launch_bounds__(256) void vts_bwd_kernel(const float* __restrict__ 
     const float gi = wave_sum(part);
     if (lane == i) g_mine = gi;
   }
-  const float gbar = wave_sum(cd.w * g_mine);  // lanes >= Kt hold weight 0
-  const float dz = cd.w * (g_mine - gbar);
+  // dz_i = w_i (g_i - sum_j w_j g_j) = w_i sum_j w_j (g_i - g_j): the differences are taken first.  When one weight
+  // is close to 1 the first form subtracts two nearly equal numbers and leaves rounding noise of the size of
+  // eps |g| where the true value is of the size of (1 - w_i) |g_i - g_j|.
+  float spread = 0.f;
+  for (int j = 0; j < Kt; ++j) {
+    const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(cd.w), j));
+    const float gj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(g_mine), j));
+    spread = fmaf(wj, g_mine - gj, spread);
+  }
+  const float dz = cd.w * spread;  // lanes >= Kt hold weight 0
   const float inv = cd.dist > 0.f ? 1.f / cd.dist : 0.f;
   const float qx = wave_sum(dz * (-p) * cd.dx * inv);
   const float qy = wave_sum(dz * (-p) * cd.dy * inv);
-  const float dpv = wave_sum(lane < Kt ? dz * (-(cd.dist + eps)) : 0.f);
+  // sum_i dz_i (-(d_i + eps)) with sum_i dz_i = 0: the distances are taken relative to the nearest candidate's, so
+  // that the sum does not cancel terms of the size of |dz| d against a result of the size of |dz| (d_i - d_j)
+  const float dnear = -wave_max(lane < Kt ? -cd.dist : -INFINITY);
+  const float dpv = wave_sum(lane < Kt ? dz * (dnear - cd.dist) : 0.f);
   if (lane < Kt) {
     weights[(size_t)gq * Kt + lane] = cd.w;
     pair_token[(size_t)gq * Kt + lane] = b * Nv + cd.idx;
@@ -633,12 +644,25 @@ __global__ __launch_bounds__(256) void vts_bwdg_kernel(const float* __restrict__
       if (sub == i0 + u && sub < Kt) g_mine = gi;
     }
   }
-  const float gbar = Group<G>::sum(cd.w * g_mine);  // lanes past Kt hold weight 0
-  const float dz = cd.w * (g_mine - gbar);
+  // dz_i = w_i (g_i - sum_j w_j g_j) = w_i sum_j w_j (g_i - g_j), the differences taken first: when one weight is
+  // close to 1, g_i minus the weighted mean cancels to rounding noise of the size of eps |g|, while the true value is
+  // of the size of (1 - w_i) |g_i - g_j|.  Lanes past Kt hold weight 0 and add nothing.
+  float spread = 0.f;
+  for (int i0 = 0; i0 < Kt; i0 += 4) {
+    uint32_t wb[4], gb[4];
+    Group<G>::bcast4(__float_as_uint(cd.w), i0, wb);
+    Group<G>::bcast4(__float_as_uint(g_mine), i0, gb);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) spread = fmaf(__uint_as_float(wb[u]), g_mine - __uint_as_float(gb[u]), spread);
+  }
+  const float dz = cd.w * spread;
   const float inv = cd.dist > 0.f ? __builtin_amdgcn_rcpf(cd.dist) : 0.f;
   const float qx = Group<G>::sum(dz * (-p) * cd.dx * inv);
   const float qy = Group<G>::sum(dz * (-p) * cd.dy * inv);
-  const float dpv = Group<G>::sum(sub < Kt ? dz * (-(cd.dist + eps)) : 0.f);
+  // sum_i dz_i (-(d_i + eps)) with sum_i dz_i = 0: distances relative to the nearest candidate's, so that the sum
+  // does not cancel terms of the size of |dz| d against a result of the size of |dz| (d_i - d_j)
+  const float dnear = -Group<G>::max(sub < Kt ? -cd.dist : -INFINITY);
+  const float dpv = Group<G>::sum(sub < Kt ? dz * (dnear - cd.dist) : 0.f);
   if (ql.live && sub < Kt) {
     weights[(size_t)gq * Kt + sub] = cd.w;
     pair_token[(size_t)gq * Kt + sub] = b * Nv + cd.idx;

@@ -119,11 +119,11 @@ def test_clustering_and_sampling_replayed_from_a_graph():
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for name in ("order", "cluster_id", "table", "out", "dquery"):
+        # (dp is the sum of the waves' parts in a fixed order: bit-equal like everything but dfeat)
+        for name in ("order", "cluster_id", "table", "out", "dquery", "dp"):
             assert torch.equal(got[name], ref[name]), f"replay {rep}: {name} differs from the eager result"
         a, b = got["dfeat"].float(), ref["dfeat"].float()
         assert float((a - b).abs().max()) <= 2e-2 * float(b.abs().max()), f"replay {rep}: dfeat"
-        assert abs(float(got["dp"]) - float(ref["dp"])) <= 1e-3 * max(1.0, abs(float(ref["dp"])))
 
 
 def test_relative_position_attention_replayed_from_a_graph():

@@ -130,9 +130,10 @@ def test_sampling_forward_backward_match_oracle(dtype, B, Mq, Nv, C, Hg, Wg, Kt,
     tol = TOL[dtype]
     assert err(out, rout) <= tol
     assert err(g["dfeat"], rg["dfeat"]) <= tol
-    # dquery and dp are fp32 outputs formed from fp32 sums of products of the stored inputs
-    assert err(g["dquery"], rg["dquery"]) <= (1e-4 if dtype == "f32" else tol)
-    assert abs(float(g["dp"].cpu()) - rg["dp"]) <= (1e-4 if dtype == "f32" else tol) * max(abs(rg["dp"]), np.abs(rg["dquery"]).sum())
+    # dquery: the stated bound, max|err| / max|ref|.  dp is one scalar, the sum of one contribution per query with
+    # both signs: its error is judged against the sum of the absolute contributions (returned by the oracle).
+    assert err(g["dquery"], rg["dquery"]) <= tol
+    assert abs(float(g["dp"].cpu()) - rg["dp"]) <= tol * rg["dp_abs"]
 
 
 def test_decoder_shape_of_the_supplement():
