@@ -270,6 +270,7 @@ def main() -> int:
     attn_ms = fwd_ms + bwd_ms
 
     # per-kernel durations (HIP events around every launch, on the launch stream), same steps again
+    aff.use_timed_library(True)   # the instrumented build of the same sources; the product library has no timing
     aff.timing_enable(True)
     aff.timing_reset()
     for i in range(args.steps):
@@ -277,6 +278,7 @@ def main() -> int:
     torch.cuda.synchronize()
     kt = aff.timing_read()
     aff.timing_enable(False)
+    aff.use_timed_library(False)
     kernels = {n: {"avg_us": 1e3 * ms / max(c, 1), "launches_per_step": c / args.steps} for n, (ms, c) in kt.items()}
     attn_kernels = {n: v for n, v in kernels.items() if n.startswith("pla_") and "plan" not in n}
     elt = 2 if cfg.dtype == "bf16" else 4

@@ -22,6 +22,7 @@
  *     and return without synchronising.  Calls that share a workspace must be
  *     ordered on one stream.  No call allocates, frees or clears device memory
  *     through the runtime: a caller may record the calls into a HIP graph.
+ *     The library keeps no state between calls and may be called from several threads.
  *   - Return value: AFFMAE_OK (0) or a negative affmae_status.  When an error
  *     is returned nothing has been enqueued.  No exception crosses the ABI.
  *   - Outputs are fully overwritten (never accumulated into).
@@ -60,6 +61,11 @@ const char* affmae_status_string(int status);
 
 /* Library version as major*10000 + minor*100 + patch. */
 int affmae_version(void);
+
+/* Digest of the sources the library was built from (hex string, never NULL;
+ * "unstamped" when built without the package's build script).  Stored profiles
+ * carry it so that a reader can tell whether they describe this build. */
+const char* affmae_build_id(void);
 
 /*
  * affmae_cluster - balanced clustering (paper, Sec. "AutoFocusFormer": tokens
@@ -273,18 +279,6 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
                    const void* dout, int B, int N, int H, int d, int K, int S, int M, float scale,
                    int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank,
                    float* dv_blank, void* workspace, size_t workspace_bytes, void* stream);
-
-/*
- * Optional per-kernel timing, for benchmarks.  While enabled, every kernel the
- * library launches is bracketed by two HIP events on the launch stream.  The
- * read and reset calls synchronise the device.  Timing must stay disabled under
- * HIP graph capture.  Not thread-safe against concurrent launches.
- *   affmae_timing_read: fills the `index`-th entry (kernel name, total
- *   milliseconds, number of launches) if it exists; returns the entry count.
- */
-void affmae_timing_enable(int on);
-void affmae_timing_reset(void);
-int affmae_timing_read(int index, char* name, int name_len, double* total_ms, int* count);
 
 /*
  * affmae_pla_fwd_relpos / affmae_pla_bwd_relpos - local attention whose bias is

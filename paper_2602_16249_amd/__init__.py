@@ -17,12 +17,14 @@ from .binding import (  # noqa: F401
     affmae_vts_bwd,
     affmae_vts_fwd,
     affmae_vts_table,
+    build_id,
     library_path,
     load_library,
     status_string,
     timing_enable,
     timing_read,
     timing_reset,
+    use_timed_library,
 )
 
 __all__ = ["AffmaeError", "affmae_cluster", "affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd", "affmae_pla_plan", "affmae_pla_fwd_relpos", "affmae_pla_bwd_relpos", "affmae_vts_table", "affmae_vts_fwd", "affmae_vts_bwd", "library_path", "load_library",

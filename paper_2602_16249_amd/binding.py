@@ -14,7 +14,9 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libaffmae.so")
-_lib = None
+_LIB_TIMED_PATH = os.path.join(_HERE, "libaffmae_timed.so")  # instrumented twin (include/affmae_timing.h), benchmarks only
+_lib = None        # the library every call goes through
+_libs = {}         # path -> loaded library
 
 AFFMAE_F32 = 0
 AFFMAE_BF16 = 1
@@ -36,17 +38,32 @@ def library_path() -> str:
 
 
 def load_library():
-    """Load libaffmae.so (building it first only if it does not exist)."""
+    """The library in use: libaffmae.so unless use_timed_library(True) switched to the instrumented build
+    (built first only if it does not exist)."""
     global _lib
-    if _lib is not None:
-        return _lib
-    if not os.path.exists(_LIB_PATH):
+    if _lib is None:
+        _lib = _load(_LIB_PATH)
+    return _lib
+
+
+def use_timed_library(on: bool) -> None:
+    """Route every call through libaffmae_timed.so (per-kernel event timing compiled in) or back through
+    libaffmae.so.  For benchmarks."""
+    global _lib
+    _lib = _load(_LIB_TIMED_PATH if on else _LIB_PATH)
+
+
+def _load(path: str):
+    if path in _libs:
+        return _libs[path]
+    if not os.path.exists(path):
         from .build import build_library  # needs hipcc
         build_library()
-    lib = ctypes.CDLL(_LIB_PATH)
+    lib = ctypes.CDLL(path)
     lib.affmae_status_string.restype = ctypes.c_char_p
     lib.affmae_status_string.argtypes = [_c_int]
     lib.affmae_version.restype = _c_int
+    lib.affmae_build_id.restype = ctypes.c_char_p
     lib.affmae_cluster_workspace_bytes.restype = _c_size_t
     lib.affmae_cluster_workspace_bytes.argtypes = [_c_int] * 2
     lib.affmae_cluster.restype = _c_int
@@ -91,8 +108,13 @@ def load_library():
     lib.affmae_pla_plan_bytes.argtypes = [_c_int] * 5
     lib.affmae_pla_plan.restype = _c_int
     lib.affmae_pla_plan.argtypes = [_c_void_p, _c_void_p] + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]
-    _lib = lib
+    _libs[path] = lib
     return lib
+
+
+def build_id() -> str:
+    """Digest of the sources the loaded library was built from."""
+    return load_library().affmae_build_id().decode()
 
 
 def status_string(status: int) -> str:
@@ -467,17 +489,18 @@ def affmae_pla_bwd_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, coo
 
 
 def timing_enable(on: bool) -> None:
-    """Bracket every kernel launch of the library with HIP events (benchmarks only)."""
-    load_library().affmae_timing_enable(int(bool(on)))
+    """Bracket every kernel launch of the instrumented library with HIP events (benchmarks only; the calls must
+    go through it: use_timed_library(True))."""
+    _load(_LIB_TIMED_PATH).affmae_timing_enable(int(bool(on)))
 
 
 def timing_reset() -> None:
-    load_library().affmae_timing_reset()
+    _load(_LIB_TIMED_PATH).affmae_timing_reset()
 
 
 def timing_read() -> Dict[str, Tuple[float, int]]:
     """Per kernel name: (total milliseconds, launches) since the last reset."""
-    lib = load_library()
+    lib = _load(_LIB_TIMED_PATH)
     lib.affmae_timing_read.restype = _c_int
     out = {}
     n = lib.affmae_timing_read(-1, None, 0, None, None)

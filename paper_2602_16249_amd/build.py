@@ -5,6 +5,7 @@ travels with the source tree; nothing is installed.
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
@@ -13,6 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libaffmae.so")
+# the same sources with per-kernel event timing compiled in (include/affmae_timing.h): loaded by the benchmark only
+LIB_TIMED = os.path.join(HERE, "libaffmae_timed.so")
 
 ARCH = "gfx950"
 COMMON = ["--offload-arch=" + ARCH, "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -31,32 +34,53 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+def source_id() -> str:
+    """Hex digest over the library's sources (csrc/*.hip, csrc/*.h, include/*.h): compiled into the library
+    (affmae_build_id) so that stored profiles can be matched to the build they were taken from."""
+    h = hashlib.sha256()
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".h"))]
+    inc = os.path.join(HERE, "..", "include")
+    files += [os.path.join(inc, f) for f in sorted(os.listdir(inc)) if f.endswith(".h")]
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def _headers_mtime() -> float:
     hs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     hs.append(os.path.join(HERE, "..", "include", "affmae.h"))
+    hs.append(os.path.join(HERE, "..", "include", "affmae_timing.h"))
     return max(os.path.getmtime(h) for h in hs)
 
 
-def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+def _compile(src: str, force: bool, timed: bool = False) -> str:
+    obj = os.path.join(OBJ, src.replace(".hip", ".timed.o" if timed else ".o"))
     path = os.path.join(CSRC, src)
-    if not force and os.path.exists(obj) and os.path.getmtime(obj) >= max(os.path.getmtime(path), _headers_mtime()):
+    stamped = src == "api.hip"  # carries the digest of all sources: rebuilt whenever it is asked for
+    if (not force and not stamped and os.path.exists(obj)
+            and os.path.getmtime(obj) >= max(os.path.getmtime(path), _headers_mtime())):
         return obj
-    cmd = ["hipcc", "-c", path, "-o", obj] + COMMON + EXTRA.get(src, [])
+    cmd = ["hipcc", "-c", path, "-o", obj] + COMMON + EXTRA.get(src, []) + (["-DAFFMAE_TIMING"] if timed else [])
+    if stamped:
+        cmd.append('-DAFFMAE_BUILD_ID="%s"' % source_id())
     subprocess.run(cmd, check=True)
     return obj
 
 
 def build_library(force: bool = True, verbose: bool = False) -> str:
-    """Compile every .hip file and link libaffmae.so; returns its path."""
+    """Compile every .hip file and link libaffmae.so and its instrumented twin libaffmae_timed.so; returns the
+    path of the product library."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sources()
-    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), srcs))
-    cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=" + ARCH, "-o", LIB] + objs
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
+    jobs = [(s, False) for s in srcs] + [(s, True) for s in srcs]
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(lambda j: _compile(j[0], force, j[1]), jobs))
+    for lib, group in ((LIB, objs[:len(srcs)]), (LIB_TIMED, objs[len(srcs):])):
+        cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=" + ARCH, "-o", lib] + group
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True)
     return LIB
 
 

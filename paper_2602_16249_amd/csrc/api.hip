@@ -76,7 +76,12 @@ const char* affmae_status_string(int status) {
   }
 }
 
-int affmae_version(void) { return 100; }
+int affmae_version(void) { return 200; }
+
+#ifndef AFFMAE_BUILD_ID
+#define AFFMAE_BUILD_ID "unstamped"
+#endif
+const char* affmae_build_id(void) { return AFFMAE_BUILD_ID; }
 
 size_t affmae_cluster_workspace_bytes(int B, int N) {
   if (B < 1 || N < 1 || N > (1 << 24)) return 0;
@@ -224,10 +229,16 @@ size_t affmae_pla_fwd_workspace_bytes(int B, int N, int H, int d, int K, int S, 
   return 0;
 }
 
-int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
-                   const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank, int B,
-                   int N, int H, int d, int K, int S, int M, float scale, int dtype, void* out, float* lse,
-                   void* workspace, size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// affmae_pla_fwd: every check, then (with `launch`) the kernels.  Without `launch` it returns the status the call
+// would have up to its first launch: entry points that put kernels of their own in front of this one validate
+// with it first, so that an error never leaves work enqueued.
+int pla_fwd_run(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
+                const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank, int B,
+                int N, int H, int d, int K, int S, int M, float scale, int dtype, void* out, float* lse,
+                void* workspace, size_t workspace_bytes, void* stream, bool launch) {
   if (!q || !k || !v || !nbr_idx || !out || !lse) return AFFMAE_ERR_NULL;
   if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
   const int rc = check_pla_shape(B, N, H, d, K, dtype);
@@ -243,17 +254,33 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
   a.B = B; a.N = N; a.H = H; a.d = d; a.K = K; a.S = S; a.M = M; a.scale = scale; a.dtype = dtype;
   a.out = out; a.lse = lse; a.workspace = workspace;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (!affmae::pla_cluster_supported(a))
+  if (!affmae::pla_cluster_supported(a)) {
+    if (!launch) return AFFMAE_OK;
     return affmae::launch_pla_fwd_general(a, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+  }
   if (plan && misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
   if (!plan) {  // no cached plan: rebuild it in the workspace
     const size_t need = affmae::pla_plan_bytes(B, N, K, S, M);
     if (!workspace || workspace_bytes < need || misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
+  }
+  if (!launch) return AFFMAE_OK;
+  if (!plan) {
     if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, workspace, st) != hipSuccess)
       return AFFMAE_ERR_DEVICE;
     plan = workspace;
   }
   return affmae::launch_pla_fwd_cluster(a, plan, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+}  // namespace
+
+extern "C" {
+
+int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
+                   const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank, int B,
+                   int N, int H, int d, int K, int S, int M, float scale, int dtype, void* out, float* lse,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  return pla_fwd_run(q, k, v, bias, nbr_idx, near_clusters, plan, k_blank, v_blank, B, N, H, d, K, S, M, scale, dtype,
+                     out, lse, workspace, workspace_bytes, stream, true);
 }
 
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
@@ -265,11 +292,15 @@ size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, 
   return gather > tiled ? gather : tiled;
 }
 
-int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
-                   const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank,
-                   const void* out, const float* lse, const void* dout, int B, int N, int H, int d, int K, int S,
-                   int M, float scale, int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank,
-                   float* dv_blank, void* workspace, size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// affmae_pla_bwd with the same split as pla_fwd_run.
+int pla_bwd_run(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
+                const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank,
+                const void* out, const float* lse, const void* dout, int B, int N, int H, int d, int K, int S,
+                int M, float scale, int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank,
+                float* dv_blank, void* workspace, size_t workspace_bytes, void* stream, bool launch) {
   if (!q || !k || !v || !nbr_idx || !lse || !dout || !dq || !dk || !dv) return AFFMAE_ERR_NULL;
   if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
   if ((dk_blank == nullptr) != (dv_blank == nullptr)) return AFFMAE_ERR_NULL;
@@ -298,6 +329,7 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
     const size_t plan_bytes = plan ? 0 : align_up(affmae::pla_plan_bytes(B, N, K, S, M));
     const size_t need = plan_bytes + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, S, M);
     if (!workspace || workspace_bytes < need) return AFFMAE_ERR_WORKSPACE;
+    if (!launch) return AFFMAE_OK;
     char* ws = static_cast<char*>(workspace);
     if (!plan) {
       if (affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, ws, st) != hipSuccess)
@@ -308,7 +340,20 @@ int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias
   }
   const size_t need = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
   if (need && (!workspace || workspace_bytes < need)) return AFFMAE_ERR_WORKSPACE;
+  if (!launch) return AFFMAE_OK;
   return affmae::launch_pla_bwd_general(a, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+}  // namespace
+
+extern "C" {
+
+int affmae_pla_bwd(const void* q, const void* k, const void* v, const void* bias, const int32_t* nbr_idx,
+                   const int32_t* near_clusters, const void* plan, const void* k_blank, const void* v_blank,
+                   const void* out, const float* lse, const void* dout, int B, int N, int H, int d, int K, int S,
+                   int M, float scale, int dtype, void* dq, void* dk, void* dv, void* dbias, float* dk_blank,
+                   float* dv_blank, void* workspace, size_t workspace_bytes, void* stream) {
+  return pla_bwd_run(q, k, v, bias, nbr_idx, near_clusters, plan, k_blank, v_blank, out, lse, dout, B, N, H, d, K, S, M,
+                     scale, dtype, dq, dk, dv, dbias, dk_blank, dv_blank, workspace, workspace_bytes, stream, true);
 }
 
 namespace {
@@ -375,10 +420,14 @@ int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const flo
     }
     return affmae::launch_pla_fwd_cluster(a, plan, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
   }
+  // the bias is written into the workspace by a kernel of its own: validate the attention call before it
+  rc = pla_fwd_run(q, k, v, ws, nbr_idx, near_clusters, plan, k_blank, v_blank, B, N, H, d, K, S, M, scale, dtype, out,
+                   lse, ws + bb, workspace_bytes - bb, stream, false);
+  if (rc != AFFMAE_OK) return rc;
   const affmae::RelposArgs r = {coords, nbr_idx, rel_table, R, rate};
   if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, ws, st) != hipSuccess) return AFFMAE_ERR_DEVICE;
-  return affmae_pla_fwd(q, k, v, ws, nbr_idx, near_clusters, plan, k_blank, v_blank, B, N, H, d, K, S, M, scale, dtype,
-                        out, lse, ws + bb, workspace_bytes - bb, stream);
+  return pla_fwd_run(q, k, v, ws, nbr_idx, near_clusters, plan, k_blank, v_blank, B, N, H, d, K, S, M, scale, dtype, out,
+                     lse, ws + bb, workspace_bytes - bb, stream, true);
 }
 
 size_t affmae_pla_bwd_relpos_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int R, int dtype,
@@ -462,10 +511,15 @@ int affmae_pla_bwd_relpos(const void* q, const void* k, const void* v, const flo
   void* dbias = ws + bb;
   void* parts = ws + 2 * bb;
   char* inner = ws + 2 * bb + tb;
+  // validate the attention call before the kernel that writes the bias
+  rc = pla_bwd_run(q, k, v, bias, nbr_idx, near_clusters, plan, k_blank, v_blank, out, lse, dout, B, N, H, d, K, S, M,
+                   scale, dtype, dq, dk, dv, dbias, dk_blank, dv_blank, inner, workspace_bytes - (2 * bb + tb), stream,
+                   false);
+  if (rc != AFFMAE_OK) return rc;
   if (affmae::launch_relpos_bias(r, B, N, H, K, dtype, bias, st) != hipSuccess) return AFFMAE_ERR_DEVICE;
-  rc = affmae_pla_bwd(q, k, v, bias, nbr_idx, near_clusters, plan, k_blank, v_blank, out, lse, dout, B, N, H, d, K, S,
-                      M, scale, dtype, dq, dk, dv, dbias, dk_blank, dv_blank, inner, workspace_bytes - (2 * bb + tb),
-                      stream);
+  rc = pla_bwd_run(q, k, v, bias, nbr_idx, near_clusters, plan, k_blank, v_blank, out, lse, dout, B, N, H, d, K, S, M,
+                   scale, dtype, dq, dk, dv, dbias, dk_blank, dv_blank, inner, workspace_bytes - (2 * bb + tb), stream,
+                   true);
   if (rc != AFFMAE_OK) return rc;
   return affmae::launch_relpos_dtable(r, B, N, H, K, dtype, dbias, drel_table, parts, st) == hipSuccess
              ? AFFMAE_OK

@@ -1,10 +1,12 @@
-// Optional per-kernel timing with HIP events on the launch stream.  Disabled by
-// default (then a timed launch is just the launch).  Used by the benchmark to
-// report the duration of individual kernels inside one API call.
+// Kernel launch macro.  The product library (libaffmae.so) is built without AFFMAE_TIMING: a launch is just the
+// launch and the library holds no state between calls.  The instrumented build (libaffmae_timed.so, compiled with
+// -DAFFMAE_TIMING, loaded only by the benchmark) brackets every launch with two HIP events on the launch stream and
+// keeps per-kernel totals in a registry (timing.hip, declared in include/affmae_timing.h).
 #pragma once
 
 #include <hip/hip_runtime.h>
 
+#ifdef AFFMAE_TIMING
 namespace affmae {
 
 bool timing_enabled();
@@ -24,9 +26,11 @@ struct TimedScope {
 
 }  // namespace affmae
 
-// Launch a kernel, bracketed by timing events when timing is enabled.
 #define AFFMAE_LAUNCH(name, stream, ...)            \
   do {                                              \
     ::affmae::TimedScope affmae_ts_(name, stream);  \
     hipLaunchKernelGGL(__VA_ARGS__);                \
   } while (0)
+#else
+#define AFFMAE_LAUNCH(name, stream, ...) hipLaunchKernelGGL(__VA_ARGS__)
+#endif

@@ -1,7 +1,8 @@
-// Per-kernel timing registry (see timing.h) and its C entry points.
+// Per-kernel timing registry (see timing.h) and its C entry points: part of the instrumented build only.
 #include "timing.h"
 
-#include "../../include/affmae.h"
+#ifdef AFFMAE_TIMING
+#include "../../include/affmae_timing.h"
 
 #include <cstring>
 #include <mutex>
@@ -114,3 +115,4 @@ int affmae_timing_read(int index, char* name, int name_len, double* total_ms, in
 }
 
 }  // extern "C"
+#endif  // AFFMAE_TIMING

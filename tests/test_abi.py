@@ -11,8 +11,8 @@ import paper_2602_16249_amd as aff
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "affmae.h")).read()
+def _declared_symbols(header="affmae.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(affmae_[a-z_]+)\s*\(", text)))
 
@@ -23,6 +23,19 @@ def test_header_symbols_are_exported():
     assert {"affmae_knn", "affmae_pla_fwd", "affmae_pla_bwd"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_product_library_has_no_timing_registry():
+    """The per-kernel timing lives in the instrumented twin only (include/affmae_timing.h)."""
+    lib = aff.load_library()
+    timed = ctypes.CDLL(os.path.join(os.path.dirname(aff.library_path()), "libaffmae_timed.so"))
+    names = _declared_symbols("affmae_timing.h")
+    assert names == ["affmae_timing_enable", "affmae_timing_read", "affmae_timing_reset"]
+    for n in names:
+        assert hasattr(timed, n), n
+        assert not hasattr(lib, n), n
+    for n in _declared_symbols():
+        assert hasattr(timed, n), n
 
 
 def test_status_strings():
@@ -153,3 +166,32 @@ def test_relpos_rejects_bad_arguments_on_host():
     assert lib.affmae_pla_fwd_relpos_workspace_bytes(1, 64, 2, 32, 8, 0, 0, 0, 0) >= 64 * 2 * 8 * 4
     assert lib.affmae_pla_bwd_relpos_workspace_bytes(1, 64, 2, 32, 8, 0, 0, 2, 0, 0) >= 2 * 64 * 2 * 8 * 4
     assert lib.affmae_pla_bwd_relpos_workspace_bytes(1, 64, 2, 32, 8, 0, 0, 32, 0, 0) == 0
+
+
+def test_relpos_validates_the_attention_call_before_its_first_launch():
+    """The composed relative-position paths put a kernel of their own (the bias) in front of the attention call.
+    Arguments that the attention call rejects must be rejected before that kernel: on this GPU-less host a launch
+    attempt would surface as AFFMAE_ERR_DEVICE (-6) instead of the validation status."""
+    lib = aff.load_library()
+    one = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4098)
+    f = ctypes.c_float
+    big = 1 << 30
+
+    def fwd(q=one, kb=None, vb=None, near=None, S=0, M=0):
+        return lib.affmae_pla_fwd_relpos(q, one, one, one, one, one, near, None, kb, vb, 1, 64, 2, 32, 8, S, M, f(0.2), 2,
+                                         f(0.125), 0, one, one, one, big, None)
+
+    assert fwd(q=odd) == -2            # misaligned rows: found by the attention call's own checks
+    assert fwd(kb=one) == -1           # blank key without blank value
+    assert fwd(near=one, S=7, M=2) == -2
+
+    def bwd(q=one, kb=None, vb=None, dkb=None, dvb=None, dq=one):
+        return lib.affmae_pla_bwd_relpos(q, one, one, one, one, one, None, None, kb, vb, one, one, one, 1, 64, 2, 32, 8, 0,
+                                         0, f(0.2), 2, f(0.125), 0, dq, one, one, one, dkb, dvb, one, big, None)
+
+    assert bwd(q=odd) == -2
+    assert bwd(kb=one) == -1
+    assert bwd(dkb=one) == -1          # dk_blank without dv_blank
+    assert bwd(dq=odd) == -2
+
