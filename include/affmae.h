@@ -22,7 +22,8 @@
  *     and return without synchronising.  Calls that share a workspace must be
  *     ordered on one stream.  No call allocates, frees or clears device memory
  *     through the runtime: a caller may record the calls into a HIP graph.
- *     The library keeps no state between calls and may be called from several threads.
+ *     The library keeps no state between calls (the one exception is the fixed
+ *     scratch array of affmae_knn_static) and may be called from several threads.
  *   - Return value: AFFMAE_OK (0) or a negative affmae_status.  When an error
  *     is returned nothing has been enqueued.  No exception crosses the ABI.
  *   - Outputs are fully overwritten (never accumulated into).
@@ -183,6 +184,26 @@ size_t affmae_knn_workspace_bytes(int B, int N, int S, int M, int K);
 int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int S, int M, int K,
                int32_t* nbr_idx, int32_t* near_clusters, void* workspace, size_t workspace_bytes,
                void* stream);
+
+/*
+ * affmae_knn_static - affmae_knn for callers that cannot allocate device memory
+ * or size a workspace (code recorded into a HIP graph by a harness that forbids
+ * allocation, tight serving loops): the same search, same arguments and results,
+ * with the scratch (centroids, the near-cluster table when near_clusters is NULL,
+ * member lists) in a fixed array of AFFMAE_KNN_STATIC_SCRATCH_BYTES inside the
+ * library's device image.  Each GPU the library runs on holds one copy of that
+ * array until the process ends.  The call allocates and frees nothing.
+ *
+ * Errors: as affmae_knn, with AFFMAE_ERR_WORKSPACE when
+ * affmae_knn_workspace_bytes(B, N, S, M, K) exceeds AFFMAE_KNN_STATIC_SCRATCH_BYTES
+ * (about B * (N * 4 + G * (8 + 4 M)) bytes: a million tokens fit), and
+ * AFFMAE_ERR_DEVICE when the runtime cannot give the array's address.
+ * All calls on one GPU share the array: calls that may overlap in time (on
+ * different streams, or from different threads) race; order them on one stream.
+ */
+#define AFFMAE_KNN_STATIC_SCRATCH_BYTES (4u << 20)
+int affmae_knn_static(const float* coords, const int32_t* cluster_id, int B, int N, int S, int M, int K,
+                      int32_t* nbr_idx, int32_t* near_clusters, void* stream);
 
 /*
  * affmae_pla_plan - re-tiles a clustered neighbour table for the cluster-tiled

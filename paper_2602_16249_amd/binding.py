@@ -84,6 +84,8 @@ def _load(path: str):
     lib.affmae_knn.restype = _c_int
     lib.affmae_knn.argtypes = [_c_void_p, _c_void_p] + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_void_p, _c_size_t,
                                                                       _c_void_p]
+    lib.affmae_knn_static.restype = _c_int
+    lib.affmae_knn_static.argtypes = [_c_void_p, _c_void_p] + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_void_p]
     for name in ("affmae_pla_fwd_workspace_bytes", "affmae_pla_bwd_workspace_bytes"):
         f = getattr(lib, name)
         f.restype = _c_size_t
@@ -287,6 +289,17 @@ def affmae_knn(coords: torch.Tensor, cluster_id: Optional[torch.Tensor], S: int,
     if rc != 0:
         raise AffmaeError("affmae_knn", rc)
     return nbr_idx, near_clusters
+
+
+def affmae_knn_static(coords: torch.Tensor, cluster_id: Optional[torch.Tensor], S: int, M: int, K: int,
+                      nbr_idx: torch.Tensor, near_clusters: Optional[torch.Tensor] = None) -> None:
+    """affmae_knn into caller-given outputs with the library's fixed scratch: no allocation anywhere."""
+    lib = load_library()
+    B, N, _ = coords.shape
+    rc = lib.affmae_knn_static(_ptr(coords), _ptr(cluster_id), B, N, S, M, K, _ptr(nbr_idx), _ptr(near_clusters),
+                               _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_knn_static", rc)
 
 
 def affmae_pla_plan(nbr_idx: torch.Tensor, near_clusters: torch.Tensor, S: int, M: int,

@@ -4,6 +4,8 @@
 
 #include "launch.h"
 
+#include <atomic>
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -204,6 +206,45 @@ int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int
   a.centroid = reinterpret_cast<float*>(ws + plan.centroid_off);
   a.members = reinterpret_cast<int32_t*>(ws + plan.members_off);
   return affmae::launch_knn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+
+}  // extern "C"
+
+// Scratch of affmae_knn_static: a fixed array in device memory, one copy per GPU, held until the process ends.
+// In host code the array's name is only a handle; its device address comes from hipGetSymbolAddress, once per
+// device (with that device current), and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[AFFMAE_KNN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, or nullptr when the runtime refuses it.
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // (two first callers store the same address)
+  }
+  return ptr;
+}
+}  // namespace
+
+extern "C" {
+
+int affmae_knn_static(const float* coords, const int32_t* cluster_id, int B, int N, int S, int M, int K,
+                      int32_t* nbr_idx, int32_t* near_clusters, void* stream) {
+  if (!coords || !nbr_idx) return AFFMAE_ERR_NULL;
+  const int rc = check_knn_shape(B, N, S, M, K);
+  if (rc != AFFMAE_OK) return rc;
+  if (knn_plan(B, N, S, M).total > (size_t)AFFMAE_KNN_STATIC_SCRATCH_BYTES) return AFFMAE_ERR_WORKSPACE;
+  void* ptr = static_scratch();
+  if (!ptr) return AFFMAE_ERR_DEVICE;
+  // every word of the scratch that the kernels read is written earlier in the same call: nothing to clear
+  return affmae_knn(coords, cluster_id, B, N, S, M, K, nbr_idx, near_clusters, ptr, AFFMAE_KNN_STATIC_SCRATCH_BYTES,
+                    stream);
 }
 
 size_t affmae_pla_plan_bytes(int B, int N, int K, int S, int M) {

@@ -195,3 +195,12 @@ def test_relpos_validates_the_attention_call_before_its_first_launch():
     assert bwd(dkb=one) == -1          # dk_blank without dv_blank
     assert bwd(dq=odd) == -2
 
+
+def test_knn_static_rejects_on_host():
+    lib = aff.load_library()
+    one = ctypes.c_void_p(256)
+    B, N, S, M, K = 64, 32768, 64, 8, 48
+    assert lib.affmae_knn_workspace_bytes(B, N, S, M, K) > (4 << 20)
+    assert lib.affmae_knn_static(one, None, B, N, S, M, K, one, None, None) == -4   # beyond the fixed scratch
+    assert lib.affmae_knn_static(None, None, 1, 64, 8, 2, 4, one, None, None) == -1
+    assert lib.affmae_knn_static(one, None, 1, 65, 8, 2, 4, one, None, None) == -2
