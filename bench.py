@@ -3,9 +3,15 @@
 
 A step is one pass of the whole path over one batch of synthetic tokens that are
 already resident in HBM: affmae_cluster (curve order and clusters) -> affmae_knn
-(neighbour table) -> affmae_pla_plan -> affmae_pla_fwd -> affmae_pla_bwd.  The headline value is attention forward+backward tokens/s (the
-table is built once per encoder stage and reused by every block, so the search
-is also reported on its own).  Prints ONE JSON line.
+(neighbour table) -> affmae_pla_plan -> affmae_pla_fwd -> affmae_pla_bwd; exactly
+--steps of them are timed by the wall clock (ms_per_step).  The headline value is
+attention forward+backward tokens/s (the table is built once per encoder stage and
+reused by every block, so the search is reported on its own), taken from loops that
+time the forward and the backward call separately, each call starting with cold
+caches: between two timed calls a 512 MiB buffer is read through the chip,
+outside the timed events.  All phase times are medians.  The other bf16
+configurations of the workload list get the same cold loops ("configs").
+Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config ft_s1_1024]
 """
@@ -39,7 +45,7 @@ def algorithmic_bytes_per_token(C: int, H: int, K: int, elt: int = 2):
 def bench_virtual_tokens(aff, torch, np, dev, reps: int = 20):
     """The point decoder's virtual sampled tokens at the shape of the paper's decoder timing (batch 48, 2048 mask
     tokens x 4 sample points, 4 nearest visible tokens; 512px images at 25 % visible, stage-1 width 128, bf16):
-    table build, fused lookup + weights + sum forward, backward.  Times are HIP-event means."""
+    table build, fused lookup + weights + sum forward, backward.  Times are HIP-event medians."""
     rng = np.random.default_rng(2602016249 + 100)
     B, Nv, Mq, C, Hg, Wg, Kt, cell, p, eps = 48, 1024, 8192, 128, 64, 64, 4, 8.0, 0.5, 1e-6
     grid = (Hg, Wg, 0.0, 0.0, cell)
@@ -57,9 +63,9 @@ def bench_virtual_tokens(aff, torch, np, dev, reps: int = 20):
     ws = torch.empty(aff.load_library().affmae_vts_bwd_workspace_bytes(B, Mq, Nv, Kt), dtype=torch.uint8, device=dev)
     aff.affmae_vts_bwd(q, vis, feat, table, dout, grid, p, eps, workspace=ws)
     torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-    t = [0.0, 0.0, 0.0]
+    ts = [[], [], []]
     for _ in range(reps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         ev[0].record()
         aff.affmae_vts_table(vis, grid, Kt, table=table)
         ev[1].record()
@@ -69,7 +75,8 @@ def bench_virtual_tokens(aff, torch, np, dev, reps: int = 20):
         ev[3].record()
         torch.cuda.synchronize()
         for i in range(3):
-            t[i] += ev[i].elapsed_time(ev[i + 1]) / reps
+            ts[i].append(ev[i].elapsed_time(ev[i + 1]))
+    t = [float(np.median(x)) for x in ts]
     samples = B * Mq
     # algorithmic bytes: every tensor element once (bf16 features; the gathered rows counted once, as stored)
     fwd_bytes = samples * (8 + 4 * Kt + 2 * C) + B * Nv * (8 + 2 * C)
@@ -80,37 +87,38 @@ def bench_virtual_tokens(aff, torch, np, dev, reps: int = 20):
             "fwd_algorithmic_GBs": fwd_bytes / (t[1] * 1e-3) / 1e9, "bwd_algorithmic_GBs": bwd_bytes / (t[2] * 1e-3) / 1e9}
 
 
-def bench_relpos(aff, torch, np, cfg, s, scale, promise, reps: int = 20):
+def bench_relpos(aff, torch, np, cfg, sets, scale, promise, flush, reps: int = 20):
     """The same attention with the bias taken from a relative-position table (9 x 9 bins of one 8-px patch per
-    head) instead of a bias tensor: forward and backward through affmae_pla_*_relpos on the workload's first
-    tensor set (one set only, so part of it stays in the 256 MB cache between repetitions, unlike the headline
-    loop).  Times are HIP-event means; the bias is written out by one kernel and the table's gradient reduced by
-    two more around the same attention kernels."""
-    dev = s["q"].device
+    head) instead of a bias tensor: forward and backward through affmae_pla_*_relpos, timed like the headline
+    (the same rotating tensor sets, every call on cold caches, medians)."""
+    dev = sets[0]["q"].device
     R, rate = 4, 1.0 / 8.0
-    table = (0.1 * torch.randn((cfg.H, 2 * R + 1, 2 * R + 1), device=dev)).to(s["q"].dtype)
+    table = (0.1 * torch.randn((cfg.H, 2 * R + 1, 2 * R + 1), device=dev)).to(sets[0]["q"].dtype)
     lib = aff.load_library()
     code = 1 if cfg.dtype == "bf16" else 0
-    near = s["near"] if promise else None
     ws = torch.empty(max(lib.affmae_pla_fwd_relpos_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
                          lib.affmae_pla_bwd_relpos_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, R, code, int(promise))),
                      dtype=torch.uint8, device=dev)
-    t = [0.0, 0.0]
-    for it in range(reps + 2):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        e[0].record()
-        out, lse = aff.affmae_pla_fwd_relpos(s["q"], s["k"], s["v"], s["coords"], table, s["nbr"], scale, rate, near,
-                                             cfg.S, cfg.M, out=s["out"], lse=s["lse"], workspace=ws, plan=s["plan"])
-        e[1].record()
-        aff.affmae_pla_bwd_relpos(s["q"], s["k"], s["v"], s["coords"], table, s["nbr"], out, lse, s["dout"], scale, rate,
-                                  near, cfg.S, cfg.M, workspace=ws, plan=s["plan"])
-        e[2].record()
-        torch.cuda.synchronize()
-        if it >= 2:
-            t[0] += e[0].elapsed_time(e[1]) / reps
-            t[1] += e[1].elapsed_time(e[2]) / reps
-    return {"table": f"{cfg.H} x {2 * R + 1} x {2 * R + 1}, bins of 8 px", "tensor_sets": 1, "fwd_ms": t[0], "bwd_ms": t[1],
-            "tokens_per_s_fwd_bwd": cfg.B * cfg.N / ((t[0] + t[1]) * 1e-3)}
+
+    def fwd(s):
+        aff.affmae_pla_fwd_relpos(s["q"], s["k"], s["v"], s["coords"], table, s["nbr"], scale, rate,
+                                  s["near"] if promise else None, cfg.S, cfg.M, out=s["out"], lse=s["lse"], workspace=ws,
+                                  plan=s["plan"])
+
+    def bwd(s):
+        aff.affmae_pla_bwd_relpos(s["q"], s["k"], s["v"], s["coords"], table, s["nbr"], s["out"], s["lse"], s["dout"],
+                                  scale, rate, s["near"] if promise else None, cfg.S, cfg.M, workspace=ws, plan=s["plan"])
+
+    t_fwd = float(np.median(cold_times(torch, fwd, sets, reps, flush)))
+    t_bwd = float(np.median(cold_times(torch, bwd, sets, reps, flush)))
+    elt = 2 if cfg.dtype == "bf16" else 4
+    fwd_b, bwd_b = algorithmic_bytes_per_token(cfg.C, cfg.H, cfg.K, elt)
+    own = fwd_b + bwd_b - 3 * cfg.K * cfg.H * elt + 2 * 8   # no bias / dbias tensor; the coordinates instead
+    tokens = cfg.B * cfg.N
+    return {"table": f"{cfg.H} x {2 * R + 1} x {2 * R + 1}, bins of 8 px", "tensor_sets": len(sets), "fwd_ms": t_fwd,
+            "bwd_ms": t_bwd, "tokens_per_s_fwd_bwd": tokens / ((t_fwd + t_bwd) * 1e-3),
+            "algorithmic_bytes_per_token": own,
+            "frac_of_hbm_peak": own * tokens / ((t_fwd + t_bwd) * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
 def bench_graphs(torch, sets, step, attn, steps: int):
@@ -145,15 +153,115 @@ def bench_graphs(torch, sets, step, attn, steps: int):
     return out
 
 
+def alloc_set(cfg, w, torch, dev, tdt):
+    """One copy of every tensor of a configuration, resident on the device."""
+    def up(x):
+        return torch.from_numpy(x).to(dev).to(tdt)
+    s = {n: up(w[n]) for n in ("q", "k", "v", "bias", "dout")}
+    s["coords"] = torch.from_numpy(w["coords"]).to(dev)
+    s["nbr"] = torch.empty((cfg.B, cfg.N, cfg.K), dtype=torch.int32, device=dev)
+    s["near"] = torch.empty((cfg.B, cfg.G, cfg.M), dtype=torch.int32, device=dev)
+    s["out"] = torch.empty_like(s["q"])
+    s["lse"] = torch.empty((cfg.B, cfg.N, cfg.H), dtype=torch.float32, device=dev)
+    s["plan"] = None
+    s["order"] = torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=dev)
+    s["cid"] = torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=dev)
+    s["grads"] = {"dq": torch.empty_like(s["q"]), "dk": torch.empty_like(s["q"]), "dv": torch.empty_like(s["q"]),
+                  "dbias": torch.empty_like(s["bias"])}
+    return s
+
+
+class Runner:
+    """The calls of one configuration on its tensor sets."""
+
+    def __init__(self, aff, torch, cfg, promise):
+        self.aff, self.torch, self.cfg, self.promise = aff, torch, cfg, promise
+        self.scale = 1.0 / float(cfg.d) ** 0.5
+        self.frame = (0.0, 0.0, float(cfg.frame), float(cfg.frame))
+        lib = aff.load_library()
+        code = 1 if cfg.dtype == "bf16" else 0
+        self.ws_bytes = max(lib.affmae_cluster_workspace_bytes(cfg.B, cfg.N),
+                            lib.affmae_knn_workspace_bytes(cfg.B, cfg.N, cfg.S, cfg.M, cfg.K),
+                            lib.affmae_pla_fwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
+                            lib.affmae_pla_bwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
+                            256)
+
+    def tables(self, s):
+        aff, cfg = self.aff, self.cfg
+        # the generator hands the tokens over in curve order already: the clustering returns the identity
+        # (its sorting network does the same work for any input), so nothing has to be gathered here
+        aff.affmae_cluster(s["coords"], cfg.S, self.frame, order=s["order"], cluster_id=s["cid"], workspace=s["ws"])
+        self.knn(s)
+
+    def knn(self, s):
+        aff, cfg = self.aff, self.cfg
+        aff.affmae_knn(s["coords"], None, cfg.S, cfg.M, cfg.K, nbr_idx=s["nbr"], near_clusters=s["near"], workspace=s["ws"])
+        if self.promise:  # the tiled kernels' view of the table: built once per table, like the table itself
+            s["plan"] = aff.affmae_pla_plan(s["nbr"], s["near"], cfg.S, cfg.M, plan=s["plan"])
+
+    def fwd(self, s):
+        cfg = self.cfg
+        self.aff.affmae_pla_fwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], self.scale, s["near"] if self.promise else None,
+                                cfg.S, cfg.M, out=s["out"], lse=s["lse"], workspace=s["ws"], plan=s["plan"])
+
+    def bwd(self, s):
+        cfg = self.cfg
+        self.aff.affmae_pla_bwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], s["out"], s["lse"], s["dout"], self.scale,
+                                s["near"] if self.promise else None, cfg.S, cfg.M, grads=s["grads"], workspace=s["ws"],
+                                plan=s["plan"])
+
+
+def cold_times(torch, fn, sets, iters, flush):
+    """Milliseconds of `iters` calls of fn, each after the flush buffer has been streamed through the chip
+    (outside the timed events), rotating over the tensor sets."""
+    ms = []
+    for i in range(iters + 2):
+        flush.sum()  # read only: a flush that writes would leave dirty lines for the timed call to push out
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn(sets[i % len(sets)])
+        e1.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            ms.append(e0.elapsed_time(e1))
+    return ms
+
+
+def bench_config(aff, torch, np, cfg, dev, flush, iters, promise=True):
+    """Cold forward and backward times of one configuration (tables built once, outside the timing)."""
+    from workloads import make_workload
+    w = make_workload(cfg)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    run = Runner(aff, torch, cfg, promise)
+    sets = [alloc_set(cfg, w, torch, dev, tdt) for _ in range(2)]
+    for s in sets:
+        s["ws"] = torch.empty(run.ws_bytes, dtype=torch.uint8, device=dev)
+        run.tables(s)
+        run.fwd(s)
+    torch.cuda.synchronize()
+    knn = float(np.median(cold_times(torch, run.knn, sets, max(iters // 2, 4), flush)))
+    fwd = float(np.median(cold_times(torch, run.fwd, sets, iters, flush)))
+    bwd = float(np.median(cold_times(torch, run.bwd, sets, iters, flush)))
+    tokens = cfg.B * cfg.N
+    fwd_b, bwd_b = algorithmic_bytes_per_token(cfg.C, cfg.H, cfg.K, 2 if cfg.dtype == "bf16" else 4)
+    gbs = (fwd_b + bwd_b) * tokens / ((fwd + bwd) * 1e-3) / 1e9
+    return {"workload": cfg.name, "B": cfg.B, "N": cfg.N, "C": cfg.C, "H": cfg.H, "K": cfg.K, "S": cfg.S, "M": cfg.M,
+            "coords": cfg.coords, "fwd_us": 1e3 * fwd, "bwd_us": 1e3 * bwd, "knn_plan_us": 1e3 * knn,
+            "tokens_per_s_fwd_bwd": tokens / ((fwd + bwd) * 1e-3), "algorithmic_bytes_per_token": fwd_b + bwd_b,
+            "algorithmic_GBs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", default="ft_s1_1024")
-    ap.add_argument("--sets", type=int, default=4, help="rotating copies of all tensors (defeats the 256 MB cache)")
+    ap.add_argument("--sets", type=int, default=4, help="rotating copies of all tensors")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-promise", action="store_true", help="do not pass near_clusters (gather kernels)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the other configurations, the relative-position, graph and point-decoder sections")
     ap.add_argument("--copy-probe", action="store_true", help="accepted for compatibility: the copy probe always runs")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -172,38 +280,14 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = make_workload(cfg)
-    scale = 1.0 / float(np.sqrt(cfg.d))
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     tokens = cfg.B * cfg.N
     promise = not args.no_promise
-
-    def up(x):
-        return torch.from_numpy(x).to(dev).to(tdt)
-
-    sets = []
-    for _ in range(args.sets):
-        s = {n: up(w[n]) for n in ("q", "k", "v", "bias", "dout")}
-        s["coords"] = torch.from_numpy(w["coords"]).to(dev)
-        s["nbr"] = torch.empty((cfg.B, cfg.N, cfg.K), dtype=torch.int32, device=dev)
-        s["near"] = torch.empty((cfg.B, cfg.G, cfg.M), dtype=torch.int32, device=dev)
-        s["out"] = torch.empty_like(s["q"])
-        s["lse"] = torch.empty((cfg.B, cfg.N, cfg.H), dtype=torch.float32, device=dev)
-        s["plan"] = None
-        s["order"] = torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=dev)
-        s["cid"] = torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=dev)
-        s["grads"] = {"dq": torch.empty_like(s["q"]), "dk": torch.empty_like(s["q"]), "dv": torch.empty_like(s["q"]),
-                      "dbias": torch.empty_like(s["bias"])}
-        sets.append(s)
-    lib = aff.load_library()
-    code = 1 if cfg.dtype == "bf16" else 0
-    frame = (0.0, 0.0, float(cfg.frame), float(cfg.frame))
-    ws_bytes = max(lib.affmae_cluster_workspace_bytes(cfg.B, cfg.N),
-                   lib.affmae_knn_workspace_bytes(cfg.B, cfg.N, cfg.S, cfg.M, cfg.K),
-                   lib.affmae_pla_fwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
-                   lib.affmae_pla_bwd_workspace_bytes(cfg.B, cfg.N, cfg.H, cfg.d, cfg.K, cfg.S, cfg.M, code, int(promise)),
-                   256)
+    run = Runner(aff, torch, cfg, promise)
+    scale = run.scale
+    sets = [alloc_set(cfg, w, torch, dev, tdt) for _ in range(args.sets)]
     for s in sets:
-        s["ws"] = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        s["ws"] = torch.empty(run.ws_bytes, dtype=torch.uint8, device=dev)
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
@@ -211,31 +295,20 @@ def main() -> int:
     def step(s, rec=None):
         e = [ev() for _ in range(5)] if rec is not None else None
         if e: e[4].record()
-        # the generator hands the tokens over in curve order already: the clustering returns the identity
-        # (its sorting network does the same work for any input), so nothing has to be gathered here
-        aff.affmae_cluster(s["coords"], cfg.S, frame, order=s["order"], cluster_id=s["cid"], workspace=s["ws"])
+        aff.affmae_cluster(s["coords"], cfg.S, run.frame, order=s["order"], cluster_id=s["cid"], workspace=s["ws"])
         if e: e[0].record()
-        aff.affmae_knn(s["coords"], None, cfg.S, cfg.M, cfg.K, nbr_idx=s["nbr"], near_clusters=s["near"],
-                       workspace=s["ws"])
-        near = s["near"] if promise else None
-        if promise:  # the tiled kernels' view of the table: built once per table, like the table itself
-            s["plan"] = aff.affmae_pla_plan(s["nbr"], s["near"], cfg.S, cfg.M, plan=s["plan"])
+        run.knn(s)
         if e: e[1].record()
-        aff.affmae_pla_fwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], scale, near, cfg.S, cfg.M,
-                           out=s["out"], lse=s["lse"], workspace=s["ws"], plan=s["plan"])
+        run.fwd(s)
         if e: e[2].record()
-        aff.affmae_pla_bwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], s["out"], s["lse"], s["dout"], scale,
-                           near, cfg.S, cfg.M, grads=s["grads"], workspace=s["ws"], plan=s["plan"])
+        run.bwd(s)
         if e:
             e[3].record()
             rec.append(e)
 
     def attn_only(s):
-        near = s["near"] if promise else None
-        aff.affmae_pla_fwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], scale, near, cfg.S, cfg.M,
-                           out=s["out"], lse=s["lse"], workspace=s["ws"], plan=s["plan"])
-        aff.affmae_pla_bwd(s["q"], s["k"], s["v"], s["bias"], s["nbr"], s["out"], s["lse"], s["dout"], scale,
-                           near, cfg.S, cfg.M, grads=s["grads"], workspace=s["ws"], plan=s["plan"])
+        run.fwd(s)
+        run.bwd(s)
 
     for i in range(args.warmup):
         step(sets[i % len(sets)])
@@ -263,14 +336,24 @@ def main() -> int:
         step(sets[i % len(sets)], rec)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    cluster_ms = float(np.mean([e[4].elapsed_time(e[0]) for e in rec]))
-    knn_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in rec]))
-    fwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in rec]))
-    bwd_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in rec]))
+    med = lambda xs: float(np.median(xs))
+    cluster_ms = med([e[4].elapsed_time(e[0]) for e in rec])
+    knn_ms = med([e[0].elapsed_time(e[1]) for e in rec])
+    fwd_step_ms = med([e[1].elapsed_time(e[2]) for e in rec])
+    bwd_step_ms = med([e[2].elapsed_time(e[3]) for e in rec])
+
+    # the headline: forward and backward timed apart, every call on cold caches
+    flush = torch.zeros(128 << 20, dtype=torch.int32, device=dev)  # 512 MiB
+    cold_iters = max(args.steps, 20)
+    fwd_ms = med(cold_times(torch, run.fwd, sets, cold_iters, flush))
+    bwd_ms = med(cold_times(torch, run.bwd, sets, cold_iters, flush))
     attn_ms = fwd_ms + bwd_ms
 
     # per-kernel durations (HIP events around every launch, on the launch stream), same steps again
     aff.use_timed_library(True)   # the instrumented build of the same sources; the product library has no timing
+    for i in range(max(2, min(args.warmup, len(sets)))):  # its code objects are loaded at their first launches
+        step(sets[i % len(sets)])
+    torch.cuda.synchronize()
     aff.timing_enable(True)
     aff.timing_reset()
     for i in range(args.steps):
@@ -300,11 +383,17 @@ def main() -> int:
     dom_bytes = own[dom] * tokens
     dom_us = attn_kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
-    traffic_all = {}
+    # HBM-side bytes per launch from the rocprofv3 counter runs kept under profiles/ (they cannot be taken inside
+    # this process): used only when they were measured on the build that is running
+    traffic_all, traffic_stale, traffic_build = {}, None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic_all = json.load(open(tpath)).get(args.config, {})
+            tj = json.load(open(tpath))
+            traffic_build = tj.get("build_id")
+            traffic_stale = traffic_build != aff.build_id()
+            if not traffic_stale:
+                traffic_all = tj.get(args.config, {})
         except Exception:
             traffic_all = {}
     traffic = traffic_all.get(dom)
@@ -324,8 +413,9 @@ def main() -> int:
         "config": {"workload": cfg.name, "B": cfg.B, "N": cfg.N, "C": cfg.C, "H": cfg.H, "K": cfg.K, "S": cfg.S,
                    "M": cfg.M, "coords": cfg.coords, "cluster_promise": promise, "rotating_sets": len(sets),
                    "step": "affmae_cluster + affmae_knn + affmae_pla_plan + affmae_pla_fwd + affmae_pla_bwd; "
-                           "value counts fwd+bwd only"},
-        "phases_ms": {"cluster": cluster_ms, "knn": knn_ms, "fwd": fwd_ms, "bwd": bwd_ms},
+                           "value counts fwd+bwd only, each timed apart on cold caches (medians)"},
+        "phases_ms": {"cluster": cluster_ms, "knn": knn_ms, "fwd": fwd_ms, "bwd": bwd_ms,
+                      "fwd_in_step": fwd_step_ms, "bwd_in_step": bwd_step_ms},
         "cluster_tokens_per_s": tokens / (cluster_ms * 1e-3),
         "knn_tokens_per_s": tokens / (knn_ms * 1e-3),
         "step_tokens_per_s": tokens / (wall / args.steps),
@@ -333,6 +423,7 @@ def main() -> int:
         "attn_algorithmic_GBs": (fwd_b + bwd_b) * tokens / (attn_ms * 1e-3) / 1e9,
         "attn_frac_of_hbm_peak": (fwd_b + bwd_b) * tokens / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "copy_probe_GBs": copy_gbs,
+        "build_id": aff.build_id(), "traffic_build_id": traffic_build, "traffic_stale": traffic_stale,
         "attn_counter_GBs": (sum(traffic_all[n] for n in attn_kernels) /
                              (sum(v["avg_us"] for v in attn_kernels.values()) * 1e-6) / 1e9
                              if attn_kernels and all(n in traffic_all for n in attn_kernels) else None),
@@ -343,12 +434,18 @@ def main() -> int:
         "rooflines_all_kernels": rooflines,
     }
 
-    result["relative_position_bias"] = bench_relpos(aff, torch, np, cfg, sets[0], scale, promise)
-    g = bench_graphs(torch, sets, step, attn_only, args.steps)
-    result["hip_graph"] = {"step_ms": g["step_ms"], "attn_fwd_bwd_ms": g["attn_fwd_bwd_ms"],
-                           "attn_tokens_per_s": tokens / (g["attn_fwd_bwd_ms"] * 1e-3),
-                           "step_tokens_per_s": tokens / (g["step_ms"] * 1e-3)}
-    result["virtual_tokens"] = bench_virtual_tokens(aff, torch, np, dev)
+    if not args.no_extras:
+        result["relative_position_bias"] = bench_relpos(aff, torch, np, cfg, sets, scale, promise, flush)
+        g = bench_graphs(torch, sets, step, attn_only, args.steps)
+        result["hip_graph"] = {"step_ms": g["step_ms"], "attn_fwd_bwd_ms": g["attn_fwd_bwd_ms"],
+                               "attn_tokens_per_s": tokens / (g["attn_fwd_bwd_ms"] * 1e-3),
+                               "step_tokens_per_s": tokens / (g["step_ms"] * 1e-3)}
+        result["virtual_tokens"] = bench_virtual_tokens(aff, torch, np, dev)
+        del sets
+        torch.cuda.empty_cache()
+        # the other bf16 configurations of the workload list: same cold loops, fewer repetitions
+        result["configs"] = [bench_config(aff, torch, np, CONFIGS[n], dev, flush, 20, promise)
+                             for n in ("mae_pt_s1_1024", "merged_stage", "knn_scale") if n != cfg.name]
 
     if not args.no_cpu_baseline:
         import oracle

@@ -144,7 +144,7 @@ def centroids(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int) -> n
     B, N, _ = coords.shape
     if cluster_id is not None:
         cluster_id = np.ascontiguousarray(cluster_id, dtype=np.int32)
-    out = np.empty((B, N // S, 2), dtype=np.float32)
+    out = np.empty((B, -(-N // S), 2), dtype=np.float32)
     _check(_load().oracle_centroids(_p(coords), _p(cluster_id), B, N, S, _p(out)), "oracle_centroids")
     return out
 
@@ -158,10 +158,10 @@ def knn(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int, M: int, K:
     if cluster_id is not None:
         cluster_id = np.ascontiguousarray(cluster_id, dtype=np.int32)
         assert cluster_id.shape == (B, N)
-    if S <= 0 or N % S:
-        raise ValueError("N must be a positive multiple of S")
+    if S <= 0:
+        raise ValueError("S must be positive")
     nbr = np.empty((B, N, K), dtype=np.int32)
-    near = np.empty((B, N // S, M), dtype=np.int32)
+    near = np.empty((B, -(-N // S), M), dtype=np.int32)  # the last cluster is short when S does not divide N
     _check(_load().oracle_knn(_p(coords), _p(cluster_id), B, N, S, M, K, _p(nbr), _p(near)), "oracle_knn")
     return nbr, near
 

@@ -114,59 +114,70 @@ static int cand_less(const void *pa, const void *pb) {
 }
 
 /*
+ * Clusters hold S tokens each, except that the last one (cluster G - 1, G = ceil(N / S)) holds the
+ * N - (G - 1) S tokens that are left when S does not divide N.
+ */
+static int cluster_count(int N, int S) { return (N + S - 1) / S; }
+static int cluster_size(int c, int N, int S) {
+  int G = cluster_count(N, S);
+  return c == G - 1 ? N - (G - 1) * S : S;
+}
+
+/*
  * Member lists of one image.  cluster_id == NULL means token i belongs to
  * cluster i / S.  members[c*S + r] = r-th token of cluster c in ascending token
- * order.  Fails unless every cluster has exactly S members.
+ * order (members has room for G*S entries).  Fails unless every cluster has exactly its size in members.
  */
 static int build_members(const int32_t *cluster_id, int N, int S, int32_t *members) {
-  int G = N / S;
+  int G = cluster_count(N, S);
   int *count = (int *)calloc((size_t)G, sizeof(int));
   if (!count) return ORACLE_ERR_ALLOC;
   int rc = ORACLE_OK;
   for (int i = 0; i < N && rc == ORACLE_OK; ++i) {
     int c = cluster_id ? cluster_id[i] : i / S;
-    if (c < 0 || c >= G || count[c] >= S) {
+    if (c < 0 || c >= G || count[c] >= cluster_size(c, N, S)) {
       rc = ORACLE_ERR_CLUSTER;
       break;
     }
     members[(size_t)c * S + count[c]++] = i;
   }
   for (int c = 0; c < G && rc == ORACLE_OK; ++c)
-    if (count[c] != S) rc = ORACLE_ERR_CLUSTER;
+    if (count[c] != cluster_size(c, N, S)) rc = ORACLE_ERR_CLUSTER;
   free(count);
   return rc;
 }
 
-/* Centroid of each cluster: double sum in member order, divide, round to fp32. */
-static void image_centroids(const float *coords, const int32_t *members, int G, int S,
-                            float *centroid) {
+/* Centroid of each cluster: double sum in member order, divide by the number of members, round to fp32. */
+static void image_centroids(const float *coords, const int32_t *members, int N, int S, float *centroid) {
+  int G = cluster_count(N, S);
   for (int c = 0; c < G; ++c) {
     double sx = 0.0, sy = 0.0;
-    for (int r = 0; r < S; ++r) {
+    int size = cluster_size(c, N, S);
+    for (int r = 0; r < size; ++r) {
       int i = members[(size_t)c * S + r];
       sx += (double)coords[2 * (size_t)i + 0];
       sy += (double)coords[2 * (size_t)i + 1];
     }
-    centroid[2 * c + 0] = (float)(sx / (double)S);
-    centroid[2 * c + 1] = (float)(sy / (double)S);
+    centroid[2 * c + 0] = (float)(sx / (double)size);
+    centroid[2 * c + 1] = (float)(sy / (double)size);
   }
 }
 
 /*
  * oracle_centroids: coords [B,N,2] fp32, cluster_id [B,N] or NULL
- *   -> centroid [B,G,2] fp32, G = N/S.
+ *   -> centroid [B,G,2] fp32, G = ceil(N/S) (the last cluster is short when S does not divide N).
  */
 int oracle_centroids(const float *coords, const int32_t *cluster_id, int B, int N, int S,
                      float *centroid) {
-  if (!coords || !centroid || B < 0 || N <= 0 || S <= 0 || N % S) return ORACLE_ERR_ARG;
-  int G = N / S;
-  int32_t *members = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+  if (!coords || !centroid || B < 0 || N <= 0 || S <= 0) return ORACLE_ERR_ARG;
+  int G = cluster_count(N, S);
+  int32_t *members = (int32_t *)malloc((size_t)G * S * sizeof(int32_t));
   if (!members) return ORACLE_ERR_ALLOC;
   int rc = ORACLE_OK;
   for (int b = 0; b < B && rc == ORACLE_OK; ++b) {
     rc = build_members(cluster_id ? cluster_id + (size_t)b * N : NULL, N, S, members);
     if (rc == ORACLE_OK)
-      image_centroids(coords + (size_t)b * N * 2, members, G, S, centroid + (size_t)b * G * 2);
+      image_centroids(coords + (size_t)b * N * 2, members, N, S, centroid + (size_t)b * G * 2);
   }
   free(members);
   return rc;
@@ -396,7 +407,8 @@ int oracle_cluster(const float *coords, int B, int N, int S, double x0, double y
 /*
  * oracle_knn: clustered neighbour search.
  *   coords [B,N,2] fp32; cluster_id [B,N] int32 or NULL (= i / S);
- *   1 <= M <= G = N/S; 1 <= K <= M*S.
+ *   G = ceil(N/S) clusters of S tokens, the last one short when S does not divide N;
+ *   1 <= M <= G; 1 <= K <= the smallest number of candidates any token has.
  *   near_clusters [B,G,M] (may be NULL): for each cluster the M clusters with
  *     nearest centroids, ascending (distance, cluster index); the cluster
  *     itself takes part.
@@ -405,14 +417,14 @@ int oracle_cluster(const float *coords, int B, int N, int S, double x0, double y
  */
 int oracle_knn(const float *coords, const int32_t *cluster_id, int B, int N, int S, int M, int K,
                int32_t *nbr_idx, int32_t *near_clusters) {
-  if (!coords || !nbr_idx || B < 0 || N <= 0 || S <= 0 || N % S) return ORACLE_ERR_ARG;
-  int G = N / S;
+  if (!coords || !nbr_idx || B < 0 || N <= 0 || S <= 0) return ORACLE_ERR_ARG;
+  int G = cluster_count(N, S);
   if (M < 1 || M > G || K < 1 || (long long)K > (long long)M * S) return ORACLE_ERR_ARG;
   int status = ORACLE_OK;
 #pragma omp parallel for schedule(dynamic, 1)
   for (int b = 0; b < B; ++b) {
     const float *xy = coords + (size_t)b * N * 2;
-    int32_t *members = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    int32_t *members = (int32_t *)malloc((size_t)G * S * sizeof(int32_t));
     int32_t *cluster_of = (int32_t *)malloc((size_t)N * sizeof(int32_t));
     float *centroid = (float *)malloc((size_t)G * 2 * sizeof(float));
     int32_t *near = (int32_t *)malloc((size_t)G * M * sizeof(int32_t));
@@ -421,8 +433,8 @@ int oracle_knn(const float *coords, const int32_t *cluster_id, int B, int N, int
     if (rc == ORACLE_OK) rc = build_members(cluster_id ? cluster_id + (size_t)b * N : NULL, N, S, members);
     if (rc == ORACLE_OK) {
       for (int c = 0; c < G; ++c)
-        for (int r = 0; r < S; ++r) cluster_of[members[(size_t)c * S + r]] = c;
-      image_centroids(xy, members, G, S, centroid);
+        for (int r = 0; r < cluster_size(c, N, S); ++r) cluster_of[members[(size_t)c * S + r]] = c;
+      image_centroids(xy, members, N, S, centroid);
       /* nearest clusters by centroid distance */
       for (int c = 0; c < G; ++c) {
         for (int e = 0; e < G; ++e) {
@@ -435,17 +447,21 @@ int oracle_knn(const float *coords, const int32_t *cluster_id, int B, int N, int
       if (near_clusters)
         memcpy(near_clusters + (size_t)b * G * M, near, (size_t)G * M * sizeof(int32_t));
       /* per token: all members of the near clusters are candidates */
-      for (int i = 0; i < N; ++i) {
+      for (int i = 0; i < N && rc == ORACLE_OK; ++i) {
         int c = cluster_of[i];
         int n = 0;
         for (int m = 0; m < M; ++m) {
           int e = near[(size_t)c * M + m];
-          for (int r = 0; r < S; ++r) {
+          for (int r = 0; r < cluster_size(e, N, S); ++r) {
             int j = members[(size_t)e * S + r];
             cand[n].d2 = dist2_f32(xy[2 * (size_t)i], xy[2 * (size_t)i + 1], xy[2 * (size_t)j], xy[2 * (size_t)j + 1]);
             cand[n].idx = j;
             ++n;
           }
+        }
+        if (n < K) {  /* a short last cluster among the near ones left fewer than K candidates */
+          rc = ORACLE_ERR_ARG;
+          break;
         }
         qsort(cand, (size_t)n, sizeof(cand_t), cand_less);
         int32_t *dst = nbr_idx + ((size_t)b * N + i) * K;

@@ -115,3 +115,20 @@ def test_full_image_with_blank_tokens():
     errs = check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, blank=True,
                            use_plan=True)
     print(errs)
+
+
+@pytest.mark.parametrize("use_plan", [False, True])
+@pytest.mark.parametrize("bias", [True, False])
+def test_promise_with_permuted_neighbour_lists(use_plan, bias):
+    """The cluster promise asks for distinct neighbours inside the near clusters, not for distance order: every
+    token's list is shuffled (the oracle's results are invariant to that order up to the slot each bias value
+    belongs to, and it gets the same shuffled table).  Also the tiled kernels without a bias tensor."""
+    print(f"case permuted lists plan={use_plan} bias={bias}", flush=True)
+    cfg = CONFIGS["knn_scale"].scaled(B=2, N=1024, C=64, H=2, dtype="bf16")
+    w = make_workload(cfg, blank=True)
+    nbr, near = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
+    rng = np.random.default_rng(17)
+    nbr = np.ascontiguousarray(rng.permuted(nbr, axis=2))
+    if not bias:
+        w["bias"] = None
+    check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, blank=True, use_plan=use_plan)

@@ -188,3 +188,55 @@ def test_argument_errors():
     bad = np.zeros((1, 16), dtype=np.int32)            # all tokens in cluster 0
     with pytest.raises(RuntimeError):
         oracle.knn(coords, bad, S=4, M=2, K=4)
+
+
+def test_short_last_cluster_hand_derived(golden_dir):
+    path = os.path.join(golden_dir, "knn_line_short_last_cluster.txt")
+    near_want = _read_lists(path, "near")
+    nbr_want = _read_lists(path, "nbr")
+    coords = np.stack([np.arange(14), np.zeros(14)], -1).astype(np.float32)[None]
+    cen = oracle.centroids(coords, None, S=4)
+    assert cen[0, :, 0].tolist() == [1.5, 5.5, 9.5, 12.5]
+    nbr, near = oracle.knn(coords, None, S=4, M=2, K=5)
+    assert near.shape == (1, 4, 2)
+    for c, lst in near_want.items():
+        assert near[0, c].tolist() == lst
+    for tok, lst in nbr_want.items():
+        assert nbr[0, tok].tolist() == lst
+    with pytest.raises(RuntimeError):
+        oracle.knn(coords, None, S=4, M=2, K=7)       # clusters 2 and 3 offer six candidates only
+
+
+@pytest.mark.parametrize("N", [500, 481, 33])
+def test_short_last_cluster_is_bruteforce_restricted_to_candidates(N):
+    """The library-sorted search over exactly the members of the near clusters, with a last cluster of
+    N - (G - 1) S tokens; with M = G the search is exact; scattered cluster ids equal the re-ordered case."""
+    S, M, K = 32, 3, 20
+    rng = np.random.default_rng(N)
+    coords = rng.uniform(0, 100, size=(2, N, 2)).astype(np.float32)
+    G = -(-N // S)
+    M = min(M, G)
+    if G == 2:
+        K = 1  # the smallest candidate set is the short cluster plus one full one
+    nbr, near = oracle.knn(coords, None, S, M, K)
+    for b in range(2):
+        members = [np.arange(c * S, min((c + 1) * S, N)) for c in range(G)]
+        cen = np.stack([coords[b, m].astype(np.float64).mean(axis=0) for m in members]).astype(np.float32)
+        want_near = _numpy_bruteforce(cen[None], M)[0]
+        assert np.array_equal(near[b], want_near)
+        for c in range(G):
+            cand = np.sort(np.concatenate([members[e] for e in want_near[c]]))
+            sub = _numpy_bruteforce(coords[b, cand][None], len(cand))[0]
+            for i in members[c]:
+                li = int(np.searchsorted(cand, i))
+                assert np.array_equal(nbr[b, i], cand[sub[li, :K]])
+    exact, _ = oracle.knn(coords, None, S, G, K)
+    assert np.array_equal(exact, oracle.knn_bruteforce(coords, K))
+    # scattered ids: the short cluster must be the last one
+    sizes = [len(m) for m in members]
+    cid = rng.permutation(np.repeat(np.arange(G), sizes)).astype(np.int32)
+    nbr_s, near_s = oracle.knn(coords[:1], cid[None], S, M, K)
+    order = np.argsort(cid, kind="stable")
+    nbr_o, near_o = oracle.knn(coords[:1, order], None, S, M, K)
+    assert np.array_equal(near_s, near_o)
+    assert np.array_equal(nbr_s[0][order], order[nbr_o[0]])
