@@ -12,7 +12,7 @@
  *     never allocates, frees or keeps them.  Tensors are dense, row-major, in
  *     the shapes stated below.  B = images, N = tokens per image, H = heads,
  *     d = channels per head, K = neighbours per token, S = tokens per cluster,
- *     G = N / S clusters per image, M = clusters searched per cluster.
+ *     G = ceil(N / S) clusters per image, M = clusters searched per cluster.
  *   - Token and cluster indices are per image (0..N-1, 0..G-1), int32.
  *   - `workspace` is caller-owned device scratch of at least the number of
  *     bytes the matching *_workspace_bytes() call returns (256-byte aligned);
@@ -163,11 +163,14 @@ int affmae_vts_bwd(const float* query_xy, const float* vis_xy, const void* feat,
  * the table is built once per encoder stage and reused, Sec. "Limitations").
  *
  *   coords        in  [B,N,2] fp32 (x,y), finite.
- *   cluster_id    in  [B,N] int32 with every cluster holding exactly S tokens,
- *                     or NULL meaning cluster_id[b,i] = i / S (tokens stored in
- *                     cluster order).
- *   B,N,S,M,K         N % S == 0, 1 <= M <= min(G, AFFMAE_MAX_NEAR),
- *                     1 <= K <= min(M*S, AFFMAE_MAX_K).  M == G is exact kNN.
+ *   cluster_id    in  [B,N] int32 with every cluster holding exactly S tokens
+ *                     (the last one, cluster G-1, the N - (G-1) S that are left
+ *                     when S does not divide N), or NULL meaning
+ *                     cluster_id[b,i] = i / S (tokens stored in cluster order).
+ *   B,N,S,M,K         G = ceil(N / S) clusters; 1 <= M <= min(G, AFFMAE_MAX_NEAR);
+ *                     1 <= K <= AFFMAE_MAX_K, and K at most the smallest candidate
+ *                     set any token can have, (M-1) S + N - (G-1) S (= M*S when S
+ *                     divides N); M*S <= 4096.  M == G is exact kNN.
  *   nbr_idx       out [B,N,K]: the K nearest tokens among the members of the M
  *                     clusters nearest to the token's own cluster, ascending in
  *                     (distance, token index).  The token itself takes part.
@@ -218,7 +221,8 @@ int affmae_knn_static(const float* coords, const int32_t* cluster_id, int B, int
  *   plan                    out caller-owned device buffer of affmae_pla_plan_bytes()
  *                               bytes, 256-byte aligned; opaque.
  * affmae_pla_plan_bytes returns 0, and affmae_pla_plan AFFMAE_ERR_UNSUPPORTED,
- * when the shapes are outside what the tiled kernels take (they need S % 16 == 0,
+ * when the shapes are outside what the tiled kernels take (they need S % 16 == 0
+ * and N % 16 == 0 - S need not divide N: the last cluster may be short -,
  * M*S <= 1024, N < 2^20 and N*S < 2^31); the attention calls then use the gather
  * kernels and ignore `plan`.
  */
@@ -251,8 +255,10 @@ int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B,
  *                     of near_clusters[b,c,:], and that a token's neighbours
  *                     are pairwise distinct - what affmae_knn produces with
  *                     cluster_id == NULL.  It allows the cluster-tiled kernels
- *                     (bf16 storage, d == 32, S % 16 == 0, M*S <= 1024); inputs
- *                     must then be finite.  With NULL, S and M are ignored.
+ *                     (bf16 storage, d == 32, S % 16 == 0, N % 16 == 0,
+ *                     M*S <= 1024; other shapes, head sizes 16 and 64 among them,
+ *                     are served by the slower gather kernels, same results);
+ *                     inputs must then be finite.  With NULL, S and M are ignored.
  *   plan          in  NULL, or the buffer affmae_pla_plan filled for this
  *                     nbr_idx / near_clusters and these B,N,K,S,M.
  *   k_blank,v_blank in [H,d] of `dtype`, or both NULL.

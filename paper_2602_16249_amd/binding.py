@@ -274,7 +274,7 @@ def affmae_knn(coords: torch.Tensor, cluster_id: Optional[torch.Tensor], S: int,
         raise ValueError("coords must be [B,N,2]")
     if cluster_id is not None:
         _dev(cluster_id, "cluster_id", torch.int32, (B, N))
-    G = N // S if S > 0 else 0
+    G = -(-N // S) if S > 0 else 0  # the last cluster is short when S does not divide N
     if nbr_idx is None:
         nbr_idx = torch.empty((B, N, K), dtype=torch.int32, device=coords.device)
     if near_clusters is None:
@@ -309,7 +309,7 @@ def affmae_pla_plan(nbr_idx: torch.Tensor, near_clusters: torch.Tensor, S: int, 
     lib = load_library()
     _dev(nbr_idx, "nbr_idx", torch.int32)
     B, N, K = nbr_idx.shape
-    _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+    _dev(near_clusters, "near_clusters", torch.int32, (B, -(-N // S), M))
     need = lib.affmae_pla_plan_bytes(B, N, K, S, M)
     if need == 0:
         return None
@@ -340,7 +340,7 @@ def affmae_pla_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
     if bias is not None:
         _dev(bias, "bias", q.dtype, (B, N, H, K))
     if near_clusters is not None:
-        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+        _dev(near_clusters, "near_clusters", torch.int32, (B, -(-N // S), M))
     if k_blank is not None:
         _dev(k_blank, "k_blank", q.dtype, (H, d))
         _dev(v_blank, "v_blank", q.dtype, (H, d))
@@ -384,7 +384,7 @@ def affmae_pla_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Opti
     if bias is not None:
         _dev(bias, "bias", q.dtype, (B, N, H, K))
     if near_clusters is not None:
-        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+        _dev(near_clusters, "near_clusters", torch.int32, (B, -(-N // S), M))
     if k_blank is not None:
         _dev(k_blank, "k_blank", q.dtype, (H, d))
         _dev(v_blank, "v_blank", q.dtype, (H, d))
@@ -437,7 +437,7 @@ def affmae_pla_fwd_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, coo
     K = nbr_idx.shape[2]
     _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
     if near_clusters is not None:
-        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+        _dev(near_clusters, "near_clusters", torch.int32, (B, -(-N // S), M))
     if k_blank is not None:
         _dev(k_blank, "k_blank", q.dtype, (H, d))
         _dev(v_blank, "v_blank", q.dtype, (H, d))
@@ -479,7 +479,7 @@ def affmae_pla_bwd_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, coo
     _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
     _dev(lse, "lse", torch.float32, (B, N, H))
     if near_clusters is not None:
-        _dev(near_clusters, "near_clusters", torch.int32, (B, N // S, M))
+        _dev(near_clusters, "near_clusters", torch.int32, (B, -(-N // S), M))
     g = {name: torch.empty_like(q) for name in ("dq", "dk", "dv")}
     g["drel_table"] = torch.empty((H, W, W), dtype=torch.float32, device=q.device)
     if k_blank is not None:

@@ -18,7 +18,7 @@ struct KnnPlan {
 };
 KnnPlan knn_plan(int B, int N, int S, int M) {
   KnnPlan p;
-  const size_t G = (size_t)N / S;
+  const size_t G = ((size_t)N + S - 1) / S;
   size_t off = 0;
   p.centroid_off = off;
   off += align_up((size_t)B * G * 2 * sizeof(float));
@@ -32,10 +32,11 @@ KnnPlan knn_plan(int B, int N, int S, int M) {
 
 int check_knn_shape(int B, int N, int S, int M, int K) {
   if (B < 1 || N < 1 || S < 1 || M < 1 || K < 1) return AFFMAE_ERR_SHAPE;
-  if (N % S) return AFFMAE_ERR_SHAPE;
-  const int G = N / S;
+  const int G = (int)(((long long)N + S - 1) / S);
   if (M > G) return AFFMAE_ERR_SHAPE;
-  if ((long long)K > (long long)M * S) return AFFMAE_ERR_SHAPE;
+  // every token needs K candidates: the smallest candidate set holds the short last cluster (if there is one)
+  const long long last = (long long)N - (long long)(G - 1) * S;
+  if ((long long)K > (long long)(M - 1) * S + last) return AFFMAE_ERR_SHAPE;
   if (K > AFFMAE_MAX_K || M > AFFMAE_MAX_NEAR) return AFFMAE_ERR_UNSUPPORTED;
   if ((long long)M * S > 4096) return AFFMAE_ERR_UNSUPPORTED;  // candidate staging: 16 B each in 64 KB of LDS
   return AFFMAE_OK;
@@ -58,7 +59,7 @@ bool tiled_shape_ok(int B, int N, int K, int S, int M) {
   a.B = B; a.N = N; a.K = K; a.S = S; a.M = M; a.d = 32; a.dtype = AFFMAE_BF16;
   static const int32_t dummy = 0;
   a.near_clusters = &dummy;  // only tested for being non-null
-  return B >= 1 && N >= 1 && K >= 1 && S >= 1 && M >= 1 && N % S == 0 && affmae::pla_cluster_supported(a);
+  return B >= 1 && N >= 1 && K >= 1 && S >= 1 && M >= 1 && affmae::pla_cluster_supported(a);
 }
 
 }  // namespace
@@ -200,7 +201,7 @@ int affmae_knn(const float* coords, const int32_t* cluster_id, int B, int N, int
   affmae::KnnArgs a;
   a.coords = coords;
   a.cluster_id = cluster_id;
-  a.B = B; a.N = N; a.S = S; a.M = M; a.K = K; a.G = N / S;
+  a.B = B; a.N = N; a.S = S; a.M = M; a.K = K; a.G = (N + S - 1) / S;
   a.nbr_idx = nbr_idx;
   a.near_clusters = near_clusters ? near_clusters : reinterpret_cast<int32_t*>(ws + plan.near_off);
   a.centroid = reinterpret_cast<float*>(ws + plan.centroid_off);
@@ -255,7 +256,7 @@ size_t affmae_pla_plan_bytes(int B, int N, int K, int S, int M) {
 int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B, int N, int K, int S, int M,
                     void* plan, size_t plan_bytes, void* stream) {
   if (!nbr_idx || !near_clusters || !plan) return AFFMAE_ERR_NULL;
-  if (B < 1 || N < 1 || K < 1 || S < 1 || M < 1 || N % S || M > N / S) return AFFMAE_ERR_SHAPE;
+  if (B < 1 || N < 1 || K < 1 || S < 1 || M < 1 || M > (N + S - 1) / S) return AFFMAE_ERR_SHAPE;
   if (!tiled_shape_ok(B, N, K, S, M)) return AFFMAE_ERR_UNSUPPORTED;
   if (plan_bytes < affmae::pla_plan_bytes(B, N, K, S, M) || misaligned(plan, kAlign)) return AFFMAE_ERR_WORKSPACE;
   return affmae::launch_pla_plan(nbr_idx, near_clusters, B, N, K, S, M, plan, static_cast<hipStream_t>(stream)) ==
@@ -266,7 +267,7 @@ int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B,
 
 size_t affmae_pla_fwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
   if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
-  if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && N % S == 0) return affmae_pla_plan_bytes(B, N, K, S, M);
+  if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0) return affmae_pla_plan_bytes(B, N, K, S, M);
   return 0;
 }
 
@@ -285,7 +286,7 @@ int pla_fwd_run(const void* q, const void* k, const void* v, const void* bias, c
   const int rc = check_pla_shape(B, N, H, d, K, dtype);
   if (rc != AFFMAE_OK) return rc;
   if (near_clusters) {
-    if (S < 1 || M < 1 || N % S || M > N / S) return AFFMAE_ERR_SHAPE;
+    if (S < 1 || M < 1 || M > (N + S - 1) / S) return AFFMAE_ERR_SHAPE;
   }
   if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16)) return AFFMAE_ERR_SHAPE;
   if ((k_blank && misaligned(k_blank, 16)) || (v_blank && misaligned(v_blank, 16))) return AFFMAE_ERR_SHAPE;
@@ -328,7 +329,7 @@ size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, 
   if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
   const size_t gather = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
   size_t tiled = 0;
-  if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && N % S == 0 && tiled_shape_ok(B, N, K, S, M))
+  if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && tiled_shape_ok(B, N, K, S, M))
     tiled = align_up(affmae::pla_plan_bytes(B, N, K, S, M)) + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, S, M);
   return gather > tiled ? gather : tiled;
 }
@@ -348,7 +349,7 @@ int pla_bwd_run(const void* q, const void* k, const void* v, const void* bias, c
   const int rc = check_pla_shape(B, N, H, d, K, dtype);
   if (rc != AFFMAE_OK) return rc;
   if (near_clusters) {
-    if (S < 1 || M < 1 || N % S || M > N / S) return AFFMAE_ERR_SHAPE;
+    if (S < 1 || M < 1 || M > (N + S - 1) / S) return AFFMAE_ERR_SHAPE;
   }
   if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(dout, 16) || misaligned(dq, 16) ||
       misaligned(dk, 16) || misaligned(dv, 16))
@@ -442,7 +443,7 @@ int affmae_pla_fwd_relpos(const void* q, const void* k, const void* v, const flo
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (relpos_in_kernel(B, N, d, K, S, M, dtype, near_clusters != nullptr)) {
     // the tiled kernel looks the bias up itself: no bias tensor
-    if (M > N / S) return AFFMAE_ERR_SHAPE;
+    if (M > (N + S - 1) / S) return AFFMAE_ERR_SHAPE;
     affmae::PlaArgs a = {};
     a.q = q; a.k = k; a.v = v; a.nbr_idx = nbr_idx; a.near_clusters = near_clusters;
     a.k_blank = k_blank; a.v_blank = v_blank;
@@ -511,7 +512,7 @@ int affmae_pla_bwd_relpos(const void* q, const void* k, const void* v, const flo
     if (!out) return AFFMAE_ERR_NULL;
     if ((k_blank == nullptr) != (v_blank == nullptr)) return AFFMAE_ERR_NULL;
     if ((dk_blank == nullptr) != (dv_blank == nullptr)) return AFFMAE_ERR_NULL;
-    if (M > N / S) return AFFMAE_ERR_SHAPE;
+    if (M > (N + S - 1) / S) return AFFMAE_ERR_SHAPE;
     if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(dout, 16) || misaligned(dq, 16) ||
         misaligned(dk, 16) || misaligned(dv, 16) || misaligned(out, 16))
       return AFFMAE_ERR_SHAPE;

@@ -18,6 +18,9 @@
 namespace affmae {
 namespace {
 
+// Clusters hold S tokens, except that the last one (cluster G - 1, G = ceil(N / S)) holds what is left.
+__device__ __forceinline__ int cluster_size(int c, int N, int S, int G) { return c == G - 1 ? N - (G - 1) * S : S; }
+
 // members[b, c*S + r] = r-th token (ascending) whose cluster id is c.  One
 // workgroup per image; a thread owns a cluster and scans the id array, which is
 // staged through LDS in chunks.  Slots that an invalid assignment leaves unset
@@ -41,7 +44,7 @@ __global__ __launch_bounds__(256) void members_kernel(const int32_t* __restrict_
       __syncthreads();
       if (c < G) {
         for (int t = 0; t < n; ++t) {
-          if (ids[t] == c && count < S) {
+          if (ids[t] == c && count < cluster_size(c, N, S, G)) {
             mem[(size_t)c * S + count] = base + t;
             ++count;
           }
@@ -62,8 +65,9 @@ __global__ __launch_bounds__(256) void centroid_kernel(const float* __restrict__
   const int b = gc / G, c = gc % G;
   const float* xy = coords + (size_t)b * N * 2;
   double sx = 0.0, sy = 0.0;
-  for (int base = 0; base < S; base += kWave) {
-    const int n = min(kWave, S - base);
+  const int size = cluster_size(c, N, S, G);
+  for (int base = 0; base < size; base += kWave) {
+    const int n = min(kWave, size - base);
     float x = 0.f, y = 0.f;
     if (lane < n) {
       int tok = c * S + base + lane;
@@ -77,8 +81,8 @@ __global__ __launch_bounds__(256) void centroid_kernel(const float* __restrict__
     }
   }
   if (lane == 0) {
-    centroid[2 * (size_t)gc + 0] = (float)(sx / (double)S);
-    centroid[2 * (size_t)gc + 1] = (float)(sy / (double)S);
+    centroid[2 * (size_t)gc + 0] = (float)(sx / (double)size);
+    centroid[2 * (size_t)gc + 1] = (float)(sy / (double)size);
   }
 }
 
@@ -124,9 +128,10 @@ __global__ __launch_bounds__(kKnnWaves* kWave) void knn_kernel(const float* __re
     const int m = p / S, r = p - m * S;
     int e = near[((size_t)b * G + c) * M + m];
     e = min(max(e, 0), G - 1);
-    int tok = e * S + r;
+    const bool real = r < cluster_size(e, N, S, G);  // a short last cluster fills only part of its places
+    int tok = min(e * S + r, N - 1);
     if (mem) tok = min(max(mem[tok], 0), N - 1);
-    cand[p] = make_float4(xy[2 * (size_t)tok], xy[2 * (size_t)tok + 1], __int_as_float(tok), 0.f);
+    cand[p] = make_float4(xy[2 * (size_t)tok], xy[2 * (size_t)tok + 1], __int_as_float(real ? tok : -1), 0.f);
   }
   __syncthreads();
   const int lane = threadIdx.x & (kWave - 1);
@@ -135,9 +140,11 @@ __global__ __launch_bounds__(kKnnWaves* kWave) void knn_kernel(const float* __re
   auto cand_key = [&](int p, float qx, float qy) -> key_t {
     if (p >= Cn) return kKeyMax;
     const float4 cp = cand[p];
+    if (__float_as_int(cp.z) < 0) return kKeyMax;  // an empty place of a short cluster
     return make_key(dist2(qx, qy, cp.x, cp.y), __float_as_int(cp.z));
   };
-  for (int r = wave; r < S; r += kKnnWaves) {
+  const int my_size = cluster_size(c, N, S, G);
+  for (int r = wave; r < my_size; r += kKnnWaves) {
     int qtok = c * S + r;
     if (mem) qtok = min(max(mem[qtok], 0), N - 1);
     const float qx = xy[2 * (size_t)qtok], qy = xy[2 * (size_t)qtok + 1];
@@ -202,19 +209,20 @@ __global__ __launch_bounds__(kKnnWaves* kWave) void knn_fast_kernel(const float*
 #pragma unroll
   for (int row = 0; row < kFastRows; ++row) {
     const int p = row * kWave + lane;
-    cok[row] = p < Cn;
-    const int pp = cok[row] ? p : 0;
+    const int pp = p < Cn ? p : 0;
     const int m = pp / S, r = pp - m * S;
     int e = near[((size_t)b * G + c) * M + m];
     e = min(max(e, 0), G - 1);
-    int tok = e * S + r;
+    cok[row] = p < Cn && r < cluster_size(e, N, S, G);  // a short last cluster fills only part of its places
+    int tok = min(e * S + r, N - 1);
     if (mem) tok = min(max(mem[tok], 0), N - 1);
     cx[row] = xy[2 * (size_t)tok];
     cy[row] = xy[2 * (size_t)tok + 1];
     cid[row] = cok[row] ? (uint32_t)tok : 0xffffffffu;
   }
   uint32_t guess = 0u;  // threshold that worked for the previous token (0: none yet)
-  for (int r = wave; r < S; r += kKnnWaves) {
+  const int my_size = cluster_size(c, N, S, G);
+  for (int r = wave; r < my_size; r += kKnnWaves) {
     int qtok = c * S + r;
     if (mem) qtok = min(max(mem[qtok], 0), N - 1);
     const float qx = xy[2 * (size_t)qtok], qy = xy[2 * (size_t)qtok + 1];

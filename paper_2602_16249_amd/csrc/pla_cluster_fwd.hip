@@ -363,7 +363,8 @@ bool pla_cluster_relpos_supported(const PlaArgs& a) {
 
 bool pla_cluster_supported(const PlaArgs& a) {
   if (!a.near_clusters || a.dtype != 1 || a.d != kD) return false;
-  if (a.S % 16 || a.S < 16) return false;                         // token tiles must not straddle clusters
+  if (a.S % 16 || a.S < 16 || a.N % 16) return false;             // token tiles: whole, and never straddling clusters
+  if (a.M > (a.N + a.S - 1) / a.S) return false;
   if ((long long)a.M * a.S / 16 > kMaxSlots) return false;        // tile set of a strip is a 64-bit mask
   if (a.K > 64 || a.N / 16 > 65535) return false;                 // 16-bit plan entries and tile ids
   if ((long long)a.N * a.S >= (1ll << 31)) return false;          // range of the reciprocal division

@@ -254,7 +254,7 @@ hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, i
   char* base = static_cast<char*>(plan);
   PlanParams p;
   p.nbr_idx = nbr_idx; p.near = near;
-  p.N = N; p.K = K; p.S = S; p.M = M; p.G = N / S;
+  p.N = N; p.K = K; p.S = S; p.M = M; p.G = (N + S - 1) / S;  // the last cluster may be short (whole tiles: N % 16 == 0)
   p.s_magic = div_magic(S); p.k_magic = div_magic(K);
   p.strips = L.strips; p.strips_per_image = N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
   p.slots = reinterpret_cast<uint16_t*>(base + L.slots_off);

@@ -49,14 +49,15 @@ def test_knn_rejects_bad_arguments_on_host():
     lib = aff.load_library()
     one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
     assert lib.affmae_knn(None, None, 1, 64, 8, 2, 4, one, None, one, 1 << 20, None) == -1
-    assert lib.affmae_knn(one, None, 1, 65, 8, 2, 4, one, None, one, 1 << 20, None) == -2     # N % S
+    assert lib.affmae_knn(one, None, 1, 65, 8, 2, 10, one, None, one, 1 << 20, None) == -2    # a last cluster of one token: 9 candidates
     assert lib.affmae_knn(one, None, 1, 64, 8, 9, 4, one, None, one, 1 << 20, None) == -2     # M > G
     assert lib.affmae_knn(one, None, 1, 64, 8, 2, 17, one, None, one, 1 << 20, None) == -2    # K > M*S
     assert lib.affmae_knn(one, None, 1, 1024, 16, 8, 64 + 1, one, None, one, 1 << 20, None) == -5
     assert lib.affmae_knn(one, None, 1, 64, 8, 2, 4, one, None, None, 0, None) == -4          # no workspace
     assert lib.affmae_knn(one, None, 1, 64, 8, 2, 4, one, None, one, 16, None) == -4          # too small
     assert lib.affmae_knn_workspace_bytes(1, 64, 8, 2, 4) > 0
-    assert lib.affmae_knn_workspace_bytes(1, 65, 8, 2, 4) == 0
+    assert lib.affmae_knn_workspace_bytes(1, 65, 8, 2, 4) > 0
+    assert lib.affmae_knn_workspace_bytes(1, 65, 8, 2, 10) == 0
 
 
 def test_cluster_rejects_bad_arguments_on_host():
@@ -128,7 +129,7 @@ def test_attention_rejects_bad_arguments_on_host():
     assert fwd(d=24) == -5
     assert fwd(K=65) == -5
     assert fwd(B=0) == -2
-    assert fwd(near=p, S=7) == -2     # N % S with a cluster promise
+    assert fwd(near=p, S=64, M=2) == -2   # more near clusters than clusters, with a cluster promise
     assert fwd(q=ctypes.c_void_p(4098)) == -2   # misaligned rows
 
     def bwd(ws=None, ws_bytes=0, dq=p, **kw):
@@ -184,7 +185,7 @@ def test_relpos_validates_the_attention_call_before_its_first_launch():
 
     assert fwd(q=odd) == -2            # misaligned rows: found by the attention call's own checks
     assert fwd(kb=one) == -1           # blank key without blank value
-    assert fwd(near=one, S=7, M=2) == -2
+    assert fwd(near=one, S=64, M=2) == -2   # more near clusters than clusters
 
     def bwd(q=one, kb=None, vb=None, dkb=None, dvb=None, dq=one):
         return lib.affmae_pla_bwd_relpos(q, one, one, one, one, one, None, None, kb, vb, one, one, one, 1, 64, 2, 32, 8, 0,
@@ -203,4 +204,4 @@ def test_knn_static_rejects_on_host():
     assert lib.affmae_knn_workspace_bytes(B, N, S, M, K) > (4 << 20)
     assert lib.affmae_knn_static(one, None, B, N, S, M, K, one, None, None) == -4   # beyond the fixed scratch
     assert lib.affmae_knn_static(None, None, 1, 64, 8, 2, 4, one, None, None) == -1
-    assert lib.affmae_knn_static(one, None, 1, 65, 8, 2, 4, one, None, None) == -2
+    assert lib.affmae_knn_static(one, None, 1, 65, 8, 2, 10, one, None, None) == -2

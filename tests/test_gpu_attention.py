@@ -132,3 +132,30 @@ def test_promise_with_permuted_neighbour_lists(use_plan, bias):
     if not bias:
         w["bias"] = None
     check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, blank=True, use_plan=use_plan)
+
+
+@pytest.mark.parametrize("N,tiled", [(4000, True), (4001, False)])
+def test_short_last_cluster_end_to_end(N, tiled):
+    """coords -> affmae_cluster -> affmae_knn -> affmae_pla_fwd / affmae_pla_bwd with N not a multiple of the
+    cluster size (a masked batch keeps whatever number of tokens the mask leaves): curve order, neighbour table
+    and near clusters bit-equal to the oracle, attention within the bf16 bound.  N = 4000 (whole 16-token tiles)
+    runs the tiled kernels; N = 4001 takes the gather kernels although the promise is given."""
+    import torch
+    import paper_2602_16249_amd as aff
+    print(f"case end to end N={N}", flush=True)
+    S, M, K, H, d = 64, 8, 48, 2, 32
+    cfg = CONFIGS["mae_pt_s1_1024"].scaled(B=2, N=N, C=H * d, H=H, K=K, S=S, M=M, dtype="bf16")
+    w = make_workload(cfg)
+    rng = np.random.default_rng(N)
+    perm = np.stack([rng.permutation(N) for _ in range(cfg.B)])
+    shuffled = np.ascontiguousarray(np.take_along_axis(w["coords"], perm[..., None], axis=1))
+    frame = (0.0, 0.0, float(cfg.frame), float(cfg.frame))
+    order, cid = aff.affmae_cluster(torch.from_numpy(shuffled).cuda(), S, frame)
+    rorder, rcid = oracle.cluster(shuffled, S, frame)
+    assert np.array_equal(order.cpu().numpy(), rorder) and np.array_equal(cid.cpu().numpy(), rcid)
+    coords = np.ascontiguousarray(np.take_along_axis(shuffled, rorder[..., None].astype(np.int64), axis=1))
+    nbr_d, near_d = aff.affmae_knn(torch.from_numpy(coords).cuda(), None, S, M, K)
+    nbr, near = oracle.knn(coords, None, S, M, K)
+    assert np.array_equal(nbr_d.cpu().numpy(), nbr) and np.array_equal(near_d.cpu().numpy(), near)
+    assert (aff.load_library().affmae_pla_plan_bytes(cfg.B, N, K, S, M) > 0) == tiled
+    check_attention(w, nbr, "bf16", 1.0 / np.sqrt(d), near=near, S=S, M=M, use_plan=tiled)

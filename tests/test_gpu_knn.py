@@ -94,3 +94,36 @@ def test_knn_full_size_configs(name):
     # the table produced without an explicit assignment (tokens are in cluster order) is the same
     nbr2, near2 = _gpu_knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
     assert np.array_equal(nbr2, rnbr) and np.array_equal(near2, rnear)
+
+
+RAGGED = [
+    # name, B, N, S, M, K: the last cluster holds N - (G - 1) S tokens
+    ("mae_pt_s1_1024", 2, 4000, 64, 8, 48),    # 62 clusters of 64 and one of 32
+    ("knn_scale", 2, 481, 32, 3, 20),          # a last cluster of one token
+    ("knn_scale", 3, 33, 32, 2, 1),            # two clusters, the second a single token
+    ("merged_stage", 2, 1001, 32, 8, 48),      # N odd: nothing is a whole tile
+    ("tiny_f32", 2, 1000, 128, 8, 48),         # 1024 candidate places (general kernel), 104 tokens in the last cluster
+    ("knn_scale", 1, 100, 64, 2, 100),         # M == G: exact search over 100 tokens, K = all of them... capped below
+]
+
+
+@pytest.mark.parametrize("name,B,N,S,M,K", RAGGED)
+def test_knn_short_last_cluster(name, B, N, S, M, K):
+    K = min(K, 64)
+    cfg = CONFIGS[name].scaled(B=B, N=N, S=S, M=M, K=K)
+    print(f"case ragged {name} B={B} N={N} S={S} M={M} K={K}", flush=True)
+    w = make_workload(cfg, features=False)
+    nbr, near = _gpu_knn(w["coords"], None, S, M, K)
+    rnbr, rnear = oracle.knn(w["coords"], None, S, M, K)
+    assert near.shape == rnear.shape == (B, -(-N // S), M)
+    assert np.array_equal(near, rnear)
+    assert np.array_equal(nbr, rnbr)
+    # the same clusters given as an explicit (scattered) assignment
+    rng = np.random.default_rng(N)
+    perm = np.stack([rng.permutation(N) for _ in range(B)])
+    coords = np.ascontiguousarray(np.take_along_axis(w["coords"], perm[..., None], axis=1))
+    cid = (perm // S).astype(np.int32)
+    nbr_s, near_s = _gpu_knn(coords, cid, S, M, K)
+    rnbr_s, rnear_s = oracle.knn(coords, cid, S, M, K)
+    assert np.array_equal(near_s, rnear_s)
+    assert np.array_equal(nbr_s, rnbr_s)

@@ -48,7 +48,7 @@ class WorkloadConfig:
 
     @property
     def G(self) -> int:
-        return self.N // self.S
+        return -(-self.N // self.S)  # the last cluster is short when S does not divide N
 
     @property
     def seed(self) -> int:
@@ -181,8 +181,6 @@ def make_workload(cfg: WorkloadConfig, seed: Optional[int] = None, blank: bool =
                   features: bool = True) -> Dict[str, np.ndarray]:
     """Coordinates in cluster order, cluster ids, and (optionally) features."""
     rng = np.random.default_rng(cfg.seed if seed is None else seed)
-    if cfg.N % cfg.S:
-        raise ValueError("N must be a multiple of S")
     coords = make_coords(cfg.coords, cfg.B, cfg.N, cfg.frame, rng)
     perm = morton_cluster_order(coords, cfg.frame)
     coords = np.ascontiguousarray(np.take_along_axis(coords, perm[..., None], axis=1))
