@@ -39,6 +39,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         for name in ("oracle_centroids", "oracle_knn", "oracle_knn_bruteforce", "oracle_cluster", "oracle_vts_table", "oracle_vts_fwd", "oracle_vts_bwd",
+                     "oracle_merge_select", "oracle_merge_fwd", "oracle_merge_bwd",
                      "oracle_pla_fwd", "oracle_pla_bwd", "oracle_relpos_bias", "oracle_relpos_dtable", "oracle_num_threads"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_set_num_threads.restype = None
@@ -137,6 +138,54 @@ def vts_bwd(query_xy, vis_xy, feat, table, dout, grid, p: float, eps: float):
                                   cell, Kt, ctypes.c_double(p), ctypes.c_double(eps), _p(dfeat), _p(dq),
                                   ctypes.byref(dp), ctypes.byref(dp_abs)), "oracle_vts_bwd")
     return {"dfeat": dfeat, "dquery": dq, "dp": float(dp.value), "dp_abs": float(dp_abs.value)}
+
+
+def merge_select(score: np.ndarray, n_keep: int) -> np.ndarray:
+    """Anchors of the neighbourhood merging: score [B,N] fp32 -> anchor_idx [B,n_keep] int32, the n_keep tokens
+    with the largest score (equal scores: lower index first), in ascending token index."""
+    score = np.ascontiguousarray(score, dtype=np.float32)
+    B, N = score.shape
+    out = np.empty((B, n_keep), dtype=np.int32)
+    _check(_load().oracle_merge_select(_p(score), B, N, n_keep, _p(out)), "oracle_merge_select")
+    return out
+
+
+def merge_fwd(coords, feat, score, nbr_idx, anchor_idx, p: float, want_weights: bool = False):
+    """Merged features [B,n_keep,C] (and the aggregation weights [B,n_keep,K] on request)."""
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    feat = _f64(feat)
+    score = np.ascontiguousarray(score, dtype=np.float32)
+    nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    anchor_idx = np.ascontiguousarray(anchor_idx, dtype=np.int32)
+    B, N, C = feat.shape
+    K = nbr_idx.shape[2]
+    n_keep = anchor_idx.shape[1]
+    out = np.empty((B, n_keep, C), dtype=np.float64)
+    w = np.empty((B, n_keep, K), dtype=np.float64) if want_weights else None
+    _check(_load().oracle_merge_fwd(_p(coords), _p(feat), _p(score), _p(nbr_idx), _p(anchor_idx), B, N, C, K, n_keep,
+                                    ctypes.c_double(p), _p(out), _p(w)), "oracle_merge_fwd")
+    return (out, w) if want_weights else out
+
+
+def merge_bwd(coords, feat, score, nbr_idx, anchor_idx, dout, p: float):
+    """Backward of merge_fwd -> dict(dfeat [B,N,C], dscore [B,N], dp float, dp_abs float)."""
+    coords = np.ascontiguousarray(coords, dtype=np.float32)
+    feat = _f64(feat)
+    dout = _f64(dout)
+    score = np.ascontiguousarray(score, dtype=np.float32)
+    nbr_idx = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    anchor_idx = np.ascontiguousarray(anchor_idx, dtype=np.int32)
+    B, N, C = feat.shape
+    K = nbr_idx.shape[2]
+    n_keep = anchor_idx.shape[1]
+    dfeat = np.empty((B, N, C), dtype=np.float64)
+    dscore = np.empty((B, N), dtype=np.float64)
+    dp = ctypes.c_double(0.0)
+    dp_abs = ctypes.c_double(0.0)
+    _check(_load().oracle_merge_bwd(_p(coords), _p(feat), _p(score), _p(nbr_idx), _p(anchor_idx), _p(dout), B, N, C, K,
+                                    n_keep, ctypes.c_double(p), _p(dfeat), _p(dscore), ctypes.byref(dp),
+                                    ctypes.byref(dp_abs)), "oracle_merge_bwd")
+    return {"dfeat": dfeat, "dscore": dscore, "dp": float(dp.value), "dp_abs": float(dp_abs.value)}
 
 
 def centroids(coords: np.ndarray, cluster_id: Optional[np.ndarray], S: int) -> np.ndarray:

@@ -49,7 +49,19 @@
  *     equal-size clusters with a space-filling curve it does not name; reading:
  *     Z-order (Morton) curve over coordinates quantised to 16 bits per axis of a
  *     caller-given frame, x in the even key bits, ties by token index, clusters
- *     = consecutive runs of S tokens along the curve (the last may be short).
+ *     = consecutive runs of S tokens along the curve (the last may be short);
+ *   - neighbourhood merging (oracle_merge_*): Sec. "AutoFocusFormer", the paragraph
+ *     on downsampling (a learned importance score per token, the top share d_s of
+ *     the tokens kept as anchors, the rest merged into nearby anchors by a
+ *     differentiable, location-aware aggregation; the anchors keep their
+ *     coordinates); the paper leaves the operator to the AFF paper.  Readings:
+ *     the score is an input (the one-layer MLP is the caller's layer); the
+ *     n_keep = d_s N tokens with the largest score are the anchors, equal scores
+ *     going to the lower index, listed in ascending token index (which keeps the
+ *     curve order); an anchor aggregates the K tokens of its own neighbourhood
+ *     (itself among them) with the weights softmax_j(score_j - p |x_j - x_anchor|);
+ *     the merged token carries the weighted sum of their features and the
+ *     anchor's coordinates;
  *
  * Parity pins (tests/test_oracle_*.py): brute force over all pairs with a
  * library sort, hand-derived grid fixtures, exact integer arithmetic on integer
@@ -335,6 +347,158 @@ int oracle_vts_bwd(const float *query_xy, const float *vis_xy, const double *fea
       dp_abs_sum += fabs(dp_query);
       dquery[((size_t)b * Mq + m) * 2] = dqx;
       dquery[((size_t)b * Mq + m) * 2 + 1] = dqy;
+    }
+  }
+  if (dp) *dp = dp_sum;
+  if (dp_abs) *dp_abs = dp_abs_sum;
+  return ORACLE_OK;
+}
+
+/*
+ * Neighbourhood merging (Sec. "AutoFocusFormer": after several local-attention blocks the token set is
+ * downsampled; an importance score per token, the top-ranked tokens kept as anchors, the remaining tokens merged
+ * into nearby anchors by a differentiable, location-aware aggregation).
+ *
+ * oracle_merge_select: score [B,N] fp32 (finite) -> anchor_idx [B,n_keep]: the n_keep tokens with the largest
+ * score (equal scores: the lower index first), listed in ascending token index.
+ */
+typedef struct {
+  float s;
+  int32_t idx;
+} score_t;
+
+static int score_before(const void *pa, const void *pb) {
+  const score_t *a = (const score_t *)pa, *b = (const score_t *)pb;
+  if (a->s > b->s) return -1;
+  if (a->s < b->s) return 1;
+  if (a->idx < b->idx) return -1;
+  if (a->idx > b->idx) return 1;
+  return 0;
+}
+
+static int int_less(const void *pa, const void *pb) {
+  const int32_t a = *(const int32_t *)pa, b = *(const int32_t *)pb;
+  return (a > b) - (a < b);
+}
+
+int oracle_merge_select(const float *score, int B, int N, int n_keep, int32_t *anchor_idx) {
+  if (!score || !anchor_idx || B < 0 || N <= 0 || n_keep < 1 || n_keep > N) return ORACLE_ERR_ARG;
+  for (size_t t = 0; t < (size_t)B * N; ++t)
+    if (!(score[t] - score[t] == 0.f)) return ORACLE_ERR_ARG; /* NaN or infinite */
+  score_t *all = (score_t *)malloc((size_t)N * sizeof(score_t));
+  if (!all) return ORACLE_ERR_ALLOC;
+  for (int b = 0; b < B; ++b) {
+    for (int i = 0; i < N; ++i) {
+      all[i].s = score[(size_t)b * N + i];
+      all[i].idx = i;
+    }
+    qsort(all, (size_t)N, sizeof(score_t), score_before);
+    int32_t *dst = anchor_idx + (size_t)b * n_keep;
+    for (int a = 0; a < n_keep; ++a) dst[a] = all[a].idx;
+    qsort(dst, (size_t)n_keep, sizeof(int32_t), int_less);
+  }
+  free(all);
+  return ORACLE_OK;
+}
+
+/* The aggregation weights of one anchor: w_j = softmax_j(score[n_j] - p |x_{n_j} - x_anchor|), j < K. */
+static void merge_weights(const float *xy, const float *score, const int32_t *row, int anchor, int K, double p,
+                          double *w, double *dist) {
+  double zmax = -INFINITY, sum = 0.0;
+  for (int j = 0; j < K; ++j) {
+    const double dx = (double)xy[2 * (size_t)row[j]] - (double)xy[2 * (size_t)anchor];
+    const double dy = (double)xy[2 * (size_t)row[j] + 1] - (double)xy[2 * (size_t)anchor + 1];
+    dist[j] = sqrt(dx * dx + dy * dy);
+    w[j] = (double)score[row[j]] - p * dist[j];
+    if (w[j] > zmax) zmax = w[j];
+  }
+  for (int j = 0; j < K; ++j) {
+    w[j] = exp(w[j] - zmax);
+    sum += w[j];
+  }
+  for (int j = 0; j < K; ++j) w[j] /= sum;
+}
+
+static int merge_check(const int32_t *nbr_idx, const int32_t *anchor_idx, int B, int N, int K, int n_keep) {
+  for (size_t t = 0; t < (size_t)B * N * K; ++t)
+    if (nbr_idx[t] < 0 || nbr_idx[t] >= N) return ORACLE_ERR_ARG;
+  for (size_t t = 0; t < (size_t)B * n_keep; ++t)
+    if (anchor_idx[t] < 0 || anchor_idx[t] >= N) return ORACLE_ERR_ARG;
+  return ORACLE_OK;
+}
+
+/*
+ * oracle_merge_fwd: coords [B,N,2] fp32, feat [B,N,C], score [B,N] fp32, nbr_idx [B,N,K] (the stage's neighbour
+ * table), anchor_idx [B,n_keep] -> out [B,n_keep,C]: out[a] = sum_j w_j feat[n(anchor_a, j)];
+ * weights [B,n_keep,K] may be NULL.  (The merged token's coordinates are the anchor's: nothing to compute.)
+ */
+int oracle_merge_fwd(const float *coords, const double *feat, const float *score, const int32_t *nbr_idx,
+                     const int32_t *anchor_idx, int B, int N, int C, int K, int n_keep, double p, double *out,
+                     double *weights) {
+  if (!coords || !feat || !score || !nbr_idx || !anchor_idx || !out) return ORACLE_ERR_ARG;
+  if (B < 0 || N <= 0 || C <= 0 || K < 1 || K > 64 || n_keep < 1 || n_keep > N) return ORACLE_ERR_ARG;
+  if (merge_check(nbr_idx, anchor_idx, B, N, K, n_keep) != ORACLE_OK) return ORACLE_ERR_ARG;
+  for (int b = 0; b < B; ++b) {
+    const float *xy = coords + (size_t)b * N * 2;
+    for (int a = 0; a < n_keep; ++a) {
+      const int t = anchor_idx[(size_t)b * n_keep + a];
+      const int32_t *row = nbr_idx + ((size_t)b * N + t) * K;
+      double w[64], dist[64];
+      merge_weights(xy, score + (size_t)b * N, row, t, K, p, w, dist);
+      double *o = out + ((size_t)b * n_keep + a) * C;
+      for (int c = 0; c < C; ++c) o[c] = 0.0;
+      for (int j = 0; j < K; ++j) {
+        if (weights) weights[((size_t)b * n_keep + a) * K + j] = w[j];
+        const double *f = feat + ((size_t)b * N + row[j]) * C;
+        for (int c = 0; c < C; ++c) o[c] += w[j] * f[c];
+      }
+    }
+  }
+  return ORACLE_OK;
+}
+
+/*
+ * oracle_merge_bwd: chain rule on oracle_merge_fwd for L = sum(dout * out).  With g_j = <dout_a, feat_{n_j}> and
+ * dz_j = w_j (g_j - sum_i w_i g_i):
+ *   dfeat [B,N,C]: dfeat[n_j] += w_j dout_a;   dscore [B,N]: dscore[n_j] += dz_j;
+ *   dp (scalar, summed over all anchors) = sum_j dz_j (-|x_{n_j} - x_anchor|);
+ *   dp_abs (optional, a scale for judging errors of dp, no part of the method): the sum over the anchors of the
+ *   absolute value of each anchor's contribution to dp.
+ */
+int oracle_merge_bwd(const float *coords, const double *feat, const float *score, const int32_t *nbr_idx,
+                     const int32_t *anchor_idx, const double *dout, int B, int N, int C, int K, int n_keep, double p,
+                     double *dfeat, double *dscore, double *dp, double *dp_abs) {
+  if (!coords || !feat || !score || !nbr_idx || !anchor_idx || !dout || !dfeat || !dscore) return ORACLE_ERR_ARG;
+  if (B < 0 || N <= 0 || C <= 0 || K < 1 || K > 64 || n_keep < 1 || n_keep > N) return ORACLE_ERR_ARG;
+  if (merge_check(nbr_idx, anchor_idx, B, N, K, n_keep) != ORACLE_OK) return ORACLE_ERR_ARG;
+  for (size_t t = 0; t < (size_t)B * N * C; ++t) dfeat[t] = 0.0;
+  for (size_t t = 0; t < (size_t)B * N; ++t) dscore[t] = 0.0;
+  double dp_sum = 0.0, dp_abs_sum = 0.0;
+  for (int b = 0; b < B; ++b) {
+    const float *xy = coords + (size_t)b * N * 2;
+    for (int a = 0; a < n_keep; ++a) {
+      const int t = anchor_idx[(size_t)b * n_keep + a];
+      const int32_t *row = nbr_idx + ((size_t)b * N + t) * K;
+      const double *go = dout + ((size_t)b * n_keep + a) * C;
+      double w[64], dist[64], g[64], gbar = 0.0, dp_anchor = 0.0;
+      merge_weights(xy, score + (size_t)b * N, row, t, K, p, w, dist);
+      for (int j = 0; j < K; ++j) {
+        const double *f = feat + ((size_t)b * N + row[j]) * C;
+        double *df = dfeat + ((size_t)b * N + row[j]) * C;
+        g[j] = 0.0;
+        for (int c = 0; c < C; ++c) {
+          g[j] += go[c] * f[c];
+          df[c] += w[j] * go[c];
+        }
+        gbar += w[j] * g[j];
+      }
+      for (int j = 0; j < K; ++j) {
+        const double dz = w[j] * (g[j] - gbar);
+        dscore[(size_t)b * N + row[j]] += dz;
+        dp_anchor += dz * (-dist[j]);
+      }
+      dp_sum += dp_anchor;
+      dp_abs_sum += fabs(dp_anchor);
     }
   }
   if (dp) *dp = dp_sum;
