@@ -87,6 +87,36 @@ def bench_virtual_tokens(aff, torch, np, dev, reps: int = 20):
             "fwd_algorithmic_GBs": fwd_bytes / (t[1] * 1e-3) / 1e9, "bwd_algorithmic_GBs": bwd_bytes / (t[2] * 1e-3) / 1e9}
 
 
+def bench_merging(aff, torch, np, cfg, s, flush, reps: int = 20):
+    """Neighbourhood merging between two stages of the configuration: d_s = 0.25 of the tokens kept as anchors,
+    every anchor aggregating its K neighbours (the stage's own table), forward and backward; cold medians."""
+    dev = s["q"].device
+    B, N, C, K = cfg.B, cfg.N, cfg.C, cfg.K
+    n_keep = N // 4
+    p = 0.25
+    feat = s["q"].reshape(B, N, C)
+    score = torch.randn((B, N), device=dev)
+    dout = torch.randn((B, n_keep, C), device=dev).to(feat.dtype)
+    anchors, axy = aff.affmae_merge_select(score, n_keep, s["coords"])
+    out = aff.affmae_merge_fwd(feat, s["coords"], score, s["nbr"], anchors, p)
+    ws = torch.empty(aff.load_library().affmae_merge_bwd_workspace_bytes(B, N, K, n_keep), dtype=torch.uint8, device=dev)
+    grads = aff.affmae_merge_bwd(feat, s["coords"], score, s["nbr"], anchors, dout, p, want_dp=False, workspace=ws)
+    one = [s]
+    t_sel = float(np.median(cold_times(torch, lambda _: aff.affmae_merge_select(score, n_keep, s["coords"], anchors, axy), one, reps, flush)))
+    t_fwd = float(np.median(cold_times(torch, lambda _: aff.affmae_merge_fwd(feat, s["coords"], score, s["nbr"], anchors, p, out=out), one, reps, flush)))
+    t_bwd = float(np.median(cold_times(torch, lambda _: aff.affmae_merge_bwd(feat, s["coords"], score, s["nbr"], anchors, dout, p, want_dp=False, grads=grads, workspace=ws), one, reps, flush)))
+    elt = 2 if cfg.dtype == "bf16" else 4
+    tokens, anch = B * N, B * n_keep
+    # every tensor element once; the gathered feature rows counted once, as stored
+    fwd_bytes = anch * (4 * K + elt * C + 4) + tokens * (elt * C + 8 + 4)
+    bwd_bytes = anch * (4 * K + elt * C + 4) + tokens * (elt * C + 8 + 4 + elt * C + 4)
+    return {"workload": f"{cfg.name}: {B} x {N} tokens -> {n_keep} anchors each (d_s = 0.25), C = {C}, K = {K}, {cfg.dtype}",
+            "select_ms": t_sel, "fwd_ms": t_fwd, "bwd_ms": t_bwd,
+            "tokens_per_s_fwd_bwd": tokens / ((t_fwd + t_bwd) * 1e-3),
+            "fwd_algorithmic_GBs": fwd_bytes / (t_fwd * 1e-3) / 1e9, "bwd_algorithmic_GBs": bwd_bytes / (t_bwd * 1e-3) / 1e9,
+            "frac_of_hbm_peak": (fwd_bytes + bwd_bytes) / ((t_fwd + t_bwd) * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def bench_relpos(aff, torch, np, cfg, sets, scale, promise, flush, reps: int = 20):
     """The same attention with the bias taken from a relative-position table (9 x 9 bins of one 8-px patch per
     head) instead of a bias tensor: forward and backward through affmae_pla_*_relpos, timed like the headline
@@ -436,6 +466,7 @@ def main() -> int:
 
     if not args.no_extras:
         result["relative_position_bias"] = bench_relpos(aff, torch, np, cfg, sets, scale, promise, flush)
+        result["neighbourhood_merging"] = bench_merging(aff, torch, np, cfg, sets[0], flush)
         g = bench_graphs(torch, sets, step, attn_only, args.steps)
         result["hip_graph"] = {"step_ms": g["step_ms"], "attn_fwd_bwd_ms": g["attn_fwd_bwd_ms"],
                                "attn_tokens_per_s": tokens / (g["attn_fwd_bwd_ms"] * 1e-3),

@@ -5,7 +5,8 @@
  * hierarchical backbone: balanced clustering of the tokens along a space-filling
  * curve, the batched neighbour search that builds fixed-size neighbourhoods over
  * irregular 2-D token coordinates, local attention, forward and backward, over
- * each token's K neighbours, and the point decoder's virtual sampled tokens.
+ * each token's K neighbours, the neighbourhood merging that downsamples the token
+ * set between stages, and the point decoder's virtual sampled tokens.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library
@@ -155,6 +156,62 @@ int affmae_vts_bwd(const float* query_xy, const float* vis_xy, const void* feat,
                    const void* dout, int B, int Mq, int Nv, int C, int Hg, int Wg, float x0, float y0, float cell,
                    int Kt, float p, float eps, int dtype, void* dfeat, float* dquery, float* dp, void* workspace,
                    size_t workspace_bytes, void* stream);
+
+/*
+ * Neighbourhood merging (paper, Sec. "AutoFocusFormer": after several local-
+ * attention blocks the token set is downsampled; an importance score is learned
+ * per token by a one-layer MLP, the top-ranked share d_s of the tokens is kept as
+ * anchors, and the remaining tokens are merged into nearby anchors through a
+ * differentiable, location-aware aggregation; supplement "AFF architecture": a
+ * linear projection follows every merging block).  The paper leaves the operator
+ * to the AFF paper; this library takes the following form.  The score layer and
+ * the projection are the caller's dense layers.
+ *
+ * affmae_merge_select  anchors of every image: the n_keep (= d_s N) tokens with the
+ *                      largest score, equal scores (-0 and +0 are equal) going to
+ *                      the lower token index, listed in ascending token index -
+ *                      tokens stored in curve order stay in curve order, so the
+ *                      next stage's clusters are again consecutive runs.
+ *   score      in  [B,N] fp32, finite      coords     in  [B,N,2] fp32 or NULL
+ *   anchor_idx out [B,n_keep] int32        anchor_xy  out [B,n_keep,2] fp32 or NULL:
+ *                      the anchors' coordinates, which the merged tokens keep
+ *
+ * affmae_merge_fwd     out[b,a,:] = sum_j w_j feat[b, n(t,j), :] over the K tokens
+ *                      n(t,j) of the neighbourhood of the anchor's token t =
+ *                      anchor_idx[b,a] (row t of nbr_idx, the token itself among
+ *                      them), w_j = softmax_j(score[b,n(t,j)] - p |x_n(t,j) - x_t|),
+ *                      distances in fp32.  A token in no anchor's neighbourhood is
+ *                      dropped; one in several contributes to each.
+ *   feat   in [B,N,C] dtype     nbr_idx in [B,N,K] int32 (values clamped to 0..N-1)
+ *   out    out [B,n_keep,C] dtype, fp32 sums, round to nearest even
+ *
+ * affmae_merge_bwd     gradients of L = <dout, out>, with g_j = <dout[b,a,:],
+ *                      feat[b,n(t,j),:]> and dz_j = w_j (g_j - sum_i w_i g_i):
+ *   dfeat  out [B,N,C] dtype: sum over the (anchor, j) pairs with n(t,j) = the token
+ *                      of w_j dout[b,a,:] (fp32 sums; 0 for tokens no anchor uses)
+ *   dscore out [B,N] fp32: the same sum of dz_j - the gradient that trains the score
+ *   dp     out device scalar fp32 or NULL: sum over all pairs of dz_j (-|x_n - x_t|)
+ *   workspace  affmae_merge_bwd_workspace_bytes(B, N, K, n_keep) bytes
+ *   (the order of the additions into dfeat and dscore, hence their last bits, may
+ *   vary from run to run)
+ *
+ * Limits: 1 <= K <= AFFMAE_MAX_K, 1 <= n_keep <= N <= 2^24, 0 <= p finite, B*N and
+ * B*n_keep*K below 2^31 - 8; coords 8-byte aligned.  Rows that are whole 16-byte
+ * pieces (C a multiple of 8 for bf16, of 4 for fp32) in 16-byte aligned tensors run
+ * the fast kernels, other shapes slower ones, same results.
+ * Errors: AFFMAE_ERR_NULL, AFFMAE_ERR_SHAPE, AFFMAE_ERR_DTYPE, AFFMAE_ERR_UNSUPPORTED,
+ * AFFMAE_ERR_WORKSPACE.
+ */
+int affmae_merge_select(const float* score, const float* coords, int B, int N, int n_keep, int32_t* anchor_idx,
+                        float* anchor_xy, void* stream);
+int affmae_merge_fwd(const void* feat, const float* coords, const float* score, const int32_t* nbr_idx,
+                     const int32_t* anchor_idx, int B, int N, int C, int K, int n_keep, float p, int dtype, void* out,
+                     void* stream);
+size_t affmae_merge_bwd_workspace_bytes(int B, int N, int K, int n_keep);
+int affmae_merge_bwd(const void* feat, const float* coords, const float* score, const int32_t* nbr_idx,
+                     const int32_t* anchor_idx, const void* dout, int B, int N, int C, int K, int n_keep, float p,
+                     int dtype, void* dfeat, float* dscore, float* dp, void* workspace, size_t workspace_bytes,
+                     void* stream);
 
 /*
  * affmae_knn - neighbourhood construction (paper, Sec. "AutoFocusFormer":

@@ -10,6 +10,9 @@ from .binding import (  # noqa: F401
     affmae_cluster,
     affmae_knn,
     affmae_knn_static,
+    affmae_merge_bwd,
+    affmae_merge_fwd,
+    affmae_merge_select,
     affmae_pla_bwd,
     affmae_pla_bwd_relpos,
     affmae_pla_fwd,
@@ -28,5 +31,5 @@ from .binding import (  # noqa: F401
     use_timed_library,
 )
 
-__all__ = ["AffmaeError", "affmae_cluster", "affmae_knn", "affmae_knn_static", "affmae_pla_fwd", "affmae_pla_bwd", "affmae_pla_plan", "affmae_pla_fwd_relpos", "affmae_pla_bwd_relpos", "affmae_vts_table", "affmae_vts_fwd", "affmae_vts_bwd", "library_path", "load_library",
+__all__ = ["AffmaeError", "affmae_cluster", "affmae_knn", "affmae_knn_static", "affmae_merge_select", "affmae_merge_fwd", "affmae_merge_bwd", "affmae_pla_fwd", "affmae_pla_bwd", "affmae_pla_plan", "affmae_pla_fwd_relpos", "affmae_pla_bwd_relpos", "affmae_vts_table", "affmae_vts_fwd", "affmae_vts_bwd", "library_path", "load_library",
            "status_string"]

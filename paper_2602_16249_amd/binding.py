@@ -79,6 +79,15 @@ def _load(path: str):
     lib.affmae_vts_bwd.restype = _c_int
     lib.affmae_vts_bwd.argtypes = ([_c_void_p] * 5 + [_c_int] * 6 + [_c_float] * 3 + [_c_int] + [_c_float] * 2 + [_c_int]
                                    + [_c_void_p] * 4 + [_c_size_t, _c_void_p])
+    lib.affmae_merge_select.restype = _c_int
+    lib.affmae_merge_select.argtypes = [_c_void_p, _c_void_p] + [_c_int] * 3 + [_c_void_p] * 3
+    lib.affmae_merge_fwd.restype = _c_int
+    lib.affmae_merge_fwd.argtypes = [_c_void_p] * 5 + [_c_int] * 5 + [_c_float, _c_int, _c_void_p, _c_void_p]
+    lib.affmae_merge_bwd_workspace_bytes.restype = _c_size_t
+    lib.affmae_merge_bwd_workspace_bytes.argtypes = [_c_int] * 4
+    lib.affmae_merge_bwd.restype = _c_int
+    lib.affmae_merge_bwd.argtypes = ([_c_void_p] * 6 + [_c_int] * 5 + [_c_float, _c_int] + [_c_void_p] * 4
+                                     + [_c_size_t, _c_void_p])
     lib.affmae_knn_workspace_bytes.restype = _c_size_t
     lib.affmae_knn_workspace_bytes.argtypes = [_c_int] * 5
     lib.affmae_knn.restype = _c_int
@@ -260,6 +269,89 @@ def affmae_vts_bwd(query_xy: torch.Tensor, vis_xy: torch.Tensor, feat: torch.Ten
     g = {"dfeat": dfeat, "dquery": dquery}
     if want_dp:
         g["dp"] = dp
+    return g
+
+
+def affmae_merge_select(score: torch.Tensor, n_keep: int, coords: Optional[torch.Tensor] = None,
+                        anchor_idx: Optional[torch.Tensor] = None, anchor_xy: Optional[torch.Tensor] = None
+                        ) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """score [B,N] fp32 -> (anchor_idx [B,n_keep] int32, anchor_xy [B,n_keep,2] fp32 or None without coords)."""
+    lib = load_library()
+    _dev(score, "score", torch.float32)
+    B, N = score.shape
+    if coords is not None:
+        _dev(coords, "coords", torch.float32, (B, N, 2))
+    if anchor_idx is None:
+        anchor_idx = torch.empty((B, n_keep), dtype=torch.int32, device=score.device)
+    _dev(anchor_idx, "anchor_idx", torch.int32, (B, n_keep))
+    if anchor_xy is None and coords is not None:
+        anchor_xy = torch.empty((B, n_keep, 2), dtype=torch.float32, device=score.device)
+    if anchor_xy is not None:
+        _dev(anchor_xy, "anchor_xy", torch.float32, (B, n_keep, 2))
+    rc = lib.affmae_merge_select(_ptr(score), _ptr(coords), B, N, n_keep, _ptr(anchor_idx), _ptr(anchor_xy), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_merge_select", rc)
+    return anchor_idx, anchor_xy
+
+
+def affmae_merge_fwd(feat: torch.Tensor, coords: torch.Tensor, score: torch.Tensor, nbr_idx: torch.Tensor,
+                     anchor_idx: torch.Tensor, p: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Merged features [B,n_keep,C] in feat's dtype."""
+    lib = load_library()
+    code = _dtype_code(feat)
+    _dev(feat, "feat")
+    B, N, C = feat.shape
+    _dev(coords, "coords", torch.float32, (B, N, 2))
+    _dev(score, "score", torch.float32, (B, N))
+    _dev(nbr_idx, "nbr_idx", torch.int32)
+    K = nbr_idx.shape[2]
+    _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
+    _dev(anchor_idx, "anchor_idx", torch.int32)
+    n_keep = anchor_idx.shape[1]
+    _dev(anchor_idx, "anchor_idx", torch.int32, (B, n_keep))
+    if out is None:
+        out = torch.empty((B, n_keep, C), dtype=feat.dtype, device=feat.device)
+    _dev(out, "out", feat.dtype, (B, n_keep, C))
+    rc = lib.affmae_merge_fwd(_ptr(feat), _ptr(coords), _ptr(score), _ptr(nbr_idx), _ptr(anchor_idx), B, N, C, K, n_keep,
+                              float(p), code, _ptr(out), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_merge_fwd", rc)
+    return out
+
+
+def affmae_merge_bwd(feat: torch.Tensor, coords: torch.Tensor, score: torch.Tensor, nbr_idx: torch.Tensor,
+                     anchor_idx: torch.Tensor, dout: torch.Tensor, p: float, want_dp: bool = True,
+                     grads: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None
+                     ) -> Dict[str, torch.Tensor]:
+    """Gradients of the merging -> dict(dfeat [B,N,C], dscore [B,N] fp32[, dp scalar fp32])."""
+    lib = load_library()
+    code = _dtype_code(feat)
+    _dev(feat, "feat")
+    B, N, C = feat.shape
+    K = nbr_idx.shape[2]
+    n_keep = anchor_idx.shape[1]
+    _dev(coords, "coords", torch.float32, (B, N, 2))
+    _dev(score, "score", torch.float32, (B, N))
+    _dev(nbr_idx, "nbr_idx", torch.int32, (B, N, K))
+    _dev(anchor_idx, "anchor_idx", torch.int32, (B, n_keep))
+    _dev(dout, "dout", feat.dtype, (B, n_keep, C))
+    g = grads if grads is not None else {}
+    if "dfeat" not in g:
+        g["dfeat"] = torch.empty_like(feat)
+    if "dscore" not in g:
+        g["dscore"] = torch.empty((B, N), dtype=torch.float32, device=feat.device)
+    if want_dp and "dp" not in g:
+        g["dp"] = torch.empty((), dtype=torch.float32, device=feat.device)
+    _dev(g["dfeat"], "dfeat", feat.dtype, (B, N, C))
+    _dev(g["dscore"], "dscore", torch.float32, (B, N))
+    need = lib.affmae_merge_bwd_workspace_bytes(B, N, K, n_keep)
+    if workspace is None:
+        workspace = _workspace(max(need, 256), feat.device)
+    rc = lib.affmae_merge_bwd(_ptr(feat), _ptr(coords), _ptr(score), _ptr(nbr_idx), _ptr(anchor_idx), _ptr(dout), B, N, C,
+                              K, n_keep, float(p), code, _ptr(g["dfeat"]), _ptr(g["dscore"]),
+                              _ptr(g["dp"]) if want_dp else None, _ptr(workspace), workspace.numel(), _stream())
+    if rc != 0:
+        raise AffmaeError("affmae_merge_bwd", rc)
     return g
 
 

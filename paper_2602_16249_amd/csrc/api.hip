@@ -185,6 +185,73 @@ int affmae_vts_bwd(const float* query_xy, const float* vis_xy, const void* feat,
   return affmae::launch_vts_bwd(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
 }
 
+}  // extern "C"
+
+namespace {
+int check_merge_shape(int B, int N, int C, int K, int n_keep) {
+  if (B < 1 || N < 1 || C < 1 || K < 1 || n_keep < 1 || n_keep > N) return AFFMAE_ERR_SHAPE;
+  if (K > AFFMAE_MAX_K) return AFFMAE_ERR_UNSUPPORTED;
+  if ((long long)B * N > (1ll << 31) - 8 || (long long)B * n_keep * K > (1ll << 31) - 8)
+    return AFFMAE_ERR_UNSUPPORTED;  // tokens and (anchor, neighbour) pairs are indexed with int32
+  return AFFMAE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int affmae_merge_select(const float* score, const float* coords, int B, int N, int n_keep, int32_t* anchor_idx,
+                        float* anchor_xy, void* stream) {
+  if (!score || !anchor_idx) return AFFMAE_ERR_NULL;
+  if (anchor_xy && !coords) return AFFMAE_ERR_NULL;
+  if (B < 1 || N < 1 || n_keep < 1 || n_keep > N) return AFFMAE_ERR_SHAPE;
+  if (N > (1 << 24) || (long long)B * N > (1ll << 31) - 8) return AFFMAE_ERR_UNSUPPORTED;
+  return affmae::launch_merge_select(score, coords, B, N, n_keep, anchor_idx, anchor_xy,
+                                     static_cast<hipStream_t>(stream)) == hipSuccess
+             ? AFFMAE_OK
+             : AFFMAE_ERR_DEVICE;
+}
+
+int affmae_merge_fwd(const void* feat, const float* coords, const float* score, const int32_t* nbr_idx,
+                     const int32_t* anchor_idx, int B, int N, int C, int K, int n_keep, float p, int dtype, void* out,
+                     void* stream) {
+  if (!feat || !coords || !score || !nbr_idx || !anchor_idx || !out) return AFFMAE_ERR_NULL;
+  if (dtype != AFFMAE_F32 && dtype != AFFMAE_BF16) return AFFMAE_ERR_DTYPE;
+  const int rc = check_merge_shape(B, N, C, K, n_keep);
+  if (rc != AFFMAE_OK) return rc;
+  if (!(p >= 0.f) || !(p < 3e38f)) return AFFMAE_ERR_SHAPE;
+  if (misaligned(coords, 8) || misaligned(feat, dtype == AFFMAE_BF16 ? 2 : 4) || misaligned(out, dtype == AFFMAE_BF16 ? 2 : 4))
+    return AFFMAE_ERR_SHAPE;
+  affmae::MergeArgs a = {};
+  a.feat = feat; a.coords = coords; a.score = score; a.nbr_idx = nbr_idx; a.anchor_idx = anchor_idx;
+  a.B = B; a.N = N; a.C = C; a.K = K; a.n_keep = n_keep; a.dtype = dtype; a.p = p; a.out = out;
+  return affmae::launch_merge_fwd(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+
+size_t affmae_merge_bwd_workspace_bytes(int B, int N, int K, int n_keep) {
+  if (check_merge_shape(B, N, 1, K, n_keep) != AFFMAE_OK) return 0;
+  return align_up(affmae::merge_bwd_workspace_bytes(B, N, K, n_keep));
+}
+
+int affmae_merge_bwd(const void* feat, const float* coords, const float* score, const int32_t* nbr_idx,
+                     const int32_t* anchor_idx, const void* dout, int B, int N, int C, int K, int n_keep, float p,
+                     int dtype, void* dfeat, float* dscore, float* dp, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  if (!feat || !coords || !score || !nbr_idx || !anchor_idx || !dout || !dfeat || !dscore) return AFFMAE_ERR_NULL;
+  if (dtype != AFFMAE_F32 && dtype != AFFMAE_BF16) return AFFMAE_ERR_DTYPE;
+  const int rc = check_merge_shape(B, N, C, K, n_keep);
+  if (rc != AFFMAE_OK) return rc;
+  if (!(p >= 0.f) || !(p < 3e38f)) return AFFMAE_ERR_SHAPE;
+  const size_t el = dtype == AFFMAE_BF16 ? 2 : 4;
+  if (misaligned(coords, 8) || misaligned(feat, el) || misaligned(dout, el) || misaligned(dfeat, el)) return AFFMAE_ERR_SHAPE;
+  const size_t need = align_up(affmae::merge_bwd_workspace_bytes(B, N, K, n_keep));
+  if (!workspace || workspace_bytes < need || misaligned(workspace, kAlign)) return AFFMAE_ERR_WORKSPACE;
+  affmae::MergeArgs a = {};
+  a.feat = feat; a.coords = coords; a.score = score; a.nbr_idx = nbr_idx; a.anchor_idx = anchor_idx; a.dout = dout;
+  a.B = B; a.N = N; a.C = C; a.K = K; a.n_keep = n_keep; a.dtype = dtype; a.p = p;
+  a.dfeat = dfeat; a.dscore = dscore; a.dp = dp; a.workspace = workspace;
+  return affmae::launch_merge_bwd(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
+}
+
 size_t affmae_knn_workspace_bytes(int B, int N, int S, int M, int K) {
   if (check_knn_shape(B, N, S, M, K) != AFFMAE_OK) return 0;
   return knn_plan(B, N, S, M).total;

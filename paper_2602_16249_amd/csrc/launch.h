@@ -47,6 +47,37 @@ hipError_t launch_vts_fwd(const VtsArgs& a, hipStream_t stream);
 size_t vts_bwd_workspace_bytes(int B, int Mq, int Nv, int Kt);
 hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream);
 
+// Building blocks shared by the gather-style backward passes (vts.hip): a sum of partial results in a fixed order,
+// the filing of (query, candidate) pairs per token, and the per-token sum of weighted upstream rows.
+size_t sum_parts_scratch_floats(size_t n);
+hipError_t launch_sum_parts(const float* part, size_t n, float* part2, float* out, hipStream_t stream);
+hipError_t launch_pair_lists(const int32_t* pair_token, int B, int Nv, int pairs_per_image, int32_t* offset,
+                             int32_t* list, hipStream_t stream);
+hipError_t launch_pair_gather(const void* dout, const float* weights, const int32_t* offset, const int32_t* list,
+                              size_t tokens, int C, int Kt, int dtype, void* dfeat, bool pieces, hipStream_t stream);
+
+// Neighbourhood merging (merge.hip): anchor selection, location-aware aggregation, backward.
+struct MergeArgs {
+  const void* feat;           // [B,N,C]
+  const float* coords;        // [B,N,2]
+  const float* score;         // [B,N]
+  const int32_t* nbr_idx;     // [B,N,K]
+  const int32_t* anchor_idx;  // [B,n_keep]
+  const void* dout;           // [B,n_keep,C]
+  int B, N, C, K, n_keep, dtype;
+  float p;
+  void* out;      // [B,n_keep,C]
+  void* dfeat;    // [B,N,C]
+  float* dscore;  // [B,N]
+  float* dp;      // device scalar or nullptr
+  void* workspace;
+};
+hipError_t launch_merge_select(const float* score, const float* coords, int B, int N, int n_keep, int32_t* anchor_idx,
+                               float* anchor_xy, hipStream_t stream);
+hipError_t launch_merge_fwd(const MergeArgs& a, hipStream_t stream);
+size_t merge_bwd_workspace_bytes(int B, int N, int K, int n_keep);
+hipError_t launch_merge_bwd(const MergeArgs& a, hipStream_t stream);
+
 // Relative-position bias from a per-head table over quantised offsets (relpos.hip).
 struct RelposArgs {
   const float* coords;     // [B,N,2]

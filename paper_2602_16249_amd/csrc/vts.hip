@@ -1013,49 +1013,71 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
   if (a.dp) {
     // parts: one per wave of the grouped kernels, one per query otherwise
     const size_t n = grouped ? (size_t)gridg.x * 4 : (size_t)a.B * a.Mq;
-    const size_t blocks = (n + kDpPer - 1) / kDpPer;
-    if (blocks == 1) {
-      AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part, n, n, a.dp);
-    } else {
-      AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3((unsigned)blocks), dim3(1024), 0, stream, dp_part, n,
-                    (size_t)kDpPer, dp_part2);
-      AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, dp_part2, blocks, blocks,
-                    a.dp);
-    }
+    const hipError_t e = launch_sum_parts(dp_part, n, dp_part2, a.dp, stream);
+    if (e != hipSuccess) return e;
   }
-  {
-    // token ranges per image: enough workgroups to fill the chip, never more tokens than the LDS counters hold
-    const int want = (192 + a.B - 1) / a.B;
-    int range = std::max(64, (a.Nv + want - 1) / want);
-    range = std::min(range, kListRange);
-    const int ranges = (a.Nv + range - 1) / range;
-    const dim3 lgrid((unsigned)(a.B * ranges));
-    const int ppi = a.Mq * a.Kt, pieces_max = (ppi + 3) / 4 + 1;  // + 1: an image may start inside a piece
+  const hipError_t e = launch_pair_lists(pair_token, a.B, a.Nv, a.Mq * a.Kt, offset, list, stream);
+  if (e != hipSuccess) return e;
+  const bool pieces = vts_grouped(a, a.dout, a.dfeat, nullptr);  // (Kt <= 16 is not needed here, only the row shape)
+  return launch_pair_gather(a.dout, weights, offset, list, tokens, a.C, a.Kt, a.dtype, a.dfeat, pieces, stream);
+}
+
+// out = sum of part[0..n) in a fixed order (part2: room for ceil(n / 16384) floats).
+size_t sum_parts_scratch_floats(size_t n) { return (n + kDpPer - 1) / kDpPer; }
+hipError_t launch_sum_parts(const float* part, size_t n, float* part2, float* out, hipStream_t stream) {
+  const size_t blocks = (n + kDpPer - 1) / kDpPer;
+  if (blocks <= 1) {
+    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, part, n, n, out);
+  } else {
+    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3((unsigned)blocks), dim3(1024), 0, stream, part, n,
+                  (size_t)kDpPer, part2);
+    AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, part2, blocks, blocks, out);
+  }
+  return hipGetLastError();
+}
+
+// Files pairs per token: pair_token[b * pairs_per_image + i] = the (global, b * Nv + t) token of pair i of image b
+// -> offset [B * Nv + 1] (start of every token's list) and list [B * pairs_per_image] (pair ids grouped by token).
+hipError_t launch_pair_lists(const int32_t* pair_token, int B, int Nv, int pairs_per_image, int32_t* offset,
+                             int32_t* list, hipStream_t stream) {
+  // token ranges per image: enough workgroups to fill the chip, never more tokens than the LDS counters hold
+  const int want = (192 + B - 1) / B;
+  int range = std::max(64, (Nv + want - 1) / want);
+  range = std::min(range, kListRange);
+  const int ranges = (Nv + range - 1) / range;
+  const dim3 lgrid((unsigned)(B * ranges));
+  const int ppi = pairs_per_image, pieces_max = (ppi + 3) / 4 + 1;  // + 1: an image may start inside a piece
 #define AFFMAE_VTS_LISTS(NP)                                                                                         \
   AFFMAE_LAUNCH("vts_lists_kernel", stream, vts_lists_kernel<NP>, lgrid, dim3(kListThreads), 0, stream, pair_token, \
-                a.B, a.Nv, ppi, range, ranges, offset, list)
-    if (pieces_max <= 4 * kListThreads) AFFMAE_VTS_LISTS(4);
-    else if (pieces_max <= 9 * kListThreads) AFFMAE_VTS_LISTS(9);
-    else AFFMAE_VTS_LISTS(0);
+                B, Nv, ppi, range, ranges, offset, list)
+  if (pieces_max <= 4 * kListThreads) AFFMAE_VTS_LISTS(4);
+  else if (pieces_max <= 9 * kListThreads) AFFMAE_VTS_LISTS(9);
+  else AFFMAE_VTS_LISTS(0);
 #undef AFFMAE_VTS_LISTS
-  }
-  if (vts_grouped(a, a.dout, a.dfeat, nullptr)) {  // (Kt <= 16 is not needed here, only the row shape)
+  return hipGetLastError();
+}
+
+// dfeat[token] = sum over the token's pairs of weights[pair] * dout[pair / Kt]  (rows of C channels of `dtype`;
+// `pieces`: rows are whole 16-byte pieces, 16-byte aligned, and every row offset fits 32 bits).
+hipError_t launch_pair_gather(const void* dout, const float* weights, const int32_t* offset, const int32_t* list,
+                              size_t tokens, int C, int Kt, int dtype, void* dfeat, bool pieces, hipStream_t stream) {
+  if (pieces) {
     const dim3 per4(round_up8(((long long)tokens + 15) / 16));
-    if (a.dtype == 1)
+    if (dtype == 1)
       AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat16_kernel<bf16_t>, per4, dim3(256), 0, stream,
-                    (const bf16_t*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (bf16_t*)a.dfeat);
+                    (const bf16_t*)dout, weights, offset, list, (int)tokens, C, Kt, (bf16_t*)dfeat);
     else
       AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat16_kernel<float>, per4, dim3(256), 0, stream,
-                    (const float*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (float*)a.dfeat);
+                    (const float*)dout, weights, offset, list, (int)tokens, C, Kt, (float*)dfeat);
     return hipGetLastError();
   }
   const dim3 per_token(round_up8(((long long)tokens + 3) / 4));
-  if (a.dtype == 1)
+  if (dtype == 1)
     AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<bf16_t>, per_token, dim3(256), 0, stream,
-                  (const bf16_t*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (bf16_t*)a.dfeat);
+                  (const bf16_t*)dout, weights, offset, list, (int)tokens, C, Kt, (bf16_t*)dfeat);
   else
     AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<float>, per_token, dim3(256), 0, stream,
-                  (const float*)a.dout, weights, offset, list, (int)tokens, a.C, a.Kt, (float*)a.dfeat);
+                  (const float*)dout, weights, offset, list, (int)tokens, C, Kt, (float*)dfeat);
   return hipGetLastError();
 }
 
