@@ -149,7 +149,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const char* kimg = reinterpret_cast<const char*>(p.k + (size_t)img_base * C);
   const char* vimg = reinterpret_cast<const char*>(p.v + (size_t)img_base * C);
   const int la = lane >> 2, lc = lane & 3;
-  const uint32_t lane_off = (uint32_t)(la * C * 2 + lc * 16);
+  const uint32_t lane_off_h = (uint32_t)(la * C * 2 + lc * 16 + h * kD * 2);  // the lane's piece of a tile's rows, head h
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
   u32x4* kv = kv_all[wave];
   const int wr_chunk = tile_chunk(la, lc);
@@ -306,18 +306,18 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
 
       const int npairs = (nsl + 1) >> 1;
       auto load_pair = [&](int pr, u32x4& k0, u32x4& v0, u32x4& k1, u32x4& v1) {
+        // the image's rows as a scalar base + a 32-bit vector offset (an image is smaller than 4 GB): the tile's
+        // byte offset is one scalar product, added to the lane's offset by one vector add per tile that serves the
+        // K and the V load (64-bit scalar arithmetic per tile costs ten instructions, and a wave issues one
+        // instruction per turn of whatever kind); made opaque, or the compiler rebuilds 64-bit vector addresses
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
-        const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
-        const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
-        // scalar tile address + 32-bit lane offset (made opaque here, or the compiler keeps image + lane offset
-        // as a 64-bit vector and adds the tile's offset with two vector instructions per load)
-        uint32_t off = lane_off;
-        asm volatile("" : "+v"(off));
-        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + off);
-        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + off);
-        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + off);
-        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + off);
+        uint32_t off0 = lane_off_h + tile0 * tile_bytes, off1 = lane_off_h + tile1 * tile_bytes;
+        asm volatile("" : "+v"(off0), "+v"(off1));
+        k0 = *reinterpret_cast<const u32x4*>(kimg + off0);
+        v0 = *reinterpret_cast<const u32x4*>(vimg + off0);
+        k1 = *reinterpret_cast<const u32x4*>(kimg + off1);
+        v1 = *reinterpret_cast<const u32x4*>(vimg + off1);
       };
       // pieces as loaded -> LDS -> operand pieces
       auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],

@@ -133,7 +133,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   const char* kimg = reinterpret_cast<const char*>(p.k + (size_t)img_base * C);
   const char* vimg = reinterpret_cast<const char*>(p.v + (size_t)img_base * C);
   const int la = lane >> 2, lc = lane & 3;
-  const uint32_t lane_off = (uint32_t)(la * C * 2 + lc * 16);
+  const uint32_t lane_off_h = (uint32_t)(la * C * 2 + lc * 16 + h * kD * 2);  // the lane's piece of a tile's rows, head h
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
   u32x4* kv = kv_all[wave];
   const int wr_chunk = tile_chunk(la, lc);
@@ -175,14 +175,14 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         }
       }
       wave_lds_sync();
-      const uint32_t lo = (uint32_t)slot0 * 256u, span = (uint32_t)nsl * 256u;
+      const uint32_t lo = (uint32_t)slot0 * 256u;
       const int RW = 2 * p.R + 1;
       const bf16_t* tab = REL ? p.rel_table + h * RW * RW : nullptr;
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
 #pragma unroll
         for (int e = 0; e < (VEC ? 8 : 1); ++e) {
-          // entries of other passes, kNoEntry and dead items fall outside [0, span): they go to the spare cell
+          // entries of other passes, kNoEntry and dead items fall outside the pass: they go to the spare cell
           const uint32_t off = VEC ? ((ent[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : (ent[t][0] & 0xffffu);
           const uint32_t rel = off - lo;
           uint32_t bits;
@@ -194,26 +194,28 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
           } else {
             bits = VEC ? ((bw[t][e >> 1] >> (16 * (e & 1))) & 0xffffu) : bw[t][0];
           }
-          scratch[rel < span ? rel : (uint32_t)kSlotCap * 256u] = (bf16_t)bits;
+          // (every pass but the last is full, so an offset outside the pass is at least kSlotCap * 256 away,
+          // wrapped around or not: one unsigned minimum steers it to the spare cell)
+          scratch[min(rel, (uint32_t)kSlotCap * 256u)] = (bf16_t)bits;
         }
       }
       wave_lds_sync();
 
       const int npairs = (nsl + 1) >> 1;
       auto load_pair = [&](int pr, u32x4& k0, u32x4& v0, u32x4& k1, u32x4& v1) {
+        // Address = the image's K (V) rows as a scalar base + a 32-bit vector offset (an image is smaller than
+        // 4 GB): the tile's byte offset is one scalar product, broadcast and added to the lane's offset by ONE vector
+        // add per tile, which serves the K and the V load.  (Folding the tile into the scalar base instead costs
+        // ten scalar instructions of 64-bit arithmetic per tile, and a wave issues one instruction per turn of
+        // whatever kind.)  The offsets are made opaque, or the compiler rebuilds 64-bit vector addresses.
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
-        const size_t base0 = (size_t)tile0 * tile_bytes + (size_t)(h * kD * 2);
-        const size_t base1 = (size_t)tile1 * tile_bytes + (size_t)(h * kD * 2);
-        // scalar tile address + 32-bit lane offset, so that the address needs no vector arithmetic: the lane
-        // offset is made opaque here, or the compiler keeps (image + lane offset) as a 64-bit vector and adds
-        // the tile's offset to it with two vector instructions per load
-        uint32_t off = lane_off;
-        asm volatile("" : "+v"(off));
-        k0 = *reinterpret_cast<const u32x4*>(kimg + base0 + off);
-        v0 = *reinterpret_cast<const u32x4*>(vimg + base0 + off);
-        k1 = *reinterpret_cast<const u32x4*>(kimg + base1 + off);
-        v1 = *reinterpret_cast<const u32x4*>(vimg + base1 + off);
+        uint32_t off0 = lane_off_h + tile0 * tile_bytes, off1 = lane_off_h + tile1 * tile_bytes;
+        asm volatile("" : "+v"(off0), "+v"(off1));
+        k0 = *reinterpret_cast<const u32x4*>(kimg + off0);
+        v0 = *reinterpret_cast<const u32x4*>(vimg + off0);
+        k1 = *reinterpret_cast<const u32x4*>(kimg + off1);
+        v1 = *reinterpret_cast<const u32x4*>(vimg + off1);
       };
       // pieces as loaded -> LDS -> operand pieces
       auto stage_pair = [&](const u32x4& k0, const u32x4& v0, const u32x4& k1, const u32x4& v1, Frag8(&kf)[2],
