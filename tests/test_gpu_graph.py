@@ -173,3 +173,52 @@ def test_relative_position_attention_replayed_from_a_graph():
                     assert float((got[name] - t).abs().max()) <= 1e-6 * float(t.abs().max()), f"R={R} replay {rep}"
                 else:
                     assert torch.equal(got[name], t), f"R={R} replay {rep}: {name} differs from the eager result"
+
+
+def test_neighbour_search_and_merging_replayed_from_a_graph():
+    """Neighbour table, anchor selection, merging forward and backward in one graph, replayed with new coordinates,
+    scores, features and gradients.  Indices, merged features and dp are deterministic (bit-equal to the eager
+    results); dfeat and dscore are sums over per-token lists whose order may vary, compared with the bf16 bound."""
+    rng = np.random.default_rng(12)
+    B, N, C, K, S, M, n_keep, p = 2, 2048, 64, 48, 64, 8, 512, 0.3
+
+    def inputs(rep):
+        cfg = CONFIGS["knn_scale"].scaled(B=B, N=N, S=S, M=M, K=K)
+        w = make_workload(cfg, seed=100 + rep, features=False)
+        feat = torch.from_numpy(rng.normal(size=(B, N, C)).astype(np.float32)).cuda().to(torch.bfloat16)
+        dout = torch.from_numpy(rng.normal(size=(B, n_keep, C)).astype(np.float32)).cuda().to(torch.bfloat16)
+        score = torch.from_numpy(rng.normal(size=(B, N)).astype(np.float32)).cuda()
+        return torch.from_numpy(w["coords"]).cuda(), score, feat, dout
+
+    def run(coords, score, feat, dout):
+        nbr, _ = aff.affmae_knn(coords, None, S, M, K)
+        anchors, axy = aff.affmae_merge_select(score, n_keep, coords)
+        out = aff.affmae_merge_fwd(feat, coords, score, nbr, anchors, p)
+        g = aff.affmae_merge_bwd(feat, coords, score, nbr, anchors, dout, p)
+        return {"nbr": nbr, "anchors": anchors, "anchor_xy": axy, "out": out, **g}
+
+    s_in = inputs(-1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(*s_in)  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        got = run(*s_in)
+
+    for rep in range(3):
+        new = inputs(rep)
+        ref = run(*new)  # eager work between the replays
+        torch.cuda.synchronize()
+        for dst, src in zip(s_in, new):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("nbr", "anchors", "anchor_xy", "out", "dp"):
+            assert torch.equal(got[name], ref[name]), f"replay {rep}: {name} differs from the eager result"
+        for name in ("dfeat", "dscore"):
+            a, b = got[name].float(), ref[name].float()
+            assert float((a - b).abs().max()) <= 2e-2 * float(b.abs().max()), f"replay {rep}: {name}"
