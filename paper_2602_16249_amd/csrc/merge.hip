@@ -92,14 +92,15 @@ __global__ __launch_bounds__(kSelThreads) void merge_select_kernel(const float* 
       hist[0][tid] = t;  // (each thread reads and writes its own column only)
     }
     __syncthreads();
-    if (tid == 0) {
-      int above = 0, digit = 255;
-      for (; digit > 0; --digit) {  // the largest digit whose keys, with all larger ones, reach `remaining`
-        if (above + hist[0][digit] >= remaining) break;
-        above += hist[0][digit];
+    if (tid < 256) {
+      // the largest digit whose keys, with all larger ones, reach `remaining`: thread d adds up the digits above d
+      // (independent loads; one thread walking down the 256 counters is a chain of 256 dependent LDS reads)
+      int above = 0;
+      for (int d = tid + 1; d < 256; ++d) above += hist[0][d];
+      if (above < remaining && above + hist[0][tid] >= remaining) {  // true for exactly one digit
+        s_prefix = prefix | ((uint32_t)tid << shift);
+        s_remaining = remaining - above;
       }
-      s_prefix = prefix | ((uint32_t)digit << shift);
-      s_remaining = remaining - above;
     }
     __syncthreads();
     prefix = s_prefix;
