@@ -42,6 +42,8 @@ struct BwdParams {
   int N, H, K, strips, strips_per_image, slot_stride, max_slots, runs_stride, places;
   uint32_t k_magic, cq_magic;  // reciprocals of K and of K / 8
   uint32_t h_magic, spi_magic;  // ... of H and of strips_per_image
+  int head_groups;              // key-stationary kernel: H / heads per wave
+  uint32_t hgr_magic;           // ... its reciprocal
   float scale;
   bf16_t *dq, *dk, *dv;
   bf16_t* ds;    // [B,N,H,K] dS = dbias, or nullptr when the caller does not want it
@@ -491,8 +493,11 @@ struct KeyItem {
   uint32_t len;          // places in the run (wave-uniform)
 };
 
-// HG = heads handled per sweep over the tile's list (2 when H is even: one walk of the list, one load of
-// the entry values and one pass over the q / dout rows serve both).
+// HG = heads handled by one wave's sweep over the tile's list (2 when H is even: one walk of the list, one load of
+// the entry values and one pass over the q / dout rows serve both).  One wave per (token tile, group of HG heads),
+// the groups of a tile in consecutive waves: they walk the same list over the same strips at the same time, so the
+// strips' rows, the entry values and the list are fetched into the XCD's L2 once for all heads, and the rows that an
+// XCD has in use at a time do not grow with the number of heads.
 template <int HG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
   __shared__ __align__(16) bf16_t tile_all[4][HG * 256];  // per wave and head: p[token][query]
@@ -504,8 +509,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps per-wave indices in SGPRs
   const int g = lane >> 4, r = lane & 15;
   const int lane_cell = tile_cell(r, 4 * g);  // the lane's piece of a 16 x 16 tile: row r, columns 4g..4g+3
-  const int kt = xcd_contiguous_block() * 4 + wave;  // token tile, global
+  const int unit = xcd_contiguous_block() * 4 + wave;
+  const int kt = exact_div(unit, p.head_groups, p.hgr_magic);  // token tile, global
   if (kt >= p.strips) return;
+  const int hg = (unit - kt * p.head_groups) * HG;  // first head of the wave's group
   bf16_t* tile = tile_all[wave];
   u32x4* rows0 = rows_all[wave][0];
   u32x4* rows1 = rows_all[wave][1];
@@ -552,7 +559,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 #pragma unroll
   for (int hh = 0; hh < HG; ++hh) gf_chunk[hh] = HG * 64 + r * PR + ((4 * hh + g) ^ swz(r));
 
-  for (int hg = 0; hg < p.H; hg += HG) {
+  {
     // The hand-over carries p only: dS = p (dP - D) is formed here, with dP - D = <dout[query], v[token]> - D from one
     // more MFMA on the tile's own V rows (operand: lane (token r, channels 8g..8g+7)) and the dout rows that
     // are staged anyway.  It comes out as lane (token r, queries 4g..4g+3), the operand layout of dK^T = Q^T dS.
@@ -792,7 +799,11 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
 
   p.coords = a.rel_coords; p.rel_table = (const bf16_t*)a.rel_table; p.R = a.rel_R; p.rate = a.rel_rate;
   p.rel_part = a.rel_part;
-  const dim3 grid(((L.strips + 3) / 4 + 7) / 8 * 8);  // multiple of 8 for the XCD-contiguous mapping
+  const int key_hg = a.H % 2 == 0 ? 2 : 1;  // heads per wave of the key-stationary kernel
+  p.head_groups = a.H / key_hg;
+  p.hgr_magic = div_magic(p.head_groups);
+  // one wave per (token tile, head group); multiple of 8 for the XCD-contiguous mapping
+  const dim3 grid((((long long)L.strips * p.head_groups + 3) / 4 + 7) / 8 * 8);
   const dim3 grid_q((((long long)L.strips * a.H + 3) / 4 + 7) / 8 * 8);  // one wave per (strip, head)
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);

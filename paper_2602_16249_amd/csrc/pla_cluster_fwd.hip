@@ -370,6 +370,7 @@ bool pla_cluster_supported(const PlaArgs& a) {
   if ((long long)a.M * a.S / 16 > kMaxSlots) return false;        // tile set of a strip is a 64-bit mask
   if (a.K > 64 || a.N / 16 > 65535) return false;                 // 16-bit plan entries and tile ids
   if ((long long)a.N * a.S >= (1ll << 31)) return false;          // range of the reciprocal division
+  if ((long long)a.N * a.H * kD * 2 >= (1ll << 32)) return false; // 32-bit byte offsets inside an image's K / V
   return true;
 }
 
