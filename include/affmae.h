@@ -175,6 +175,7 @@ int affmae_vts_bwd(const float* query_xy, const float* vis_xy, const void* feat,
  *   score      in  [B,N] fp32, finite      coords     in  [B,N,2] fp32 or NULL
  *   anchor_idx out [B,n_keep] int32        anchor_xy  out [B,n_keep,2] fp32 or NULL:
  *                      the anchors' coordinates, which the merged tokens keep
+ *                      (coords and anchor_xy aligned to 8 bytes when both are given)
  *
  * affmae_merge_fwd     out[b,a,:] = sum_j w_j feat[b, n(t,j), :] over the K tokens
  *                      n(t,j) of the neighbourhood of the anchor's token t =

@@ -204,6 +204,7 @@ int affmae_merge_select(const float* score, const float* coords, int B, int N, i
   if (!score || !anchor_idx) return AFFMAE_ERR_NULL;
   if (anchor_xy && !coords) return AFFMAE_ERR_NULL;
   if (B < 1 || N < 1 || n_keep < 1 || n_keep > N) return AFFMAE_ERR_SHAPE;
+  if (anchor_xy && (misaligned(coords, 8) || misaligned(anchor_xy, 8))) return AFFMAE_ERR_SHAPE;  // moved as pairs
   if (N > (1 << 24) || (long long)B * N > (1ll << 31) - 8) return AFFMAE_ERR_UNSUPPORTED;
   return affmae::launch_merge_select(score, coords, B, N, n_keep, anchor_idx, anchor_xy,
                                      static_cast<hipStream_t>(stream)) == hipSuccess

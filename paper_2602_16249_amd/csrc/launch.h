@@ -52,7 +52,8 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream);
 size_t sum_parts_scratch_floats(size_t n);
 hipError_t launch_sum_parts(const float* part, size_t n, float* part2, float* out, hipStream_t stream);
 hipError_t launch_pair_lists(const int32_t* pair_token, int B, int Nv, int pairs_per_image, int32_t* offset,
-                             int32_t* list, hipStream_t stream);
+                             int32_t* list, hipStream_t stream, const int32_t* group_bounds = nullptr,
+                             int group_size = 0);
 hipError_t launch_pair_gather(const void* dout, const float* weights, const int32_t* offset, const int32_t* list,
                               size_t tokens, int C, int Kt, int dtype, void* dfeat, bool pieces, hipStream_t stream);
 

@@ -3,10 +3,11 @@
 // differentiable, location-aware aggregation; the paper leaves the operator itself to the AFF paper).  What this
 // file computes:
 //   select  : the n_keep tokens of every image with the largest score, equal scores going to the lower index,
-//             listed in ascending token index.  One workgroup per image: a radix select on the order-preserving
-//             bit pattern of the scores (four 8-bit digits, histograms in LDS) finds the score of the last kept
-//             token and how many tokens of exactly that score are kept; one more sweep in index order keeps the
-//             larger scores and the first so many of the equal ones (two block-wide prefix counts per 1024 tokens).
+//             listed in ascending token index.  One workgroup per image finds, on the order-preserving bit pattern
+//             of the scores, the score of the last kept token and how many tokens of exactly that score are kept
+//             (up to 32768 tokens per image: keys in registers, the pattern built bit by bit from counts; larger
+//             images: a radix select, four 8-bit digits, histograms in LDS); then, in index order, the larger
+//             scores and the first so many of the equal ones are kept, their places given by block-wide prefix counts.
 //   forward : one wave per anchor.  Lane j holds neighbour j of the anchor's row of the stage's neighbour table:
 //             distance to the anchor, z_j = score_j - p dist_j, w = softmax_j(z) by wave reductions.  The weighted
 //             sum of the feature rows moves 16 bytes per lane: a row takes PP lanes, 64 / PP rows are in flight per
@@ -129,6 +130,116 @@ __global__ __launch_bounds__(kSelThreads) void merge_select_kernel(const float* 
     equal_before += equal_total;
     kept_before += kept_total;
   }
+}
+
+// Sum of v over the earlier threads of the workgroup, and over all of them (two barriers).
+__device__ __forceinline__ int block_exclusive_sum(int v, int* wave_total, int& total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int up = __shfl_up(incl, o);
+    incl += lane >= o ? up : 0;
+  }
+  __syncthreads();  // the previous use of wave_total has been read
+  if (lane == kWave - 1) wave_total[wave] = incl;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int t = wave_total[w];
+    before += w < wave ? t : 0;
+    all += t;
+  }
+  total = all;
+  return before + incl - v;
+}
+
+// The same selection for images of at most KPT * 1024 tokens, with the keys held in registers: thread t keeps the
+// keys of tokens t KPT .. t KPT + KPT - 1.  The key of the last kept token is built bit by bit from the top: a bit
+// stays set when at least n_keep keys are >= the candidate (a compare and a wave-wide count per key, one barrier per
+// bit).  The radix form above re-reads the scores for each digit and adds into LDS counters, where the lanes of a
+// wave meet in the few counters that the leading bits of real scores fall into; this form has no contended address.
+template <int KPT>
+__global__ __launch_bounds__(kSelThreads) void merge_select_bits_kernel(const float* __restrict__ score,
+                                                                       const float* __restrict__ coords, int N,
+                                                                       int n_keep, int32_t* __restrict__ anchor_idx,
+                                                                       float* __restrict__ anchor_xy) {
+  __shared__ int wave_count[2][kSelWaves];
+  __shared__ int wave_total[kSelWaves];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int b = blockIdx.x;
+  const float* sc = score + (size_t)b * N;
+  const int first = tid * KPT;
+  uint32_t key[KPT];  // 0 past the end: below the key of every finite score
+  if (KPT % 4 == 0 && N % 4 == 0 && reinterpret_cast<uintptr_t>(sc) % 16 == 0) {
+#pragma unroll
+    for (int e = 0; e < KPT; e += 4) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      const bool in = first + e < N;  // N % 4 == 0: a piece is inside or outside as a whole
+      if (in) v = *reinterpret_cast<const float4*>(sc + first + e);
+      key[e] = in ? score_key(v.x) : 0u;
+      key[e + 1] = in ? score_key(v.y) : 0u;
+      key[e + 2] = in ? score_key(v.z) : 0u;
+      key[e + 3] = in ? score_key(v.w) : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < KPT; ++e) key[e] = first + e < N ? score_key(sc[first + e]) : 0u;
+  }
+  // number of keys of the workgroup that are >= cand (cand > 0); `turn` alternates the LDS row so that one barrier
+  // per count is enough: a row is rewritten only after every thread has passed the barrier of the next count
+  auto count_at_least = [&](uint32_t cand, int turn) {
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < KPT; ++e) c += __popcll(__ballot(key[e] >= cand));  // wave-uniform
+    if (lane == 0) wave_count[turn][wave] = c;
+    __syncthreads();
+    int all = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) all += wave_count[turn][w];
+    return all;
+  };
+  uint32_t prefix = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = prefix | (1u << bit);
+    if (count_at_least(cand, bit & 1) >= n_keep) prefix = cand;
+  }
+  // prefix = key of the last kept token; `remaining` of the tokens with exactly that key are kept, lowest index first
+  // (row 1 was last used for bit 1; the barrier of bit 0 lies between)
+  const int larger = prefix == 0xffffffffu ? 0 : count_at_least(prefix + 1u, 1);
+  const int remaining = n_keep - larger;
+  int equal = 0;
+#pragma unroll
+  for (int e = 0; e < KPT; ++e) equal += key[e] == prefix ? 1 : 0;
+  int total;
+  int equal_before = block_exclusive_sum(equal, wave_total, total);
+  int kept = 0;
+#pragma unroll
+  for (int e = 0; e < KPT; ++e) {
+    const bool eq = key[e] == prefix;
+    kept += (key[e] > prefix || (eq && equal_before < remaining)) ? 1 : 0;
+    equal_before += eq ? 1 : 0;
+  }
+  equal_before -= equal;
+  int place = block_exclusive_sum(kept, wave_total, total);
+  int32_t* idx_out = anchor_idx + (size_t)b * n_keep;
+#pragma unroll
+  for (int e = 0; e < KPT; ++e) {
+    const bool eq = key[e] == prefix;
+    const bool keep = key[e] > prefix || (eq && equal_before < remaining);
+    equal_before += eq ? 1 : 0;
+    if (keep && first + e < N && place < n_keep) idx_out[place] = first + e;
+    place += keep ? 1 : 0;
+  }
+  if (!anchor_xy) return;
+  // the anchors' coordinates: the list just written is read back in order (its writes are visible to the workgroup
+  // after the fence and the barrier), so the gathers of a thread are independent loads and the stores are coalesced
+  __threadfence_block();
+  __syncthreads();
+  const float2* xy_in = reinterpret_cast<const float2*>(coords) + (size_t)b * N;
+  float2* xy_out = reinterpret_cast<float2*>(anchor_xy) + (size_t)b * n_keep;
+  for (int a = tid; a < n_keep; a += kSelThreads) xy_out[a] = xy_in[min(max(idx_out[a], 0), N - 1)];
 }
 
 // 16 bytes of channels
@@ -260,7 +371,8 @@ __global__ __launch_bounds__(256) void merge_bwd_kernel(const T* __restrict__ fe
                                                        const int32_t* __restrict__ anchor, const T* __restrict__ dout,
                                                        int B, int N, int C, int K, int n_keep, float p, int PP,
                                                        float* __restrict__ wpair, float* __restrict__ dzpair,
-                                                       int32_t* __restrict__ pair_token, float* __restrict__ dp_part) {
+                                                       int32_t* __restrict__ pair_token, int2* __restrict__ pair_bounds,
+                                                       float* __restrict__ dp_part) {
   __shared__ float g_all[4][kWave];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -325,6 +437,14 @@ __global__ __launch_bounds__(256) void merge_bwd_kernel(const T* __restrict__ fe
     pair_token[pair] = nb.b * N + nb.idx;
   }
   if (lane == 0 && dp_part) dp_part[slot] = dpv;
+  // the lowest and highest token of the anchor's pairs, for the list builder (lanes >= K hold the anchor's token)
+  int tmin = nb.b * N + nb.idx, tmax = tmin;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    tmin = min(tmin, __shfl_xor(tmin, o));
+    tmax = max(tmax, __shfl_xor(tmax, o));
+  }
+  if (lane == 0) pair_bounds[slot] = make_int2(tmin, tmax);
 }
 
 // dscore[token] = sum of dz over the token's pairs.
@@ -342,7 +462,7 @@ __global__ __launch_bounds__(256) void merge_dscore_kernel(const float* __restri
 
 size_t merge_align(size_t n) { return (n + 255) / 256 * 256; }
 struct MergeBwdLayout {
-  size_t w_off, dz_off, pair_off, offset_off, list_off, dp_off, dp2_off, total;
+  size_t w_off, dz_off, pair_off, bounds_off, offset_off, list_off, dp_off, dp2_off, total;
 };
 MergeBwdLayout merge_bwd_layout(int B, int N, int K, int n_keep) {
   MergeBwdLayout L;
@@ -351,6 +471,7 @@ MergeBwdLayout merge_bwd_layout(int B, int N, int K, int n_keep) {
   L.w_off = off;      off += merge_align(pairs * sizeof(float));
   L.dz_off = off;     off += merge_align(pairs * sizeof(float));
   L.pair_off = off;   off += merge_align(pairs * sizeof(int32_t));
+  L.bounds_off = off; off += merge_align(anchors * 2 * sizeof(int32_t));
   L.offset_off = off; off += merge_align((tokens + 1) * sizeof(int32_t));
   L.list_off = off;   off += merge_align(pairs * sizeof(int32_t));
   L.dp_off = off;     off += merge_align(anchors * sizeof(float));
@@ -377,8 +498,14 @@ int lanes_per_row(const MergeArgs& a) {
 
 hipError_t launch_merge_select(const float* score, const float* coords, int B, int N, int n_keep, int32_t* anchor_idx,
                                float* anchor_xy, hipStream_t stream) {
-  AFFMAE_LAUNCH("merge_select_kernel", stream, merge_select_kernel, dim3(B), dim3(kSelThreads), 0, stream, score,
-                coords, N, n_keep, anchor_idx, anchor_xy);
+#define AFFMAE_SELECT(KERNEL) \
+  AFFMAE_LAUNCH("merge_select_kernel", stream, KERNEL, dim3(B), dim3(kSelThreads), 0, stream, score, coords, N, \
+                n_keep, anchor_idx, anchor_xy)
+  if (N <= 4 * kSelThreads) AFFMAE_SELECT(merge_select_bits_kernel<4>);
+  else if (N <= 16 * kSelThreads) AFFMAE_SELECT(merge_select_bits_kernel<16>);
+  else if (N <= 32 * kSelThreads) AFFMAE_SELECT(merge_select_bits_kernel<32>);
+  else AFFMAE_SELECT(merge_select_kernel);  // larger images: the keys do not fit a workgroup's registers
+#undef AFFMAE_SELECT
   return hipGetLastError();
 }
 
@@ -405,6 +532,7 @@ hipError_t launch_merge_bwd(const MergeArgs& a, hipStream_t stream) {
   float* wpair = reinterpret_cast<float*>(ws + L.w_off);
   float* dzpair = reinterpret_cast<float*>(ws + L.dz_off);
   int32_t* pair_token = reinterpret_cast<int32_t*>(ws + L.pair_off);
+  int2* pair_bounds = reinterpret_cast<int2*>(ws + L.bounds_off);
   int32_t* offset = reinterpret_cast<int32_t*>(ws + L.offset_off);
   int32_t* list = reinterpret_cast<int32_t*>(ws + L.list_off);
   float* dp_part = a.dp ? reinterpret_cast<float*>(ws + L.dp_off) : nullptr;
@@ -416,7 +544,7 @@ hipError_t launch_merge_bwd(const MergeArgs& a, hipStream_t stream) {
 #define AFFMAE_MERGE_BWD(T, P)                                                                                     \
   AFFMAE_LAUNCH("merge_bwd_kernel", stream, (merge_bwd_kernel<T, P>), grid, dim3(256), 0, stream, (const T*)a.feat, \
                 a.coords, a.score, a.nbr_idx, a.anchor_idx, (const T*)a.dout, a.B, a.N, a.C, a.K, a.n_keep, a.p, pp, \
-                wpair, dzpair, pair_token, dp_part)
+                wpair, dzpair, pair_token, pair_bounds, dp_part)
   if (a.dtype == 1 && pieces) AFFMAE_MERGE_BWD(bf16_t, true);
   else if (a.dtype == 1) AFFMAE_MERGE_BWD(bf16_t, false);
   else if (pieces) AFFMAE_MERGE_BWD(float, true);
@@ -426,7 +554,8 @@ hipError_t launch_merge_bwd(const MergeArgs& a, hipStream_t stream) {
     const hipError_t e = launch_sum_parts(dp_part, anchors, dp_part2, a.dp, stream);
     if (e != hipSuccess) return e;
   }
-  hipError_t e = launch_pair_lists(pair_token, a.B, a.N, a.n_keep * a.K, offset, list, stream);
+  hipError_t e = launch_pair_lists(pair_token, a.B, a.N, a.n_keep * a.K, offset, list, stream,
+                                   reinterpret_cast<const int32_t*>(pair_bounds), a.K);
   if (e != hipSuccess) return e;
   AFFMAE_LAUNCH("merge_dscore_kernel", stream, merge_dscore_kernel, dim3((unsigned)((tokens + 255) / 256)), dim3(256),
                 0, stream, dzpair, offset, list, (int)tokens, a.dscore);

@@ -21,6 +21,7 @@
 // This file is compiled with -ffp-contract=off (grid points and table distances are defined unfused).
 #include <algorithm>
 
+#include "cluster_common.h"
 #include "device_util.h"
 #include "launch.h"
 #include "select_util.h"
@@ -792,6 +793,90 @@ __global__ __launch_bounds__(kListThreads) void vts_lists_kernel(const int32_t* 
   });
 }
 
+// The same filing when the pairs come in groups of `gs` consecutive pairs (one group per anchor) whose lowest and
+// highest token are known (bounds[group] = (min, max), global token ids): a workgroup first lists the groups that can
+// hold a token of its range and then walks only their pairs.  Groups that end before the range count as a whole for
+// the range's first list start; those that begin before it and reach into it are among the listed ones.  With
+// tokens stored along a space-filling curve a group spans a small part of the image, so a range walks a fraction of
+// the image's pairs instead of all of them.
+constexpr int kGroupCap = 8192;  // groups of one image that a workgroup can list
+__global__ __launch_bounds__(kListThreads) void pair_lists_grouped_kernel(
+    const int32_t* __restrict__ pair_token, const int2* __restrict__ bounds, int B, int Nv, int groups, int gs,
+    uint32_t gs_magic, int range, int ranges, int32_t* __restrict__ offset, int32_t* __restrict__ list) {
+  __shared__ int32_t cnt[kListRange];
+  __shared__ int32_t glist[kGroupCap];
+  __shared__ int32_t wave_total[kListThreads / kWave], wave_below[kListThreads / kWave];
+  __shared__ int32_t s_listed, s_whole;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int b = blockIdx.x / ranges, rg = blockIdx.x - b * ranges;
+  const int t0 = rg * range;
+  const int span = min(range, Nv - t0);  // >= 1: ranges = ceil(Nv / range)
+  const int first = b * Nv + t0, end = first + span;
+  const int lo = b * groups * gs;  // the image's first pair
+  if (tid == 0) {
+    s_listed = 0;
+    s_whole = 0;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) cnt[4 * tid + i] = 0;
+  __syncthreads();
+  int whole = 0;
+  for (int g = tid; g < groups; g += kListThreads) {
+    const int2 bd = bounds[(size_t)b * groups + g];
+    if (bd.y < first) whole += 1;
+    else if (bd.x < end) glist[atomicAdd(&s_listed, 1)] = g;  // at most `groups` <= kGroupCap entries
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) whole += __shfl_xor(whole, o);
+  if (lane == 0 && whole) atomicAdd(&s_whole, whole);
+  __syncthreads();
+  const int items = s_listed * gs;
+  // fn(token, pair) for every pair of the listed groups that this thread looks at
+  auto each_pair = [&](auto&& fn) {
+    for (int i = tid; i < items; i += kListThreads) {
+      const int gi = exact_div(i, gs, gs_magic);
+      const int pair = lo + glist[gi] * gs + (i - gi * gs);
+      fn(pair_token[pair], pair);
+    }
+  };
+  int below = 0;
+  each_pair([&](int tok, int) {
+    const int rel = tok - first;
+    below += rel < 0 ? 1 : 0;
+    if ((unsigned)rel < (unsigned)span) atomicAdd(&cnt[rel], 1);
+  });
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o);
+  __syncthreads();
+  int c[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) c[i] = cnt[4 * tid + i];  // zero past the span
+  const int mine = c[0] + c[1] + c[2] + c[3];
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+  if (lane == kWave - 1) wave_total[wave] = incl;
+  if (lane == 0) wave_below[wave] = below;
+  __syncthreads();
+  int run = lo + s_whole * gs + incl - mine;
+  for (int w = 0; w < kListThreads / kWave; ++w) run += wave_below[w] + (w < wave ? wave_total[w] : 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (4 * tid + i < span) offset[(size_t)first + 4 * tid + i] = run;
+    cnt[4 * tid + i] = run;  // from here on: the next free place of the token's list
+    run += c[i];
+  }
+  if (blockIdx.x == gridDim.x - 1 && tid == 0) offset[(size_t)B * Nv] = B * groups * gs;
+  __syncthreads();
+  each_pair([&](int tok, int pair) {
+    const int rel = tok - first;
+    if ((unsigned)rel < (unsigned)span) list[atomicAdd(&cnt[rel], 1)] = pair;
+  });
+}
+
 // Four visible tokens per wave (16 lanes each) when the rows are whole 16-byte pieces: dfeat = sum over the
 // token's pairs of w * dout[query].
 template <typename T>
@@ -1038,8 +1123,23 @@ hipError_t launch_sum_parts(const float* part, size_t n, float* part2, float* ou
 
 // Files pairs per token: pair_token[b * pairs_per_image + i] = the (global, b * Nv + t) token of pair i of image b
 // -> offset [B * Nv + 1] (start of every token's list) and list [B * pairs_per_image] (pair ids grouped by token).
+// group_bounds (optional): [B * pairs_per_image / group_size][2], the lowest and highest token of every run of
+// group_size consecutive pairs.
 hipError_t launch_pair_lists(const int32_t* pair_token, int B, int Nv, int pairs_per_image, int32_t* offset,
-                             int32_t* list, hipStream_t stream) {
+                             int32_t* list, hipStream_t stream, const int32_t* group_bounds, int group_size) {
+  if (group_bounds && group_size >= 1 && pairs_per_image % group_size == 0 &&
+      pairs_per_image / group_size <= kGroupCap) {
+    // a range walks only the groups that reach into it: many small ranges cost little
+    const int groups = pairs_per_image / group_size;
+    const int want = (512 + B - 1) / B;
+    int range = std::max(64, (Nv + want - 1) / want);
+    range = std::min(range, kListRange);
+    const int ranges = (Nv + range - 1) / range;
+    AFFMAE_LAUNCH("vts_lists_kernel", stream, pair_lists_grouped_kernel, dim3((unsigned)(B * ranges)),
+                  dim3(kListThreads), 0, stream, pair_token, reinterpret_cast<const int2*>(group_bounds), B, Nv, groups,
+                  group_size, div_magic(group_size), range, ranges, offset, list);
+    return hipGetLastError();
+  }
   // token ranges per image: enough workgroups to fill the chip, never more tokens than the LDS counters hold
   const int want = (192 + B - 1) / B;
   int range = std::max(64, (Nv + want - 1) / want);

@@ -17,6 +17,9 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}
 @pytest.mark.parametrize("B,N,n_keep,kind", [
     (3, 1000, 250, "normal"), (2, 16384, 4096, "normal"), (2, 5000, 1, "ties"), (4, 777, 777, "ties"),
     (2, 4096, 1638, "ties"), (1, 100000, 40000, "ties"), (2, 64, 33, "equal"), (1, 2049, 1024, "normal"),
+    # each size class of the selection: keys in registers (4, 16, 32 per thread), sizes that are not whole pieces
+    (2, 4097, 1000, "ties"), (2, 16383, 16383, "normal"), (2, 20000, 5000, "ties"), (1, 32768, 1, "normal"),
+    (1, 32769, 8192, "ties"), (3, 5, 5, "equal"), (2, 16384, 16384, "equal"),
 ])
 def test_select_matches_oracle(B, N, n_keep, kind):
     print(f"case select B={B} N={N} n_keep={n_keep} {kind}", flush=True)
