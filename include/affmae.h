@@ -355,6 +355,9 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
  *   dbias         out [B,N,H,K] of `dtype`, or NULL to skip.
  *   dk_blank,dv_blank out [H,d] fp32, or NULL (both required when blanks given
  *                     and their gradients are wanted).
+ *   workspace     always required (affmae_pla_bwd_workspace_bytes); the gather
+ *                     kernels number the (query, slot) pairs in 32 bits:
+ *                     B*N*K < 2^31, else AFFMAE_ERR_UNSUPPORTED.
  */
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype,
                                       int clustered);

@@ -395,7 +395,7 @@ int affmae_pla_fwd(const void* q, const void* k, const void* v, const void* bias
 
 size_t affmae_pla_bwd_workspace_bytes(int B, int N, int H, int d, int K, int S, int M, int dtype, int clustered) {
   if (check_pla_shape(B, N, H, d, K, dtype) != AFFMAE_OK) return 0;
-  const size_t gather = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
+  const size_t gather = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, K));
   size_t tiled = 0;
   if (clustered && dtype == AFFMAE_BF16 && d == 32 && S > 0 && tiled_shape_ok(B, N, K, S, M))
     tiled = align_up(affmae::pla_plan_bytes(B, N, K, S, M)) + affmae::pla_bwd_cluster_workspace_bytes(B, N, H, K, S, M);
@@ -448,8 +448,9 @@ int pla_bwd_run(const void* q, const void* k, const void* v, const void* bias, c
     }
     return affmae::launch_pla_bwd_cluster(a, plan, ws + plan_bytes, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
   }
-  const size_t need = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, d, dtype));
-  if (need && (!workspace || workspace_bytes < need)) return AFFMAE_ERR_WORKSPACE;
+  if ((long long)B * N * K >= (1ll << 31)) return AFFMAE_ERR_UNSUPPORTED;  // (query, slot) pairs are numbered in 32 bits
+  const size_t need = align_up(affmae::pla_bwd_general_workspace_bytes(B, N, H, K));
+  if (!workspace || workspace_bytes < need) return AFFMAE_ERR_WORKSPACE;
   if (!launch) return AFFMAE_OK;
   return affmae::launch_pla_bwd_general(a, st) == hipSuccess ? AFFMAE_OK : AFFMAE_ERR_DEVICE;
 }

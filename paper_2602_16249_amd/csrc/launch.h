@@ -121,7 +121,7 @@ struct PlaArgs {
 };
 hipError_t launch_pla_fwd_general(const PlaArgs& a, hipStream_t stream);
 hipError_t launch_pla_bwd_general(const PlaArgs& a, hipStream_t stream);
-size_t pla_bwd_general_workspace_bytes(int B, int N, int H, int d, int dtype);
+size_t pla_bwd_general_workspace_bytes(int B, int N, int H, int K);
 
 // Cluster-tiled kernels (bf16, d = 32, cluster promise given), driven by a plan.
 bool pla_cluster_supported(const PlaArgs& a);

@@ -793,13 +793,13 @@ __global__ __launch_bounds__(kListThreads) void vts_lists_kernel(const int32_t* 
   });
 }
 
-// The same filing when the pairs come in groups of `gs` consecutive pairs (one group per anchor) whose lowest and
-// highest token are known (bounds[group] = (min, max), global token ids): a workgroup first lists the groups that can
-// hold a token of its range and then walks only their pairs.  Groups that end before the range count as a whole for
-// the range's first list start; those that begin before it and reach into it are among the listed ones.  With
-// tokens stored along a space-filling curve a group spans a small part of the image, so a range walks a fraction of
-// the image's pairs instead of all of them.
-constexpr int kGroupCap = 8192;  // groups of one image that a workgroup can list
+// The same filing when the pairs come in groups of `gs` consecutive pairs (one group per anchor or per query) whose
+// lowest and highest token are known (bounds[group] = (min, max), global token ids): a workgroup lists the groups
+// that can hold a token of its range, kGroupCap groups of the image at a time, and walks only their pairs.  Groups
+// that end before the range count as a whole for the range's first list start; those that begin before it and
+// reach into it are among the listed ones.  With tokens stored along a space-filling curve a group spans a small
+// part of the image, so a range walks a fraction of the image's pairs instead of all of them.
+constexpr int kGroupCap = 8192;  // groups of one image that a workgroup lists at a time
 __global__ __launch_bounds__(kListThreads) void pair_lists_grouped_kernel(
     const int32_t* __restrict__ pair_token, const int2* __restrict__ bounds, int B, int Nv, int groups, int gs,
     uint32_t gs_magic, int range, int ranges, int32_t* __restrict__ offset, int32_t* __restrict__ list) {
@@ -813,26 +813,24 @@ __global__ __launch_bounds__(kListThreads) void pair_lists_grouped_kernel(
   const int span = min(range, Nv - t0);  // >= 1: ranges = ceil(Nv / range)
   const int first = b * Nv + t0, end = first + span;
   const int lo = b * groups * gs;  // the image's first pair
-  if (tid == 0) {
-    s_listed = 0;
-    s_whole = 0;
-  }
+  if (tid == 0) s_whole = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) cnt[4 * tid + i] = 0;
-  __syncthreads();
+  // fn(token, pair) for every pair of the groups [g0, g0 + kGroupCap) that reach into the range; `whole` counts the
+  // groups that end before it
   int whole = 0;
-  for (int g = tid; g < groups; g += kListThreads) {
-    const int2 bd = bounds[(size_t)b * groups + g];
-    if (bd.y < first) whole += 1;
-    else if (bd.x < end) glist[atomicAdd(&s_listed, 1)] = g;  // at most `groups` <= kGroupCap entries
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) whole += __shfl_xor(whole, o);
-  if (lane == 0 && whole) atomicAdd(&s_whole, whole);
-  __syncthreads();
-  const int items = s_listed * gs;
-  // fn(token, pair) for every pair of the listed groups that this thread looks at
-  auto each_pair = [&](auto&& fn) {
+  auto each_pair = [&](int g0, bool count_whole, auto&& fn) {
+    __syncthreads();  // the previous list has been walked (and, the first time, cnt / s_whole are set)
+    if (tid == 0) s_listed = 0;
+    __syncthreads();
+    const int g1 = min(g0 + kGroupCap, groups);
+    for (int g = g0 + tid; g < g1; g += kListThreads) {
+      const int2 bd = bounds[(size_t)b * groups + g];
+      if (bd.y < first) whole += count_whole ? 1 : 0;
+      else if (bd.x < end) glist[atomicAdd(&s_listed, 1)] = g;
+    }
+    __syncthreads();
+    const int items = s_listed * gs;
     for (int i = tid; i < items; i += kListThreads) {
       const int gi = exact_div(i, gs, gs_magic);
       const int pair = lo + glist[gi] * gs + (i - gi * gs);
@@ -840,13 +838,18 @@ __global__ __launch_bounds__(kListThreads) void pair_lists_grouped_kernel(
     }
   };
   int below = 0;
-  each_pair([&](int tok, int) {
-    const int rel = tok - first;
-    below += rel < 0 ? 1 : 0;
-    if ((unsigned)rel < (unsigned)span) atomicAdd(&cnt[rel], 1);
-  });
+  for (int g0 = 0; g0 < groups; g0 += kGroupCap)
+    each_pair(g0, true, [&](int tok, int) {
+      const int rel = tok - first;
+      below += rel < 0 ? 1 : 0;
+      if ((unsigned)rel < (unsigned)span) atomicAdd(&cnt[rel], 1);
+    });
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o);
+  for (int o = 32; o > 0; o >>= 1) {
+    below += __shfl_xor(below, o);
+    whole += __shfl_xor(whole, o);
+  }
+  if (lane == 0 && whole) atomicAdd(&s_whole, whole);
   __syncthreads();
   int c[4];
 #pragma unroll
@@ -870,11 +873,11 @@ __global__ __launch_bounds__(kListThreads) void pair_lists_grouped_kernel(
     run += c[i];
   }
   if (blockIdx.x == gridDim.x - 1 && tid == 0) offset[(size_t)B * Nv] = B * groups * gs;
-  __syncthreads();
-  each_pair([&](int tok, int pair) {
-    const int rel = tok - first;
-    if ((unsigned)rel < (unsigned)span) list[atomicAdd(&cnt[rel], 1)] = pair;
-  });
+  for (int g0 = 0; g0 < groups; g0 += kGroupCap)
+    each_pair(g0, false, [&](int tok, int pair) {
+      const int rel = tok - first;
+      if ((unsigned)rel < (unsigned)span) list[atomicAdd(&cnt[rel], 1)] = pair;
+    });
 }
 
 // Four visible tokens per wave (16 lanes each) when the rows are whole 16-byte pieces: dfeat = sum over the
@@ -1127,8 +1130,7 @@ hipError_t launch_sum_parts(const float* part, size_t n, float* part2, float* ou
 // group_size consecutive pairs.
 hipError_t launch_pair_lists(const int32_t* pair_token, int B, int Nv, int pairs_per_image, int32_t* offset,
                              int32_t* list, hipStream_t stream, const int32_t* group_bounds, int group_size) {
-  if (group_bounds && group_size >= 1 && pairs_per_image % group_size == 0 &&
-      pairs_per_image / group_size <= kGroupCap) {
+  if (group_bounds && group_size >= 1 && pairs_per_image % group_size == 0) {
     // a range walks only the groups that reach into it: many small ranges cost little
     const int groups = pairs_per_image / group_size;
     const int want = (512 + B - 1) / B;

@@ -139,9 +139,11 @@ def test_attention_rejects_bad_arguments_on_host():
                                   a["K"], a["S"], a["M"], 1.0, 1, dq, p, p, None, None, None, ws, ws_bytes, None)
 
     assert bwd(dq=None) == -1
-    assert bwd() == -4                # bf16 needs an fp32 accumulation workspace
-    assert lib.affmae_pla_bwd_workspace_bytes(1, 64, 2, 32, 8, 8, 2, 1, 0) >= 2 * 64 * 64 * 4
-    assert lib.affmae_pla_bwd_workspace_bytes(1, 64, 2, 32, 8, 8, 2, 0, 0) == 0
+    assert bwd() == -4                # the backward keeps p and dS of every pair and the per-token pair lists
+    pairs = 64 * 8
+    for dtype in (0, 1):              # p, dS (fp32 per head), pair tokens, lists
+        assert lib.affmae_pla_bwd_workspace_bytes(1, 64, 2, 32, 8, 8, 2, dtype, 0) >= (2 * 2 * 4 + 4 + 4) * pairs
+    assert bwd(B=1 << 15, N=1 << 15, K=8) == -5   # pairs are numbered in 32 bits
 
 
 def test_binding_refuses_host_tensors():
