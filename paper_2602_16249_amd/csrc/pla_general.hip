@@ -99,6 +99,30 @@ __device__ __forceinline__ void rows_sum(float (&a)[8], int lane) {
 }
 __device__ __forceinline__ float all_sum(float x, int lane) { return sum_bits<1, 32>(x, lane); }
 __device__ __forceinline__ float all_max(float x, int lane) { return max_bits<1, 32>(x, lane); }
+// exp(x) for x <= 0 or so: the library routine for fp32 storage (1e-5 bar), the hardware exp2 for bf16 storage
+template <typename T>
+__device__ __forceinline__ float exp_for(float x) {
+  if constexpr (sizeof(T) == 2) return __builtin_amdgcn_exp2f(x * 1.4426950408889634f);
+  else return expf(x);
+}
+
+// <a, b> over the 16 bytes at pa and pb: fp32 pieces by fused multiply-adds, bf16 pieces by four two-element dot
+// instructions on the packed values (no unpacking)
+__device__ __forceinline__ float dot_raw(const float* pa, const float* pb) {
+  const float4 a = *reinterpret_cast<const float4*>(pa), b = *reinterpret_cast<const float4*>(pb);
+  return fmaf(a.w, b.w, fmaf(a.z, b.z, fmaf(a.y, b.y, a.x * b.x)));
+}
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ float dot_raw(const uint4& a, const uint4& b) {
+  float acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), 0.f, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), acc, false);
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), acc, false);
+}
+__device__ __forceinline__ float dot_raw(const bf16_t* pa, const bf16_t* pb) {
+  return dot_raw(*reinterpret_cast<const uint4*>(pa), *reinterpret_cast<const uint4*>(pb));
+}
+
 template <int E>
 __device__ __forceinline__ float dot_piece(const float (&a)[8], const float (&b)[8]) {
   float acc = 0.f;
@@ -146,16 +170,13 @@ __global__ __launch_bounds__(256) void pla_fwd_general_kernel(
     const int mynb = min(max(nbr_idx[tok * K + min(lane, K - 1)], 0), N - 1);
     const LaneRows<TR> rows = lane_rows<PP, E>(mynb, img_base, C, K, lane);
     for (int h = 0; h < H; ++h) {
-      float qv[8];
-      Piece<T>::load(q + (tok * H + h) * D + pc * E, qv);
+      const T* qrow = q + (tok * H + h) * D + pc * E;
       float s[TR], smax = -INFINITY;
 #pragma unroll
       for (int t = 0; t < TR; ++t) {
         s[t] = -INFINITY;
         if (t < trips) {
-          float kp[8];
-          Piece<T>::load(k + rows.off[t] + (size_t)h * D, kp);
-          const float dot = row_sum<PP>(dot_piece<E>(qv, kp), lane);
+          const float dot = row_sum<PP>(dot_raw(qrow, k + rows.off[t] + (size_t)h * D), lane);
           const float bj = (bias && rows.valid[t]) ? Elem<T>::load(bias + (tok * H + h) * K + t * RPT + rl) : 0.f;
           s[t] = rows.valid[t] ? fmaf(scale, dot, bj) : -INFINITY;
           smax = fmaxf(smax, s[t]);
@@ -163,18 +184,19 @@ __global__ __launch_bounds__(256) void pla_fwd_general_kernel(
       }
       float sb = -INFINITY, eb = 0.f;
       if (k_blank) {
-        float kb[8];
-        Piece<T>::load(k_blank + (size_t)h * D + pc * E, kb);
-        sb = scale * row_sum<PP>(dot_piece<E>(qv, kb), lane);
+        sb = scale * row_sum<PP>(dot_raw(qrow, k_blank + (size_t)h * D + pc * E), lane);
       }
       const float m = fmaxf(all_max(smax, lane), sb);
       float e[TR], zl = 0.f;
 #pragma unroll
       for (int t = 0; t < TR; ++t) {
-        e[t] = (t < trips && rows.valid[t]) ? expf(s[t] - m) : 0.f;
-        zl += e[t];
+        e[t] = 0.f;
+        if (t < trips) {
+          e[t] = rows.valid[t] ? exp_for<T>(s[t] - m) : 0.f;
+          zl += e[t];
+        }
       }
-      if (k_blank) eb = expf(sb - m);
+      if (k_blank) eb = exp_for<T>(sb - m);
       const float z = all_sum(pc == 0 ? zl : 0.f, lane) + eb;  // every row once
       float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -243,9 +265,8 @@ __global__ __launch_bounds__(256) void pla_bwd_general_kernel(
       if (lane == 0) bounds[tok] = make_int2(tmin, tmax);
     }
     for (int h = 0; h < H; ++h) {
-      float qv[8], gv[8];
-      Piece<T>::load(q + (tok * H + h) * D + pc * E, qv);
-      Piece<T>::load(dout + (tok * H + h) * D + pc * E, gv);
+      const T* qrow = q + (tok * H + h) * D + pc * E;
+      const T* grow = dout + (tok * H + h) * D + pc * E;
       const float l = lse[tok * H + h];
       float kp[TR][8], p[TR], dP[TR], Dl = 0.f;
 #pragma unroll
@@ -253,23 +274,19 @@ __global__ __launch_bounds__(256) void pla_bwd_general_kernel(
         p[t] = 0.f;
         dP[t] = 0.f;
         if (t < trips) {
-          float vp[8];
           Piece<T>::load(k + rows.off[t] + (size_t)h * D, kp[t]);
-          Piece<T>::load(v + rows.off[t] + (size_t)h * D, vp);
-          const float dot = row_sum<PP>(dot_piece<E>(qv, kp[t]), lane);
-          dP[t] = row_sum<PP>(dot_piece<E>(gv, vp), lane);
+          const float dot = row_sum<PP>(dot_raw(qrow, k + rows.off[t] + (size_t)h * D), lane);
+          dP[t] = row_sum<PP>(dot_raw(grow, v + rows.off[t] + (size_t)h * D), lane);
           const float bj = (bias && rows.valid[t]) ? Elem<T>::load(bias + (tok * H + h) * K + t * RPT + rl) : 0.f;
-          p[t] = rows.valid[t] ? expf(fmaf(scale, dot, bj) - l) : 0.f;
+          p[t] = rows.valid[t] ? exp_for<T>(fmaf(scale, dot, bj) - l) : 0.f;
           Dl = fmaf(p[t], dP[t], Dl);
         }
       }
       float pb = 0.f, dPb = 0.f, kb[8];
       if (k_blank) {
-        float vb[8];
         Piece<T>::load(k_blank + (size_t)h * D + pc * E, kb);
-        Piece<T>::load(v_blank + (size_t)h * D + pc * E, vb);
-        pb = expf(scale * row_sum<PP>(dot_piece<E>(qv, kb), lane) - l);
-        dPb = row_sum<PP>(dot_piece<E>(gv, vb), lane);
+        pb = exp_for<T>(scale * row_sum<PP>(dot_raw(qrow, k_blank + (size_t)h * D + pc * E), lane) - l);
+        dPb = row_sum<PP>(dot_raw(grow, v_blank + (size_t)h * D + pc * E), lane);
       }
       const float Dsum = all_sum(pc == 0 ? Dl : 0.f, lane) + pb * dPb;  // every row once
       float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -298,6 +315,9 @@ __global__ __launch_bounds__(256) void pla_bwd_general_kernel(
         for (int i = 0; i < E; ++i) acc[i] *= scale;
         Piece<T>::store(dq + (tok * H + h) * D + pc * E, acc);
         if (blank_grad) {
+          float qv[8], gv[8];
+          Piece<T>::load(qrow, qv);
+          Piece<T>::load(grow, gv);
 #pragma unroll
           for (int i = 0; i < E; ++i) {
             bacc[h * D + pc * E + i] += scale * dsb * qv[i];
