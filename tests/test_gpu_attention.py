@@ -32,6 +32,9 @@ GATHER_CASES = [
     ("bf16", 1, 130, 8, 32, 48, True, False),
     ("bf16", 1, 77, 2, 64, 33, True, True),
     ("bf16", 1, 300, 4, 16, 5, False, False),
+    ("bf16", 2, 150, 2, 16, 64, True, False),  # two pieces per row, both trips full; tokens that nobody lists
+    ("f32", 1, 90, 2, 16, 64, False, True),
+    ("bf16", 1, 70, 1, 64, 64, False, True),
 ]
 
 
@@ -115,6 +118,22 @@ def test_full_image_with_blank_tokens():
     errs = check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, blank=True,
                            use_plan=True)
     print(errs)
+
+
+def test_gather_kernels_on_full_images():
+    """Two full 1024px images without the cluster promise: the gather kernels at the benchmark's shape (16384
+    queries per image: the list builder of the backward takes them in two sweeps), every element compared; the
+    same with a table whose neighbours are drawn from the whole image (no locality: every token range of the list
+    builder has to walk every query)."""
+    cfg = CONFIGS["ft_s1_1024"].scaled(B=2)
+    print("case ft_s1_1024 B=2 gather kernels", flush=True)
+    w = make_workload(cfg, blank=True)
+    nbr, _ = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
+    print(check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), blank=True))
+    print("case ft_s1_1024 B=2 gather kernels, neighbours without locality", flush=True)
+    rng = np.random.default_rng(77)
+    nbr = random_neighbours(cfg.B, cfg.N, cfg.K, rng, distinct=False)
+    print(check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), blank=True))
 
 
 @pytest.mark.parametrize("use_plan", [False, True])
