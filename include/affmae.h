@@ -280,8 +280,8 @@ int affmae_knn_static(const float* coords, const int32_t* cluster_id, int B, int
  *                               bytes, 256-byte aligned; opaque.
  * affmae_pla_plan_bytes returns 0, and affmae_pla_plan AFFMAE_ERR_UNSUPPORTED,
  * when the shapes are outside what the tiled kernels take (they need S % 16 == 0
- * and N % 16 == 0 - S need not divide N: the last cluster may be short -,
- * M*S <= 1024, N < 2^20 and N*S < 2^31); the attention calls then use the gather
+ * - S need not divide N, nor 16: the last cluster, strip and token tile of an
+ * image may be short -, M*S <= 1024, N < 2^20 and N*S < 2^31); the attention calls then use the gather
  * kernels and ignore `plan`.
  */
 size_t affmae_pla_plan_bytes(int B, int N, int K, int S, int M);
@@ -313,7 +313,7 @@ int affmae_pla_plan(const int32_t* nbr_idx, const int32_t* near_clusters, int B,
  *                     of near_clusters[b,c,:], and that a token's neighbours
  *                     are pairwise distinct - what affmae_knn produces with
  *                     cluster_id == NULL.  It allows the cluster-tiled kernels
- *                     (bf16 storage, d == 32, S % 16 == 0, N % 16 == 0,
+ *                     (bf16 storage, d == 32, S % 16 == 0, any N,
  *                     M*S <= 1024; other shapes, head sizes 16 and 64 among them,
  *                     are served by the slower gather kernels, same results);
  *                     inputs must then be finite.  With NULL, S and M are ignored.

@@ -47,7 +47,7 @@ union Frag4 {
 // contiguous piece.  The reverse tables list, per token tile, the incidences that touch it (sorted, so
 // that sums formed along a list do not depend on scheduling), each with the place of its run.
 struct PlanLayout {
-  int strips;        // B * N / 16 (also the number of token tiles)
+  int strips;        // B * ceil(N / 16) (also the number of token tiles)
   int max_slots;     // M * S / 16
   int slot_stride;   // uint16 per strip in the slot table: [0] = count, [1 + s] = token tile of slot s
   int runs_stride;   // uint16 per strip in the run table: [s] = first place of slot s, [count] = places used
@@ -68,7 +68,7 @@ inline size_t plan_align(size_t n) { return (n + 255) / 256 * 256; }
 
 inline PlanLayout make_plan_layout(int B, int N, int K, int S, int M) {
   PlanLayout L;
-  L.strips = (int)((long long)B * N / 16);
+  L.strips = (int)((long long)B * ((N + 15) / 16));  // the last strip / token tile of an image may be short
   int max_slots = (int)((long long)M * S / 16);
   L.max_slots = max_slots;
   L.slot_stride = 1 + max_slots + (max_slots & 1);  // room to pad to an even number of slots

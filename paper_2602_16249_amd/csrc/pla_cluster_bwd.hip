@@ -109,7 +109,11 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   if (lane == 0) pdtile[kSpare] = 0u;  // (ordered before its first read by the fences of the passes)
   const int b = exact_div(sg, p.strips_per_image, p.spi_magic);
   const long long img_base = (long long)b * p.N;
-  const long long tok0 = (long long)sg * 16;
+  const int q0 = (sg - b * p.strips_per_image) * 16;  // first query of the strip, within the image
+  const long long tok0 = img_base + q0;
+  // An image's last strip and last token tile may be short (N % 16 != 0): rows past the end are never addressed -
+  // loads repeat the last real row (no plan entry refers to it, so p = dS = 0 there), stores are skipped.
+  const int nq = min(16, p.N - q0);
   const int C = p.H * kD;
   const int K = p.K;
 
@@ -126,21 +130,22 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   for (int t = 0; t < NT; ++t) {
     const int i = t * kWave + lane;
     const bool live = i < items;
-    item_live[t] = live;
     const int ii = live ? i : 0;
+    int qi;
     if (VEC) {
       const uint4 w = *reinterpret_cast<const uint4*>(p.entries + (size_t)sg * 16 * K + (size_t)ii * 8);
       ent[t][0] = live ? w.x : 0xffffffffu;
       ent[t][EW > 1 ? 1 : 0] = live ? w.y : 0xffffffffu;
       ent[t][EW > 2 ? 2 : 0] = live ? w.z : 0xffffffffu;
       ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
-      const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
-      item_off[t] = (uint32_t)(qi * p.H * K + j0);
+      qi = fast_div(ii, p.cq_magic);
+      item_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * chunks_per_query) * 8);
     } else {
       ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
-      const int qi = fast_div(ii, p.k_magic);
+      qi = fast_div(ii, p.k_magic);
       item_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
     }
+    item_live[t] = live && qi < nq;  // items of queries past the image's end: no bias is read, no dbias written
   }
   const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
   const int tr_off[2] = {tile_tr_offset(g, r, 0), tile_tr_offset(g, r, 1)};
@@ -153,6 +158,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const int la = lane >> 2, lc = lane & 3;
   const uint32_t lane_off_h = (uint32_t)(la * C * 2 + lc * 16 + h * kD * 2);  // the lane's piece of a tile's rows, head h
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
+  const uint32_t lane_off_max = (uint32_t)(p.N - 1) * (uint32_t)C * 2u + (uint32_t)(lc * 16 + h * kD * 2);  // same piece of the image's last row
   u32x4* kv = kv_all[wave];
   const int wr_chunk = tile_chunk(la, lc);
   const int rd_chunk = tile_chunk(r, g);
@@ -163,7 +169,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
     {  // the strip's rows cross through LDS like the K/V rows
-      const size_t qrow = (size_t)(tok0 + la) * C + h * kD + lc * 8;
+      const size_t qrow = (size_t)(tok0 + min(la, nq - 1)) * C + h * kD + lc * 8;
       const u32x4 qraw = *reinterpret_cast<const u32x4*>(p.q + qrow);
       const u32x4 graw = *reinterpret_cast<const u32x4*>(p.dout + qrow);
       const u32x4 oraw = *reinterpret_cast<const u32x4*>(p.out + qrow);
@@ -192,7 +198,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
     for (int i = 0; i < 8; ++i) Dq = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(of.h[i]), Dq);
     Dq = group_sum(Dq);
     if (g == 0) p.dsum[((size_t)sg * p.H + h) * 16 + r] = -Dq;  // the key-stationary kernel forms dS with it
-    const float nl2 = -p.lse[(size_t)(tok0 + r) * p.H + h] * kLog2e;
+    const float nl2 = -p.lse[(size_t)(tok0 + min(r, nq - 1)) * p.H + h] * kLog2e;
     const size_t head_rows = strip_rows + (size_t)h * K;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
     if (p.k_blank) {
@@ -208,7 +214,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       }
       sq = group_sum(sq);
       gv = group_sum(gv);
-      const float pb = __builtin_amdgcn_exp2f(fmaf(p.scale * sq, kLog2e, nl2));
+      const float pb = r < nq ? __builtin_amdgcn_exp2f(fmaf(p.scale * sq, kLog2e, nl2)) : 0.f;  // no blank column for a query past the end
       const float dsb = pb * (gv - Dq);
       // dq^T[channel 16dt + 4g + i][query r] += dS k_blank (the scale is applied when dq is written)
 #pragma unroll
@@ -255,7 +261,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
           if (VEC) {
             uint4 w = make_uint4(0, 0, 0, 0);
             if (REL) {  // the query's coordinates instead
-              const int ii = item_live[t] ? t * kWave + lane : 0;
+              const int ii = item_live[t] ? t * kWave + lane : 0;  // (a live item's query is inside the image)
               const float2 c = (reinterpret_cast<const float2*>(p.coords) + tok0)[fast_div(ii, p.cq_magic)];
               w.x = __float_as_uint(c.x);
               w.y = __float_as_uint(c.y);
@@ -279,7 +285,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
 #pragma unroll
           for (int i = 0; i < (kSlotCapB * 16 + kWave - 1) / kWave; ++i) {
             const int tile = __shfl(my_tile, slot0 + min(4 * i + g, nsl - 1));
-            reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)(tile * 16 + r)];
+            reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)min(tile * 16 + r, p.N - 1)];
           }
         }
         wave_lds_sync();
@@ -314,7 +320,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         // instruction per turn of whatever kind); made opaque, or the compiler rebuilds 64-bit vector addresses
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
-        uint32_t off0 = lane_off_h + tile0 * tile_bytes, off1 = lane_off_h + tile1 * tile_bytes;
+        uint32_t off0 = min(lane_off_h + tile0 * tile_bytes, lane_off_max), off1 = min(lane_off_h + tile1 * tile_bytes, lane_off_max);
         asm volatile("" : "+v"(off0), "+v"(off1));
         k0 = *reinterpret_cast<const u32x4*>(kimg + off0);
         v0 = *reinterpret_cast<const u32x4*>(vimg + off0);
@@ -462,7 +468,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       reinterpret_cast<uint2*>(kv)[tile_chunk(r, 2 * dt + (g >> 1)) * 2 + (g & 1)] = o;
     }
     wave_lds_sync();
-    *reinterpret_cast<u32x4*>(p.dq + (size_t)(tok0 + la) * C + h * kD + lc * 8) = kv[wr_chunk];
+    if (la < nq) *reinterpret_cast<u32x4*>(p.dq + (size_t)(tok0 + la) * C + h * kD + lc * 8) = kv[wr_chunk];
     wave_lds_sync();
   }
 }
@@ -519,6 +525,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   const int b = exact_div(kt, p.strips_per_image, p.spi_magic);
   const int C = p.H * kD;
   const size_t strip_base = (size_t)b * p.strips_per_image;
+  // rows of the image; its last token tile and last strip may be short (N % 16 != 0): loads past the end repeat the
+  // last real row (its p is 0: no entry refers to it), stores past the end are skipped
+  const size_t img_row0 = (size_t)b * p.N;
+  const int t0 = (kt - b * p.strips_per_image) * 16;  // the tile's first token, within the image
+  const int nt = min(16, p.N - t0);
   const int lo = __builtin_amdgcn_readfirstlane(p.rev_offset[kt]);
   const int n = __builtin_amdgcn_readfirstlane(p.rev_offset[kt + 1]) - lo;
   // q / dout rows cross through LDS: a lane loads 16 contiguous bytes of a row so that a quad reads 64
@@ -537,11 +548,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   }
   // element offset, within the strip's rows, of the piece this lane fetches in load i: row i * 64 / PR + la, and
   // the piece whose place in the tile is lc, i.e. piece lc ^ swz(row)
-  uint32_t q_dma[HG];
+  uint32_t q_dma_row[HG], q_dma_piece[HG];
 #pragma unroll
   for (int i = 0; i < HG; ++i) {
     const int row = i * (64 / PR) + la;
-    q_dma[i] = (uint32_t)(row * C + ((lc ^ swz(row)) * 8));
+    q_dma_row[i] = (uint32_t)row;
+    q_dma_piece[i] = (uint32_t)((lc ^ swz(row)) * 8);
   }
   // what this lane gives to lds_read_tr to receive, for channel 16dt + r of head hh, the values of rows (queries)
   // 4g..4g+3: the quarter r % 4 of those 16 channels in row 4g + r / 4
@@ -566,7 +578,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     Frag8 vop[HG];
 #pragma unroll
     for (int hh = 0; hh < HG; ++hh)
-      vop[hh].u4 = *reinterpret_cast<const uint4*>(p.v + ((size_t)kt * 16 + r) * C + (size_t)((hg + hh) * kD) + g * 8);
+      vop[hh].u4 = *reinterpret_cast<const uint4*>(p.v + (img_row0 + t0 + min(r, nt - 1)) * C + (size_t)((hg + hh) * kD) + g * 8);
     f32x4 dk[HG][2], dv[HG][2];
 #pragma unroll
     for (int hh = 0; hh < HG; ++hh)
@@ -587,13 +599,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         const size_t sgq = strip_base + (inc >> 8);
         const uint32_t start = run & 0xffffu;
         it.len = run >> 16;
-        const size_t qbase = sgq * 16 * C + (size_t)(hg * kD);
+        const int sq0 = (int)(inc >> 8) * 16;  // the strip's first query, within the image
+        const uint32_t last_q = (uint32_t)min(15, p.N - 1 - sq0);
+        const size_t qbase = (img_row0 + sq0) * C + (size_t)(hg * kD);
         typedef const __attribute__((address_space(1))) void* gptr_t;
         typedef __attribute__((address_space(3))) void* lptr_t;
 #pragma unroll
         for (int i = 0; i < HG; ++i) {  // load i: rows i * 64 / PR onwards
-          __builtin_amdgcn_global_load_lds((gptr_t)(p.q + qbase + q_dma[i]), (lptr_t)(rows + i * 64), 16, 0, 0);
-          __builtin_amdgcn_global_load_lds((gptr_t)(p.dout + qbase + q_dma[i]), (lptr_t)(rows + HG * 64 + i * 64), 16, 0, 0);
+          const uint32_t at = min(q_dma_row[i], last_q) * (uint32_t)C + q_dma_piece[i];
+          __builtin_amdgcn_global_load_lds((gptr_t)(p.q + qbase + at), (lptr_t)(rows + i * 64), 16, 0, 0);
+          __builtin_amdgcn_global_load_lds((gptr_t)(p.dout + qbase + at), (lptr_t)(rows + HG * 64 + i * 64), 16, 0, 0);
         }
         // runs start at even places and the rows hold an even number of places: aligned pairs
         const uint16_t* codes = p.sorted_pos + sgq * p.places + start;
@@ -704,9 +719,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     wave_lds_sync();
 #pragma unroll
     for (int i = 0; i < HG; ++i) {
-      const size_t at = ((size_t)kt * 16 + i * (64 / PR)) * C + (size_t)(hg * kD) + q_lane;
-      *reinterpret_cast<u32x4*>(p.dk + at) = rows0[wr_chunk[i]];
-      *reinterpret_cast<u32x4*>(p.dv + at) = rows0[HG * 64 + wr_chunk[i]];
+      const size_t at = (img_row0 + t0 + i * (64 / PR)) * C + (size_t)(hg * kD) + q_lane;
+      if (i * (64 / PR) + la < nt) {
+        *reinterpret_cast<u32x4*>(p.dk + at) = rows0[wr_chunk[i]];
+        *reinterpret_cast<u32x4*>(p.dv + at) = rows0[HG * 64 + wr_chunk[i]];
+      }
     }
     wave_lds_sync();
   }
@@ -759,7 +776,7 @@ __global__ __launch_bounds__(256) void pla_rel_reduce_kernel(const float* __rest
 size_t pla_bwd_cluster_rel_workspace_bytes(int B, int N, int H, int R) {
   // tables of the waves, then the tables of pla_rel_reduce_kernel
   const size_t cells = (size_t)(2 * R + 1) * (2 * R + 1);
-  return plan_align((size_t)B * (N / 16) * H * cells * sizeof(float)) + plan_align((size_t)kRelParts * H * cells * sizeof(float));
+  return plan_align((size_t)B * ((N + 15) / 16) * H * cells * sizeof(float)) + plan_align((size_t)kRelParts * H * cells * sizeof(float));
 }
 bool pla_bwd_cluster_rel_sums(int R) { return (2 * R + 1) * (2 * R + 1) <= kRelCells; }
 
@@ -784,7 +801,7 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.runs = reinterpret_cast<const uint16_t*>(base + L.runs_off);
   p.runs_stride = L.runs_stride; p.places = L.places;
   p.N = a.N; p.H = a.H; p.K = a.K;
-  p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
+  p.strips = L.strips; p.strips_per_image = (a.N + 15) / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
   p.scale = a.scale;
   p.dq = (bf16_t*)a.dq; p.dk = (bf16_t*)a.dk; p.dv = (bf16_t*)a.dv;
   const size_t ph_bytes = plan_align((size_t)L.strips * a.H * L.places * sizeof(bf16_t));
@@ -808,7 +825,7 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   p.h_magic = div_magic(a.H);
-  p.spi_magic = div_magic(a.N / 16);
+  p.spi_magic = div_magic((a.N + 15) / 16);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0) &&
                    (!p.ds || reinterpret_cast<uintptr_t>(p.ds) % 16 == 0);
 #define AFFMAE_BWDQ(KERNEL, NT) \

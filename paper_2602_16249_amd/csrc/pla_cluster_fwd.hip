@@ -78,7 +78,11 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   bf16_t* scratch = scratch_all[wave];
   const int b = exact_div(sg, p.strips_per_image, p.spi_magic);
   const long long img_base = (long long)b * p.N;
-  const long long tok0 = (long long)sg * 16;
+  const int q0 = (sg - b * p.strips_per_image) * 16;  // first query of the strip, within the image
+  const long long tok0 = img_base + q0;
+  // An image's last strip and last token tile may be short (N % 16 != 0): rows past the end are never addressed -
+  // loads repeat the last real row (no plan entry refers to it, so it meets probability 0), stores are skipped.
+  const int nq = min(16, p.N - q0);
   const int C = p.H * kD;
   const int K = p.K;
 
@@ -104,7 +108,8 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         ent[t][EW > 1 ? 1 : 0] = live ? w.y : 0xffffffffu;
         ent[t][EW > 2 ? 2 : 0] = live ? w.z : 0xffffffffu;
         ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
-        const int qi = fast_div(ii, p.cq_magic), j0 = (ii - qi * chunks_per_query) * 8;
+        const int qi_raw = fast_div(ii, p.cq_magic), j0 = (ii - qi_raw * chunks_per_query) * 8;
+        const int qi = min(qi_raw, nq - 1);
         uint4 bv = make_uint4(0, 0, 0, 0);
         if (REL) {  // the query's coordinates instead
           const float2 c = (reinterpret_cast<const float2*>(p.coords) + tok0)[qi];
@@ -119,8 +124,8 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         bw[t][EW > 3 ? 3 : 0] = bv.w;
       } else {
         ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
-        const int qi = fast_div(ii, p.k_magic);
-        bw[t][0] = bias_head ? (uint32_t)bias_head[(uint32_t)(qi * p.H * K + (ii - qi * K))] : 0u;
+        const int qi_raw = fast_div(ii, p.k_magic), qi = min(qi_raw, nq - 1);
+        bw[t][0] = bias_head ? (uint32_t)bias_head[(uint32_t)(qi * p.H * K + (ii - qi_raw * K))] : 0u;
       }
     }
   };
@@ -135,6 +140,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   const int la = lane >> 2, lc = lane & 3;
   const uint32_t lane_off_h = (uint32_t)(la * C * 2 + lc * 16 + h * kD * 2);  // the lane's piece of a tile's rows, head h
   const uint32_t tile_bytes = 16u * (uint32_t)C * 2u;
+  const uint32_t lane_off_max = (uint32_t)(p.N - 1) * (uint32_t)C * 2u + (uint32_t)(lc * 16 + h * kD * 2);  // same piece of the image's last row
   u32x4* kv = kv_all[wave];
   const int wr_chunk = tile_chunk(la, lc);
   const int rd_chunk = tile_chunk(r, g);
@@ -150,7 +156,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
     load_items(ent, bw);
     // the Q^T operand: lane (query r, channels 8g..8g+7)
     const u32x4 qraw =
-        *reinterpret_cast<const u32x4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8));
+        *reinterpret_cast<const u32x4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(min(la, nq - 1) * C + lc * 8));
     // first use of a loaded value: everything the strip streams in is in flight by now
     const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
     kv[wr_chunk] = qraw;  // the q rows cross through LDS like the K/V rows
@@ -171,7 +177,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
 #pragma unroll
         for (int i = 0; i < (kSlotCap * 16 + kWave - 1) / kWave; ++i) {
           const int tile = __shfl(my_tile, slot0 + min(4 * i + g, nsl - 1));
-          reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)(tile * 16 + r)];
+          reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)min(tile * 16 + r, p.N - 1)];
         }
       }
       wave_lds_sync();
@@ -210,7 +216,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         // whatever kind.)  The offsets are made opaque, or the compiler rebuilds 64-bit vector addresses.
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
-        uint32_t off0 = lane_off_h + tile0 * tile_bytes, off1 = lane_off_h + tile1 * tile_bytes;
+        uint32_t off0 = min(lane_off_h + tile0 * tile_bytes, lane_off_max), off1 = min(lane_off_h + tile1 * tile_bytes, lane_off_max);
         asm volatile("" : "+v"(off0), "+v"(off1));
         k0 = *reinterpret_cast<const u32x4*>(kimg + off0);
         v0 = *reinterpret_cast<const u32x4*>(vimg + off0);
@@ -335,8 +341,9 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       reinterpret_cast<uint2*>(kv)[tile_chunk(r, 2 * dt + (g >> 1)) * 2 + (g & 1)] = o;
     }
     wave_lds_sync();
-    *reinterpret_cast<u32x4*>(p.out + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8)) = kv[wr_chunk];
-    if (g == 0) (p.lse + (size_t)tok0 * p.H + h)[(uint32_t)(r * p.H)] = m_fin + __logf(l_tot);
+    if (la < nq)
+      *reinterpret_cast<u32x4*>(p.out + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8)) = kv[wr_chunk];
+    if (g == 0 && r < nq) (p.lse + (size_t)tok0 * p.H + h)[(uint32_t)(r * p.H)] = m_fin + __logf(l_tot);
   }
 }
 
@@ -365,10 +372,10 @@ bool pla_cluster_relpos_supported(const PlaArgs& a) {
 
 bool pla_cluster_supported(const PlaArgs& a) {
   if (!a.near_clusters || a.dtype != 1 || a.d != kD) return false;
-  if (a.S % 16 || a.S < 16 || a.N % 16) return false;             // token tiles: whole, and never straddling clusters
+  if (a.S % 16 || a.S < 16) return false;                         // token tiles never straddle clusters
   if (a.M > (a.N + a.S - 1) / a.S) return false;
   if ((long long)a.M * a.S / 16 > kMaxSlots) return false;        // tile set of a strip is a 64-bit mask
-  if (a.K > 64 || a.N / 16 > 65535) return false;                 // 16-bit plan entries and tile ids
+  if (a.K > 64 || (a.N + 15) / 16 > 65535) return false;          // 16-bit plan entries and tile ids
   if ((long long)a.N * a.S >= (1ll << 31)) return false;          // range of the reciprocal division
   if ((long long)a.N * a.H * kD * 2 >= (1ll << 32)) return false; // 32-bit byte offsets inside an image's K / V
   return true;
@@ -384,14 +391,14 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   p.slots = reinterpret_cast<const uint16_t*>(static_cast<const char*>(plan) + L.slots_off);
   p.entries = reinterpret_cast<const uint16_t*>(static_cast<const char*>(plan) + L.entries_off);
   p.N = a.N; p.H = a.H; p.K = a.K;
-  p.strips = L.strips; p.strips_per_image = a.N / 16; p.slot_stride = L.slot_stride;
+  p.strips = L.strips; p.strips_per_image = (a.N + 15) / 16; p.slot_stride = L.slot_stride;
   p.scale = a.scale;
   p.out = (bf16_t*)a.out; p.lse = a.lse;
   p.coords = a.rel_coords; p.rel_table = (const bf16_t*)a.rel_table; p.R = a.rel_R; p.rate = a.rel_rate;
   p.k_magic = div_magic(a.K);
   p.cq_magic = div_magic(a.K >= 8 ? a.K / 8 : 1);
   p.h_magic = div_magic(a.H);
-  p.spi_magic = div_magic(a.N / 16);
+  p.spi_magic = div_magic((a.N + 15) / 16);
   // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
   const dim3 grid((((long long)L.strips * a.H + kFwdWaves - 1) / kFwdWaves + 7) / 8 * 8);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);

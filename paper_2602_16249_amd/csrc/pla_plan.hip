@@ -57,6 +57,7 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
   const int32_t* near_c = p.near + ((size_t)b * p.G + c) * p.M;
   const int tiles_per_cluster = p.S / 16;
   const int nent = 16 * p.K;
+  const int nent_real = min(16, p.N - q0) * p.K;  // the image's last strip may hold fewer than 16 queries
   const int32_t* nbr = p.nbr_idx + ((size_t)b * p.N + q0) * p.K;
 
   // candidate-list tile of every (query, slot): m * (S/16) + (token % S) / 16
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(256) void pla_plan_kernel(PlanParams p) {
 #pragma unroll
   for (int t = 0; t < NE; ++t) {
     const int e = t * kWave + lane;
-    const int n = (e < nent) ? nbr[e] : -1;
+    const int n = (e < nent_real) ? nbr[e] : -1;  // queries past the end have no entries
     const int nn = min(max(n, 0), p.N - 1);
     inr[t] = e < nent && n == nn;
     tok[t] = nn;
@@ -254,9 +255,9 @@ hipError_t launch_pla_plan(const int32_t* nbr_idx, const int32_t* near, int B, i
   char* base = static_cast<char*>(plan);
   PlanParams p;
   p.nbr_idx = nbr_idx; p.near = near;
-  p.N = N; p.K = K; p.S = S; p.M = M; p.G = (N + S - 1) / S;  // the last cluster may be short (whole tiles: N % 16 == 0)
+  p.N = N; p.K = K; p.S = S; p.M = M; p.G = (N + S - 1) / S;  // the last cluster may be short
   p.s_magic = div_magic(S); p.k_magic = div_magic(K);
-  p.strips = L.strips; p.strips_per_image = N / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
+  p.strips = L.strips; p.strips_per_image = (N + 15) / 16; p.slot_stride = L.slot_stride; p.max_slots = L.max_slots;
   p.slots = reinterpret_cast<uint16_t*>(base + L.slots_off);
   p.entries = reinterpret_cast<uint16_t*>(base + L.entries_off);
   p.rev_count = reinterpret_cast<int32_t*>(base + L.rev_count_off);

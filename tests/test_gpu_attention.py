@@ -67,6 +67,9 @@ CLUSTER_CASES = [
     ("tiny_f32", 1, 256, 64, 2, 16, 256, 1, False),    # one cluster per image (exact kNN), bf16 storage here
     ("merged_stage", 2, 224, 96, 3, 8, 32, 3, True),   # K = 8: one 16-byte chunk of slots per query
     ("merged_stage", 2, 64, 64, 2, 1, 16, 2, False),   # K = 1: every token attends to itself only
+    ("mae_pt_s1_1024", 2, 1000, 64, 2, 48, 64, 8, True),   # N % 16 = 8: short last strip and token tile, blank sums
+    ("merged_stage", 3, 250, 256, 8, 16, 32, 4, False),    # N % 16 = 10, eight heads (four head groups per tile)
+    ("knn_scale", 1, 33, 64, 2, 12, 16, 2, True),          # three strips, the last of one query
 ]
 
 
@@ -153,12 +156,13 @@ def test_promise_with_permuted_neighbour_lists(use_plan, bias):
     check_attention(w, nbr, cfg.dtype, 1.0 / np.sqrt(cfg.d), near=near, S=cfg.S, M=cfg.M, blank=True, use_plan=use_plan)
 
 
-@pytest.mark.parametrize("N,tiled", [(4000, True), (4001, False)])
+@pytest.mark.parametrize("N,tiled", [(4000, True), (4001, True), (3983, True)])
 def test_short_last_cluster_end_to_end(N, tiled):
     """coords -> affmae_cluster -> affmae_knn -> affmae_pla_fwd / affmae_pla_bwd with N not a multiple of the
     cluster size (a masked batch keeps whatever number of tokens the mask leaves): curve order, neighbour table
-    and near clusters bit-equal to the oracle, attention within the bf16 bound.  N = 4000 (whole 16-token tiles)
-    runs the tiled kernels; N = 4001 takes the gather kernels although the promise is given."""
+    and near clusters bit-equal to the oracle, attention within the bf16 bound, in the tiled kernels: N = 4000
+    (whole 16-token tiles, short last cluster), N = 4001 (a last strip and token tile of one token, which is also
+    the whole last cluster), N = 3983 (fifteen tokens in the last tile)."""
     import torch
     import paper_2602_16249_amd as aff
     print(f"case end to end N={N}", flush=True)

@@ -64,6 +64,8 @@ def test_relpos_any_neighbour_table(dtype, B, N, H, d, K, R, rate, blank):
     ("merged_stage", 1, 1024, 64, 4, 20, 8, 2, 0.01, True, True),     # K not a multiple of 8
     ("knn_scale", 1, 1024, 16, 16, 64, 2, 4, 0.1, True, False),       # strips that touch more tiles than one pass holds
     ("ft_s1_1024", 3, 1024, 32, 4, 8, 1, 31, 2.0, False, True),        # the largest table, one head
+    ("knn_scale", 2, 1001, 64, 8, 48, 2, 4, 0.05, True, True),        # a last strip / token tile of 9 tokens
+    ("mae_pt_s1_1024", 2, 1000, 32, 4, 24, 2, 6, 0.125, False, False),  # ... of 8, table too large for the in-kernel sums
 ])
 def test_relpos_clustered(name, B, N, S, M, K, H, R, rate, blank, use_plan):
     print(f"case relpos tiled {name} B={B} N={N} S={S} M={M} K={K} H={H} R={R}", flush=True)
