@@ -55,7 +55,8 @@ hipError_t launch_pair_lists(const int32_t* pair_token, int B, int Nv, int pairs
                              int32_t* list, hipStream_t stream, const int32_t* group_bounds = nullptr,
                              int group_size = 0);
 hipError_t launch_pair_gather(const void* dout, const float* weights, const int32_t* offset, const int32_t* list,
-                              size_t tokens, int C, int Kt, int dtype, void* dfeat, bool pieces, hipStream_t stream);
+                              size_t tokens, int C, int Kt, int dtype, void* dfeat, bool pieces, hipStream_t stream,
+                              const float* extra = nullptr, float* extra_sum = nullptr);
 
 // Neighbourhood merging (merge.hip): anchor selection, location-aware aggregation, backward.
 struct MergeArgs {

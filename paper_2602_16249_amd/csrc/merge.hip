@@ -447,18 +447,6 @@ __global__ __launch_bounds__(256) void merge_bwd_kernel(const T* __restrict__ fe
   if (lane == 0) pair_bounds[slot] = make_int2(tmin, tmax);
 }
 
-// dscore[token] = sum of dz over the token's pairs.
-__global__ __launch_bounds__(256) void merge_dscore_kernel(const float* __restrict__ dzpair,
-                                                          const int32_t* __restrict__ offset,
-                                                          const int32_t* __restrict__ list, int tokens,
-                                                          float* __restrict__ dscore) {
-  const int tok = blockIdx.x * blockDim.x + threadIdx.x;
-  if (tok >= tokens) return;
-  const int lo = offset[tok], n = offset[tok + 1] - lo;
-  float s = 0.f;
-  for (int i = 0; i < n; ++i) s += dzpair[list[lo + i]];
-  dscore[tok] = s;
-}
 
 size_t merge_align(size_t n) { return (n + 255) / 256 * 256; }
 struct MergeBwdLayout {
@@ -557,10 +545,10 @@ hipError_t launch_merge_bwd(const MergeArgs& a, hipStream_t stream) {
   hipError_t e = launch_pair_lists(pair_token, a.B, a.N, a.n_keep * a.K, offset, list, stream,
                                    reinterpret_cast<const int32_t*>(pair_bounds), a.K);
   if (e != hipSuccess) return e;
-  AFFMAE_LAUNCH("merge_dscore_kernel", stream, merge_dscore_kernel, dim3((unsigned)((tokens + 255) / 256)), dim3(256),
-                0, stream, dzpair, offset, list, (int)tokens, a.dscore);
+  // one walk over every token's list serves both sums: dfeat = sum of w * dout, dscore = sum of dz
   const bool gpieces = merge_pieces(a, a.dout, a.dfeat) && (long long)a.n_keep * a.C < (1ll << 31);
-  return launch_pair_gather(a.dout, wpair, offset, list, tokens, a.C, a.K, a.dtype, a.dfeat, gpieces, stream);
+  return launch_pair_gather(a.dout, wpair, offset, list, tokens, a.C, a.K, a.dtype, a.dfeat, gpieces, stream, dzpair,
+                            a.dscore);
 }
 
 }  // namespace affmae

@@ -881,12 +881,13 @@ __global__ __launch_bounds__(kListThreads) void pair_lists_grouped_kernel(
 }
 
 // Four visible tokens per wave (16 lanes each) when the rows are whole 16-byte pieces: dfeat = sum over the
-// token's pairs of w * dout[query].
+// token's pairs of w * dout[query]; with `extra`, also extra_sum[token] = sum over the same pairs of extra[pair].
 template <typename T>
 __global__ __launch_bounds__(256) void vts_dfeat16_kernel(const T* __restrict__ dout, const float* __restrict__ weights,
                                                          const int32_t* __restrict__ offset,
                                                          const int32_t* __restrict__ list, int tokens, int C, int Kt,
-                                                         T* __restrict__ dfeat) {
+                                                         T* __restrict__ dfeat, const float* __restrict__ extra,
+                                                         float* __restrict__ extra_sum) {
   constexpr int CH = Piece<T>::kCh;
   const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
   const long long want = (xcd_contiguous_block() * 4 + threadIdx.x / kWave) * 4 + (lane >> 4);
@@ -897,6 +898,7 @@ __global__ __launch_bounds__(256) void vts_dfeat16_kernel(const T* __restrict__ 
   int nmax = n;
   nmax = max(nmax, __shfl_xor(nmax, 16));
   nmax = max(nmax, __shfl_xor(nmax, 32));
+  float xsum = 0.f;
   for (int base = 0; base < C; base += 16 * CH) {
     const int c0 = base + sub * CH;
     const bool on = live && c0 < C;
@@ -906,6 +908,7 @@ __global__ __launch_bounds__(256) void vts_dfeat16_kernel(const T* __restrict__ 
       // places past the end of a list repeat its last pair at weight 0 (an empty list: pair 0)
       const int mine = n > 0 ? list[lo + min(chunk + sub, n - 1)] : 0;
       const float wmine = have ? weights[mine] : 0.f;
+      if (extra && base == 0 && have) xsum += extra[mine];
       const int qmine = mine / Kt;
       const int m = min(16, nmax - chunk);
       // four pairs per trip, their rows in flight together
@@ -935,18 +938,24 @@ __global__ __launch_bounds__(256) void vts_dfeat16_kernel(const T* __restrict__ 
     }
     if (on) Piece<T>::store(dfeat + (size_t)tok * C + c0, acc);
   }
+  if (extra) {  // wave-uniform
+    xsum = Group<16>::sum(xsum);
+    if (live && sub == 0) extra_sum[tok] = xsum;
+  }
 }
 
-// One wave per visible token: dfeat = sum over the token's pairs of w * dout[query].
+// One wave per visible token: dfeat = sum over the token's pairs of w * dout[query] (and extra_sum, as above).
 template <typename T>
 __global__ __launch_bounds__(256) void vts_dfeat_kernel(const T* __restrict__ dout, const float* __restrict__ weights,
                                                        const int32_t* __restrict__ offset,
                                                        const int32_t* __restrict__ list, int tokens, int C, int Kt,
-                                                       T* __restrict__ dfeat) {
+                                                       T* __restrict__ dfeat, const float* __restrict__ extra,
+                                                       float* __restrict__ extra_sum) {
   const int lane = threadIdx.x & (kWave - 1);
   const long long tok = xcd_contiguous_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   if (tok >= tokens) return;  // wave-uniform
   const int lo = offset[tok], n = offset[tok + 1] - lo;
+  float xsum = 0.f;
   for (int base = 0; base < C; base += 2 * kWave) {  // wave-uniform trips; only the memory accesses are predicated
     const int c0 = base + 2 * lane;
     const bool on = c0 < C;
@@ -955,6 +964,7 @@ __global__ __launch_bounds__(256) void vts_dfeat_kernel(const T* __restrict__ do
       const int m = min(kWave, n - chunk);
       const int mine = lane < m ? list[lo + chunk + lane] : 0;
       float wmine = lane < m ? weights[mine] : 0.f;
+      if (extra && base == 0 && lane < m) xsum += extra[mine];
       int qmine = mine / Kt;
       asm volatile("" : "+v"(wmine), "+v"(qmine));  // broadcast below: computed here with every lane active
       for (int i = 0; i < m; ++i) {
@@ -969,6 +979,10 @@ __global__ __launch_bounds__(256) void vts_dfeat_kernel(const T* __restrict__ do
       }
     }
     if (on) store2(dfeat + (size_t)tok * C + c0, a0, a1);
+  }
+  if (extra) {  // wave-uniform
+    xsum = wave_sum(xsum);
+    if (lane == 0) extra_sum[tok] = xsum;
   }
 }
 
@@ -1114,7 +1128,7 @@ hipError_t launch_vts_bwd(const VtsArgs& a, hipStream_t stream) {
 size_t sum_parts_scratch_floats(size_t n) { return (n + kDpPer - 1) / kDpPer; }
 hipError_t launch_sum_parts(const float* part, size_t n, float* part2, float* out, hipStream_t stream) {
   const size_t blocks = (n + kDpPer - 1) / kDpPer;
-  if (blocks <= 1) {
+  if (blocks <= 8) {  // up to 128 values per thread: one workgroup is quicker than a second launch
     AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3(1), dim3(1024), 0, stream, part, n, n, out);
   } else {
     AFFMAE_LAUNCH("vts_dp_kernel", stream, vts_dp_kernel, dim3((unsigned)blocks), dim3(1024), 0, stream, part, n,
@@ -1160,26 +1174,28 @@ hipError_t launch_pair_lists(const int32_t* pair_token, int B, int Nv, int pairs
 }
 
 // dfeat[token] = sum over the token's pairs of weights[pair] * dout[pair / Kt]  (rows of C channels of `dtype`;
-// `pieces`: rows are whole 16-byte pieces, 16-byte aligned, and every row offset fits 32 bits).
+// `pieces`: rows are whole 16-byte pieces, 16-byte aligned, and every row offset fits 32 bits).  With `extra`
+// (one value per pair), also extra_sum[token] = sum over the token's pairs of extra[pair].
 hipError_t launch_pair_gather(const void* dout, const float* weights, const int32_t* offset, const int32_t* list,
-                              size_t tokens, int C, int Kt, int dtype, void* dfeat, bool pieces, hipStream_t stream) {
+                              size_t tokens, int C, int Kt, int dtype, void* dfeat, bool pieces, hipStream_t stream,
+                              const float* extra, float* extra_sum) {
   if (pieces) {
     const dim3 per4(round_up8(((long long)tokens + 15) / 16));
     if (dtype == 1)
       AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat16_kernel<bf16_t>, per4, dim3(256), 0, stream,
-                    (const bf16_t*)dout, weights, offset, list, (int)tokens, C, Kt, (bf16_t*)dfeat);
+                    (const bf16_t*)dout, weights, offset, list, (int)tokens, C, Kt, (bf16_t*)dfeat, extra, extra_sum);
     else
       AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat16_kernel<float>, per4, dim3(256), 0, stream,
-                    (const float*)dout, weights, offset, list, (int)tokens, C, Kt, (float*)dfeat);
+                    (const float*)dout, weights, offset, list, (int)tokens, C, Kt, (float*)dfeat, extra, extra_sum);
     return hipGetLastError();
   }
   const dim3 per_token(round_up8(((long long)tokens + 3) / 4));
   if (dtype == 1)
     AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<bf16_t>, per_token, dim3(256), 0, stream,
-                  (const bf16_t*)dout, weights, offset, list, (int)tokens, C, Kt, (bf16_t*)dfeat);
+                  (const bf16_t*)dout, weights, offset, list, (int)tokens, C, Kt, (bf16_t*)dfeat, extra, extra_sum);
   else
     AFFMAE_LAUNCH("vts_dfeat_kernel", stream, vts_dfeat_kernel<float>, per_token, dim3(256), 0, stream,
-                  (const float*)dout, weights, offset, list, (int)tokens, C, Kt, (float*)dfeat);
+                  (const float*)dout, weights, offset, list, (int)tokens, C, Kt, (float*)dfeat, extra, extra_sum);
   return hipGetLastError();
 }
 
