@@ -82,7 +82,8 @@ __device__ __forceinline__ int xcd_contiguous_block() {
 // in the wave's row tile, bin per pair, value through the vector cache), and the table's gradient is summed per
 // wave: each pair's dS is added to its bin in an fp64 table in LDS (ds_add_f64 runs at the speed of an integer
 // LDS atomic on this chip; the fp32 form is several times slower) and the wave writes its table out at the end.
-template <int NT, bool VEC, bool REL, bool SUMS>
+// RAG: N is not a multiple of 16 (only then do the row clamps and store tests below exist in the code).
+template <int NT, bool VEC, bool REL, bool SUMS, bool RAG>
 __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   static_assert(!SUMS || REL, "the table's gradient belongs to the table form");
   static_assert(!REL || VEC, "the table form is built for 16-byte items");
@@ -113,7 +114,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   const long long tok0 = img_base + q0;
   // An image's last strip and last token tile may be short (N % 16 != 0): rows past the end are never addressed -
   // loads repeat the last real row (no plan entry refers to it, so p = dS = 0 there), stores are skipped.
-  const int nq = min(16, p.N - q0);
+  const int nq = RAG ? min(16, p.N - q0) : 16;
   const int C = p.H * kD;
   const int K = p.K;
 
@@ -145,7 +146,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       qi = fast_div(ii, p.k_magic);
       item_off[t] = (uint32_t)(qi * p.H * K + (ii - qi * K));
     }
-    item_live[t] = live && qi < nq;  // items of queries past the image's end: no bias is read, no dbias written
+    item_live[t] = live && (!RAG || qi < nq);  // items of queries past the image's end: no bias is read, no dbias written
   }
   const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
   const int tr_off[2] = {tile_tr_offset(g, r, 0), tile_tr_offset(g, r, 1)};
@@ -169,7 +170,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
   {
     Frag8 qf, gf, of;  // lane (query r, channels 8g..8g+7) of q, dout, out
     {  // the strip's rows cross through LDS like the K/V rows
-      const size_t qrow = (size_t)(tok0 + min(la, nq - 1)) * C + h * kD + lc * 8;
+      const size_t qrow = (size_t)(tok0 + (RAG ? min(la, nq - 1) : la)) * C + h * kD + lc * 8;
       const u32x4 qraw = *reinterpret_cast<const u32x4*>(p.q + qrow);
       const u32x4 graw = *reinterpret_cast<const u32x4*>(p.dout + qrow);
       const u32x4 oraw = *reinterpret_cast<const u32x4*>(p.out + qrow);
@@ -198,7 +199,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
     for (int i = 0; i < 8; ++i) Dq = fmaf(bf16_to_f32(gf.h[i]), bf16_to_f32(of.h[i]), Dq);
     Dq = group_sum(Dq);
     if (g == 0) p.dsum[((size_t)sg * p.H + h) * 16 + r] = -Dq;  // the key-stationary kernel forms dS with it
-    const float nl2 = -p.lse[(size_t)(tok0 + min(r, nq - 1)) * p.H + h] * kLog2e;
+    const float nl2 = -p.lse[(size_t)(tok0 + (RAG ? min(r, nq - 1) : r)) * p.H + h] * kLog2e;
     const size_t head_rows = strip_rows + (size_t)h * K;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
     if (p.k_blank) {
@@ -214,7 +215,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       }
       sq = group_sum(sq);
       gv = group_sum(gv);
-      const float pb = r < nq ? __builtin_amdgcn_exp2f(fmaf(p.scale * sq, kLog2e, nl2)) : 0.f;  // no blank column for a query past the end
+      const float pb = (!RAG || r < nq) ? __builtin_amdgcn_exp2f(fmaf(p.scale * sq, kLog2e, nl2)) : 0.f;  // no blank column for a query past the end
       const float dsb = pb * (gv - Dq);
       // dq^T[channel 16dt + 4g + i][query r] += dS k_blank (the scale is applied when dq is written)
 #pragma unroll
@@ -285,7 +286,7 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
 #pragma unroll
           for (int i = 0; i < (kSlotCapB * 16 + kWave - 1) / kWave; ++i) {
             const int tile = __shfl(my_tile, slot0 + min(4 * i + g, nsl - 1));
-            reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)min(tile * 16 + r, p.N - 1)];
+            reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)(RAG ? min(tile * 16 + r, p.N - 1) : tile * 16 + r)];
           }
         }
         wave_lds_sync();
@@ -320,7 +321,11 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
         // instruction per turn of whatever kind); made opaque, or the compiler rebuilds 64-bit vector addresses
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
-        uint32_t off0 = min(lane_off_h + tile0 * tile_bytes, lane_off_max), off1 = min(lane_off_h + tile1 * tile_bytes, lane_off_max);
+        uint32_t off0 = lane_off_h + tile0 * tile_bytes, off1 = lane_off_h + tile1 * tile_bytes;
+        if (RAG) {
+          off0 = min(off0, lane_off_max);
+          off1 = min(off1, lane_off_max);
+        }
         asm volatile("" : "+v"(off0), "+v"(off1));
         k0 = *reinterpret_cast<const u32x4*>(kimg + off0);
         v0 = *reinterpret_cast<const u32x4*>(vimg + off0);
@@ -468,26 +473,26 @@ __device__ __forceinline__ void pla_bwd_query_body(const BwdParams& p) {
       reinterpret_cast<uint2*>(kv)[tile_chunk(r, 2 * dt + (g >> 1)) * 2 + (g & 1)] = o;
     }
     wave_lds_sync();
-    if (la < nq) *reinterpret_cast<u32x4*>(p.dq + (size_t)(tok0 + la) * C + h * kD + lc * 8) = kv[wr_chunk];
+    if (!RAG || la < nq) *reinterpret_cast<u32x4*>(p.dq + (size_t)(tok0 + la) * C + h * kD + lc * 8) = kv[wr_chunk];
     wave_lds_sync();
   }
 }
 
-template <int NT>
+template <int NT, bool RAG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) void pla_bwd_query_kernel(BwdParams p) {
-  pla_bwd_query_body<NT, true, false, false>(p);
+  pla_bwd_query_body<NT, true, false, false, RAG>(p);
 }
-template <int NT>
+template <int NT, bool RAG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pla_bwd_query_rel_kernel(BwdParams p) {
-  pla_bwd_query_body<NT, true, true, true>(p);
+  pla_bwd_query_body<NT, true, true, true, RAG>(p);
 }
-template <int NT>
+template <int NT, bool RAG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) void pla_bwd_query_rel_ds_kernel(BwdParams p) {
-  pla_bwd_query_body<NT, true, true, false>(p);
+  pla_bwd_query_body<NT, true, true, false, RAG>(p);
 }
-template <int NT>
+template <int NT, bool RAG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void pla_bwd_query_scalar_kernel(BwdParams p) {
-  pla_bwd_query_body<NT, false, false, false>(p);
+  pla_bwd_query_body<NT, false, false, false, RAG>(p);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -504,7 +509,7 @@ struct KeyItem {
 // the groups of a tile in consecutive waves: they walk the same list over the same strips at the same time, so the
 // strips' rows, the entry values and the list are fetched into the XCD's L2 once for all heads, and the rows that an
 // XCD has in use at a time do not grow with the number of heads.
-template <int HG>
+template <int HG, bool RAG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_bwd_key_kernel(BwdParams p) {
   __shared__ __align__(16) bf16_t tile_all[4][HG * 256];  // per wave and head: p[token][query]
   // per wave, twice (two incidences in flight): the strip's q rows, then its dout rows.  They come straight from
@@ -529,7 +534,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   // last real row (its p is 0: no entry refers to it), stores past the end are skipped
   const size_t img_row0 = (size_t)b * p.N;
   const int t0 = (kt - b * p.strips_per_image) * 16;  // the tile's first token, within the image
-  const int nt = min(16, p.N - t0);
+  const int nt = RAG ? min(16, p.N - t0) : 16;
   const int lo = __builtin_amdgcn_readfirstlane(p.rev_offset[kt]);
   const int n = __builtin_amdgcn_readfirstlane(p.rev_offset[kt + 1]) - lo;
   // q / dout rows cross through LDS: a lane loads 16 contiguous bytes of a row so that a quad reads 64
@@ -548,12 +553,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   }
   // element offset, within the strip's rows, of the piece this lane fetches in load i: row i * 64 / PR + la, and
   // the piece whose place in the tile is lc, i.e. piece lc ^ swz(row)
-  uint32_t q_dma_row[HG], q_dma_piece[HG];
+  uint32_t q_dma[HG], q_dma_row[HG], q_dma_piece[HG];  // whole offset (full strips); row and piece apart (RAG)
 #pragma unroll
   for (int i = 0; i < HG; ++i) {
     const int row = i * (64 / PR) + la;
     q_dma_row[i] = (uint32_t)row;
     q_dma_piece[i] = (uint32_t)((lc ^ swz(row)) * 8);
+    q_dma[i] = (uint32_t)(row * C) + q_dma_piece[i];
   }
   // what this lane gives to lds_read_tr to receive, for channel 16dt + r of head hh, the values of rows (queries)
   // 4g..4g+3: the quarter r % 4 of those 16 channels in row 4g + r / 4
@@ -578,7 +584,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     Frag8 vop[HG];
 #pragma unroll
     for (int hh = 0; hh < HG; ++hh)
-      vop[hh].u4 = *reinterpret_cast<const uint4*>(p.v + (img_row0 + t0 + min(r, nt - 1)) * C + (size_t)((hg + hh) * kD) + g * 8);
+      vop[hh].u4 = *reinterpret_cast<const uint4*>(p.v + (img_row0 + t0 + (RAG ? min(r, nt - 1) : r)) * C + (size_t)((hg + hh) * kD) + g * 8);
     f32x4 dk[HG][2], dv[HG][2];
 #pragma unroll
     for (int hh = 0; hh < HG; ++hh)
@@ -606,7 +612,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
         typedef __attribute__((address_space(3))) void* lptr_t;
 #pragma unroll
         for (int i = 0; i < HG; ++i) {  // load i: rows i * 64 / PR onwards
-          const uint32_t at = min(q_dma_row[i], last_q) * (uint32_t)C + q_dma_piece[i];
+          const uint32_t at = RAG ? min(q_dma_row[i], last_q) * (uint32_t)C + q_dma_piece[i] : q_dma[i];
           __builtin_amdgcn_global_load_lds((gptr_t)(p.q + qbase + at), (lptr_t)(rows + i * 64), 16, 0, 0);
           __builtin_amdgcn_global_load_lds((gptr_t)(p.dout + qbase + at), (lptr_t)(rows + HG * 64 + i * 64), 16, 0, 0);
         }
@@ -720,7 +726,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 #pragma unroll
     for (int i = 0; i < HG; ++i) {
       const size_t at = (img_row0 + t0 + i * (64 / PR)) * C + (size_t)(hg * kD) + q_lane;
-      if (i * (64 / PR) + la < nt) {
+      if (!RAG || i * (64 / PR) + la < nt) {
         *reinterpret_cast<u32x4*>(p.dk + at) = rows0[wr_chunk[i]];
         *reinterpret_cast<u32x4*>(p.dv + at) = rows0[HG * 64 + wr_chunk[i]];
       }
@@ -828,8 +834,12 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
   p.spi_magic = div_magic((a.N + 15) / 16);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0) &&
                    (!p.ds || reinterpret_cast<uintptr_t>(p.ds) % 16 == 0);
-#define AFFMAE_BWDQ(KERNEL, NT) \
-  AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (KERNEL<NT>), grid_q, dim3(256), 0, stream, p)
+  const bool rag = a.N % 16 != 0;  // a short last strip / token tile per image: the variants with row clamps
+#define AFFMAE_BWDQ(KERNEL, NT)                                                                              \
+  do {                                                                                                       \
+    if (rag) AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (KERNEL<NT, true>), grid_q, dim3(256), 0, stream, p);  \
+    else AFFMAE_LAUNCH("pla_bwd_query_kernel", stream, (KERNEL<NT, false>), grid_q, dim3(256), 0, stream, p);     \
+  } while (0)
   if (a.rel_table && a.rel_part) {  // callers check pla_cluster_relpos_supported first
     if (2 * a.K <= kWave) AFFMAE_BWDQ(pla_bwd_query_rel_kernel, 1); else AFFMAE_BWDQ(pla_bwd_query_rel_kernel, 2);
   } else if (a.rel_table) {
@@ -844,10 +854,13 @@ hipError_t launch_pla_bwd_cluster(const PlaArgs& a, const void* plan, void* work
     else AFFMAE_BWDQ(pla_bwd_query_scalar_kernel, 16);
   }
 #undef AFFMAE_BWDQ
-  if (a.H % 2 == 0)
-    AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<2>, grid, dim3(256), 0, stream, p);
-  else
-    AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, pla_bwd_key_kernel<1>, grid, dim3(256), 0, stream, p);
+  if (a.H % 2 == 0) {
+    if (rag) AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, (pla_bwd_key_kernel<2, true>), grid, dim3(256), 0, stream, p);
+    else AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, (pla_bwd_key_kernel<2, false>), grid, dim3(256), 0, stream, p);
+  } else {
+    if (rag) AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, (pla_bwd_key_kernel<1, true>), grid, dim3(256), 0, stream, p);
+    else AFFMAE_LAUNCH("pla_bwd_key_kernel", stream, (pla_bwd_key_kernel<1, false>), grid, dim3(256), 0, stream, p);
+  }
   if (a.rel_table && a.rel_part) {
     const int cells = (2 * a.rel_R + 1) * (2 * a.rel_R + 1);
     float* second = reinterpret_cast<float*>(reinterpret_cast<char*>(a.rel_part) +

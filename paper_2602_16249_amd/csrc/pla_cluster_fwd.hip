@@ -58,7 +58,8 @@ constexpr int kFwdWaves = 4;  // waves per workgroup; they share nothing but the
 // read from a tensor.  The coordinates of the pass's token tiles are staged once in the wave's K/V tile (free
 // until the first pair is staged); a lane then reads the neighbour's coordinates by the entry's (slot, token)
 // fields, takes the bin against its query's coordinates and fetches the table value through the vector cache.
-template <int NT, bool VEC, bool REL>
+// RAG: N is not a multiple of 16 (only then do the row clamps and store tests below exist in the code).
+template <int NT, bool VEC, bool REL, bool RAG>
 __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   static_assert(!REL || VEC, "the table form is built for 16-byte items");
   __shared__ __align__(16) bf16_t scratch_all[kFwdWaves][kSlotCap * 256 + 8];  // + a cell that absorbs skipped entries
@@ -82,7 +83,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
   const long long tok0 = img_base + q0;
   // An image's last strip and last token tile may be short (N % 16 != 0): rows past the end are never addressed -
   // loads repeat the last real row (no plan entry refers to it, so it meets probability 0), stores are skipped.
-  const int nq = min(16, p.N - q0);
+  const int nq = RAG ? min(16, p.N - q0) : 16;
   const int C = p.H * kD;
   const int K = p.K;
 
@@ -109,7 +110,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         ent[t][EW > 2 ? 2 : 0] = live ? w.z : 0xffffffffu;
         ent[t][EW > 3 ? 3 : 0] = live ? w.w : 0xffffffffu;
         const int qi_raw = fast_div(ii, p.cq_magic), j0 = (ii - qi_raw * chunks_per_query) * 8;
-        const int qi = min(qi_raw, nq - 1);
+        const int qi = RAG ? min(qi_raw, nq - 1) : qi_raw;
         uint4 bv = make_uint4(0, 0, 0, 0);
         if (REL) {  // the query's coordinates instead
           const float2 c = (reinterpret_cast<const float2*>(p.coords) + tok0)[qi];
@@ -124,7 +125,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         bw[t][EW > 3 ? 3 : 0] = bv.w;
       } else {
         ent[t][0] = live ? (uint32_t)p.entries[(size_t)sg * 16 * K + ii] : kNoEntry;
-        const int qi_raw = fast_div(ii, p.k_magic), qi = min(qi_raw, nq - 1);
+        const int qi_raw = fast_div(ii, p.k_magic), qi = RAG ? min(qi_raw, nq - 1) : qi_raw;
         bw[t][0] = bias_head ? (uint32_t)bias_head[(uint32_t)(qi * p.H * K + (ii - qi_raw * K))] : 0u;
       }
     }
@@ -156,7 +157,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
     load_items(ent, bw);
     // the Q^T operand: lane (query r, channels 8g..8g+7)
     const u32x4 qraw =
-        *reinterpret_cast<const u32x4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(min(la, nq - 1) * C + lc * 8));
+        *reinterpret_cast<const u32x4*>(p.q + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)((RAG ? min(la, nq - 1) : la) * C + lc * 8));
     // first use of a loaded value: everything the strip streams in is in flight by now
     const int ntiles = min((int)__builtin_amdgcn_readfirstlane(cnt_raw), kMaxSlots);
     kv[wr_chunk] = qraw;  // the q rows cross through LDS like the K/V rows
@@ -177,7 +178,7 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
 #pragma unroll
         for (int i = 0; i < (kSlotCap * 16 + kWave - 1) / kWave; ++i) {
           const int tile = __shfl(my_tile, slot0 + min(4 * i + g, nsl - 1));
-          reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)min(tile * 16 + r, p.N - 1)];
+          reinterpret_cast<float2*>(kv)[i * kWave + lane] = cimg[(uint32_t)(RAG ? min(tile * 16 + r, p.N - 1) : tile * 16 + r)];
         }
       }
       wave_lds_sync();
@@ -216,7 +217,11 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
         // whatever kind.)  The offsets are made opaque, or the compiler rebuilds 64-bit vector addresses.
         const uint32_t tile0 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr, nsl - 1));
         const uint32_t tile1 = (uint32_t)__builtin_amdgcn_readlane(my_tile, slot0 + min(2 * pr + 1, nsl - 1));
-        uint32_t off0 = min(lane_off_h + tile0 * tile_bytes, lane_off_max), off1 = min(lane_off_h + tile1 * tile_bytes, lane_off_max);
+        uint32_t off0 = lane_off_h + tile0 * tile_bytes, off1 = lane_off_h + tile1 * tile_bytes;
+        if (RAG) {
+          off0 = min(off0, lane_off_max);
+          off1 = min(off1, lane_off_max);
+        }
         asm volatile("" : "+v"(off0), "+v"(off1));
         k0 = *reinterpret_cast<const u32x4*>(kimg + off0);
         v0 = *reinterpret_cast<const u32x4*>(vimg + off0);
@@ -341,25 +346,25 @@ __device__ __forceinline__ void pla_fwd_cluster_body(const FwdParams& p) {
       reinterpret_cast<uint2*>(kv)[tile_chunk(r, 2 * dt + (g >> 1)) * 2 + (g & 1)] = o;
     }
     wave_lds_sync();
-    if (la < nq)
+    if (!RAG || la < nq)
       *reinterpret_cast<u32x4*>(p.out + ((size_t)tok0 * C + (size_t)(h * kD)) + (uint32_t)(la * C + lc * 8)) = kv[wr_chunk];
-    if (g == 0 && r < nq) (p.lse + (size_t)tok0 * p.H + h)[(uint32_t)(r * p.H)] = m_fin + __logf(l_tot);
+    if (g == 0 && (!RAG || r < nq)) (p.lse + (size_t)tok0 * p.H + h)[(uint32_t)(r * p.H)] = m_fin + __logf(l_tot);
   }
 }
 
 // The 16-byte path keeps four waves per SIMD; the single-entry path (K not a multiple of 8) holds more
 // per-lane state and is built for two.
-template <int NT>
+template <int NT, bool RAG>
 __global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_kernel(FwdParams p) {
-  pla_fwd_cluster_body<NT, true, false>(p);
+  pla_fwd_cluster_body<NT, true, false, RAG>(p);
 }
-template <int NT>
+template <int NT, bool RAG>
 __global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void pla_fwd_cluster_rel_kernel(FwdParams p) {
-  pla_fwd_cluster_body<NT, true, true>(p);
+  pla_fwd_cluster_body<NT, true, true, RAG>(p);
 }
-template <int NT>
+template <int NT, bool RAG>
 __global__ __launch_bounds__(kFwdWaves* kWave) __attribute__((amdgpu_waves_per_eu(3, 4))) void pla_fwd_cluster_scalar_kernel(FwdParams p) {
-  pla_fwd_cluster_body<NT, false, false>(p);
+  pla_fwd_cluster_body<NT, false, false, RAG>(p);
 }
 
 }  // namespace
@@ -402,8 +407,14 @@ hipError_t launch_pla_fwd_cluster(const PlaArgs& a, const void* plan, hipStream_
   // the XCD-contiguous mapping needs a grid that is a multiple of 8; surplus waves exit at once
   const dim3 grid((((long long)L.strips * a.H + kFwdWaves - 1) / kFwdWaves + 7) / 8 * 8);
   const bool vec = a.K % 8 == 0 && (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 16 == 0);
-#define AFFMAE_FWD(KERNEL, NT) \
-  AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT>), grid, dim3(kFwdWaves * kWave), 0, stream, p)
+  const bool rag = a.N % 16 != 0;  // a short last strip / token tile per image: the variants with row clamps
+#define AFFMAE_FWD(KERNEL, NT)                                                                                   \
+  do {                                                                                                           \
+    if (rag)                                                                                                     \
+      AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT, true>), grid, dim3(kFwdWaves * kWave), 0, stream, p);  \
+    else                                                                                                         \
+      AFFMAE_LAUNCH("pla_fwd_cluster_kernel", stream, (KERNEL<NT, false>), grid, dim3(kFwdWaves * kWave), 0, stream, p); \
+  } while (0)
   if (a.rel_table) {  // callers check pla_cluster_relpos_supported first
     if (2 * a.K <= kWave) AFFMAE_FWD(pla_fwd_cluster_rel_kernel, 1); else AFFMAE_FWD(pla_fwd_cluster_rel_kernel, 2);
   } else if (vec) {
