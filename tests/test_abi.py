@@ -146,6 +146,40 @@ def test_attention_rejects_bad_arguments_on_host():
     assert bwd(B=1 << 15, N=1 << 15, K=8) == -5   # pairs are numbered in 32 bits
 
 
+def test_merging_rejects_bad_arguments_on_host():
+    lib = aff.load_library()
+    p = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
+
+    def select(score=p, idx=p, xy=None, coords=None, B=2, N=100, n_keep=25):
+        return lib.affmae_merge_select(score, coords, B, N, n_keep, idx, xy, None)
+
+    assert select(score=None) == -1 and select(idx=None) == -1
+    assert select(xy=p) == -1                     # coordinates wanted but none given
+    assert select(n_keep=0) == -2 and select(n_keep=101) == -2 and select(B=0) == -2
+    assert select(xy=ctypes.c_void_p(4100), coords=p) == -2   # pairs are moved 8 bytes at a time
+    assert select(N=(1 << 24) + 1, n_keep=5) == -5
+
+    def fwd(feat=p, out=p, K=8, n_keep=25, pw=0.5, dtype=1, coords=p):
+        return lib.affmae_merge_fwd(feat, coords, p, p, p, 2, 100, 64, K, n_keep, ctypes.c_float(pw), dtype, out, None)
+
+    assert fwd(feat=None) == -1 and fwd(out=None) == -1
+    assert fwd(dtype=5) == -3
+    assert fwd(K=65) == -5 and fwd(K=0) == -2 and fwd(n_keep=101) == -2
+    assert fwd(pw=-1.0) == -2 and fwd(pw=float("nan")) == -2   # p >= 0, finite
+    assert fwd(coords=ctypes.c_void_p(4100)) == -2
+
+    def bwd(ws=p, nbytes=1 << 30, dscore=p, K=8):
+        return lib.affmae_merge_bwd(p, p, p, p, p, p, 2, 100, 64, K, 25, ctypes.c_float(0.5), 1, p, dscore, None, ws,
+                                    nbytes, None)
+
+    assert bwd(dscore=None) == -1
+    assert bwd(ws=None, nbytes=0) == -4 and bwd(nbytes=64) == -4 and bwd(ws=ctypes.c_void_p(4100)) == -4
+    need = lib.affmae_merge_bwd_workspace_bytes(2, 100, 8, 25)
+    assert need >= 2 * 25 * 8 * (4 + 4 + 4 + 4) + 2 * 100 * 4   # w, dz, token and list place of every pair; offsets
+    assert lib.affmae_merge_bwd_workspace_bytes(2, 100, 65, 25) == 0
+    assert bwd(nbytes=need - 1) == -4
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
