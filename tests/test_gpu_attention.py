@@ -70,6 +70,7 @@ CLUSTER_CASES = [
     ("mae_pt_s1_1024", 2, 1000, 64, 2, 48, 64, 8, True),   # N % 16 = 8: short last strip and token tile, blank sums
     ("merged_stage", 3, 250, 256, 8, 16, 32, 4, False),    # N % 16 = 10, eight heads (four head groups per tile)
     ("knn_scale", 1, 33, 64, 2, 12, 16, 2, True),          # three strips, the last of one query
+    ("merged_stage", 2, 250, 96, 3, 7, 32, 4, True),       # short last strip with single-entry items and one head per sweep
 ]
 
 
