@@ -124,6 +124,32 @@ def test_full_image_with_blank_tokens():
     print(errs)
 
 
+def test_instrumented_library_gives_the_same_bits():
+    """The bench takes its per-kernel times in the instrumented twin library (the same sources with events around
+    every launch): its tiled forward and backward results are bit-equal to the product library's."""
+    import paper_2602_16249_amd as aff
+    from helpers import run_gpu_attention
+    cfg = CONFIGS["ft_s1_1024"].scaled(B=1)
+    print("case ft_s1_1024 B=1 product against instrumented library", flush=True)
+    w = make_workload(cfg)
+    nbr, near = oracle.knn(w["coords"], None, cfg.S, cfg.M, cfg.K)
+    scale = 1.0 / np.sqrt(cfg.d)
+    out, lse, g = run_gpu_attention(w, nbr, cfg.dtype, scale, near, cfg.S, cfg.M, use_plan=True)
+    aff.use_timed_library(True)
+    try:
+        tout, tlse, tg = run_gpu_attention(w, nbr, cfg.dtype, scale, near, cfg.S, cfg.M, use_plan=True)
+    finally:
+        aff.use_timed_library(False)
+    assert torch_equal(out, tout) and torch_equal(lse, tlse)
+    for name in g:
+        assert torch_equal(g[name], tg[name]), name
+
+
+def torch_equal(a, b):
+    import torch
+    return a is None and b is None or torch.equal(a, b)
+
+
 def test_gather_kernels_on_full_images():
     """Two full 1024px images without the cluster promise: the gather kernels at the benchmark's shape (16384
     queries per image: the list builder of the backward takes them in two sweeps), every element compared; the
