@@ -13,9 +13,9 @@
 //             sum of the feature rows moves 16 bytes per lane: a row takes PP lanes, 64 / PP rows are in flight per
 //             trip, and the row groups are added up with lane shuffles at the end.
 //   backward: the same wave forms g_j = <dout_anchor, feat_j> (partial dot per lane, reduced inside a row's
-//             lanes), dz_j = w_j sum_i w_i (g_j - g_i) (differences first: the form does not cancel when one
-//             weight saturates), its part of dp (distances relative to the nearest neighbour's, for the same
-//             reason), and keeps w, dz and the token of every (anchor, neighbour) pair.  dfeat and dscore are then
+//             lanes), dz_j = w_j (d_j - sum_i w_i d_i) with d_i = g_i - g_ref relative to the neighbour of largest
+//             weight (differences first: the form does not cancel when one weight saturates), its part of dp
+//             (distances relative to the nearest neighbour's, for the same reason), and keeps w, dz and the token of every (anchor, neighbour) pair.  dfeat and dscore are then
 //             gathered, not scattered: the pairs are filed per token (the list builder of the virtual-token
 //             backward) and every token adds up w * dout, respectively dz, over its own list.
 #include <algorithm>
@@ -419,13 +419,17 @@ __global__ __launch_bounds__(256) void merge_bwd_kernel(const T* __restrict__ fe
   wave_lds_sync();
   float g_mine = lane < K ? g[lane] : 0.f;
   asm volatile("" : "+v"(g_mine));
-  // dz_j = w_j (g_j - sum_i w_i g_i) = w_j sum_i w_i (g_j - g_i): the differences first
-  float spread = 0.f;
-  for (int i = 0; i < K; ++i) {
-    const float wi = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(nb.w), i));
-    const float gi = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(g_mine), i));
-    spread = fmaf(wi, g_mine - gi, spread);
-  }
+  // dz_j = w_j (g_j - sum_i w_i g_i).  Taken relative to the neighbour with the largest weight (the first of
+  // them), d_i = g_i - g_ref: dz_j = w_j (d_j - sum_i w_i d_i), since the weights add up to 1.  The differences are
+  // formed first, the reference's own term is exactly 0 and every other term carries a small weight when one
+  // weight saturates - the form does not cancel then, like sum_i w_i (g_j - g_i), at two wave reductions instead of
+  // K broadcasts per lane.
+  const float wmax = wave_max(nb.w);  // lanes >= K hold weight 0
+  const unsigned long long at_max = __ballot(lane < K && nb.w == wmax);  // not empty: K >= 1 and wmax is some lane's
+  const int ref = __builtin_amdgcn_readfirstlane((int)__builtin_ctzll(at_max));
+  const float gref = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(g_mine), ref));
+  const float delta = g_mine - gref;
+  const float spread = delta - wave_sum(nb.w * delta);
   const float dz = nb.w * spread;  // lanes >= K hold weight 0
   // sum_j dz_j (-dist_j) with sum_j dz_j = 0: distances relative to the nearest neighbour's
   const float dnear = -wave_max(lane < K ? -nb.dist : -INFINITY);

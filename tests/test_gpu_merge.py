@@ -48,6 +48,8 @@ CASES = [
     ("bf16", 1, 512, 1032, 33, 64, 4, 77, 0.1),   # more than 64 pieces per row: several trips over the pieces
     ("bf16", 3, 300, 6, 64, 50, 6, 299, 2.0),     # K at the limit, odd rows, nearly every token an anchor
     ("bf16", 1, 128, 8, 1, 16, 2, 64, 1.0),       # K = 1: the merged token is the anchor itself
+    ("f32", 2, 512, 64, 16, 32, 4, 128, 3.0),     # weights close to saturated on the anchor itself: gradients are small differences
+    ("f32", 1, 256, 32, 12, 32, 2, 64, 8.0),
 ]
 
 
