@@ -279,6 +279,20 @@ struct Piece16<bf16_t> {
   }
 };
 
+// <a, b> over 16 bytes: bf16 by four two-element dot instructions on the packed values, fp32 by multiply-adds
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ float dot16(const bf16_t* pa, const uint4& b) {
+  const uint4 a = *reinterpret_cast<const uint4*>(pa);
+  float acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), 0.f, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), acc, false);
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), acc, false);
+}
+__device__ __forceinline__ float dot16(const float* pa, const uint4& b) {
+  const float4 a = *reinterpret_cast<const float4*>(pa);
+  return fmaf(a.w, __uint_as_float(b.w), fmaf(a.z, __uint_as_float(b.z), fmaf(a.y, __uint_as_float(b.y), a.x * __uint_as_float(b.x))));
+}
+
 // The anchor of this wave and the neighbour of this lane: index, distance, weight.  Every lane runs this.
 struct Nbr {
   int anchor_slot;  // b * n_keep + a
@@ -339,7 +353,7 @@ __global__ __launch_bounds__(256) void merge_fwd_kernel(const T* __restrict__ fe
         const int ij = __shfl(nb.idx, jj);
         const float wj = j < K ? wraw : 0.f;
         float f[8];
-        Piece16<T>::load(rows + (size_t)ij * C + c0, f);
+        Piece16<T>::load(rows + (uint32_t)(ij * C + c0), f);  // (row offsets inside an image fit 32 bits on this path)
 #pragma unroll
         for (int e = 0; e < CH; ++e) acc[e] = fmaf(wj, f[e], acc[e]);
       }
@@ -392,16 +406,12 @@ __global__ __launch_bounds__(256) void merge_bwd_kernel(const T* __restrict__ fe
     for (int pc0 = 0; pc0 < pieces; pc0 += PP) {
       const bool pon = pc0 + pc < pieces;
       const int c0 = min(pc0 + pc, pieces - 1) * CH;
-      float go[8];
-      Piece16<T>::load(grow + c0, go);
+      const uint4 go = *reinterpret_cast<const uint4*>(grow + c0);
       for (int j0 = 0; j0 < K; j0 += RW) {
         const int j = j0 + rs;
         const int ij = __shfl(nb.idx, min(j, K - 1));
-        float f[8];
-        Piece16<T>::load(rows + (size_t)ij * C + c0, f);
-        float part = 0.f;
-#pragma unroll
-        for (int e = 0; e < CH; ++e) part = fmaf(go[e], f[e], part);
+        // (row offsets inside an image fit 32 bits on this path)
+        float part = dot16(rows + (uint32_t)(ij * C + c0), go);
         part = pon ? part : 0.f;
         for (int o = 1; o < PP; o <<= 1) part += __shfl_xor(part, o);  // over the lanes of the row
         if (pc == 0 && j < K) g[j] += part;                            // (one lane per j: no two lanes add to one cell)
