@@ -124,6 +124,30 @@ def test_full_image_with_blank_tokens():
     print(errs)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_through_the_tiled_kernels(seed):
+    """Seeded random N (mostly not a multiple of 16 or of S), S, M, K, H, batch and blank tokens: neighbour table by
+    the oracle's clustered search, tiled kernels with the plan rebuilt inside the call and with a plan built once."""
+    rng = np.random.default_rng(9000 + seed)
+    while True:
+        S = int(rng.choice([16, 32, 48, 64]))
+        N = int(rng.integers(1, 70 if seed % 4 == 0 else 1500))
+        G = (N + S - 1) // S
+        M = int(rng.integers(1, min(G, 8) + 1))
+        kmax = min(64, (M - 1) * S + N - (G - 1) * S)
+        if M * S <= 1024 and kmax >= 1:
+            break
+    K, H, B = int(rng.integers(1, kmax + 1)), int(rng.choice([1, 2, 3, 4, 8])), int(rng.integers(1, 4))
+    blank = bool(rng.integers(0, 2))
+    name = ["mae_pt_s1_1024", "merged_stage", "knn_scale"][int(rng.integers(0, 3))]
+    print(f"case {name} B={B} N={N} S={S} M={M} K={K} H={H} blank={blank}", flush=True)
+    cfg = CONFIGS[name].scaled(B=B, N=N, C=32 * H, H=H, K=K, S=S, M=M, dtype="bf16")
+    w = make_workload(cfg, blank=blank)
+    nbr, near = oracle.knn(w["coords"], None, S, M, K)
+    for use_plan in (False, True):
+        check_attention(w, nbr, "bf16", 1.0 / np.sqrt(32), near=near, S=S, M=M, blank=blank, use_plan=use_plan)
+
+
 def test_instrumented_library_gives_the_same_bits():
     """The bench takes its per-kernel times in the instrumented twin library (the same sources with events around
     every launch): its tiled forward and backward results are bit-equal to the product library's."""
